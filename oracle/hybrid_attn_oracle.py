@@ -1,0 +1,213 @@
+"""fp64 CPU oracle for the hybrid-attention forward of "Attention Surgery" (arXiv 2509.24899).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the HIP path is
+checked against.  It shares no code with the GPU library and must never be imported by the
+product path: only tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+
+What it computes (Sec. 3.2, Eq. "hybrid"): for every query token i of one head
+
+            sum_{j in T_S} exp(scale * q_i.k_j - c_i) v_j  +  phi_q(q_i) . S
+    y_i  =  -------------------------------------------------------------------
+            sum_{j in T_S} exp(scale * q_i.k_j - c_i)      +  phi_q(q_i) . z
+
+    S = sum_{j in T_L} phi_k(k_j)^T v_j   (F x d),     z = sum_{j in T_L} phi_k(k_j)   (F)
+
+with T_S the uniformly strided softmax tokens, T_L the rest, c_i the largest exponent of row i
+over T_S, and phi the learnable polynomial feature map of Sec. 3.2 ("Characterization of phi").
+
+Readings of the paper taken here (each is a decision, listed again in the design notes):
+  * T_S = {i | i mod R = 1} over 1-indexed tokens  ==  0-indexed j % R == 0  (Sec. 3.2).
+  * R = 1 is "full softmax" (Sec. 3.3, block-rate optimisation): T_S = all tokens, T_L empty.
+  * R = 0 encodes a purely linear block (Tab. "vsnodist" rows "Linear"): T_S empty, no c_i.
+  * c_i is subtracted inside the softmax exponents only, exactly as Eq. "hybrid" is printed;
+    the linear terms are NOT multiplied by exp(-c_i).  The maximum runs over T_S only.
+  * Attention is per head; scale is passed in (1/sqrt(d_head) for the paper's operator);
+    the feature maps see the unscaled q and k.
+  * phi: per-head 2-layer MLP (a grouped 1x1 convolution per layer) with ReLU between the
+    layers; the output is made positive by a softmax over all F output channels of the token,
+    then split into P contiguous slices and slice p (1-based) is raised elementwise to the
+    power p and the slices are concatenated in channel order.
+
+All arithmetic is float64; nothing is rounded inside.  Inputs are whatever the caller hands in
+(already rounded to the io dtype of the GPU path and widened).
+
+Pins (tests/test_oracle_pins.py): R=1 against library softmax attention; the feature map against
+torch's grouped conv1d; closed forms for constant feature maps and for the two-token case; the
+explicit N x N loop form `hybrid_attn_dense_loops`; convexity / permutation / row-independence
+invariants; planted-mistake variants that the pins must reject.  No function here is
+"parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+ACT_SOFTMAX = 0
+ACT_EXP = 1
+ACT_RELU = 2
+
+
+class FeatureMap:
+    """Parameters of one feature map (phi_q or phi_k) for all heads.
+
+    w1: [H, Hd, d]   b1: [H, Hd]   w2: [H, F, Hd]   b2: [H, F]   (Sec. 3.2: per-head embedding
+    network realised as grouped 1x1 convolutions), P = polynomial degree, act = output
+    positivity (softmax over the F channels by default).
+    """
+
+    def __init__(self, w1, b1, w2, b2, poly_degree=2, act=ACT_SOFTMAX):
+        self.w1 = np.asarray(w1, dtype=np.float64)
+        self.w2 = np.asarray(w2, dtype=np.float64)
+        H, Hd, _ = self.w1.shape
+        F = self.w2.shape[1]
+        self.b1 = np.zeros((H, Hd)) if b1 is None else np.asarray(b1, dtype=np.float64)
+        self.b2 = np.zeros((H, F)) if b2 is None else np.asarray(b2, dtype=np.float64)
+        self.P = int(poly_degree)
+        self.act = int(act)
+        if F % self.P != 0:
+            raise ValueError("poly_degree must divide the feature width F")
+
+    @property
+    def F(self):
+        return self.w2.shape[1]
+
+    def n_params(self):
+        """Learnable parameter count of this one map over all heads (weights and biases)."""
+        return self.w1.size + self.b1.size + self.w2.size + self.b2.size
+
+
+def token_split(N: int, R: int):
+    """Index sets (0-based) of softmax tokens T_S and linear tokens T_L (Sec. 3.2)."""
+    if R < 0:
+        raise ValueError("R must be >= 0")
+    idx = np.arange(N)
+    if R == 0:
+        is_s = np.zeros(N, dtype=bool)
+    else:
+        is_s = (idx % R) == 0  # 1-indexed "i mod R = 1"; for R = 1 every token (full softmax)
+    return idx[is_s], idx[~is_s]
+
+
+def feature_map(x, fm: FeatureMap, head: int):
+    """phi(x) for rows x [n, d] of one head -> [n, F]  (Sec. 3.2, "Characterization of phi")."""
+    x = np.asarray(x, dtype=np.float64)
+    hidden = np.maximum(x @ fm.w1[head].T + fm.b1[head], 0.0)        # [n, Hd], ReLU
+    u = hidden @ fm.w2[head].T + fm.b2[head]                         # [n, F]
+    if fm.act == ACT_SOFTMAX:
+        u = u - u.max(axis=-1, keepdims=True)
+        t = np.exp(u)
+        t = t / t.sum(axis=-1, keepdims=True)
+    elif fm.act == ACT_EXP:
+        t = np.exp(u)
+    elif fm.act == ACT_RELU:
+        t = np.maximum(u, 0.0)
+    else:
+        raise ValueError("unknown activation")
+    Dp = fm.F // fm.P
+    out = np.empty_like(t)
+    for p in range(1, fm.P + 1):                                     # psi_p(x) ** p
+        sl = slice((p - 1) * Dp, p * Dp)
+        out[:, sl] = t[:, sl] ** p
+    return out
+
+
+def linear_state(k, v, phi_k: FeatureMap, head: int, R: int):
+    """S = sum_{j in T_L} phi_k(k_j)^T v_j  [F, d]  and  z = sum_{j in T_L} phi_k(k_j)  [F]."""
+    N, d = k.shape
+    _, idx_l = token_split(N, R)
+    if idx_l.size == 0:
+        F = phi_k.F if phi_k is not None else 0
+        return np.zeros((F, d)), np.zeros(F)
+    f = feature_map(k[idx_l], phi_k, head)                           # [N_L, F]
+    return f.T @ np.asarray(v, dtype=np.float64)[idx_l], f.sum(axis=0)
+
+
+def softmax_part(q_rows, k, v, R: int, scale: float):
+    """a_i = sum_{T_S} exp(s_ij - c_i) v_j, l_i = sum_{T_S} exp(s_ij - c_i), c_i = max_j s_ij."""
+    N, d = k.shape
+    idx_s, _ = token_split(N, R)
+    n = q_rows.shape[0]
+    if idx_s.size == 0:
+        return np.zeros((n, d)), np.zeros(n), np.full(n, -np.inf)
+    ks = np.asarray(k, dtype=np.float64)[idx_s]
+    vs = np.asarray(v, dtype=np.float64)[idx_s]
+    s = (np.asarray(q_rows, dtype=np.float64) @ ks.T) * scale       # [n, N_S]
+    c = s.max(axis=1)
+    p = np.exp(s - c[:, None])
+    return p @ vs, p.sum(axis=1), c
+
+
+def hybrid_attn_head(q, k, v, phi_q, phi_k, head, R, scale, rows=None, row_chunk=2048):
+    """Eq. "hybrid" for one (batch, head): q,k,v [N, d] -> y [N or len(rows), d]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    N, d = q.shape
+    sel = np.arange(N) if rows is None else np.asarray(rows)
+    _, idx_l = token_split(N, R)
+    has_linear = idx_l.size > 0
+    if has_linear:
+        S, z = linear_state(k, v, phi_k, head, R)
+    out = np.empty((sel.size, d))
+    for lo in range(0, sel.size, row_chunk):
+        r = sel[lo:lo + row_chunk]
+        a, l, _ = softmax_part(q[r], k, v, R, scale)
+        num, den = a, l
+        if has_linear:
+            g = feature_map(q[r], phi_q, head)                      # [n, F]
+            num = num + g @ S
+            den = den + g @ z
+        out[lo:lo + row_chunk] = num / den[:, None]
+    return out
+
+
+def hybrid_attn(q, k, v, phi_q, phi_k, R, scale, rows=None):
+    """Eq. "hybrid" for q,k,v [B, H, N, d] -> y [B, H, N or len(rows), d] (float64).
+
+    `rows` (optional, 1-D indices) restricts the per-query part to a sample of query rows; the
+    state S, z always runs over every linear key.
+    """
+    B, H, N, d = q.shape
+    n_out = N if rows is None else len(rows)
+    y = np.empty((B, H, n_out, d))
+    for b in range(B):
+        for h in range(H):
+            y[b, h] = hybrid_attn_head(q[b, h], k[b, h], v[b, h], phi_q, phi_k, h, R, scale, rows)
+    return y
+
+
+def hybrid_attn_dense_loops(q, k, v, phi_q, phi_k, head, R, scale):
+    """Second, independent form for tiny inputs: the N x N weight matrix of Eq. "hybrid" built
+    entry by entry with Python loops, no cached state and no matrix products.
+
+    w_ij = exp(scale q_i.k_j - c_i) if j is a softmax token, phi_q(q_i).phi_k(k_j) otherwise;
+    y_i = sum_j w_ij v_j / sum_j w_ij.
+    """
+    N, d = q.shape
+    is_s = [(R >= 1 and (j + 1) % R == (1 % R)) for j in range(N)]   # the rule in 1-indexed form
+    gq = feature_map(q, phi_q, head) if phi_q is not None else None
+    fk = feature_map(k, phi_k, head) if phi_k is not None else None
+    y = np.zeros((N, d))
+    for i in range(N):
+        logits = {}
+        for j in range(N):
+            if is_s[j]:
+                acc = 0.0
+                for t in range(d):
+                    acc += float(q[i, t]) * float(k[j, t])
+                logits[j] = acc * scale
+        c = max(logits.values()) if logits else 0.0
+        den = 0.0
+        num = [0.0] * d
+        for j in range(N):
+            if is_s[j]:
+                w = float(np.exp(logits[j] - c))
+            else:
+                w = 0.0
+                for f in range(gq.shape[1]):
+                    w += float(gq[i, f]) * float(fk[j, f])
+            den += w
+            for t in range(d):
+                num[t] += w * float(v[j, t])
+        for t in range(d):
+            y[i, t] = num[t] / den
+    return y
