@@ -1,0 +1,128 @@
+/*
+ * hybrid_attn.h -- C ABI of the MI355X (gfx950) hybrid-attention forward.
+ *
+ * The operator is the hybrid attention of "Attention Surgery" (arXiv 2509.24899), Sec. 3.2,
+ * Eq. "hybrid": per (batch, head) and query token i
+ *
+ *            sum_{j in T_S} exp(scale q_i.k_j - c_i) v_j  +  phi_q(q_i) . S
+ *    y_i  =  ------------------------------------------------------------------ ,
+ *            sum_{j in T_S} exp(scale q_i.k_j - c_i)      +  phi_q(q_i) . z
+ *
+ *    S = sum_{j in T_L} phi_k(k_j)^T v_j  (F x d),   z = sum_{j in T_L} phi_k(k_j)  (F),
+ *
+ * T_S = every R-th token starting with the first (Sec. 3.2: 1-indexed "i mod R = 1"),
+ * T_L = the other tokens, c_i = max_{j in T_S} scale q_i.k_j (it stabilises the softmax terms
+ * only, exactly as the equation is printed), and phi the polynomial feature map of Sec. 3.2
+ * ("Characterization of phi"): per-head 2-layer MLP with ReLU, a positive output activation,
+ * P equal channel slices, slice p raised to the power p.
+ *
+ * Everything is plain C: POD structs, raw pointers, sizes.  Unless a parameter says "host", a
+ * data pointer is a DEVICE pointer (HIP global memory on the current device).  The library never
+ * allocates or frees device memory, never synchronises, and launches all work on the stream the
+ * caller passes; the caller owns every buffer.  No exception crosses the boundary: every entry
+ * point that can fail returns an ha_status, and all argument checks run on the host before the
+ * first HIP call (they work on a machine without a GPU).
+ */
+#ifndef HYBRID_ATTN_H
+#define HYBRID_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HA_OK = 0,
+  HA_ERR_NULL = 1,        /* a required pointer is NULL */
+  HA_ERR_SHAPE = 2,       /* non-positive or inconsistent sizes / strides */
+  HA_ERR_UNSUPPORTED = 3, /* a valid problem this build has no kernel for */
+  HA_ERR_ALIGN = 4,       /* a device pointer or stride breaks the 16-byte rule */
+  HA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than hybrid_attn_workspace_bytes() */
+  HA_ERR_DEVICE = 6       /* a HIP call failed; see hybrid_attn_last_device_error() */
+} ha_status;
+
+typedef enum { HA_BF16 = 0, HA_F32 = 1 } ha_dtype;
+
+/* Output activation that makes phi non-negative (Sec. 3.1 requires phi >= 0).  SOFTMAX runs over
+ * all F output channels of one token and head, before the slice / power step. */
+typedef enum { HA_ACT_SOFTMAX = 0, HA_ACT_EXP = 1, HA_ACT_RELU = 2 } ha_act;
+
+/* One feature map (phi_q or phi_k).  Weights are per head and shared over the batch
+ * (Sec. 3.2: "per-head embedding network ... grouped 1x1 convolutions").
+ *   hidden = relu(W1 x + b1),  u = W2 hidden + b2,  t = act(u),
+ *   phi(x)[c] = t[c] ^ (1 + c / (F / P))          (integer division: slice p gets power p). */
+typedef struct {
+  const void  *w1;        /* device [H, d_hidden, d_head], io dtype, row-major, contiguous */
+  const float *b1;        /* device [H, d_hidden] fp32, or NULL for zero bias */
+  const void  *w2;        /* device [H, d_out, d_hidden], io dtype, row-major, contiguous */
+  const float *b2;        /* device [H, d_out] fp32, or NULL for zero bias */
+  int32_t d_hidden;       /* Hd: multiple of 32 */
+  int32_t d_out;          /* F = P * D': multiple of 32 */
+  int32_t poly_degree;    /* P in 1..8, must divide d_out */
+  int32_t out_act;        /* ha_act */
+} ha_feature_map;
+
+/* One forward problem.  q, k, v and out are [B, H, N, d_head] views: element (b, h, n, c) lives at
+ * base + b*stride_b + h*stride_h + n*stride_n + c (strides in ELEMENTS, the innermost d_head run is
+ * contiguous), the same strides for all four tensors. */
+typedef struct {
+  int32_t B, H, N, d_head;
+  int32_t dtype;          /* ha_dtype of q, k, v, out, w1, w2.  HA_F32 inputs are rounded to bf16
+                             on load (the matrix cores run in bf16 with fp32 accumulation) and
+                             the result is written as fp32. */
+  int32_t block_size;     /* 64 or 128: the key tile staged through LDS per loop step; the query
+                             tile of one workgroup is 2 * block_size rows.  A tiling knob only:
+                             the result does not depend on it beyond fp32 summation order. */
+  int32_t hybrid_rate;    /* R.  0: no softmax tokens (pure linear attention, r = 0);
+                             1: every token is a softmax token (plain softmax attention, r = 1);
+                             R >= 2: tokens 0, R, 2R, ... (0-indexed) are softmax tokens, r = 1/R.
+                             Any R <= N is accepted; it is never rounded. */
+  float   softmax_scale;  /* multiplies q.k; pass 1/sqrt(d_head) for the paper's operator */
+  int64_t stride_b, stride_h, stride_n;
+} ha_problem;
+
+/* Host-only argument check (no HIP call).  phi_q and phi_k may be NULL iff the problem has no
+ * linear tokens (hybrid_rate == 1); otherwise both are required and must agree in d_out.
+ * Pointers inside the feature maps are checked for NULL and alignment but never dereferenced.
+ * Supported here: d_head in {64, 128} with d_hidden == d_out == d_head, or d_head == 128 with
+ * d_hidden == d_out == 256 (the paper's default widths, Tab. "phi"). */
+ha_status hybrid_attn_validate(const ha_problem *p, const ha_feature_map *phi_q,
+                               const ha_feature_map *phi_k);
+
+/* Bytes of device scratch hybrid_attn_forward needs for this problem (0 if the problem does not
+ * validate).  Holds the compacted softmax keys / values, the MLP weights in matrix-core operand
+ * order, the per-chunk partial states and the reduced state S, z.  Host only. */
+size_t hybrid_attn_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q,
+                                   const ha_feature_map *phi_k);
+
+/* Enqueue one forward on `hip_stream` (a hipStream_t passed as void*, NULL = the default stream)
+ * and return without waiting.  q, k, v: device, read-only.  out: device, written in full.
+ * workspace: device, 256-byte aligned, at least hybrid_attn_workspace_bytes() bytes, contents
+ * undefined before and after.  out and workspace must not overlap the inputs.  Two calls that
+ * share a workspace must be ordered on one stream.  Returns HA_OK once everything is enqueued. */
+ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k, const void *v,
+                              const ha_feature_map *phi_q, const ha_feature_map *phi_k,
+                              void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Debug / test taps into the same pipeline: run only the key-side passes (weight re-ordering,
+ * softmax-key compaction, state pass) and copy the reduced state out in plain layout.
+ * state_S: device fp32 [B, H, F, d_head]; state_z: device fp32 [B, H, F]. */
+ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const void *v,
+                                   const ha_feature_map *phi_k, float *state_S, float *state_z,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *hybrid_attn_status_string(ha_status s);
+
+/* hipError_t (as int) behind the most recent HA_ERR_DEVICE on the calling thread, 0 if none. */
+int hybrid_attn_last_device_error(void);
+
+/* Version of this ABI (bumped on any incompatible change). */
+int hybrid_attn_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYBRID_ATTN_H */

@@ -1,0 +1,188 @@
+// C ABI of the hybrid-attention library: host-side validation, workspace planning and the launch
+// sequence.  Nothing here touches the device except through the launchers and hipMemcpyAsync.
+#include <cmath>
+#include <cstring>
+
+#include "ha_plan.h"
+
+namespace ha {
+
+static thread_local int g_last_device_error = 0;
+
+static inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static ha_status check_map(const ha_feature_map *fm, const ha_problem &p) {
+  if (!fm->w1 || !fm->w2) return HA_ERR_NULL;
+  if (fm->d_hidden <= 0 || fm->d_out <= 0 || fm->poly_degree < 1) return HA_ERR_SHAPE;
+  if (fm->d_out % fm->poly_degree != 0) return HA_ERR_SHAPE;
+  if (fm->poly_degree > 8) return HA_ERR_UNSUPPORTED;
+  if (fm->out_act != HA_ACT_SOFTMAX && fm->out_act != HA_ACT_EXP && fm->out_act != HA_ACT_RELU) return HA_ERR_UNSUPPORTED;
+  const bool square = fm->d_hidden == p.d_head && fm->d_out == p.d_head;
+  const bool paper_width = p.d_head == 128 && fm->d_hidden == 256 && fm->d_out == 256;
+  if (!square && !paper_width) return HA_ERR_UNSUPPORTED;
+  if (!aligned16(fm->w1) || !aligned16(fm->w2)) return HA_ERR_ALIGN;
+  if ((fm->b1 && (reinterpret_cast<uintptr_t>(fm->b1) & 3u)) || (fm->b2 && (reinterpret_cast<uintptr_t>(fm->b2) & 3u)))
+    return HA_ERR_ALIGN;
+  return HA_OK;
+}
+
+static ha_status validate(const ha_problem *p, const ha_feature_map *phi_q, const ha_feature_map *phi_k) {
+  if (!p) return HA_ERR_NULL;
+  if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d_head <= 0) return HA_ERR_SHAPE;
+  if (p->hybrid_rate < 0 || p->hybrid_rate > p->N) return HA_ERR_SHAPE;
+  if (!(p->softmax_scale > 0.f) || !std::isfinite(p->softmax_scale)) return HA_ERR_SHAPE;
+  if (p->dtype != HA_BF16 && p->dtype != HA_F32) return HA_ERR_UNSUPPORTED;
+  if (p->d_head != 64 && p->d_head != 128) return HA_ERR_UNSUPPORTED;
+  if (p->block_size != 64 && p->block_size != 128) return HA_ERR_UNSUPPORTED;
+  if (p->stride_n < p->d_head || p->stride_h <= 0 || p->stride_b <= 0) return HA_ERR_SHAPE;
+  if ((int64_t)p->B * p->H > 65535) return HA_ERR_UNSUPPORTED;
+  const int per16 = p->dtype == HA_BF16 ? 8 : 4;   // elements per 16 bytes
+  if (p->stride_n % per16 || p->stride_h % per16 || p->stride_b % per16) return HA_ERR_ALIGN;
+  const bool has_linear = p->hybrid_rate != 1;
+  if (has_linear) {
+    if (!phi_q || !phi_k) return HA_ERR_NULL;
+    ha_status s = check_map(phi_q, *p);
+    if (s != HA_OK) return s;
+    s = check_map(phi_k, *p);
+    if (s != HA_OK) return s;
+    if (phi_q->d_out != phi_k->d_out || phi_q->d_hidden != phi_k->d_hidden) return HA_ERR_SHAPE;
+    if (phi_q->poly_degree != phi_k->poly_degree) return HA_ERR_SHAPE;
+  }
+  return HA_OK;
+}
+
+void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, Plan &pl) {
+  std::memset(&pl, 0, sizeof(pl));
+  pl.B = p.B; pl.H = p.H; pl.N = p.N; pl.D = p.d_head; pl.R = p.hybrid_rate;
+  pl.f32 = p.dtype == HA_F32;
+  pl.sb = p.stride_b; pl.sh = p.stride_h; pl.sn = p.stride_n;
+  pl.scale = p.softmax_scale;
+  pl.NS = pl.R == 0 ? 0 : (pl.N + pl.R - 1) / pl.R;
+  pl.NL = pl.N - pl.NS;
+  const bool has_linear = pl.NL > 0 && phi_q && phi_k;
+  pl.HD = has_linear ? phi_k->d_hidden : pl.D;
+  pl.F = has_linear ? phi_k->d_out : pl.D;
+  pl.P = has_linear ? phi_k->poly_degree : 1;
+  pl.act_q = has_linear ? phi_q->out_act : 0;
+  pl.act_k = has_linear ? phi_k->out_act : 0;
+  pl.KT = p.block_size;
+  pl.QB = p.block_size / 64;
+  pl.QT = 2 * p.block_size;
+  pl.n_qtiles = (pl.N + pl.QT - 1) / pl.QT;
+  pl.n_ktiles = (pl.NS + pl.KT - 1) / pl.KT;
+  pl.n_kblocks = pl.n_ktiles * (pl.KT / 32);
+  pl.CH = 1024;
+  pl.n_chunks = has_linear ? (pl.NL + pl.CH - 1) / pl.CH : 0;
+  pl.n_state_tiles = (pl.F / 32) * (pl.D / 32 + 1);
+  const size_t BH = (size_t)pl.B * pl.H;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+  pl.off_w1q = take((size_t)pl.H * pl.HD * pl.D * 2);
+  pl.off_w2q = take((size_t)pl.H * pl.F * pl.HD * 2);
+  pl.off_w1k = take((size_t)pl.H * pl.HD * pl.D * 2);
+  pl.off_w2k = take((size_t)pl.H * pl.F * pl.HD * 2);
+  pl.off_ks = take(BH * pl.n_kblocks * 32 * pl.D * 2);
+  pl.off_vs = take(BH * pl.n_kblocks * 32 * pl.D * 2);
+  pl.off_part = take(BH * pl.n_chunks * pl.n_state_tiles * 1024 * 4);
+  pl.off_S = take(BH * pl.F * pl.D * 4);
+  pl.off_z = take(BH * pl.F * 4);
+  pl.off_sthi = take(BH * pl.F * pl.D * 2);
+  pl.off_stlo = take(BH * pl.F * pl.D * 2);
+  pl.total = off;
+}
+
+static ha_status device_error(hipError_t e) {
+  g_last_device_error = static_cast<int>(e);
+  return HA_ERR_DEVICE;
+}
+
+static ha_status run_key_side(const Plan &pl, const void *k, const void *v, const ha_feature_map *phi_k, void *ws,
+                              hipStream_t st) {
+  hipError_t e;
+  if (pl.NS > 0 && (e = launch_compact(pl, k, v, ws, st)) != hipSuccess) return device_error(e);
+  if (pl.NL > 0) {
+    if ((e = launch_weight_prep(pl, *phi_k, false, ws, st)) != hipSuccess) return device_error(e);
+    if ((e = launch_state(pl, k, v, *phi_k, ws, st)) != hipSuccess) return device_error(e);
+    if ((e = launch_state_reduce(pl, ws, st)) != hipSuccess) return device_error(e);
+  }
+  return HA_OK;
+}
+
+}  // namespace ha
+
+extern "C" {
+
+ha_status hybrid_attn_validate(const ha_problem *p, const ha_feature_map *phi_q, const ha_feature_map *phi_k) {
+  return ha::validate(p, phi_q, phi_k);
+}
+
+size_t hybrid_attn_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q, const ha_feature_map *phi_k) {
+  if (ha::validate(p, phi_q, phi_k) != HA_OK) return 0;
+  ha::Plan pl;
+  ha::make_plan(*p, phi_q, phi_k, pl);
+  return pl.total;
+}
+
+ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k, const void *v,
+                              const ha_feature_map *phi_q, const ha_feature_map *phi_k, void *out, void *workspace,
+                              size_t workspace_bytes, void *hip_stream) {
+  ha_status s = ha::validate(p, phi_q, phi_k);
+  if (s != HA_OK) return s;
+  if (!q || !k || !v || !out) return HA_ERR_NULL;
+  if (!ha::aligned16(q) || !ha::aligned16(k) || !ha::aligned16(v) || !ha::aligned16(out)) return HA_ERR_ALIGN;
+  ha::Plan pl;
+  ha::make_plan(*p, phi_q, phi_k, pl);
+  if (!workspace || workspace_bytes < pl.total) return HA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  s = ha::run_key_side(pl, k, v, phi_k, workspace, st);
+  if (s != HA_OK) return s;
+  hipError_t e;
+  if (pl.NL > 0 && (e = ha::launch_weight_prep(pl, *phi_q, true, workspace, st)) != hipSuccess) return ha::device_error(e);
+  if ((e = ha::launch_query(pl, q, phi_q, out, workspace, st)) != hipSuccess) return ha::device_error(e);
+  return HA_OK;
+}
+
+ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const void *v, const ha_feature_map *phi_k,
+                                   float *state_S, float *state_z, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream) {
+  ha_status s = ha::validate(p, phi_k, phi_k);
+  if (s != HA_OK) return s;
+  if (!k || !v || !state_S || !state_z || !phi_k) return HA_ERR_NULL;
+  if (p->hybrid_rate == 1) return HA_ERR_SHAPE;   // no linear tokens, no state
+  if (!ha::aligned16(k) || !ha::aligned16(v)) return HA_ERR_ALIGN;
+  ha::Plan pl;
+  ha::make_plan(*p, phi_k, phi_k, pl);
+  if (!workspace || workspace_bytes < pl.total) return HA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  s = ha::run_key_side(pl, k, v, phi_k, workspace, st);
+  if (s != HA_OK) return s;
+  const size_t BH = (size_t)pl.B * pl.H;
+  char *ws = static_cast<char *>(workspace);
+  hipError_t e = hipMemcpyAsync(state_S, ws + pl.off_S, BH * pl.F * pl.D * 4, hipMemcpyDeviceToDevice, st);
+  if (e != hipSuccess) return ha::device_error(e);
+  e = hipMemcpyAsync(state_z, ws + pl.off_z, BH * pl.F * 4, hipMemcpyDeviceToDevice, st);
+  if (e != hipSuccess) return ha::device_error(e);
+  return HA_OK;
+}
+
+const char *hybrid_attn_status_string(ha_status s) {
+  switch (s) {
+    case HA_OK: return "ok";
+    case HA_ERR_NULL: return "a required pointer is NULL";
+    case HA_ERR_SHAPE: return "invalid or inconsistent sizes";
+    case HA_ERR_UNSUPPORTED: return "valid problem, but no kernel for it in this build";
+    case HA_ERR_ALIGN: return "pointer or stride breaks the 16-byte alignment rule";
+    case HA_ERR_WORKSPACE: return "workspace missing or too small";
+    case HA_ERR_DEVICE: return "a HIP call failed (see hybrid_attn_last_device_error)";
+  }
+  return "unknown status";
+}
+
+int hybrid_attn_last_device_error(void) { return ha::g_last_device_error; }
+
+int hybrid_attn_abi_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,160 @@
+// Device-side building blocks shared by the hybrid-attention kernels (gfx950 only).
+//
+// Every GEMM on the path runs on v_mfma_f32_32x32x16_bf16 (wave64).  Lane l = 32*g + r:
+//   A operand (32 x 16): lane holds row r,  8 contraction slots (g, t), t = 0..7
+//   B operand (16 x 32): lane holds col r,  the same 8 slots (g, t)
+//   C / D    (32 x 32): register v of lane holds C[crow(v, g)][r],  crow = 8*(v/4) + 4*g + v%4
+// The hardware pairs slot (g, t) of A with slot (g, t) of B, so which contraction index sits in a
+// slot is the kernel's choice as long as both operands agree.  Two slot orders are used:
+//   natural   slot (g, t) of k-step s  <->  index 16*s + 8*g + t            (operands read from
+//             row-major memory as one 16-byte run)
+//   chained   slot (g, t) of k-step s  <->  index 16*s + 8*(t/4) + 4*g + t%4   = crow(8*s + t, g)
+//             (operand taken straight from the C registers 8*s .. 8*s+7 of a previous product)
+// The chained order is what lets S^T = K Q^T feed O^T += V^T P^T, and the feature-map MLP feed
+// the state contraction, without any trip through LDS.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ha {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+static constexpr float kLog2e = 1.4426950408889634f;
+
+static __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row of C register v for lane group g (also the chained slot order, see above).
+static __device__ __forceinline__ constexpr int crow(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
+
+// Combine a value with the lane that holds the other half of the same C column (lane ^ 32).
+static __device__ __forceinline__ float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
+static __device__ __forceinline__ float xhalf_sum(float x) { return x + __shfl_xor(x, 32, 64); }
+
+static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 8 consecutive elements of a row in the io dtype -> 8 bf16 (fp32 is rounded to nearest even).
+template <bool F32>
+static __device__ __forceinline__ bf16x8 load8(const void *base, int64_t elem_off) {
+  if constexpr (F32) {
+    const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + elem_off);
+    float4 a = p[0], b = p[1];
+    f32x8 f = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    return __builtin_convertvector(f, bf16x8);
+  } else {
+    return *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(base) + elem_off);
+  }
+}
+
+// Linear-token index -> token index: the tokens with j % R != 0 in increasing order (R = 0: all).
+static __device__ __forceinline__ int linear_to_token(int i, int R) { return R == 0 ? i : i + i / (R - 1) + 1; }
+
+// Feature-map output stage on one C column held as NB row blocks of 16 registers (plus the same in
+// lane ^ 32): positive activation over all channels, then channel c is raised to 1 + c / Dp.
+//   act 0: softmax over the F = 32*NB channels;  1: exp;  2: relu.
+template <int NB>
+static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g, int act, int P, int Dp) {
+  if (act == 0) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, u[b][v]);
+    mx = xhalf_max(mx);
+    float sum = 0.f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        u[b][v] = fast_exp2((u[b][v] - mx) * kLog2e);
+        sum += u[b][v];
+      }
+    sum = xhalf_sum(sum);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) u[b][v] *= inv;
+  } else if (act == 1) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) u[b][v] = fast_exp2(u[b][v] * kLog2e);
+  } else {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) u[b][v] = fmaxf(u[b][v], 0.f);
+  }
+  if (P > 1) {
+    // slice p = c / Dp (0-based) gets p extra multiplications by the activation value
+    f32x16 t[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) t[b] = u[b];
+    for (int i = 1; i < P; ++i) {
+      const int lim = i * Dp;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) u[b][v] = (32 * b + crow(v, g) >= lim) ? u[b][v] * t[b][v] : u[b][v];
+    }
+  }
+}
+
+// Two-layer feature-map MLP on one 32-token column block, all in registers.
+//   xf[ks]  : B-operand fragments of the tokens (natural slot order over d)
+//   w1f/w2f : A-operand fragments of the weights, w1 in natural order, w2 in chained order
+// Result: u[fb] = W2 relu(W1 x + b1) + b2 as C tiles (rows = channels, column = token).
+template <int D, int HD, int F>
+static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], const bf16x8 *__restrict__ w1f,
+                                                   const bf16x8 *__restrict__ w2f, const float *__restrict__ b1,
+                                                   const float *__restrict__ b2, int lane, int g,
+                                                   f32x16 (&u)[F / 32]) {
+  constexpr int KS = D / 16, HB = HD / 32, FB = F / 32;
+  bf16x8 hb16[HB][2];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    f32x16 h;
+    if (b1) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) h[v] = b1[32 * hb + crow(v, g)];
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) h[v] = 0.f;
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) h = mfma32(w1f[(hb * KS + ks) * 64 + lane], xf[ks], h);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      f32x8 t;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = fmaxf(h[8 * s + i], 0.f);
+      hb16[hb][s] = __builtin_convertvector(t, bf16x8);
+    }
+  }
+#pragma unroll
+  for (int fb = 0; fb < FB; ++fb) {
+    f32x16 acc;
+    if (b2) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = b2[32 * fb + crow(v, g)];
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+        acc = mfma32(w2f[((fb * HB + hb) * 2 + s) * 64 + lane], hb16[hb][s], acc);
+    u[fb] = acc;
+  }
+}
+
+}  // namespace ha

@@ -1,0 +1,37 @@
+// Host-side plan of one forward: tile shapes, grid sizes and the layout of the caller's workspace.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/hybrid_attn.h"
+
+namespace ha {
+
+struct Plan {
+  // problem
+  int B, H, N, D, HD, F, R, NS, NL, P, act_q, act_k;
+  bool f32;
+  int64_t sb, sh, sn;
+  float scale;
+  // softmax part: KT keys per LDS tile, QB 32-query column blocks per wave, 4 waves per workgroup
+  int KT, QB, QT, n_qtiles, n_ktiles, n_kblocks;
+  // state pass: CH linear tokens per workgroup, partial tiles per chunk
+  int CH, n_chunks, n_state_tiles;
+  // workspace byte offsets (all multiples of 256)
+  size_t off_w1q, off_w2q, off_w1k, off_w2k, off_ks, off_vs, off_part, off_S, off_z, off_sthi, off_stlo, total;
+};
+
+// Fills `pl` from a validated problem.  Pure host arithmetic.
+void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, Plan &pl);
+
+// Kernel launchers (ha_kernels.hip).  Each enqueues on `st` and returns the launch status.
+hipError_t launch_weight_prep(const Plan &pl, const ha_feature_map &fm, bool is_query, void *ws, hipStream_t st);
+hipError_t launch_compact(const Plan &pl, const void *k, const void *v, void *ws, hipStream_t st);
+hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_feature_map &phi_k, void *ws,
+                        hipStream_t st);
+hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st);
+hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
+                        hipStream_t st);
+
+}  // namespace ha

@@ -1,0 +1,226 @@
+"""ctypes binding over libhybridattn.so (include/hybrid_attn.h).
+
+Argument marshalling only: every step of the forward runs in the HIP kernels of the library.
+PyTorch supplies device memory and the current HIP stream.  There is no CPU fallback; if the
+library is not built, or no GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch  # imported before the library so that both share torch's HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libhybridattn.so")
+
+HA_OK, HA_ERR_NULL, HA_ERR_SHAPE, HA_ERR_UNSUPPORTED, HA_ERR_ALIGN, HA_ERR_WORKSPACE, HA_ERR_DEVICE = range(7)
+HA_BF16, HA_F32 = 0, 1
+HA_ACT_SOFTMAX, HA_ACT_EXP, HA_ACT_RELU = 0, 1, 2
+
+
+class ha_feature_map(ctypes.Structure):
+    _fields_ = [("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
+                ("d_hidden", ctypes.c_int32), ("d_out", ctypes.c_int32), ("poly_degree", ctypes.c_int32),
+                ("out_act", ctypes.c_int32)]
+
+
+class ha_problem(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d_head", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32), ("hybrid_rate", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
+
+
+class HybridAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        lib = _lib()
+        msg = lib.hybrid_attn_status_string(status).decode()
+        if status == HA_ERR_DEVICE:
+            msg += f" [hipError {lib.hybrid_attn_last_device_error()}]"
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+_LIB = None
+
+
+def _lib():
+    """Load the shared library once.  Raises if it has not been built (no fallback)."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2509_24899_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no CPU fallback")
+        lib = ctypes.CDLL(LIB_PATH)
+        P, FM = ctypes.POINTER(ha_problem), ctypes.POINTER(ha_feature_map)
+        vp = ctypes.c_void_p
+        lib.hybrid_attn_validate.argtypes = [P, FM, FM]
+        lib.hybrid_attn_validate.restype = ctypes.c_int
+        lib.hybrid_attn_workspace_bytes.argtypes = [P, FM, FM]
+        lib.hybrid_attn_workspace_bytes.restype = ctypes.c_size_t
+        lib.hybrid_attn_forward.argtypes = [P, vp, vp, vp, FM, FM, vp, vp, ctypes.c_size_t, vp]
+        lib.hybrid_attn_forward.restype = ctypes.c_int
+        lib.hybrid_attn_linear_state.argtypes = [P, vp, vp, FM, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.hybrid_attn_linear_state.restype = ctypes.c_int
+        lib.hybrid_attn_status_string.argtypes = [ctypes.c_int]
+        lib.hybrid_attn_status_string.restype = ctypes.c_char_p
+        lib.hybrid_attn_last_device_error.argtypes = []
+        lib.hybrid_attn_last_device_error.restype = ctypes.c_int
+        lib.hybrid_attn_abi_version.argtypes = []
+        lib.hybrid_attn_abi_version.restype = ctypes.c_int
+        _LIB = lib
+    return _LIB
+
+
+@dataclass
+class FeatureMap:
+    """Device tensors of one feature map: w1 [H, Hd, d], b1 [H, Hd] fp32 or None, w2 [H, F, Hd],
+    b2 [H, F] fp32 or None; weights in the io dtype of q, k, v."""
+    w1: torch.Tensor
+    b1: Optional[torch.Tensor]
+    w2: torch.Tensor
+    b2: Optional[torch.Tensor]
+    poly_degree: int = 2
+    out_act: int = HA_ACT_SOFTMAX
+
+    def c_struct(self) -> ha_feature_map:
+        for t in (self.w1, self.w2):
+            if not t.is_contiguous():
+                raise ValueError("feature-map weights must be contiguous")
+        for b in (self.b1, self.b2):
+            if b is not None and (b.dtype != torch.float32 or not b.is_contiguous()):
+                raise ValueError("feature-map biases must be contiguous fp32")
+        return ha_feature_map(self.w1.data_ptr(), self.b1.data_ptr() if self.b1 is not None else None,
+                              self.w2.data_ptr(), self.b2.data_ptr() if self.b2 is not None else None,
+                              self.w1.shape[1], self.w2.shape[1], self.poly_degree, self.out_act)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return HA_BF16
+    if t.dtype == torch.float32:
+        return HA_F32
+    raise ValueError(f"unsupported dtype {t.dtype}: q, k, v must be bfloat16 or float32")
+
+
+def make_problem(q: torch.Tensor, hybrid_rate: int, block_size: int, softmax_scale: float) -> ha_problem:
+    """ha_problem for a [B, H, N, d] tensor view (any strides with a contiguous last dim)."""
+    if q.dim() != 4 or q.stride(3) != 1:
+        raise ValueError("q, k, v must be [B, H, N, d] views with a contiguous last dimension")
+    B, H, N, d = q.shape
+    return ha_problem(B, H, N, d, _dtype_code(q), block_size, hybrid_rate, softmax_scale,
+                      q.stride(0), q.stride(1), q.stride(2))
+
+
+def _fm_ptr(fm):
+    if fm is None:
+        return None, None
+    s = fm.c_struct() if isinstance(fm, FeatureMap) else fm
+    return s, ctypes.byref(s)
+
+
+def hybrid_attn_validate(problem: ha_problem, phi_q=None, phi_k=None) -> int:
+    _, pq = _fm_ptr(phi_q)
+    _, pk = _fm_ptr(phi_k)
+    return _lib().hybrid_attn_validate(ctypes.byref(problem) if problem is not None else None, pq, pk)
+
+
+def hybrid_attn_workspace_bytes(problem: ha_problem, phi_q=None, phi_k=None) -> int:
+    _, pq = _fm_ptr(phi_q)
+    _, pk = _fm_ptr(phi_k)
+    return _lib().hybrid_attn_workspace_bytes(ctypes.byref(problem), pq, pk)
+
+
+def hybrid_attn_status_string(status: int) -> str:
+    return _lib().hybrid_attn_status_string(status).decode()
+
+
+def hybrid_attn_last_device_error() -> int:
+    return _lib().hybrid_attn_last_device_error()
+
+
+def hybrid_attn_abi_version() -> int:
+    return _lib().hybrid_attn_abi_version()
+
+
+def _require_gpu(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("hybrid_attn runs on the GPU only: got a CPU tensor (there is no CPU fallback)")
+
+
+def _same_layout(q, *others):
+    for t in others:
+        if t.shape != q.shape or t.stride() != q.stride() or t.dtype != q.dtype:
+            raise ValueError("q, k, v and out must share shape, strides and dtype")
+
+
+def hybrid_attn_forward(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[FeatureMap], hybrid_rate: int,
+                        block_size: int = 128, softmax_scale: Optional[float] = None, out=None, workspace=None,
+                        stream=None):
+    """Enqueue one forward of Eq. "hybrid" (Sec. 3.2) on the current (or given) stream and return
+    `out` ([B, H, N, d] with q's strides and dtype).  Does not synchronise."""
+    _require_gpu(q, k, v)
+    if softmax_scale is None:
+        softmax_scale = float(q.shape[-1]) ** -0.5
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, k, v, out)
+    prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
+    sq, pq = _fm_ptr(phi_q)
+    sk, pk = _fm_ptr(phi_k)
+    lib = _lib()
+    st = lib.hybrid_attn_validate(ctypes.byref(prob), pq, pk)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_validate")
+    need = lib.hybrid_attn_workspace_bytes(ctypes.byref(prob), pq, pk)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    stream_handle = (stream if stream is not None else torch.cuda.current_stream(q.device)).cuda_stream
+    st = lib.hybrid_attn_forward(ctypes.byref(prob), q.data_ptr(), k.data_ptr(), v.data_ptr(), pq, pk,
+                                 out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                 stream_handle)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_forward")
+    return out
+
+
+def hybrid_attn_linear_state(k, v, phi_k: FeatureMap, hybrid_rate: int, block_size: int = 128, workspace=None,
+                             stream=None):
+    """Key-side passes only: returns (S [B, H, F, d], z [B, H, F]) in fp32 (test tap)."""
+    _require_gpu(k, v)
+    _same_layout(k, v)
+    prob = make_problem(k, hybrid_rate, block_size, 1.0)
+    sk, pk = _fm_ptr(phi_k)
+    lib = _lib()
+    need = lib.hybrid_attn_workspace_bytes(ctypes.byref(prob), pk, pk)
+    if need == 0:
+        raise HybridAttnError(lib.hybrid_attn_validate(ctypes.byref(prob), pk, pk), "hybrid_attn_validate")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=k.device)
+    B, H, N, d = k.shape
+    S = torch.empty(B, H, sk.d_out, d, dtype=torch.float32, device=k.device)
+    z = torch.empty(B, H, sk.d_out, dtype=torch.float32, device=k.device)
+    stream_handle = (stream if stream is not None else torch.cuda.current_stream(k.device)).cuda_stream
+    st = lib.hybrid_attn_linear_state(ctypes.byref(prob), k.data_ptr(), v.data_ptr(), pk, S.data_ptr(), z.data_ptr(),
+                                      workspace.data_ptr(), workspace.numel(), stream_handle)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_linear_state")
+    return S, z
+
+
+def to_device(inputs, device="cuda"):
+    """workloads.Inputs (numpy float32) -> device tensors in the workload's io dtype."""
+    w = inputs.workload
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def dev(a, dtype):
+        return torch.from_numpy(a).to(device=device, dtype=dtype).contiguous()
+
+    def fm(p):
+        return FeatureMap(dev(p.w1, dt), dev(p.b1, torch.float32), dev(p.w2, dt), dev(p.b2, torch.float32),
+                          p.poly_degree)
+    return dev(inputs.q, dt), dev(inputs.k, dt), dev(inputs.v, dt), fm(inputs.phi_q), fm(inputs.phi_k)

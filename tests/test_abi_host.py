@@ -1,0 +1,147 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its argument validation and workspace planning work without a GPU (no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_24899_amd import hybrid_attn as ha
+from paper_2509_24899_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # 4 KiB-aligned, never dereferenced by the host-side checks
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ha.LIB_PATH):
+        from paper_2509_24899_amd.build import build_library
+        build_library()
+    return ha._lib()
+
+
+def _problem(B=1, H=12, N=32760, d=128, dtype=ha.HA_BF16, bs=128, R=4, scale=None, strides=None):
+    sb, sh, sn = strides if strides else (H * N * d, N * d, d)
+    return ha.ha_problem(B, H, N, d, dtype, bs, R, scale if scale is not None else d ** -0.5, sb, sh, sn)
+
+
+def _map(Hd=128, F=128, P=2, act=ha.HA_ACT_SOFTMAX, w1=FAKE, w2=FAKE + 0x100000, b1=None, b2=None):
+    return ha.ha_feature_map(w1, b1, w2, b2, Hd, F, P, act)
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "hybrid_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(hybrid_attn_\w+)\s*\(", text)
+    assert len(set(names)) == 7
+    for n in set(names):
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+    assert ha.hybrid_attn_abi_version() == 1
+
+
+def test_struct_layout_matches_header():
+    # 7 int32 + float, then three int64 at offset 32; four pointers then four int32
+    assert ha.ha_problem.stride_b.offset == 32 and ctypes.sizeof(ha.ha_problem) == 56
+    assert ha.ha_feature_map.d_hidden.offset == 32 and ctypes.sizeof(ha.ha_feature_map) == 48
+
+
+def test_valid_problems(lib):
+    fm = _map()
+    assert ha.hybrid_attn_validate(_problem(), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(R=1), None, None) == ha.HA_OK           # full softmax needs no phi
+    assert ha.hybrid_attn_validate(_problem(R=0), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(R=3), fm, fm) == ha.HA_OK               # Fig. "method" uses rate 3
+    fm64 = _map(64, 64)
+    assert ha.hybrid_attn_validate(_problem(H=2, N=1024, d=64, dtype=ha.HA_F32, bs=64), fm64, fm64) == ha.HA_OK
+    wide = _map(256, 256)
+    assert ha.hybrid_attn_validate(_problem(), wide, wide) == ha.HA_OK              # Tab. "phi" default widths
+    bnhd = _problem(strides=(32760 * 12 * 128, 128, 12 * 128))                       # [B, N, H, d] memory
+    assert ha.hybrid_attn_validate(bnhd, fm, fm) == ha.HA_OK
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(N=0), ha.HA_ERR_SHAPE), (dict(B=0), ha.HA_ERR_SHAPE), (dict(H=-1), ha.HA_ERR_SHAPE),
+    (dict(R=-1), ha.HA_ERR_SHAPE), (dict(R=40000), ha.HA_ERR_SHAPE),
+    (dict(scale=0.0), ha.HA_ERR_SHAPE), (dict(scale=-1.0), ha.HA_ERR_SHAPE), (dict(scale=float("nan")), ha.HA_ERR_SHAPE),
+    (dict(d=96), ha.HA_ERR_UNSUPPORTED), (dict(bs=32), ha.HA_ERR_UNSUPPORTED), (dict(dtype=7), ha.HA_ERR_UNSUPPORTED),
+    (dict(strides=(12 * 32760 * 128, 32760 * 128, 64)), ha.HA_ERR_SHAPE),           # rows overlap
+    (dict(strides=(12 * 32760 * 132, 32760 * 132, 132)), ha.HA_ERR_ALIGN),          # 132*2 B is not 16-byte
+])
+def test_problem_errors(lib, kw, status):
+    fm = _map()
+    assert ha.hybrid_attn_validate(_problem(**kw), fm, fm) == status
+
+
+def test_feature_map_errors(lib):
+    p, fm = _problem(), _map()
+    assert ha.hybrid_attn_validate(None, fm, fm) == ha.HA_ERR_NULL
+    assert ha.hybrid_attn_validate(p, None, fm) == ha.HA_ERR_NULL
+    assert ha.hybrid_attn_validate(p, fm, None) == ha.HA_ERR_NULL
+    assert ha.hybrid_attn_validate(p, _map(w1=None), fm) == ha.HA_ERR_NULL
+    assert ha.hybrid_attn_validate(p, fm, _map(P=3)) == ha.HA_ERR_SHAPE             # 3 does not divide 128
+    assert ha.hybrid_attn_validate(p, fm, _map(P=0)) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(p, fm, _map(P=16)) == ha.HA_ERR_UNSUPPORTED
+    assert ha.hybrid_attn_validate(p, fm, _map(act=9)) == ha.HA_ERR_UNSUPPORTED
+    assert ha.hybrid_attn_validate(p, fm, _map(Hd=96)) == ha.HA_ERR_UNSUPPORTED
+    assert ha.hybrid_attn_validate(p, fm, _map(256, 256)) == ha.HA_ERR_SHAPE        # phi_q / phi_k widths differ
+    assert ha.hybrid_attn_validate(p, fm, _map(P=4)) == ha.HA_ERR_SHAPE             # degrees differ
+    assert ha.hybrid_attn_validate(p, _map(w1=FAKE + 2), fm) == ha.HA_ERR_ALIGN
+    assert ha.hybrid_attn_validate(p, _map(b1=FAKE + 1), fm) == ha.HA_ERR_ALIGN
+
+
+def test_forward_rejects_bad_buffers_before_any_device_work(lib):
+    p, fm = _problem(N=4096), _map()
+    need = ha.hybrid_attn_workspace_bytes(p, fm, fm)
+    f = lib.hybrid_attn_forward
+    pq = ctypes.byref(fm)
+    args_ok = [FAKE, FAKE + (1 << 30), FAKE + (2 << 30), pq, pq, FAKE + (3 << 30), FAKE + (4 << 30), need, None]
+    bad = list(args_ok); bad[0] = None
+    assert f(ctypes.byref(p), *bad) == ha.HA_ERR_NULL
+    bad = list(args_ok); bad[5] = None
+    assert f(ctypes.byref(p), *bad) == ha.HA_ERR_NULL
+    bad = list(args_ok); bad[1] = FAKE + 8
+    assert f(ctypes.byref(p), *bad) == ha.HA_ERR_ALIGN
+    bad = list(args_ok); bad[6] = None
+    assert f(ctypes.byref(p), *bad) == ha.HA_ERR_WORKSPACE
+    bad = list(args_ok); bad[7] = need - 1
+    assert f(ctypes.byref(p), *bad) == ha.HA_ERR_WORKSPACE
+    bad = list(args_ok); bad[6] = FAKE + (4 << 30) + 16
+    assert f(ctypes.byref(p), *bad) == ha.HA_ERR_ALIGN
+
+
+def test_workspace_bytes(lib):
+    fm = _map()
+    assert ha.hybrid_attn_workspace_bytes(_problem(d=96), fm, fm) == 0
+    w = W.WAN_480P_81F
+    p = _problem()
+    need = ha.hybrid_attn_workspace_bytes(p, fm, fm)
+    ns_pad = -(-w.n_softmax // 128) * 128
+    compact = 2 * w.B * w.H * ns_pad * w.d * 2                   # K_S and V_S in bf16, padded to key tiles
+    assert compact <= need <= compact + 64 * 2 ** 20             # weights, partial states, S, z stay small
+    assert ha.hybrid_attn_workspace_bytes(_problem(R=1), None, None) >= 2 * 12 * 32768 * 128 * 2
+    assert ha.hybrid_attn_workspace_bytes(_problem(R=0), fm, fm) < 64 * 2 ** 20
+    # more softmax keys -> more workspace
+    sizes = [ha.hybrid_attn_workspace_bytes(_problem(R=R), fm, fm) for R in (16, 8, 4, 2)]
+    assert sizes == sorted(sizes)
+
+
+def test_status_strings(lib):
+    seen = {ha.hybrid_attn_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert ha.hybrid_attn_last_device_error() == 0
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    q = torch.zeros(1, 2, 64, 64)
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        ha.hybrid_attn_forward(q, q, q, None, None, 1)
+
+
+def test_flop_and_byte_counts():
+    assert abs(W.algorithmic_flops(W.WAN_480P_81F) / 1e9 - 1716.2) < 0.1
+    assert abs(W.algorithmic_flops(W.WAN_480P_161F) / 1e9 - 3283.5) < 0.1
+    assert abs(W.algorithmic_flops(W.TINY) / 1e9 - 0.223) < 1e-3
+    assert abs(W.algorithmic_flops(W.with_rate(W.WAN_480P_81F, 0)) / 1e9 - 77.4) < 0.1
+    assert W.WAN_480P_81F.n_softmax == 8190 and W.WAN_480P_161F.n_softmax == 7995
