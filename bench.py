@@ -1,0 +1,145 @@
+"""Benchmark of the hybrid-attention forward on one MI355X.
+
+One step = one forward of the whole hot path (softmax-key compaction, state pass, fused query
+kernel) over one batch of synthetic input that is already resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 flop/clk/CU, dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, heads=4):
+    """fp64 oracle on the host cores for a bounded sample of the same workload: the full forward
+    (every key, every query row) of `heads` of the B*H (batch, head) pairs, scaled linearly to all of
+    them (heads are independent problems of identical cost)."""
+    from oracle import hybrid_attn_oracle as O
+    from paper_2509_24899_amd import workloads as W
+    heads = min(heads, w.H)
+    inp = W.make_inputs(W.replace(w, B=1), heads=heads)
+    fq = O.FeatureMap(inp.phi_q.w1, inp.phi_q.b1, inp.phi_q.w2, inp.phi_q.b2, w.poly_degree)
+    fk = O.FeatureMap(inp.phi_k.w1, inp.phi_k.b1, inp.phi_k.w2, inp.phi_k.b2, w.poly_degree)
+    t0 = time.perf_counter()
+    O.hybrid_attn(inp.q, inp.k, inp.v, fq, fk, w.R, w.scale)
+    t_sample = time.perf_counter() - t0
+    t_full = t_sample * (w.B * w.H) / heads
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": w.B * w.N / t_full, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"full fp64 oracle forward (all {w.N} rows, all keys) of {heads} of the {w.B * w.H} (batch, head) "
+                      f"pairs: {t_sample:.1f} s, scaled to all pairs: {t_full:.1f} s per forward"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="wan_480p_81f", choices=["tiny", "wan_480p_81f", "wan_480p_161f", "wan_720p_81f_cfg"])
+    ap.add_argument("--rate", type=int, default=None, help="override the hybrid rate R (0 = pure linear, 1 = full softmax)")
+    ap.add_argument("--block-size", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_24899_amd import hybrid_attn as ha
+    from paper_2509_24899_amd import workloads as W
+
+    w = {"tiny": W.TINY, "wan_480p_81f": W.WAN_480P_81F, "wan_480p_161f": W.WAN_480P_161F,
+         "wan_720p_81f_cfg": W.WAN_720P_81F_CFG}[args.workload]
+    if args.rate is not None:
+        w = W.with_rate(w, args.rate)
+    if args.block_size is not None:
+        w = W.replace(w, block_size=args.block_size)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    # synthetic inputs drawn on the device (seeded), resident in HBM before the timed region
+    gen = torch.Generator(device=dev).manual_seed(w.seed)
+    s = w.d ** -0.5
+    q, k, v = ((torch.randn(w.B, w.H, w.N, w.d, generator=gen, device=dev) * s).to(dt) for _ in range(3))
+
+    def dmap():
+        return ha.FeatureMap((torch.randn(w.H, w.d_hidden, w.d, generator=gen, device=dev) * w.d ** -0.5).to(dt),
+                             torch.randn(w.H, w.d_hidden, generator=gen, device=dev) * 0.1,
+                             (torch.randn(w.H, w.d_feat, w.d_hidden, generator=gen, device=dev) * w.d_hidden ** -0.5).to(dt),
+                             torch.randn(w.H, w.d_feat, generator=gen, device=dev) * 0.1, w.poly_degree)
+    fq, fk = (dmap(), dmap()) if w.R != 1 else (None, None)
+    prob = ha.make_problem(q, w.R, w.block_size, w.scale)
+    ws = torch.empty(ha.hybrid_attn_workspace_bytes(prob, fq, fk), dtype=torch.uint8, device=dev)
+    out = torch.empty_like(q)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ha.hybrid_attn_forward(q, k, v, fq, fk, w.R, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ha.hybrid_attn_profile_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stage_ms = [ha.hybrid_attn_profile_read(i) for i in range(args.steps)]
+    ha.hybrid_attn_profile_enable(0)
+    assert torch.isfinite(out.float()).all().item(), "non-finite output"
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    flops = W.algorithmic_flops(w)
+    mean = [sum(r[i] for r in stage_ms) / len(stage_ms) for i in range(5)]
+    n_s, n_l = w.n_softmax, w.n_linear
+    if n_s > 0:
+        # dominant kernel: the fused query kernel; its algorithmic flops are everything except the
+        # key-side feature map and state (4 N N_S d + phi_q MLP + g.S, g.z)
+        k_flops = w.B * w.H * (4.0 * w.N * n_s * w.d + (2.0 * w.N * (w.d * w.d_hidden + w.d_hidden * w.d_feat)
+                                                         + 2.0 * w.N * w.d_feat * w.d + 2.0 * w.N * w.d_feat if n_l > 0 else 0.0))
+        achieved = k_flops / (mean[3] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "query_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_TFLOPS, "kernel_ms": mean[3], "traffic": None}
+    else:
+        by = W.algorithmic_bytes(w)
+        achieved = by / (mean[4] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "whole forward (r = 0)", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "kernel_ms": mean[4], "traffic": None}
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        roofline["traffic"] = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
+
+    rec = {
+        "metric": "hybrid-attention fwd tokens/s", "value": w.B * w.N / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype,
+                   "hybrid_rate_R": w.R, "r": (1.0 / w.R if w.R else 0.0), "block_size": w.block_size,
+                   "feature_map": f"{w.d}->{w.d_hidden}->{w.d_feat}, P={w.poly_degree}"},
+        "tflops": flops / (ms_per_step * 1e-3) / 1e12,
+        "pct_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "stage_ms": {"compact": mean[0], "state": mean[1], "wprep_q": mean[2], "query": mean[3], "forward": mean[4]},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -113,6 +113,18 @@ ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const voi
                                    const ha_feature_map *phi_k, float *state_S, float *state_z,
                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Per-stage timing tap for benchmarks.  hybrid_attn_profile_enable(n) (n >= 1) creates n sets of HIP
+ * events on the current device; from then on every hybrid_attn_forward on this host thread records
+ * one set on its stream around its stages (record i uses set i % n); n = 0 switches the tap off and
+ * destroys the events.  hybrid_attn_profile_read waits for record `index` to finish and returns the
+ * stage durations in milliseconds: ms[0] softmax-key compaction, ms[1] key-side feature map + state
+ * pass + state reduction, ms[2] query-side weight re-ordering, ms[3] the fused query kernel (softmax
+ * tile loop, phi_q, contraction with the state and merge), ms[4] the whole forward.  Stages that did
+ * not run report 0.  HA_ERR_SHAPE for an index that was never recorded.  Host memory only. */
+ha_status hybrid_attn_profile_enable(int n_records);
+ha_status hybrid_attn_profile_read(int index, float ms[5]);
+int hybrid_attn_profile_count(void);   /* forwards recorded since the last enable */
+
 /* Static, NUL-terminated description of a status code. */
 const char *hybrid_attn_status_string(ha_status s);
 

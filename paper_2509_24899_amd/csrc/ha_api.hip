@@ -9,6 +9,16 @@ namespace ha {
 
 static thread_local int g_last_device_error = 0;
 
+// Optional per-stage event records (benchmark tap): 6 events per record.
+struct Profile {
+  hipEvent_t *ev = nullptr;
+  int n = 0, count = 0;
+};
+static thread_local Profile g_prof;
+static inline hipEvent_t *prof_events() {
+  return g_prof.n > 0 ? g_prof.ev + (size_t)(g_prof.count % g_prof.n) * 6 : nullptr;
+}
+
 static inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -97,15 +107,19 @@ static ha_status device_error(hipError_t e) {
   return HA_ERR_DEVICE;
 }
 
+// ev (optional): ev[0] before compaction, ev[1] after it, ev[2] after the state is reduced.
 static ha_status run_key_side(const Plan &pl, const void *k, const void *v, const ha_feature_map *phi_k, void *ws,
-                              hipStream_t st) {
+                              hipStream_t st, hipEvent_t *ev = nullptr) {
   hipError_t e;
+  if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return device_error(e);
   if (pl.NS > 0 && (e = launch_compact(pl, k, v, ws, st)) != hipSuccess) return device_error(e);
+  if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return device_error(e);
   if (pl.NL > 0) {
     if ((e = launch_weight_prep(pl, *phi_k, false, ws, st)) != hipSuccess) return device_error(e);
     if ((e = launch_state(pl, k, v, *phi_k, ws, st)) != hipSuccess) return device_error(e);
     if ((e = launch_state_reduce(pl, ws, st)) != hipSuccess) return device_error(e);
   }
+  if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return device_error(e);
   return HA_OK;
 }
 
@@ -136,11 +150,55 @@ ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k,
   if (!workspace || workspace_bytes < pl.total) return HA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  s = ha::run_key_side(pl, k, v, phi_k, workspace, st);
+  hipEvent_t *ev = ha::prof_events();
+  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, ev);
   if (s != HA_OK) return s;
   hipError_t e;
   if (pl.NL > 0 && (e = ha::launch_weight_prep(pl, *phi_q, true, workspace, st)) != hipSuccess) return ha::device_error(e);
+  if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return ha::device_error(e);
   if ((e = ha::launch_query(pl, q, phi_q, out, workspace, st)) != hipSuccess) return ha::device_error(e);
+  if (ev) {
+    if ((e = hipEventRecord(ev[4], st)) != hipSuccess) return ha::device_error(e);
+    ++ha::g_prof.count;
+  }
+  return HA_OK;
+}
+
+ha_status hybrid_attn_profile_enable(int n_records) {
+  if (n_records < 0 || n_records > 4096) return HA_ERR_SHAPE;
+  ha::Profile &pf = ha::g_prof;
+  for (int i = 0; i < pf.n * 6; ++i) (void)hipEventDestroy(pf.ev[i]);
+  delete[] pf.ev;
+  pf.ev = nullptr;
+  pf.n = pf.count = 0;
+  if (n_records == 0) return HA_OK;
+  pf.ev = new hipEvent_t[(size_t)n_records * 6];
+  for (int i = 0; i < n_records * 6; ++i) {
+    hipError_t e = hipEventCreate(&pf.ev[i]);
+    if (e != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(pf.ev[j]);
+      delete[] pf.ev;
+      pf.ev = nullptr;
+      return ha::device_error(e);
+    }
+  }
+  pf.n = n_records;
+  return HA_OK;
+}
+
+int hybrid_attn_profile_count(void) { return ha::g_prof.count; }
+
+ha_status hybrid_attn_profile_read(int index, float ms[5]) {
+  ha::Profile &pf = ha::g_prof;
+  if (!ms) return HA_ERR_NULL;
+  if (pf.n == 0 || index < 0 || index >= pf.count || index < pf.count - pf.n) return HA_ERR_SHAPE;
+  hipEvent_t *ev = pf.ev + (size_t)(index % pf.n) * 6;
+  hipError_t e = hipEventSynchronize(ev[4]);
+  if (e != hipSuccess) return ha::device_error(e);
+  const int a[5] = {0, 1, 2, 3, 0}, b[5] = {1, 2, 3, 4, 4};
+  for (int i = 0; i < 5; ++i) {
+    if ((e = hipEventElapsedTime(&ms[i], ev[a[i]], ev[b[i]])) != hipSuccess) return ha::device_error(e);
+  }
   return HA_OK;
 }
 

@@ -69,6 +69,12 @@ def _lib():
         lib.hybrid_attn_status_string.restype = ctypes.c_char_p
         lib.hybrid_attn_last_device_error.argtypes = []
         lib.hybrid_attn_last_device_error.restype = ctypes.c_int
+        lib.hybrid_attn_profile_enable.argtypes = [ctypes.c_int]
+        lib.hybrid_attn_profile_enable.restype = ctypes.c_int
+        lib.hybrid_attn_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
+        lib.hybrid_attn_profile_read.restype = ctypes.c_int
+        lib.hybrid_attn_profile_count.argtypes = []
+        lib.hybrid_attn_profile_count.restype = ctypes.c_int
         lib.hybrid_attn_abi_version.argtypes = []
         lib.hybrid_attn_abi_version.restype = ctypes.c_int
         _LIB = lib
@@ -144,6 +150,26 @@ def hybrid_attn_last_device_error() -> int:
 
 def hybrid_attn_abi_version() -> int:
     return _lib().hybrid_attn_abi_version()
+
+
+def hybrid_attn_profile_enable(n_records: int) -> None:
+    st = _lib().hybrid_attn_profile_enable(n_records)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_profile_enable")
+
+
+def hybrid_attn_profile_count() -> int:
+    return _lib().hybrid_attn_profile_count()
+
+
+def hybrid_attn_profile_read(index: int):
+    """Stage durations (ms) of recorded forward `index`: compaction, state, q-weight prep, query
+    kernel, whole forward."""
+    ms = (ctypes.c_float * 5)()
+    st = _lib().hybrid_attn_profile_read(index, ms)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_profile_read")
+    return list(ms)
 
 
 def _require_gpu(*tensors):

@@ -1,0 +1,260 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
+
+Bar (both must hold): max |y_gpu - y_ref| <= 2e-2 and ||y_gpu - y_ref||_2 / ||y_ref||_2 <= 5e-3
+for bf16 inputs with fp32 accumulation.  With the benchmark distributions the outputs are O(1e-3),
+so the relative L2 bound is the binding one; the stress sets make the max / rescale paths matter.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hybrid_attn_oracle as O
+from paper_2509_24899_amd import hybrid_attn as ha
+from paper_2509_24899_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 2e-2, 5e-3
+LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "parity_metrics.jsonl")
+
+
+def oracle_map(p, act=O.ACT_SOFTMAX):
+    return O.FeatureMap(p.w1, p.b1, p.w2, p.b2, p.poly_degree, act)
+
+
+def metrics(y_gpu, y_ref):
+    diff = y_gpu.astype(np.float64) - y_ref
+    return float(np.abs(diff).max()), float(np.linalg.norm(diff) / max(np.linalg.norm(y_ref), 1e-300))
+
+
+def record(name, max_abs, rel_l2, **extra):
+    print(f"  [{name}] max_abs={max_abs:.3e} rel_l2={rel_l2:.3e} {extra}", flush=True)
+    try:
+        os.makedirs(os.path.dirname(LOG), exist_ok=True)
+        with open(LOG, "a") as f:
+            f.write(json.dumps(dict(case=name, max_abs=max_abs, rel_l2=rel_l2, **extra)) + "\n")
+    except OSError:
+        pass
+
+
+def gpu_forward(inp, R=None, block_size=None, act=ha.HA_ACT_SOFTMAX, layout="bhnd"):
+    w = inp.workload
+    q, k, v, fq, fk = ha.to_device(inp)
+    fq.out_act = fk.out_act = act
+    if layout == "bnhd":   # same logical [B, H, N, d] view over [B, N, H, d] memory
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    R = w.R if R is None else R
+    out = ha.hybrid_attn_forward(q, k, v, fq if R != 1 else None, fk if R != 1 else None, R,
+                                 block_size or w.block_size, w.scale)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy()
+
+
+def check(name, inp, R=None, block_size=None, rows=None, act=ha.HA_ACT_SOFTMAX, layout="bhnd", tol=(MAX_ABS, REL_L2)):
+    w = inp.workload
+    R = w.R if R is None else R
+    y = gpu_forward(inp, R, block_size, act, layout)
+    ref = O.hybrid_attn(inp.q, inp.k, inp.v, oracle_map(inp.phi_q, act), oracle_map(inp.phi_k, act), R, w.scale, rows=rows)
+    if rows is not None:
+        y = y[:, :, rows]
+    assert np.isfinite(y).all(), f"{name}: non-finite output"
+    ma, rl = metrics(y, ref)
+    record(name, ma, rl, R=R, block_size=block_size or w.block_size, N=w.N)
+    assert ma <= tol[0] and rl <= tol[1], f"{name}: max_abs {ma:.3e} rel_l2 {rl:.3e}"
+    return y, ref
+
+
+SMALL = W.Workload("small_bf16", 2, 3, 1337, 128, "bf16", 128, 4, 128, 128, seed=7)
+SMALL64 = W.Workload("small_bf16_d64", 1, 2, 777, 64, "bf16", 64, 4, 64, 64, seed=8)
+
+
+def test_tiny_config():
+    check("cfg1_tiny_f32", W.make_inputs(W.TINY))
+
+
+@pytest.mark.parametrize("R", W.RATE_SWEEP)
+def test_rate_sweep_tiny(R):
+    inp = W.make_inputs(W.TINY)
+    y64, _ = check(f"cfg3_R{R}_bs64", inp, R=R, block_size=64)
+    y128, _ = check(f"cfg3_R{R}_bs128", inp, R=R, block_size=128)
+    ma, rl = metrics(y64, y128.astype(np.float64))          # block size is a tiling knob only
+    assert rl <= 1e-4, (ma, rl)
+
+
+@pytest.mark.parametrize("R", (0, 1, 2, 3, 4, 5, 8, 16))
+@pytest.mark.parametrize("bs", (64, 128))
+def test_bf16_ragged(R, bs):
+    check(f"small_d128_R{R}_bs{bs}", W.make_inputs(SMALL), R=R, block_size=bs)
+
+
+@pytest.mark.parametrize("R", (0, 1, 3, 4))
+def test_bf16_d64(R):
+    check(f"small_d64_R{R}", W.make_inputs(SMALL64), R=R, block_size=64)
+    check(f"small_d64_R{R}_bs128", W.make_inputs(SMALL64), R=R, block_size=128)
+
+
+def test_bnhd_layout():
+    check("small_bnhd", W.make_inputs(SMALL), layout="bnhd")
+
+
+@pytest.mark.parametrize("N,R", [(1, 1), (1, 0), (5, 2), (33, 33), (64, 1), (65, 64), (130, 4), (257, 0), (300, 7)])
+def test_degenerate_sizes(N, R):
+    w = W.replace(SMALL, N=N, B=1, H=2, seed=100 + N)
+    check(f"edge_N{N}_R{R}", W.make_inputs(w), R=R, block_size=64)
+    check(f"edge_N{N}_R{R}_bs128", W.make_inputs(w), R=R, block_size=128)
+
+
+STRESS = {
+    "S1_logit_std1": dict(qk_gain=float(128 ** 0.25)),              # q.k/sqrt(d) ~ N(0, 1)
+    "S2_peaky": dict(qk_gain=float(128 ** 0.25) * 4.0),             # logit std ~ 16
+    "S4_peaky_phi": dict(w_gain=8.0),
+}
+
+
+@pytest.mark.parametrize("name", sorted(STRESS))
+@pytest.mark.parametrize("R", (0, 1, 4))
+def test_stress_distributions(name, R):
+    w = W.replace(SMALL, seed=21, **STRESS[name])
+    check(f"{name}_R{R}", W.make_inputs(w), R=R)
+
+
+def test_stress_monotone_row_max():
+    """Keys ordered so that every row's running maximum keeps increasing along T_S (worst case for
+    the online rescale), plus one huge-norm key in T_S and one in T_L."""
+    w = W.replace(SMALL, B=1, H=2, seed=22, qk_gain=float(128 ** 0.25) * 2.0)
+    inp = W.make_inputs(w)
+    u = np.ones(w.d, dtype=np.float32) / np.sqrt(w.d)
+    for h in range(w.H):
+        order = np.argsort(inp.k[0, h] @ u)
+        inp.k[0, h] = inp.k[0, h][order]
+        inp.q[0, h] = np.abs(inp.q[0, h])                  # all queries point along +u
+    inp.k[0, 0, 8] *= 6.0
+    inp.k[0, 0, 9] *= 6.0
+    inp.k[:] = W.round_to_bf16(inp.k)
+    inp.q[:] = W.round_to_bf16(inp.q)
+    check("S3_monotone_S6_huge", inp, R=4)
+    check("S3_monotone_R1", inp, R=1)
+
+
+@pytest.mark.parametrize("P", (1, 2, 4, 8))
+def test_polynomial_degrees(P):
+    w = W.replace(SMALL, B=1, H=2, poly_degree=P, seed=30 + P)
+    check(f"poly_P{P}", W.make_inputs(w), R=4)
+    check(f"poly_P{P}_R0", W.make_inputs(w), R=0)
+
+
+@pytest.mark.parametrize("act", (ha.HA_ACT_EXP, ha.HA_ACT_RELU))
+def test_alternate_activations(act):
+    w = W.replace(SMALL, B=1, H=2, seed=40)
+    check(f"act{act}", W.make_inputs(w), R=4, act=act)
+
+
+def test_paper_width_feature_map():
+    """Tab. "phi" default: d -> 2d -> 2d per head (F = 256, D' = 128)."""
+    w = W.replace(SMALL, B=1, H=2, d_hidden=256, d_feat=256, seed=50)
+    check("paper_width_R4", W.make_inputs(w), R=4)
+    check("paper_width_R0", W.make_inputs(w), R=0, block_size=64)
+
+
+def test_linear_state_tap():
+    inp = W.make_inputs(SMALL)
+    w = inp.workload
+    _, k, v, _, fk = ha.to_device(inp)
+    for R in (0, 4, 3):
+        S, z = ha.hybrid_attn_linear_state(k, v, fk, R)
+        torch.cuda.synchronize()
+        S, z = S.cpu().numpy(), z.cpu().numpy()
+        for b in range(w.B):
+            for h in range(w.H):
+                Sr, zr = O.linear_state(inp.k[b, h], inp.v[b, h], oracle_map(inp.phi_k), h, R)
+                ma, rl = metrics(S[b, h], Sr)
+                ma_z, rl_z = metrics(z[b, h], zr)
+                assert rl <= REL_L2 and rl_z <= REL_L2, (R, b, h, rl, rl_z)
+        record(f"state_tap_R{R}", ma, rl, rl_z=rl_z)
+
+
+def test_bitwise_deterministic():
+    inp = W.make_inputs(SMALL)
+    a = gpu_forward(inp, R=4)
+    b = gpu_forward(inp, R=4)
+    assert np.array_equal(a, b)
+    a = gpu_forward(inp, R=0)
+    b = gpu_forward(inp, R=0)
+    assert np.array_equal(a, b)
+
+
+def test_reading_of_c_i_is_distinguishable():
+    """The GPU follows Eq. "hybrid" as printed (c_i inside the softmax exponents only).  On logits of
+    unit scale the other reading (linear terms effectively multiplied by exp(-c_i)) lands far outside
+    the tolerance, so the parity bar does separate the two."""
+    w = W.replace(SMALL, B=1, H=2, seed=60, qk_gain=float(128 ** 0.25))
+    inp = W.make_inputs(w)
+    y, ref = check("c_i_literal", inp, R=4)
+    fq, fk = oracle_map(inp.phi_q), oracle_map(inp.phi_k)
+    alt = np.empty_like(ref)
+    for h in range(w.H):
+        S, z = O.linear_state(inp.k[0, h], inp.v[0, h], fk, h, 4)
+        a, l, c = O.softmax_part(inp.q[0, h], inp.k[0, h], inp.v[0, h], 4, w.scale)
+        g = O.feature_map(inp.q[0, h], fq, h)
+        e = np.exp(-c)[:, None]
+        alt[0, h] = (a + e * (g @ S)) / (l[:, None] + e * (g @ z)[:, None])
+    _, rl_alt = metrics(y, alt)
+    assert rl_alt > 10 * REL_L2, rl_alt
+
+
+# ------------------------------------------------------------------ full-size configs, sampled rows
+
+def _sampled(name, w, n_random=256):
+    inp = W.make_inputs(w)
+    rows = W.sample_rows(w, n_random)
+    check(name, inp, rows=rows)
+
+
+def test_config2_wan_480p_81f_sampled():
+    _sampled("cfg2_N32760_R4", W.WAN_480P_81F)
+
+
+@pytest.mark.parametrize("R", (0, 1, 16))
+def test_config2_shape_other_rates_sampled(R):
+    _sampled(f"cfg2_shape_R{R}", W.with_rate(W.WAN_480P_81F, R), n_random=64)
+
+
+def test_config4_wan_480p_161f_sampled():
+    _sampled("cfg4_N63960_R8", W.WAN_480P_161F, n_random=128)
+
+
+@pytest.mark.parametrize("layer", (0, 1, 2))
+def test_config5_stack_layer_sampled(layer):
+    """One layer of the 30-layer 720p stack (B = 2 for classifier-free guidance): rate cycles
+    16, 8, 4; inputs drawn on the device; oracle on two (batch, head) pairs and sampled rows."""
+    w = W.replace(W.WAN_720P_81F_CFG, R=W.STACK_RATES[layer % 3], seed=1000 + layer)
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    s = w.d ** -0.5
+    q, k, v = ((torch.randn(w.B, w.H, w.N, w.d, generator=gen, device="cuda", dtype=torch.float32) * s).to(torch.bfloat16)
+               for _ in range(3))
+
+    def dmap():
+        w1 = (torch.randn(w.H, w.d_hidden, w.d, generator=gen, device="cuda") * w.d ** -0.5).to(torch.bfloat16)
+        b1 = torch.randn(w.H, w.d_hidden, generator=gen, device="cuda") * 0.1
+        w2 = (torch.randn(w.H, w.d_feat, w.d_hidden, generator=gen, device="cuda") * w.d_hidden ** -0.5).to(torch.bfloat16)
+        b2 = torch.randn(w.H, w.d_feat, generator=gen, device="cuda") * 0.1
+        return ha.FeatureMap(w1, b1, w2, b2, w.poly_degree)
+    fq, fk = dmap(), dmap()
+    out = ha.hybrid_attn_forward(q, k, v, fq, fk, w.R, w.block_size, w.scale)
+    torch.cuda.synchronize()
+    rows = W.sample_rows(w, 64)
+
+    def host(m):
+        return O.FeatureMap(m.w1.float().cpu().numpy(), m.b1.cpu().numpy(), m.w2.float().cpu().numpy(),
+                            m.b2.cpu().numpy(), m.poly_degree)
+    oq, ok = host(fq), host(fk)
+    for (b, h) in ((0, 0), (1, w.H - 1)):
+        ref = O.hybrid_attn_head(q[b, h].float().cpu().numpy(), k[b, h].float().cpu().numpy(),
+                                 v[b, h].float().cpu().numpy(), oq, ok, h, w.R, w.scale, rows=rows)
+        y = out[b, h].float().cpu().numpy()[rows]
+        ma, rl = metrics(y, ref)
+        record(f"cfg5_layer{layer}_R{w.R}_b{b}h{h}", ma, rl)
+        assert ma <= MAX_ABS and rl <= REL_L2
