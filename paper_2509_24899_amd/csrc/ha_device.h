@@ -117,7 +117,9 @@ static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], c
                                                    const float *__restrict__ b2, int lane, int g,
                                                    f32x16 (&u)[F / 32]) {
   constexpr int KS = D / 16, HB = HD / 32, FB = F / 32;
-  bf16x8 hb16[HB][2];
+  // Hidden activations feed the second layer as hi + lo bf16 pairs: a peaky output softmax amplifies
+  // errors in u = W2 h + b2, so h is not allowed to lose its low mantissa bits here.
+  bf16x8 h_hi[HB][2], h_lo[HB][2];
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     f32x16 h;
@@ -132,10 +134,13 @@ static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], c
     for (int ks = 0; ks < KS; ++ks) h = mfma32(w1f[(hb * KS + ks) * 64 + lane], xf[ks], h);
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      f32x8 t;
+      f32x8 t, lo;
 #pragma unroll
       for (int i = 0; i < 8; ++i) t[i] = fmaxf(h[8 * s + i], 0.f);
-      hb16[hb][s] = __builtin_convertvector(t, bf16x8);
+      h_hi[hb][s] = __builtin_convertvector(t, bf16x8);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) lo[i] = t[i] - static_cast<float>(h_hi[hb][s][i]);
+      h_lo[hb][s] = __builtin_convertvector(lo, bf16x8);
     }
   }
 #pragma unroll
@@ -151,8 +156,11 @@ static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], c
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
-      for (int s = 0; s < 2; ++s)
-        acc = mfma32(w2f[((fb * HB + hb) * 2 + s) * 64 + lane], hb16[hb][s], acc);
+      for (int s = 0; s < 2; ++s) {
+        const bf16x8 wf = w2f[((fb * HB + hb) * 2 + s) * 64 + lane];
+        acc = mfma32(wf, h_lo[hb][s], acc);
+        acc = mfma32(wf, h_hi[hb][s], acc);
+      }
     u[fb] = acc;
   }
 }

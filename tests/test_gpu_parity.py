@@ -108,8 +108,8 @@ def test_degenerate_sizes(N, R):
 
 
 STRESS = {
-    "S1_logit_std1": dict(qk_gain=float(128 ** 0.25)),              # q.k/sqrt(d) ~ N(0, 1)
-    "S2_peaky": dict(qk_gain=float(128 ** 0.25) * 4.0),             # logit std ~ 16
+    "S1_logit_std1": dict(qk_gain=float(128 ** 0.5)),               # q, k ~ N(0, 1): q.k/sqrt(d) ~ N(0, 1)
+    "S2_peaky": dict(qk_gain=float(128 ** 0.5) * 4.0),              # q, k ~ 4 N(0, 1): logit std ~ 16
     "S4_peaky_phi": dict(w_gain=8.0),
 }
 
@@ -124,7 +124,7 @@ def test_stress_distributions(name, R):
 def test_stress_monotone_row_max():
     """Keys ordered so that every row's running maximum keeps increasing along T_S (worst case for
     the online rescale), plus one huge-norm key in T_S and one in T_L."""
-    w = W.replace(SMALL, B=1, H=2, seed=22, qk_gain=float(128 ** 0.25) * 2.0)
+    w = W.replace(SMALL, B=1, H=2, seed=22, qk_gain=float(128 ** 0.5) * 2.0)
     inp = W.make_inputs(w)
     u = np.ones(w.d, dtype=np.float32) / np.sqrt(w.d)
     for h in range(w.H):
@@ -190,7 +190,7 @@ def test_reading_of_c_i_is_distinguishable():
     """The GPU follows Eq. "hybrid" as printed (c_i inside the softmax exponents only).  On logits of
     unit scale the other reading (linear terms effectively multiplied by exp(-c_i)) lands far outside
     the tolerance, so the parity bar does separate the two."""
-    w = W.replace(SMALL, B=1, H=2, seed=60, qk_gain=float(128 ** 0.25))
+    w = W.replace(SMALL, B=1, H=2, seed=60, qk_gain=float(128 ** 0.5))
     inp = W.make_inputs(w)
     y, ref = check("c_i_literal", inp, R=4)
     fq, fk = oracle_map(inp.phi_q), oracle_map(inp.phi_k)
