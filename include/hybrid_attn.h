@@ -72,9 +72,11 @@ typedef struct {
   int32_t dtype;          /* ha_dtype of q, k, v, out, w1, w2.  HA_F32 inputs are rounded to bf16
                              on load (the matrix cores run in bf16 with fp32 accumulation) and
                              the result is written as fp32. */
-  int32_t block_size;     /* 64 or 128: the key tile staged through LDS per loop step; the query
-                             tile of one workgroup is 2 * block_size rows.  A tiling knob only:
-                             the result does not depend on it beyond fp32 summation order. */
+  int32_t block_size;     /* 64 or 128: tiling of the softmax loop.  128: workgroups of 256 queries
+                             (8 waves x 32), keys staged through LDS 64 at a time; 64: workgroups
+                             of 128 queries (4 waves x 32), keys staged 32 at a time.  A tiling knob
+                             only: every query column sees the same keys in the same order, so the
+                             result does not depend on it. */
   int32_t hybrid_rate;    /* R.  0: no softmax tokens (pure linear attention, r = 0);
                              1: every token is a softmax token (plain softmax attention, r = 1);
                              R >= 2: tokens 0, R, 2R, ... (0-indexed) are softmax tokens, r = 1/R.

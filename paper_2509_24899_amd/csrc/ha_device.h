@@ -34,8 +34,17 @@ static __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 static __device__ __forceinline__ constexpr int crow(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
 
 // Combine a value with the lane that holds the other half of the same C column (lane ^ 32).
-static __device__ __forceinline__ float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
-static __device__ __forceinline__ float xhalf_sum(float x) { return x + __shfl_xor(x, 32, 64); }
+// v_permlane32_swap exchanges the upper half of one register with the lower half of another: called
+// with the same value twice it hands every lane {its own value, the partner's} in some order.
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ float xhalf_max(float x) {
+  const u32x2 p = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(p[0]), __uint_as_float(p[1]));
+}
+static __device__ __forceinline__ float xhalf_sum(float x) {
+  const u32x2 p = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(p[0]) + __uint_as_float(p[1]);
+}
 
 static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

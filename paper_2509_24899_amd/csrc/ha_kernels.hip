@@ -210,250 +210,6 @@ __global__ __launch_bounds__(256) void state_reduce_kernel(const float *__restri
 }
 
 // ------------------------------------------------------------------------------------------------
-// query_kernel: 4 waves; wave w owns QB column blocks of 32 queries.  Workgroups are numbered so that
-// consecutive ids on one XCD (id % 8) walk the query tiles of one (batch, head) together and share its
-// K_S / V_S in that XCD's L2.
-struct QueryArgs {
-  const void *q;
-  void *out;
-  const bf16x8 *ks_frag, *vs_frag;       // [B*H][n_kblocks][D*4]
-  const bf16x8 *w1f, *w2f;               // phi_q fragments, per head
-  const float *b1, *b2;                 // phi_q biases, per head (may be null)
-  const bf16x8 *st_hi, *st_lo;           // [B*H][D/32][F/32][2][64]
-  const float *z;                       // [B*H][F]
-  int H, N, NS, n_qtiles, n_ktiles, n_kblocks, total_wg;
-  int has_linear, P, act;
-  int64_t sb, sh, sn;
-  float scale_log2e;
-};
-
-template <int D, int HD, int F, int QB, int KT, bool F32>
-__global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void query_kernel(QueryArgs a) {
-  constexpr int KS = D / 16, RB = D / 32, FB = F / 32;
-  constexpr int KBT = KT / 32;          // 32-key blocks per LDS tile
-  constexpr int FRAG = D * 4;           // bf16x8 per key block, same for K and V
-  constexpr int NLD = KBT * FRAG / 256; // bf16x8 per thread per tile per tensor
-  constexpr int QT = 128 * QB;
-  __shared__ bf16x8 lds_k[2][KBT * FRAG];
-  __shared__ bf16x8 lds_v[2][KBT * FRAG];
-
-  // XCD-aware numbering: hardware deals workgroup ids round-robin over the 8 XCDs.
-  const int per_xcd = (a.total_wg + 7) >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= a.total_wg) return;
-  const int bh = logical / a.n_qtiles, qtile = logical % a.n_qtiles;
-  const int h = bh % a.H;
-  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
-  const int q0 = qtile * QT + w * (32 * QB);
-
-  // Q^T as B-operand fragments, natural order over d
-  bf16x8 qf[QB][KS];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int qi = min(q0 + 32 * qb + r, a.N - 1);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = load8<F32>(a.q, base + (int64_t)qi * a.sn + 16 * ks + 8 * g);
-  }
-
-  f32x16 o[RB][QB];
-  float m[QB], lsum[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m[qb] = -INFINITY;
-    lsum[qb] = 0.f;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int x = 0; x < 16; ++x) o[rb][qb][x] = 0.f;
-  }
-
-  if (a.n_ktiles > 0) {
-    const bf16x8 *ksrc = a.ks_frag + (int64_t)bh * a.n_kblocks * FRAG;
-    const bf16x8 *vsrc = a.vs_frag + (int64_t)bh * a.n_kblocks * FRAG;
-    bf16x8 stk[NLD], stv[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      stk[i] = ksrc[i * 256 + tid];
-      stv[i] = vsrc[i * 256 + tid];
-    }
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      lds_k[0][i * 256 + tid] = stk[i];
-      lds_v[0][i * 256 + tid] = stv[i];
-    }
-    __syncthreads();
-    const float c = a.scale_log2e;
-    for (int t = 0; t < a.n_ktiles; ++t) {
-      const int buf = t & 1;
-      const bool more = t + 1 < a.n_ktiles;
-      if (more) {
-        const int64_t off = (int64_t)(t + 1) * KBT * FRAG;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          stk[i] = ksrc[off + i * 256 + tid];
-          stv[i] = vsrc[off + i * 256 + tid];
-        }
-      }
-      const bool tail = (t == a.n_ktiles - 1) && (a.NS % KT != 0);
-#pragma unroll
-      for (int step = 0; step < KBT / 2; ++step) {
-        const int key0 = t * KT + step * 64;
-        if (key0 < a.NS) {
-          // S^T = K Q^T for 64 keys x (32*QB) queries
-          f32x16 s[2][QB];
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-              for (int x = 0; x < 16; ++x) s[kb][qb][x] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-              const bf16x8 kf = lds_k[buf][(step * 2 + kb) * FRAG + ks * 64 + lane];
-#pragma unroll
-              for (int qb = 0; qb < QB; ++qb) s[kb][qb] = mfma32(kf, qf[qb][ks], s[kb][qb]);
-            }
-          }
-          if (tail) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-              for (int x = 0; x < 16; ++x) {
-                const bool dead = key0 + 32 * kb + crow(x, g) >= a.NS;
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) s[kb][qb][x] = dead ? -INFINITY : s[kb][qb][x];
-              }
-          }
-          // online softmax per query column; c_i stays the exact running maximum
-          bf16x8 pb[2][2][QB];
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-              for (int x = 0; x < 16; ++x) mx = fmaxf(mx, s[kb][qb][x]);
-            mx = xhalf_max(mx);
-            const float m_new = fmaxf(m[qb], mx);
-            if (__any(m_new > m[qb])) {
-              const float alpha = fast_exp2((m[qb] - m_new) * c);
-              lsum[qb] *= alpha;
-#pragma unroll
-              for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) o[rb][qb][x] *= alpha;
-              m[qb] = m_new;
-            }
-            const float mc = m[qb] * c;
-            float ps = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-              for (int sp = 0; sp < 2; ++sp) {
-                f32x8 p8;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                  p8[i] = fast_exp2(__builtin_fmaf(s[kb][qb][8 * sp + i], c, -mc));
-                  ps += p8[i];
-                }
-                pb[kb][sp][qb] = __builtin_convertvector(p8, bf16x8);
-              }
-            lsum[qb] += ps;
-          }
-          // O^T += V^T P^T
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int sp = 0; sp < 2; ++sp)
-#pragma unroll
-              for (int rb = 0; rb < RB; ++rb) {
-                const bf16x8 vf = lds_v[buf][(step * 2 + kb) * FRAG + (rb * 2 + sp) * 64 + lane];
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) o[rb][qb] = mfma32(vf, pb[kb][sp][qb], o[rb][qb]);
-              }
-        }
-      }
-      if (more) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          lds_k[buf ^ 1][i * 256 + tid] = stk[i];
-          lds_v[buf ^ 1][i * 256 + tid] = stv[i];
-        }
-      }
-      __syncthreads();
-    }
-  }
-
-  // epilogue per query column block: linear part and merge
-  const bf16x8 *w1f = a.w1f + (int64_t)h * (HD * D / 8);
-  const bf16x8 *w2f = a.w2f + (int64_t)h * (F * HD / 8);
-  const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
-  const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
-  const int Dp = F / a.P;
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    float den = xhalf_sum(lsum[qb]);
-    if (a.has_linear) {
-      f32x16 u[FB];
-      feature_mlp<D, HD, F>(qf[qb], w1f, w2f, b1, b2, lane, g, u);
-      feature_activation<FB>(u, g, a.act, a.P, Dp);
-      bf16x8 gb[FB][2];
-      float e = 0.f;
-      const float *zz = a.z + (int64_t)bh * F;
-#pragma unroll
-      for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
-          f32x8 t8;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
-          gb[fb][sp] = __builtin_convertvector(t8, bf16x8);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) e += static_cast<float>(gb[fb][sp][i]) * zz[32 * fb + crow(8 * sp + i, g)];
-        }
-      den += xhalf_sum(e);
-      const bf16x8 *sth = a.st_hi + (int64_t)bh * (RB * FB * 2 * 64);
-      const bf16x8 *stl = a.st_lo + (int64_t)bh * (RB * FB * 2 * 64);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        f32x16 n;
-#pragma unroll
-        for (int x = 0; x < 16; ++x) n[x] = 0.f;
-#pragma unroll
-        for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-          for (int sp = 0; sp < 2; ++sp) {
-            const int idx = ((rb * FB + fb) * 2 + sp) * 64 + lane;
-            n = mfma32(stl[idx], gb[fb][sp], n);
-            n = mfma32(sth[idx], gb[fb][sp], n);
-          }
-#pragma unroll
-        for (int x = 0; x < 16; ++x) o[rb][qb][x] += n[x];
-      }
-    }
-    const float inv = 1.0f / den;
-    const int qi = q0 + 32 * qb + r;
-    if (qi < a.N) {
-      const int64_t ooff = base + (int64_t)qi * a.sn;
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int x4 = 0; x4 < 4; ++x4) {
-          const int dcol = 32 * rb + 8 * x4 + 4 * g;
-          f32x4 y = {o[rb][qb][4 * x4] * inv, o[rb][qb][4 * x4 + 1] * inv, o[rb][qb][4 * x4 + 2] * inv,
-                     o[rb][qb][4 * x4 + 3] * inv};
-          if constexpr (F32) {
-            *reinterpret_cast<f32x4 *>(static_cast<float *>(a.out) + ooff + dcol) = y;
-          } else {
-            *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.out) + ooff + dcol) = __builtin_convertvector(y, bf16x4);
-          }
-        }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // host launchers
 
 template <typename T>
@@ -500,39 +256,6 @@ hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st) {
   state_reduce_kernel<<<grid, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_part), ws_ptr<float>(ws, pl.off_S),
                                             ws_ptr<float>(ws, pl.off_z), ws_ptr<__bf16>(ws, pl.off_sthi),
                                             ws_ptr<__bf16>(ws, pl.off_stlo), pl.D, pl.F, pl.n_chunks);
-  return hipGetLastError();
-}
-
-hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
-                        hipStream_t st) {
-  QueryArgs a;
-  a.q = q;
-  a.out = out;
-  a.ks_frag = ws_ptr<bf16x8>(ws, pl.off_ks);
-  a.vs_frag = ws_ptr<bf16x8>(ws, pl.off_vs);
-  a.w1f = ws_ptr<bf16x8>(ws, pl.off_w1q);
-  a.w2f = ws_ptr<bf16x8>(ws, pl.off_w2q);
-  a.b1 = phi_q ? phi_q->b1 : nullptr;
-  a.b2 = phi_q ? phi_q->b2 : nullptr;
-  a.st_hi = ws_ptr<bf16x8>(ws, pl.off_sthi);
-  a.st_lo = ws_ptr<bf16x8>(ws, pl.off_stlo);
-  a.z = ws_ptr<float>(ws, pl.off_z);
-  a.H = pl.H; a.N = pl.N; a.NS = pl.NS;
-  a.n_qtiles = pl.n_qtiles; a.n_ktiles = pl.n_ktiles; a.n_kblocks = pl.n_kblocks;
-  a.total_wg = pl.n_qtiles * pl.B * pl.H;
-  a.has_linear = pl.NL > 0; a.P = pl.P; a.act = pl.act_q;
-  a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
-  a.scale_log2e = pl.scale * kLog2e;
-  dim3 grid(((a.total_wg + 7) / 8) * 8);
-#define HA_QUERY(DD, HH, FF, F32) \
-  do { \
-    if (pl.QB == 1) query_kernel<DD, HH, FF, 1, 64, F32><<<grid, 256, 0, st>>>(a); \
-    else query_kernel<DD, HH, FF, 2, 128, F32><<<grid, 256, 0, st>>>(a); \
-  } while (0)
-  if (pl.D == 64) { if (pl.f32) HA_QUERY(64, 64, 64, true); else HA_QUERY(64, 64, 64, false); }
-  else if (pl.HD == 128) { if (pl.f32) HA_QUERY(128, 128, 128, true); else HA_QUERY(128, 128, 128, false); }
-  else { if (pl.f32) HA_QUERY(128, 256, 256, true); else HA_QUERY(128, 256, 256, false); }
-#undef HA_QUERY
   return hipGetLastError();
 }
 

@@ -1,0 +1,387 @@
+// Query-side kernels of the hybrid-attention forward (Attention Surgery, Sec. 3.2, Eq. "hybrid"), gfx950.
+#include <type_traits>
+
+#include "ha_device.h"
+#include "ha_plan.h"
+
+namespace ha {
+
+template <typename T>
+static inline T *ws_ptr(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
+
+// ------------------------------------------------------------------------------------------------
+// query_kernel: 4 waves; wave w owns QB column blocks of 32 queries.  Workgroups are numbered so that
+// consecutive ids on one XCD (id % 8) walk the query tiles of one (batch, head) together and share its
+// K_S / V_S in that XCD's L2.
+struct QueryArgs {
+  const void *q;
+  void *out;
+  const bf16x8 *ks_frag, *vs_frag;       // [B*H][n_kblocks][D*4]
+  const bf16x8 *w1f, *w2f;               // phi_q fragments, per head
+  const float *b1, *b2;                 // phi_q biases, per head (may be null)
+  const bf16x8 *st_hi, *st_lo;           // [B*H][D/32][F/32][2][64]
+  const float *z;                       // [B*H][F]
+  int H, N, NS, n_qtiles, n_ktiles, n_kblocks, total_wg;
+  int has_linear, P, act;
+  int64_t sb, sh, sn;
+  float scale_log2e;
+};
+
+// Linear part and merge for one 32-query column block (Eq. "hybrid"): g = phi_q(q), n = g S,
+// e = g.z, y = (a + n) / (l + e); `o` holds a^T (d x queries) as C tiles, `lsum` this lane's half of l.
+template <int D, int HD, int F, bool F32>
+static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane, int qi,
+                                                      const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum) {
+  constexpr int RB = D / 32, FB = F / 32;
+  const int g = lane >> 5;
+  float den = xhalf_sum(lsum);
+  if (a.has_linear) {
+    const bf16x8 *w1f = a.w1f + (int64_t)h * (HD * D / 8);
+    const bf16x8 *w2f = a.w2f + (int64_t)h * (F * HD / 8);
+    const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
+    const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
+    f32x16 u[FB];
+    feature_mlp<D, HD, F>(qf, w1f, w2f, b1, b2, lane, g, u);
+    feature_activation<FB>(u, g, a.act, a.P, F / a.P);
+    bf16x8 gb[FB][2];
+    float e = 0.f;
+    const float *zz = a.z + (int64_t)bh * F;
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+      for (int sp = 0; sp < 2; ++sp) {
+        f32x8 t8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
+        gb[fb][sp] = __builtin_convertvector(t8, bf16x8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) e += static_cast<float>(gb[fb][sp][i]) * zz[32 * fb + crow(8 * sp + i, g)];
+      }
+    den += xhalf_sum(e);
+    const bf16x8 *sth = a.st_hi + (int64_t)bh * (RB * FB * 2 * 64);
+    const bf16x8 *stl = a.st_lo + (int64_t)bh * (RB * FB * 2 * 64);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      f32x16 n;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) n[x] = 0.f;
+#pragma unroll
+      for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+          const int idx = ((rb * FB + fb) * 2 + sp) * 64 + lane;
+          n = mfma32(stl[idx], gb[fb][sp], n);
+          n = mfma32(sth[idx], gb[fb][sp], n);
+        }
+#pragma unroll
+      for (int x = 0; x < 16; ++x) o[rb][x] += n[x];
+    }
+  }
+  const float inv = 1.0f / den;
+  if (qi < a.N) {
+    const int64_t ooff = base + (int64_t)qi * a.sn;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int x4 = 0; x4 < 4; ++x4) {
+        const int dcol = 32 * rb + 8 * x4 + 4 * g;
+        f32x4 y = {o[rb][4 * x4] * inv, o[rb][4 * x4 + 1] * inv, o[rb][4 * x4 + 2] * inv, o[rb][4 * x4 + 3] * inv};
+        if constexpr (F32) {
+          *reinterpret_cast<f32x4 *>(static_cast<float *>(a.out) + ooff + dcol) = y;
+        } else {
+          *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.out) + ooff + dcol) = __builtin_convertvector(y, bf16x4);
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// query_kernel_ring: the softmax tile loop as a software pipeline.  NW waves, each owning QB column
+// blocks of 32 queries (every K / V fragment read from LDS feeds QB matrix instructions).
+//
+// K_S / V_S fragments travel global -> LDS with direct-to-LDS loads into a ring of NB 32-key blocks
+// (no staging registers).  Loop step j handles key block j:
+//   phase 1   S(j+1)^T = K(j+1) Q^T on the matrix cores   ||   softmax of S(j) on the vector ALU,
+//             V(j) fragments LDS -> registers
+//   phase 2   O^T += V(j)^T P(j)^T                          ||   K(j+2) fragments LDS -> registers
+// The block for step j + LEAD (LEAD = NB - G) is requested at the top of step j; a barrier (after
+// waiting for this wave's outstanding loads) closes every G-th step.  NB >= 2 G + 2 makes this safe:
+// the slot being refilled was last read before the latest barrier every wave has passed, and a block
+// is first read (as K(j+2)) at least one barrier after it was requested.
+template <int D, int HD, int F, int QB, int NW, int NB, int G, bool F32>
+__global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(QueryArgs a) {
+  static_assert(NB >= 2 * G + 2 && (NB & (NB - 1)) == 0, "ring too short for the barrier period");
+  constexpr int KS = D / 16, RB = D / 32;
+  constexpr int FRAG = D * 4;                 // bf16x8 per 32-key block per tensor
+  constexpr int LEAD = NB - G, QT = 32 * QB * NW;
+  constexpr int WCH = FRAG / 64;              // 1 KiB wave-chunks per block per tensor
+  __shared__ bf16x8 ring_k[NB][FRAG];
+  __shared__ bf16x8 ring_v[NB][FRAG];
+
+  const int per_xcd = (a.total_wg + 7) >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= a.total_wg) return;
+  const int bh = logical / a.n_qtiles, qtile = logical % a.n_qtiles;
+  const int h = bh % a.H;
+  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int q0 = qtile * QT + w * (32 * QB);
+
+  bf16x8 qf[QB][KS];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int qi = min(q0 + 32 * qb + r, a.N - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = load8<F32>(a.q, base + (int64_t)qi * a.sn + 16 * ks + 8 * g);
+  }
+  f32x16 o[QB][RB];
+  float m[QB], lsum[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m[qb] = -INFINITY;
+    lsum[qb] = 0.f;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) o[qb][rb][x] = 0.f;
+  }
+
+  const int nblk = (a.NS + 31) >> 5;     // key blocks that hold at least one real key
+  if (nblk > 0) {
+    const bf16x8 *ksrc = a.ks_frag + (int64_t)bh * a.n_kblocks * FRAG + lane;
+    const bf16x8 *vsrc = a.vs_frag + (int64_t)bh * a.n_kblocks * FRAG + lane;
+    // block b: global -> ring slot b % NB with direct-to-LDS loads; one instruction moves 64 lanes x 16 B
+    // = one 1 KiB wave-chunk (LDS address = M0 + 16 * lane), and the wave-chunks of a block are dealt
+    // round-robin to the waves.  Issued as inline asm so that the compiler does not make later LDS reads
+    // of OTHER ring slots wait for it; completion is awaited explicitly before each barrier.
+    auto request = [&](int b) {
+      const int slot = b & (NB - 1);
+#pragma unroll
+      for (int i = 0; i < (WCH + NW - 1) / NW; ++i) {
+        const int ch = i * NW + w;
+        if (WCH % NW == 0 || ch < WCH) {
+          const unsigned lk = __builtin_amdgcn_readfirstlane(
+              (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(&ring_k[slot][ch * 64]));
+          const unsigned lv = __builtin_amdgcn_readfirstlane(
+              (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(&ring_v[slot][ch * 64]));
+          const bf16x8 *gk = ksrc + (int64_t)b * FRAG + ch * 64;
+          const bf16x8 *gv = vsrc + (int64_t)b * FRAG + ch * 64;
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
+                       "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, off"
+                       :: "s"(lk), "v"(gk), "s"(lv), "v"(gv) : "memory");
+        }
+      }
+    };
+    // Barrier that closes a group of G steps.  Everything this wave requested must have landed before
+    // the other waves may read it, except the newest blocks: the steps up to the next barrier read no
+    // block beyond (closing step) + G + 2, so in the steady state the requests of the last
+    // NB - 2G - 2 steps may stay in flight (loads retire in order).
+    constexpr int IPB = 2 * ((WCH + NW - 1) / NW);          // load instructions per block per wave
+    constexpr int INFLIGHT = (NB - 2 * G - 2) * IPB;
+    auto ring_barrier = [&](auto steady) {
+      if constexpr (decltype(steady)::value && INFLIGHT > 0) {
+        static_assert(INFLIGHT <= 15, "vmcnt immediate too large");
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(INFLIGHT) : "memory");
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+      __syncthreads();
+    };
+    for (int b = 0; b < LEAD && b < nblk; ++b) request(b);
+    ring_barrier(std::false_type{});
+
+    const float c = a.scale_log2e;
+    bf16x8 kf[KS], vf[RB][2];
+    f32x16 s_a[QB], s_b[QB];
+    auto load_k = [&](int b) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[ks] = ring_k[b & (NB - 1)][ks * 64 + lane];
+    };
+    // logits of block b that are zero padding (keys >= NS) must not take part
+    auto mask_tail = [&](f32x16 (&s)[QB], int b) {
+      if ((b + 1) * 32 > a.NS) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const bool dead = b * 32 + crow(x, g) >= a.NS;
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) s[qb][x] = dead ? -INFINITY : s[qb][x];
+        }
+      }
+    };
+    // running maximum c_i over the blocks seen so far; the accumulators are rescaled only when
+    // some row's maximum moved (rare after the first few blocks)
+    auto fold_max = [&](const float (&mx)[QB]) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const float m_new = fmaxf(m[qb], mx[qb]);
+        if (__any(m_new > m[qb])) {
+          const float alpha = fast_exp2((m[qb] - m_new) * c);
+          lsum[qb] *= alpha;
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) o[qb][rb][x] *= alpha;
+          m[qb] = m_new;
+        }
+      }
+    };
+    auto col_max = [&](const f32x16 (&s)[QB], float (&mx)[QB]) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        float t = s[qb][0];
+#pragma unroll
+        for (int x = 1; x < 16; ++x) t = fmaxf(t, s[qb][x]);
+        mx[qb] = xhalf_max(t);
+      }
+    };
+
+    // prologue: S(0), its maximum, and the K fragments of block 1
+    load_k(0);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) s_a[qb][x] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) s_a[qb] = mfma32(kf[ks], qf[qb][ks], s_a[qb]);
+    mask_tail(s_a, 0);
+    {
+      float mx[QB];
+      col_max(s_a, mx);
+      fold_max(mx);
+    }
+    if (nblk > 1) load_k(1);
+
+    // One step.  On entry s_cur = S(j)^T (masked), m already covers block j, kf holds K(j+1).
+    // NEXT: block j+1 exists; NEXT2: block j+2 exists; MASK: block j+1 may hold padding keys.
+    auto step = [&](int j, f32x16 (&s_cur)[QB], f32x16 (&s_nxt)[QB], auto next_c, auto next2_c, auto mask_c) {
+      constexpr bool NEXT = decltype(next_c)::value, NEXT2 = decltype(next2_c)::value, MASK = decltype(mask_c)::value;
+      if constexpr (NEXT2) request(min(j + LEAD, a.n_kblocks - 1));
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) vf[rb][sp] = ring_v[j & (NB - 1)][(rb * 2 + sp) * 64 + lane];
+      __builtin_amdgcn_sched_barrier(0);   // keep the V reads up here so their latency hides under phase 1
+      // phase 1: S(j+1)^T on the matrix cores, exponentials of S(j)^T on the VALU
+      float mc[QB], ps[QB];
+      bf16x8 pb[2][QB];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        mc[qb] = m[qb] * c;
+        ps[qb] = 0.f;
+        if constexpr (NEXT) {
+#pragma unroll
+          for (int x = 0; x < 16; ++x) s_nxt[qb][x] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          if constexpr (NEXT) s_nxt[qb] = mfma32(kf[ks], qf[qb][ks], s_nxt[qb]);
+          // a slice of the exponentials rides along with every matrix instruction
+          constexpr int PER = 16 / KS;   // logits per (ks, qb) slot: 2 for d = 128, 4 for d = 64
+#pragma unroll
+          for (int i = 0; i < PER; ++i) {
+            const int x = ks * PER + i;
+            s_cur[qb][x] = fast_exp2(__builtin_fmaf(s_cur[qb][x], c, -mc[qb]));
+            ps[qb] += s_cur[qb][x];
+          }
+        }
+      }
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        lsum[qb] += ps[qb];
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+          f32x8 p8;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) p8[i] = s_cur[qb][8 * sp + i];
+          pb[sp][qb] = __builtin_convertvector(p8, bf16x8);
+        }
+      }
+      // phase 2: O^T += V(j)^T P(j)^T on the matrix cores; K(j+2) fragments come in from LDS and the
+      // column maxima of S(j+1)^T are formed on the VALU
+      if constexpr (NEXT2) load_k(j + 2);
+#pragma unroll
+      for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) o[qb][rb] = mfma32(vf[rb][sp], pb[sp][qb], o[qb][rb]);
+      if constexpr (NEXT) {
+        if constexpr (MASK) mask_tail(s_nxt, j + 1);
+        float mx[QB];
+        col_max(s_nxt, mx);
+        fold_max(mx);
+      }
+    };
+    using T = std::true_type;
+    using Fa = std::false_type;
+    // steady state: steps whose two successors exist run without any end-of-sequence checks
+    int j = 0;
+    for (; j + 3 < nblk; j += 2) {
+      step(j, s_a, s_b, T{}, T{}, Fa{});
+      if (G == 1) ring_barrier(T{});
+      step(j + 1, s_b, s_a, T{}, T{}, Fa{});
+      if (G <= 2 || (j & 2)) ring_barrier(T{});
+    }
+    // the last one to three steps (j is even here)
+    for (; j < nblk; j += 2) {
+      if (j + 2 < nblk) step(j, s_a, s_b, T{}, T{}, T{});
+      else if (j + 1 < nblk) step(j, s_a, s_b, T{}, Fa{}, T{});
+      else step(j, s_a, s_b, Fa{}, Fa{}, Fa{});
+      ring_barrier(Fa{});
+      if (j + 1 < nblk) {
+        if (j + 3 < nblk) step(j + 1, s_b, s_a, T{}, T{}, T{});
+        else if (j + 2 < nblk) step(j + 1, s_b, s_a, T{}, Fa{}, T{});
+        else step(j + 1, s_b, s_a, Fa{}, Fa{}, Fa{});
+      }
+      ring_barrier(Fa{});
+    }
+  }
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+    query_epilogue<D, HD, F, F32>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb]);
+}
+
+hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
+                        hipStream_t st) {
+  QueryArgs a;
+  a.q = q;
+  a.out = out;
+  a.ks_frag = ws_ptr<bf16x8>(ws, pl.off_ks);
+  a.vs_frag = ws_ptr<bf16x8>(ws, pl.off_vs);
+  a.w1f = ws_ptr<bf16x8>(ws, pl.off_w1q);
+  a.w2f = ws_ptr<bf16x8>(ws, pl.off_w2q);
+  a.b1 = phi_q ? phi_q->b1 : nullptr;
+  a.b2 = phi_q ? phi_q->b2 : nullptr;
+  a.st_hi = ws_ptr<bf16x8>(ws, pl.off_sthi);
+  a.st_lo = ws_ptr<bf16x8>(ws, pl.off_stlo);
+  a.z = ws_ptr<float>(ws, pl.off_z);
+  a.H = pl.H; a.N = pl.N; a.NS = pl.NS;
+  a.n_ktiles = pl.n_ktiles; a.n_kblocks = pl.n_kblocks;
+  a.has_linear = pl.NL > 0; a.P = pl.P; a.act = pl.act_q;
+  a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
+  a.scale_log2e = pl.scale * kLog2e;
+  // block_size 128: 8 waves x 32 queries, ring of 8 key blocks, barrier every 64 keys (one workgroup per CU);
+  // block_size 64: 4 waves x 32 queries, ring of 4 key blocks, barrier every 32 keys (two workgroups per CU).
+  const bool big = pl.KT == 128;
+  const int QT = big ? 256 : 128;
+  a.n_qtiles = (pl.N + QT - 1) / QT;
+  a.total_wg = a.n_qtiles * pl.B * pl.H;
+  dim3 grid(((a.total_wg + 7) / 8) * 8);
+#define HA_QUERY(DD, HH, FF, F32) \
+  do { \
+    if (big) query_kernel_ring<DD, HH, FF, 1, 8, 8, 2, F32><<<grid, 512, 0, st>>>(a); \
+    else query_kernel_ring<DD, HH, FF, 1, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \
+  } while (0)
+  if (pl.D == 64) { if (pl.f32) HA_QUERY(64, 64, 64, true); else HA_QUERY(64, 64, 64, false); }
+  else if (pl.HD == 128) { if (pl.f32) HA_QUERY(128, 128, 128, true); else HA_QUERY(128, 128, 128, false); }
+  else { if (pl.f32) HA_QUERY(128, 256, 256, true); else HA_QUERY(128, 256, 256, false); }
+#undef HA_QUERY
+  return hipGetLastError();
+}
+
+}  // namespace ha
