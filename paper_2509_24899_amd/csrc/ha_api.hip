@@ -82,8 +82,16 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.n_qtiles = (pl.N + pl.QT - 1) / pl.QT;
   pl.n_ktiles = (pl.NS + pl.KT - 1) / pl.KT;
   pl.n_kblocks = pl.n_ktiles * (pl.KT / 32);
-  pl.CH = 1024;
-  pl.n_chunks = has_linear ? (pl.NL + pl.CH - 1) / pl.CH : 0;
+  // state pass: one workgroup per CU (256 CUs) in a single round when there is enough work,
+  // chunks are whole 128-token tiles
+  {
+    const int tiles = (pl.NL + 127) / 128;
+    const int per_head = 256 / (pl.B * pl.H) > 0 ? 256 / (pl.B * pl.H) : 1;
+    const int want = tiles < per_head ? (tiles > 0 ? tiles : 1) : per_head;
+    pl.CH = ((tiles + want - 1) / want) * 128;
+    if (pl.CH < 128) pl.CH = 128;
+    pl.n_chunks = has_linear ? (pl.NL + pl.CH - 1) / pl.CH : 0;
+  }
   pl.n_state_tiles = (pl.F / 32) * (pl.D / 32 + 1);
   const size_t BH = (size_t)pl.B * pl.H;
   size_t off = 0;

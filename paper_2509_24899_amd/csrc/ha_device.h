@@ -61,14 +61,30 @@ static __device__ __forceinline__ bf16x8 load8(const void *base, int64_t elem_of
   }
 }
 
-// Linear-token index -> token index: the tokens with j % R != 0 in increasing order (R = 0: all).
-static __device__ __forceinline__ int linear_to_token(int i, int R) { return R == 0 ? i : i + i / (R - 1) + 1; }
+// Linear-token index -> token index: the tokens with j % R != 0 in increasing order (R = 0: all),
+// i.e. i + i / (R - 1) + 1.  The quotient comes from a float reciprocal plus one correction step
+// (exact for i < 2^23).
+struct LinearMap {
+  int d;        // R - 1, or a huge divisor when R == 0
+  int one;      // 1 if R != 0
+  float rcp;
+  __device__ __forceinline__ explicit LinearMap(int R) : d(R == 0 ? 0x7fffffff : R - 1), one(R != 0), rcp(1.0f / (float)d) {}
+  __device__ __forceinline__ int token(int i) const {
+    int q = (int)((float)i * rcp);
+    int rem = i - q * d;
+    q += (rem >= d) - (rem < 0);
+    return i + q + one;
+  }
+};
 
 // Feature-map output stage on one C column held as NB row blocks of 16 registers (plus the same in
 // lane ^ 32): positive activation over all channels, then channel c is raised to 1 + c / Dp.
 //   act 0: softmax over the F = 32*NB channels;  1: exp;  2: relu.
+// Dp is a multiple of 8 for every supported width, so the power of a channel depends only on its
+// group of four registers (rows 32b + 8q .. + 7): the slice tests are wave-uniform.
 template <int NB>
 static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g, int act, int P, int Dp) {
+  (void)g;
   if (act == 0) {
     float mx = -INFINITY;
 #pragma unroll
@@ -76,12 +92,13 @@ static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, u[b][v]);
     mx = xhalf_max(mx);
+    const float off = -mx * kLog2e;
     float sum = 0.f;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        u[b][v] = fast_exp2((u[b][v] - mx) * kLog2e);
+        u[b][v] = fast_exp2(__builtin_fmaf(u[b][v], kLog2e, off));
         sum += u[b][v];
       }
     sum = xhalf_sum(sum);
@@ -103,32 +120,34 @@ static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g
   }
   if (P > 1) {
     // slice p = c / Dp (0-based) gets p extra multiplications by the activation value
-    f32x16 t[NB];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) t[b] = u[b];
-    for (int i = 1; i < P; ++i) {
-      const int lim = i * Dp;
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) u[b][v] = (32 * b + crow(v, g) >= lim) ? u[b][v] * t[b][v] : u[b][v];
-    }
+      for (int q = 0; q < 4; ++q) {
+        const int extra = (32 * b + 8 * q) / Dp;       // wave-uniform
+        if (extra > 0) {
+          const float t0 = u[b][4 * q], t1 = u[b][4 * q + 1], t2 = u[b][4 * q + 2], t3 = u[b][4 * q + 3];
+          for (int i = 0; i < extra; ++i) {
+            u[b][4 * q] *= t0;
+            u[b][4 * q + 1] *= t1;
+            u[b][4 * q + 2] *= t2;
+            u[b][4 * q + 3] *= t3;
+          }
+        }
+      }
   }
 }
 
 // Two-layer feature-map MLP on one 32-token column block, all in registers.
 //   xf[ks]  : B-operand fragments of the tokens (natural slot order over d)
 //   w1f/w2f : A-operand fragments of the weights, w1 in natural order, w2 in chained order
-// Result: u[fb] = W2 relu(W1 x + b1) + b2 as C tiles (rows = channels, column = token).
-template <int D, int HD, int F>
-static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], const bf16x8 *__restrict__ w1f,
-                                                   const bf16x8 *__restrict__ w2f, const float *__restrict__ b1,
-                                                   const float *__restrict__ b2, int lane, int g,
-                                                   f32x16 (&u)[F / 32]) {
-  constexpr int KS = D / 16, HB = HD / 32, FB = F / 32;
-  // Hidden activations feed the second layer as hi + lo bf16 pairs: a peaky output softmax amplifies
-  // errors in u = W2 h + b2, so h is not allowed to lose its low mantissa bits here.
-  bf16x8 h_hi[HB][2], h_lo[HB][2];
+// Layer 1 leaves relu(W1 x + b1) as hi + lo bf16 pairs in chained order: a peaky output softmax
+// amplifies errors in u = W2 h + b2, so h is not allowed to lose its low mantissa bits.
+template <int D, int HD>
+static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D / 16], const bf16x8 *__restrict__ w1f,
+                                                          const float *__restrict__ b1, int lane, int g,
+                                                          bf16x8 (&h_hi)[HD / 32][2], bf16x8 (&h_lo)[HD / 32][2]) {
+  constexpr int KS = D / 16, HB = HD / 32;
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     f32x16 h;
@@ -152,6 +171,14 @@ static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], c
       h_lo[hb][s] = __builtin_convertvector(lo, bf16x8);
     }
   }
+}
+
+// Layer 2: u[fb] = W2 h + b2 as C tiles (rows = channels, column = token).
+template <int HD, int F>
+static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[HD / 32][2], const bf16x8 (&h_lo)[HD / 32][2],
+                                                          const bf16x8 *__restrict__ w2f, const float *__restrict__ b2,
+                                                          int lane, int g, f32x16 (&u)[F / 32]) {
+  constexpr int HB = HD / 32, FB = F / 32;
 #pragma unroll
   for (int fb = 0; fb < FB; ++fb) {
     f32x16 acc;
@@ -172,6 +199,16 @@ static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], c
       }
     u[fb] = acc;
   }
+}
+
+template <int D, int HD, int F>
+static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], const bf16x8 *__restrict__ w1f,
+                                                   const bf16x8 *__restrict__ w2f, const float *__restrict__ b1,
+                                                   const float *__restrict__ b2, int lane, int g,
+                                                   f32x16 (&u)[F / 32]) {
+  bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
+  feature_mlp_layer1<D, HD>(xf, w1f, b1, lane, g, h_hi, h_lo);
+  feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
 }
 
 }  // namespace ha

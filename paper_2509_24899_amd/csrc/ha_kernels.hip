@@ -92,89 +92,151 @@ __global__ __launch_bounds__(256) void compact_kernel(const void *__restrict__ k
 // park phi_k(k)^T and V^T in LDS with tokens contiguous, then the output tiles of
 // [S | z] = phi_k(K)^T [V | 1] are dealt round-robin to the waves and contracted over the tokens.
 // Partial tiles go to part[bh][chunk][tile][v][lane] (fp32).
+//
+// Global loads run ahead of their use: the V rows of tile t are requested before its MLP starts and
+// the K rows of tile t+1 as soon as layer 1 of tile t is done with the current ones.  Both LDS arrays hold [feature row][token] with the 8-token (16 B)
+// blocks of a row XOR-swizzled by ((row / 8) % 4) * 2, which spreads the 2-byte transposing writes
+// and the 16-byte operand reads over all banks.
 template <int D, int HD, int F, bool F32>
-__global__ __launch_bounds__(256) void state_kernel(const void *__restrict__ k, const void *__restrict__ v,
-                                                    const bf16x8 *__restrict__ w1f_all, const bf16x8 *__restrict__ w2f_all,
-                                                    const float *__restrict__ b1_all, const float *__restrict__ b2_all,
-                                                    float *__restrict__ part, int H, int NL, int R, int CH, int P,
-                                                    int act, int64_t sb, int64_t sh, int64_t sn) {
+__global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ k, const void *__restrict__ v,
+                                                       const bf16x8 *__restrict__ w1f_all,
+                                                       const bf16x8 *__restrict__ w2f_all,
+                                                       const float *__restrict__ b1_all, const float *__restrict__ b2_all,
+                                                       float *__restrict__ part, int H, int NL, int R, int CH, int P,
+                                                       int act, int64_t sb, int64_t sh, int64_t sn) {
   constexpr int TOK = 128, PITCH = TOK + 8;
-  constexpr int KS = D / 16, FB = F / 32, NCB = D / 32 + 1, NT = FB * NCB, TPW = (NT + 3) / 4;
+  constexpr int KS = D / 16, FB = F / 32, NCB = D / 32 + 1, NT = FB * NCB;
+  constexpr int RPW = FB >= 4 ? FB / 4 : 1;   // row blocks of [S | z] per wave
+  constexpr int GW = FB / RPW;                // waves that take part in the state contraction
+  constexpr int TPW = RPW * NCB;              // output tiles per such wave
+  constexpr int CG = D / 32;                  // groups of four 16-byte chunks per V row
+  constexpr int VPT = (TOK / 16) * CG / 4;    // V chunks per thread per tile
   __shared__ __align__(16) __bf16 ft[F][PITCH];
   __shared__ __align__(16) __bf16 vt[D][PITCH];
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H;
   const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept scalar
   const bf16x8 *w1f = w1f_all + (int64_t)h * (HD * D / 8);
   const bf16x8 *w2f = w2f_all + (int64_t)h * (F * HD / 8);
   const float *b1 = b1_all ? b1_all + (int64_t)h * HD : nullptr;
   const float *b2 = b2_all ? b2_all + (int64_t)h * F : nullptr;
   const int Dp = F / P;
+  const LinearMap lmap(R);
 
+  // wave w < GW owns row blocks fb = w*RPW .. + RPW - 1 of [S | z] with all NCB column blocks each
+  // (tile = fb * NCB + cb), so every A fragment read from LDS feeds NCB products
   f32x16 acc[TPW];
 #pragma unroll
   for (int i = 0; i < TPW; ++i)
 #pragma unroll
     for (int x = 0; x < 16; ++x) acc[i][x] = 0.f;
 
+  // LDS addressing.  Element (row, token) sits at row * PITCH + (((token / 8) ^ sw(row)) * 8 + token % 8),
+  // sw(row) = ((row / 8) % 4) * 2.
+  //  - phi writes: this lane owns token tf = 32 w + r and rows 32 fb + 8 q + 4 g + e; sw = 2 q is known
+  //    at compile time, so four column offsets (one per q) cover every write
+  //  - V writes: per pass this lane owns one 16-byte chunk = rows 8 c8 .. 8 c8 + 7 of one token
+  //  - operand reads: rows 32 * blk + r, 16-byte token blocks 2 ks + g
+  const int tf = w * 32 + r;
+  int fcol[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) fcol[q] = (4 * g) * PITCH + ((((tf >> 3) ^ (2 * q)) << 3) | (tf & 7));
+  const int vsw = (lane >> 4) << 1;                       // sw of rows 8 c8 + i, c8 % 4 = lane / 16
+  const int vrow0 = 8 * (lane >> 4) * PITCH;
+  const int rsw = ((r >> 3) & 3) << 1;                    // sw of operand rows 32 blk + r
+  __bf16 *ftp = &ft[0][0];
+  __bf16 *vtp = &vt[0][0];
+
   const int lt_begin = chunk * CH;
   const int lt_end = min(lt_begin + CH, NL);
-  for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
-    // phi_k on this wave's 32 tokens
-    {
-      const int lt = t0 + w * 32 + r;
-      const bool valid = lt < NL;
-      const int tok = linear_to_token(valid ? lt : NL - 1, R);
-      bf16x8 xf[KS];
+  // rows past the end of T_L are clamped to the last linear token (valid memory) and masked later
+  auto load_k = [&](int t0, bf16x8 (&dst)[KS]) {
+    const int tok = lmap.token(min(t0 + tf, NL - 1));
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) xf[ks] = load8<F32>(k, base + (int64_t)tok * sn + 16 * ks + 8 * g);
+    for (int ks = 0; ks < KS; ++ks) dst[ks] = load8<F32>(k, base + (int64_t)tok * sn + 16 * ks + 8 * g);
+  };
+  bf16x8 xf[KS];
+  load_k(lt_begin, xf);
+  for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
+    // V rows of this tile: pass p of wave w covers tokens 16 ((4p + w) % 8) .. + 15 and the four
+    // 16-byte chunks 4 (p / 2) .. + 3 of each (64 contiguous bytes per row)
+    bf16x8 vreg[VPT];
+#pragma unroll
+    for (int p = 0; p < VPT; ++p) {
+      const int trow = 16 * ((4 * p + w) & 7) + (lane & 15), c8 = 4 * (p >> 1) + (lane >> 4);
+      const int tok = lmap.token(min(t0 + trow, NL - 1));
+      vreg[p] = load8<F32>(v, base + (int64_t)tok * sn + c8 * 8);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // phi_k on this wave's 32 tokens; the K rows of the next tile are requested as soon as layer 1
+    // has consumed the current ones
+    {
       f32x16 u[FB];
-      feature_mlp<D, HD, F>(xf, w1f, w2f, b1, b2, lane, g, u);
+      {
+        bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
+        feature_mlp_layer1<D, HD>(xf, w1f, b1, lane, g, h_hi, h_lo);
+        __builtin_amdgcn_sched_barrier(0);
+        load_k(t0 + TOK, xf);
+        __builtin_amdgcn_sched_barrier(0);
+        feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
+      }
       feature_activation<FB>(u, g, act, P, Dp);
+      if (t0 + TOK > NL) {                                 // ragged end of T_L: padded tokens add nothing
+        const bool valid = t0 + tf < NL;
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) u[fb][x] = valid ? u[fb][x] : 0.f;
+      }
 #pragma unroll
       for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-        for (int x = 0; x < 16; ++x)
-          ft[32 * fb + crow(x, g)][w * 32 + r] = static_cast<__bf16>(valid ? u[fb][x] : 0.f);
+        for (int x = 0; x < 16; x += 2) {
+          typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+          typedef float f32x2 __attribute__((ext_vector_type(2)));
+          const bf16x2 pr = __builtin_convertvector(f32x2{u[fb][x], u[fb][x + 1]}, bf16x2);
+          ftp[(32 * fb + 8 * (x >> 2) + (x & 3)) * PITCH + fcol[x >> 2]] = pr[0];
+          ftp[(32 * fb + 8 * (x >> 2) + (x & 3) + 1) * PITCH + fcol[x >> 2]] = pr[1];
+        }
     }
-    // V^T of the tile's 128 tokens
-    for (int c = tid; c < TOK * (D / 8); c += 256) {
-      const int trow = c / (D / 8), c8 = c % (D / 8);
-      const int lt = min(t0 + trow, NL - 1);
-      const bf16x8 vv = load8<F32>(v, base + (int64_t)linear_to_token(lt, R) * sn + c8 * 8);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) vt[c8 * 8 + i][trow] = vv[i];
+    for (int p = 0; p < VPT; ++p) {
+      const int trow = 16 * ((4 * p + w) & 7) + (lane & 15);
+      const int col = (((trow >> 3) ^ vsw) << 3) | (trow & 7);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) vtp[(32 * (p >> 1) + i) * PITCH + vrow0 + col] = vreg[p][i];
     }
     __syncthreads();
+    if (w < GW) {
 #pragma unroll
-    for (int i = 0; i < TPW; ++i) {
-      const int ti = w + 4 * i;
-      if (ti < NT) {
-        const int fb = ti / NCB, cb = ti % NCB;
+      for (int ks = 0; ks < TOK / 16; ++ks) {
+        const int col = ((2 * ks + g) ^ rsw) << 3;
 #pragma unroll
-        for (int ks = 0; ks < TOK / 16; ++ks) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&ft[32 * fb + r][16 * ks + 8 * g]);
-          bf16x8 b;
-          if (cb < D / 32) {
-            b = *reinterpret_cast<const bf16x8 *>(&vt[32 * cb + r][16 * ks + 8 * g]);
-          } else {
-            const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);   // the "1" column that yields z
-            b = bf16x8{one, one, one, one, one, one, one, one};
+        for (int rp = 0; rp < RPW; ++rp) {
+          const bf16x8 af = *reinterpret_cast<const bf16x8 *>(&ftp[(32 * (w * RPW + rp) + r) * PITCH + col]);
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) {
+            bf16x8 bfr;
+            if (cb < D / 32) {
+              bfr = *reinterpret_cast<const bf16x8 *>(&vtp[(32 * cb + r) * PITCH + col]);
+            } else {
+              const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);   // the "1" column that yields z
+              bfr = bf16x8{one, one, one, one, one, one, one, one};
+            }
+            acc[rp * NCB + cb] = mfma32(af, bfr, acc[rp * NCB + cb]);
           }
-          acc[i] = mfma32(a, b, acc[i]);
         }
       }
     }
     __syncthreads();
   }
-  float *dst = part + ((int64_t)bh * gridDim.x + chunk) * NT * 1024;
+  if (w < GW) {
+    float *dst = part + ((int64_t)bh * gridDim.x + chunk) * NT * 1024 + (int64_t)w * TPW * 1024;
 #pragma unroll
-  for (int i = 0; i < TPW; ++i) {
-    const int ti = w + 4 * i;
-    if (ti < NT) {
+    for (int i = 0; i < TPW; ++i)
 #pragma unroll
-      for (int x = 0; x < 16; ++x) dst[ti * 1024 + x * 64 + lane] = acc[i][x];
-    }
+      for (int x = 0; x < 16; ++x) dst[i * 1024 + x * 64 + lane] = acc[i][x];
   }
 }
 

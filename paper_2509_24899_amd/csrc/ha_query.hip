@@ -124,7 +124,8 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   const int bh = logical / a.n_qtiles, qtile = logical % a.n_qtiles;
   const int h = bh % a.H;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept scalar
   const int q0 = qtile * QT + w * (32 * QB);
 
   bf16x8 qf[QB][KS];
