@@ -111,14 +111,26 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   constexpr int TPW = RPW * NCB;              // output tiles per such wave
   constexpr int CG = D / 32;                  // groups of four 16-byte chunks per V row
   constexpr int VPT = (TOK / 16) * CG / 4;    // V chunks per thread per tile
+  // the MLP weight fragments of this head live in LDS when they fit next to the two transposing arrays
+  constexpr bool WLDS = (HD * D + F * HD) * 2 <= 64 * 1024;
   __shared__ __align__(16) __bf16 ft[F][PITCH];
   __shared__ __align__(16) __bf16 vt[D][PITCH];
+  __shared__ bf16x8 wlds[WLDS ? (HD * D + F * HD) / 8 : 1];
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H;
   const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept scalar
-  const bf16x8 *w1f = w1f_all + (int64_t)h * (HD * D / 8);
-  const bf16x8 *w2f = w2f_all + (int64_t)h * (F * HD / 8);
+  const bf16x8 *w1g = w1f_all + (int64_t)h * (HD * D / 8);
+  const bf16x8 *w2g = w2f_all + (int64_t)h * (F * HD / 8);
+  if constexpr (WLDS) {
+    for (int i = tid; i < HD * D / 8; i += 256) wlds[i] = w1g[i];
+    for (int i = tid; i < F * HD / 8; i += 256) wlds[HD * D / 8 + i] = w2g[i];
+    // visible to all waves after the first barrier inside the tile loop; layer 1 of the first tile
+    // must not start before that, so synchronise once here
+    __syncthreads();
+  }
+  const bf16x8 *w1f = WLDS ? &wlds[0] : w1g;
+  const bf16x8 *w2f = WLDS ? &wlds[HD * D / 8] : w2g;
   const float *b1 = b1_all ? b1_all + (int64_t)h * HD : nullptr;
   const float *b2 = b2_all ? b2_all + (int64_t)h * F : nullptr;
   const int Dp = F / P;

@@ -29,15 +29,16 @@ struct QueryArgs {
 
 // Linear part and merge for one 32-query column block (Eq. "hybrid"): g = phi_q(q), n = g S,
 // e = g.z, y = (a + n) / (l + e); `o` holds a^T (d x queries) as C tiles, `lsum` this lane's half of l.
+// w1f / w2f / sth / stl: this head's weight fragments and this (batch, head)'s S^T fragments (global or LDS).
 template <int D, int HD, int F, bool F32>
 static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane, int qi,
-                                                      const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum) {
+                                                      const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum,
+                                                      const bf16x8 *w1f, const bf16x8 *w2f, const bf16x8 *sth,
+                                                      const bf16x8 *stl) {
   constexpr int RB = D / 32, FB = F / 32;
   const int g = lane >> 5;
   float den = xhalf_sum(lsum);
   if (a.has_linear) {
-    const bf16x8 *w1f = a.w1f + (int64_t)h * (HD * D / 8);
-    const bf16x8 *w2f = a.w2f + (int64_t)h * (F * HD / 8);
     const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
     const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
     f32x16 u[FB];
@@ -58,8 +59,6 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
         for (int i = 0; i < 8; ++i) e += static_cast<float>(gb[fb][sp][i]) * zz[32 * fb + crow(8 * sp + i, g)];
       }
     den += xhalf_sum(e);
-    const bf16x8 *sth = a.st_hi + (int64_t)bh * (RB * FB * 2 * 64);
-    const bf16x8 *stl = a.st_lo + (int64_t)bh * (RB * FB * 2 * 64);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       f32x16 n;
@@ -342,9 +341,16 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
       ring_barrier(Fa{});
     }
   }
+  // epilogue operands stay in global memory (L2-resident: 64 KiB of weights per head, 64 KiB of state
+  // per (batch, head)); staging them through the idle ring was measured slower than reading them in place
+  constexpr int NW1 = HD * D / 8, NW2 = F * HD / 8, NST = D * F / 8;
+  const bf16x8 *w1f = a.w1f + (int64_t)h * NW1;
+  const bf16x8 *w2f = a.w2f + (int64_t)h * NW2;
+  const bf16x8 *sth = a.st_hi + (int64_t)bh * NST;
+  const bf16x8 *stl = a.st_lo + (int64_t)bh * NST;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb)
-    query_epilogue<D, HD, F, F32>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb]);
+    query_epilogue<D, HD, F, F32>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb], w1f, w2f, sth, stl);
 }
 
 hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
