@@ -17,7 +17,7 @@ PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 flop/clk/CU, dense bf16
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(w, heads=4):
+def cpu_baseline(w, heads=12):
     """fp64 oracle on the host cores for a bounded sample of the same workload: the full forward
     (every key, every query row) of `heads` of the B*H (batch, head) pairs, scaled linearly to all of
     them (heads are independent problems of identical cost)."""
@@ -128,9 +128,14 @@ def main():
         achieved = by / (mean[4] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "whole forward (r = 0)", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": achieved / PEAK_HBM_GBS, "kernel_ms": mean[4], "traffic": None}
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (null when this
+    # workload has not been profiled)
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
-        roofline["traffic"] = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
+        t = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
+        if t:
+            roofline["traffic"] = t["read_bytes"] + t["written_bytes"]
+            roofline["traffic_detail"] = t
 
     rec = {
         "metric": "hybrid-attention fwd tokens/s", "value": w.B * w.N / (ms_per_step * 1e-3), "unit": "tokens/s",
