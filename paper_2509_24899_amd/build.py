@@ -17,13 +17,13 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every source and link libhybridattn.so; returns its path."""
+def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PATH, tag: str = "") -> str:
+    """Compile every source and link the shared library (libhybridattn.so by default); returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(LIB_DIR, exist_ok=True)
     objs, procs = [], []
     for src in SOURCES:
-        obj = os.path.join(LIB_DIR, src.replace(".hip", ".o"))
+        obj = os.path.join(LIB_DIR, src.replace(".hip", tag + ".o"))
         cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -36,9 +36,9 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out:
             print(out, flush=True)
-    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out_path]
     subprocess.run(link, check=True)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

@@ -116,6 +116,11 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   constexpr int WCH = FRAG / 64;              // 1 KiB wave-chunks per block per tensor
   __shared__ bf16x8 ring_k[NB][FRAG];
   __shared__ bf16x8 ring_v[NB][FRAG];
+  // The first QL of the KS Q fragments of every wave live in LDS instead of registers: with two waves per
+  // SIMD the loop is a few registers over budget otherwise, and a register spilled to scratch would make
+  // every step wait on the vector-memory counter, i.e. on the direct-to-LDS loads just issued.
+  constexpr int QL = (D == 128 && QB == 1) ? 4 : 0;
+  __shared__ bf16x8 q_lds[QL > 0 ? NW * QL * 64 : 1];
 
   const int per_xcd = (a.total_wg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -134,11 +139,19 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = load8<F32>(a.q, base + (int64_t)qi * a.sn + 16 * ks + 8 * g);
   }
+  if constexpr (QL > 0) {
+#pragma unroll
+    for (int ks = 0; ks < QL; ++ks) q_lds[(w * QL + ks) * 64 + lane] = qf[0][ks];
+  }
   f32x16 o[QB][RB];
-  float m[QB], lsum[QB];
+  // m_true: exact running maximum c_i.  m: the (possibly older) maximum the accumulators are currently
+  // expressed against; it follows m_true only when the gap would let exponentials exceed 2^kLazy.
+  constexpr float kLazy = 8.0f;
+  float m[QB], m_true[QB], lsum[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m[qb] = -INFINITY;
+    m_true[qb] = -INFINITY;
     lsum[qb] = 0.f;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
@@ -148,12 +161,14 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
 
   const int nblk = (a.NS + 31) >> 5;     // key blocks that hold at least one real key
   if (nblk > 0) {
-    const bf16x8 *ksrc = a.ks_frag + (int64_t)bh * a.n_kblocks * FRAG + lane;
-    const bf16x8 *vsrc = a.vs_frag + (int64_t)bh * a.n_kblocks * FRAG + lane;
+    const bf16x8 *ksrc = a.ks_frag + (int64_t)bh * a.n_kblocks * FRAG;
+    const bf16x8 *vsrc = a.vs_frag + (int64_t)bh * a.n_kblocks * FRAG;
+    const unsigned lane_off = lane * 16;
     // block b: global -> ring slot b % NB with direct-to-LDS loads; one instruction moves 64 lanes x 16 B
-    // = one 1 KiB wave-chunk (LDS address = M0 + 16 * lane), and the wave-chunks of a block are dealt
-    // round-robin to the waves.  Issued as inline asm so that the compiler does not make later LDS reads
-    // of OTHER ring slots wait for it; completion is awaited explicitly before each barrier.
+    // = one 1 KiB wave-chunk (LDS address = M0 + 16 * lane, global address = scalar base + 16 * lane), and
+    // the wave-chunks of a block are dealt round-robin to the waves.  Issued as inline asm so that the
+    // compiler does not make later LDS reads of OTHER ring slots wait for it; completion is awaited
+    // explicitly before each barrier.
     auto request = [&](int b) {
       const int slot = b & (NB - 1);
 #pragma unroll
@@ -166,9 +181,9 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
               (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(&ring_v[slot][ch * 64]));
           const bf16x8 *gk = ksrc + (int64_t)b * FRAG + ch * 64;
           const bf16x8 *gv = vsrc + (int64_t)b * FRAG + ch * 64;
-          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-                       "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, off"
-                       :: "s"(lk), "v"(gk), "s"(lv), "v"(gv) : "memory");
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
+                       "s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %4"
+                       :: "s"(lk), "v"(lane_off), "s"(gk), "s"(lv), "s"(gv) : "memory");
         }
       }
     };
@@ -208,20 +223,22 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
         }
       }
     };
-    // running maximum c_i over the blocks seen so far; the accumulators are rescaled only when
-    // some row's maximum moved (rare after the first few blocks)
+    // Running maximum c_i over the blocks seen so far.  The accumulators follow it lazily: they are
+    // rescaled only when some row's maximum has moved more than kLazy (in log2 units) past the reference
+    // they are expressed against, which keeps every exponential below 2^kLazy; the exact c_i is restored
+    // once after the loop.
     auto fold_max = [&](const float (&mx)[QB]) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        const float m_new = fmaxf(m[qb], mx[qb]);
-        if (__any(m_new > m[qb])) {
-          const float alpha = fast_exp2((m[qb] - m_new) * c);
+        m_true[qb] = fmaxf(m_true[qb], mx[qb]);
+        if (__any((m_true[qb] - m[qb]) * c > kLazy)) {
+          const float alpha = fast_exp2((m[qb] - m_true[qb]) * c);
           lsum[qb] *= alpha;
 #pragma unroll
           for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int x = 0; x < 16; ++x) o[qb][rb][x] *= alpha;
-          m[qb] = m_new;
+          m[qb] = m_true[qb];
         }
       }
     };
@@ -258,11 +275,16 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
     auto step = [&](int j, f32x16 (&s_cur)[QB], f32x16 (&s_nxt)[QB], auto next_c, auto next2_c, auto mask_c) {
       constexpr bool NEXT = decltype(next_c)::value, NEXT2 = decltype(next2_c)::value, MASK = decltype(mask_c)::value;
       if constexpr (NEXT2) request(min(j + LEAD, a.n_kblocks - 1));
+      // V(j) fragments come in as two halves (keys 0..15 and 16..31 of the block) to keep fewer
+      // registers live: the first now, the second once half of the K fragments have been consumed
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
+      for (int rb = 0; rb < RB; ++rb) vf[rb][0] = ring_v[j & (NB - 1)][(rb * 2 + 0) * 64 + lane];
+      bf16x8 ql[QL > 0 ? QL : 1];
+      if constexpr (QL > 0 && NEXT) {
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp) vf[rb][sp] = ring_v[j & (NB - 1)][(rb * 2 + sp) * 64 + lane];
-      __builtin_amdgcn_sched_barrier(0);   // keep the V reads up here so their latency hides under phase 1
+        for (int ks = 0; ks < QL; ++ks) ql[ks] = q_lds[(w * QL + ks) * 64 + lane];
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep these reads up here so their latency hides under phase 1
       // phase 1: S(j+1)^T on the matrix cores, exponentials of S(j)^T on the VALU
       float mc[QB], ps[QB];
       bf16x8 pb[2][QB];
@@ -275,41 +297,60 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
           for (int x = 0; x < 16; ++x) s_nxt[qb][x] = 0.f;
         }
       }
+      constexpr int PER = 16 / KS;   // logits per (ks, qb) slot: 2 for d = 128, 4 for d = 64
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
+        if (ks == KS / 2) {
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) vf[rb][1] = ring_v[j & (NB - 1)][(rb * 2 + 1) * 64 + lane];
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-          if constexpr (NEXT) s_nxt[qb] = mfma32(kf[ks], qf[qb][ks], s_nxt[qb]);
+          if constexpr (NEXT) s_nxt[qb] = mfma32(kf[ks], (QL > 0 && ks < QL) ? ql[ks] : qf[qb][ks], s_nxt[qb]);
           // a slice of the exponentials rides along with every matrix instruction
-          constexpr int PER = 16 / KS;   // logits per (ks, qb) slot: 2 for d = 128, 4 for d = 64
 #pragma unroll
           for (int i = 0; i < PER; ++i) {
             const int x = ks * PER + i;
             s_cur[qb][x] = fast_exp2(__builtin_fmaf(s_cur[qb][x], c, -mc[qb]));
-            ps[qb] += s_cur[qb][x];
+          }
+        }
+        // once a half of the block is exponentiated it is rounded to bf16 (the B operand of P V) and its
+        // row-sum contribution is taken from the rounded values, two per v_dot2, so that numerator and
+        // denominator see the same weights
+        if (ks == KS / 2 - 1 || ks == KS - 1) {
+          const int sp = ks == KS - 1;
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) {
+            f32x8 p8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p8[i] = s_cur[qb][8 * sp + i];
+            pb[sp][qb] = __builtin_convertvector(p8, bf16x8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+              const bf16x2 pr = {pb[sp][qb][2 * i], pb[sp][qb][2 * i + 1]};
+              const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+              ps[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, ps[qb], false);
+            }
           }
         }
       }
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        lsum[qb] += ps[qb];
+      for (int qb = 0; qb < QB; ++qb) lsum[qb] += ps[qb];
+      // phase 2: O^T += V(j)^T P(j)^T on the matrix cores; K(j+2) fragments come in from LDS (half after
+      // each half of the products) and the column maxima of S(j+1)^T are formed on the VALU
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
-          f32x8 p8;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) p8[i] = s_cur[qb][8 * sp + i];
-          pb[sp][qb] = __builtin_convertvector(p8, bf16x8);
-        }
-      }
-      // phase 2: O^T += V(j)^T P(j)^T on the matrix cores; K(j+2) fragments come in from LDS and the
-      // column maxima of S(j+1)^T are formed on the VALU
-      if constexpr (NEXT2) load_k(j + 2);
-#pragma unroll
-      for (int sp = 0; sp < 2; ++sp)
+      for (int sp = 0; sp < 2; ++sp) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) o[qb][rb] = mfma32(vf[rb][sp], pb[sp][qb], o[qb][rb]);
+        if constexpr (NEXT2) {
+#pragma unroll
+          for (int ks = sp * (KS / 2); ks < (sp + 1) * (KS / 2); ++ks)
+            kf[ks] = ring_k[(j + 2) & (NB - 1)][ks * 64 + lane];
+        }
+      }
       if constexpr (NEXT) {
         if constexpr (MASK) mask_tail(s_nxt, j + 1);
         float mx[QB];
@@ -340,6 +381,20 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
       }
       ring_barrier(Fa{});
     }
+    // express the accumulators against the exact c_i (Eq. "hybrid": the largest softmax weight is 1)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float alpha = fast_exp2((m[qb] - m_true[qb]) * c);
+      lsum[qb] *= alpha;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) o[qb][rb][x] *= alpha;
+    }
+  }
+  if constexpr (QL > 0) {   // the epilogue wants all Q fragments in registers again
+#pragma unroll
+    for (int ks = 0; ks < QL; ++ks) qf[0][ks] = q_lds[(w * QL + ks) * 64 + lane];
   }
   // epilogue operands stay in global memory (L2-resident: 64 KiB of weights per head, 64 KiB of state
   // per (batch, head)); staging them through the idle ring was measured slower than reading them in place

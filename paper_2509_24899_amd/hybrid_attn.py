@@ -14,7 +14,7 @@ from typing import Optional
 import torch  # imported before the library so that both share torch's HIP runtime
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "lib", "libhybridattn.so")
+LIB_PATH = os.environ.get("HYBRID_ATTN_LIB", os.path.join(_HERE, "lib", "libhybridattn.so"))
 
 HA_OK, HA_ERR_NULL, HA_ERR_SHAPE, HA_ERR_UNSUPPORTED, HA_ERR_ALIGN, HA_ERR_WORKSPACE, HA_ERR_DEVICE = range(7)
 HA_BF16, HA_F32 = 0, 1
