@@ -34,7 +34,7 @@ template <int D, int HD, int F, bool F32>
 static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane, int qi,
                                                       const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum,
                                                       const bf16x8 *w1f, const bf16x8 *w2f, const bf16x8 *sth,
-                                                      const bf16x8 *stl) {
+                                                      const bf16x8 *stl, char *stage, int q_first) {
   constexpr int RB = D / 32, FB = F / 32;
   const int g = lane >> 5;
   float den = xhalf_sum(lsum);
@@ -77,20 +77,40 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
     }
   }
   const float inv = 1.0f / den;
-  if (qi < a.N) {
-    const int64_t ooff = base + (int64_t)qi * a.sn;
+  (void)qi;
+  // Store.  The C layout has one query per lane with 4 consecutive channels per register group, i.e. 8-byte
+  // pieces 256 bytes apart across lanes.  The tile goes through this wave's LDS staging area instead
+  // ([32 queries][channels of one pass], rows padded by 16 bytes) and leaves as 16-byte pieces with
+  // consecutive lanes on consecutive addresses of a row.
+  constexpr int PASSES = F32 ? 2 : 1;               // fp32 output is staged half a row at a time
+  constexpr int DP = D / PASSES, ESZ = F32 ? 4 : 2;
+  constexpr int PITCH = DP * ESZ + 16;              // bytes
+  constexpr int CPR = DP * ESZ / 16;                // 16-byte pieces per staged row
+  const int r = lane & 31;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+  for (int pass = 0; pass < PASSES; ++pass) {
+#pragma unroll
+    for (int rbl = 0; rbl < RB / PASSES; ++rbl) {
+      const int rb = pass * (RB / PASSES) + rbl;
 #pragma unroll
       for (int x4 = 0; x4 < 4; ++x4) {
-        const int dcol = 32 * rb + 8 * x4 + 4 * g;
+        const int dloc = 32 * rbl + 8 * x4 + 4 * g;
         f32x4 y = {o[rb][4 * x4] * inv, o[rb][4 * x4 + 1] * inv, o[rb][4 * x4 + 2] * inv, o[rb][4 * x4 + 3] * inv};
-        if constexpr (F32) {
-          *reinterpret_cast<f32x4 *>(static_cast<float *>(a.out) + ooff + dcol) = y;
-        } else {
-          *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.out) + ooff + dcol) = __builtin_convertvector(y, bf16x4);
-        }
+        if constexpr (F32) *reinterpret_cast<f32x4 *>(stage + r * PITCH + dloc * 4) = y;
+        else *reinterpret_cast<bf16x4 *>(stage + r * PITCH + dloc * 2) = __builtin_convertvector(y, bf16x4);
       }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = lane; i < 32 * CPR; i += 64) {
+      const int row = i / CPR, ch = i % CPR;
+      if (q_first + row < a.N) {
+        const f32x4 piece = *reinterpret_cast<const f32x4 *>(stage + row * PITCH + ch * 16);
+        char *dst = static_cast<char *>(a.out) + (base + (int64_t)(q_first + row) * a.sn + pass * DP) * ESZ + ch * 16;
+        *reinterpret_cast<f32x4 *>(dst) = piece;
+      }
+    }
+    if (PASSES > 1) __syncthreads();
   }
 }
 
@@ -114,8 +134,11 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   constexpr int FRAG = D * 4;                 // bf16x8 per 32-key block per tensor
   constexpr int LEAD = NB - G, QT = 32 * QB * NW;
   constexpr int WCH = FRAG / 64;              // 1 KiB wave-chunks per block per tensor
-  __shared__ bf16x8 ring_k[NB][FRAG];
-  __shared__ bf16x8 ring_v[NB][FRAG];
+  __shared__ bf16x8 ring[2 * NB * FRAG];
+  // after the loop each wave stages its 32-query output tile in its share of the ring
+  static_assert(32 * ((D / (F32 ? 2 : 1)) * (F32 ? 4 : 2) + 16) <= 2 * NB * FRAG * 16 / NW, "staging tile too large");
+  bf16x8 (*ring_k)[FRAG] = reinterpret_cast<bf16x8 (*)[FRAG]>(&ring[0]);
+  bf16x8 (*ring_v)[FRAG] = reinterpret_cast<bf16x8 (*)[FRAG]>(&ring[NB * FRAG]);
   // The first QL of the KS Q fragments of every wave live in LDS instead of registers: with two waves per
   // SIMD the loop is a few registers over budget otherwise, and a register spilled to scratch would make
   // every step wait on the vector-memory counter, i.e. on the direct-to-LDS loads just issued.
@@ -405,7 +428,8 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   const bf16x8 *stl = a.st_lo + (int64_t)bh * NST;
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb)
-    query_epilogue<D, HD, F, F32>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb], w1f, w2f, sth, stl);
+    query_epilogue<D, HD, F, F32>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb], w1f, w2f, sth, stl,
+                                  reinterpret_cast<char *>(&ring[0]) + w * (2 * NB * FRAG * 16 / NW), q0 + 32 * qb);
 }
 
 hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
