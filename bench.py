@@ -44,12 +44,14 @@ def cpu_baseline(w, heads=12):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="wan_480p_81f", choices=["tiny", "wan_480p_81f", "wan_480p_161f", "wan_720p_81f_cfg"])
     ap.add_argument("--rate", type=int, default=None, help="override the hybrid rate R (0 = pure linear, 1 = full softmax)")
     ap.add_argument("--block-size", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the matrix-core probe (sustained MFMA-only rate of this device, zero and random operands)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference kernel for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -111,7 +113,25 @@ def main():
     ha.hybrid_attn_profile_enable(0)
     assert torch.isfinite(out.float()).all().item(), "non-finite output"
 
+    # sustained matrix-core rate of this device next to the published peak: a kernel of nothing but MFMA
+    # instructions, run for a few hundred ms so that power management settles; operand values matter
+    # (zero operands keep the clock at its ceiling, random ones do not)
+    mfma_probe = None
+    if not args.no_mfma_probe and w.n_softmax > 0:
+        sink = torch.empty(torch.cuda.get_device_properties(0).multi_processor_count * 512, device=dev)
+        mfma_probe = {}
+        for name, rnd in (("zero_operands", False), ("random_operands", True)):
+            ha.hybrid_attn_mfma_probe(rnd, 20000, 20, sink)          # settle
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = ha.hybrid_attn_mfma_probe(rnd, 20000, 60, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            mfma_probe[name + "_tflops"] = fl * 60 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        del sink
+
     ms_per_step = elapsed * 1e3 / args.steps
+    fwd_sorted = sorted(r[4] for r in stage_ms)
     flops = W.algorithmic_flops(w)
     mean = [sum(r[i] for r in stage_ms) / len(stage_ms) for i in range(5)]
     n_s, n_l = w.n_softmax, w.n_linear
@@ -137,6 +157,8 @@ def main():
             roofline["traffic"] = t["read_bytes"] + t["written_bytes"]
             roofline["traffic_detail"] = t
 
+    if mfma_probe and roofline["bound"] == "mfma":
+        roofline["frac_of_sustained_mfma_rate"] = roofline["achieved"] / mfma_probe["random_operands_tflops"]
     rec = {
         "metric": "hybrid-attention fwd tokens/s", "value": w.B * w.N / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -146,9 +168,12 @@ def main():
                    "feature_map": f"{w.d}->{w.d_hidden}->{w.d_feat}, P={w.poly_degree}"},
         "tflops": flops / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "forward_ms_median": fwd_sorted[len(fwd_sorted) // 2], "forward_ms_min": fwd_sorted[0],
         "stage_ms": {"compact": mean[0], "state": mean[1], "wprep_q": mean[2], "query": mean[3], "forward": mean[4]},
         "roofline": roofline,
     }
+    if mfma_probe:
+        rec["mfma_probe"] = mfma_probe
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(rec), flush=True)

@@ -127,6 +127,17 @@ ha_status hybrid_attn_profile_enable(int n_records);
 ha_status hybrid_attn_profile_read(int index, float ms[5]);
 int hybrid_attn_profile_count(void);   /* forwards recorded since the last enable */
 
+/* Measurement aid for benchmarks (no part of the method): enqueue `launches` launches of a kernel that
+ * issues nothing but dense bf16 32x32x16 matrix instructions on register operands, one 512-thread
+ * workgroup per compute unit of the current device, 16 * iters instructions per wave.  Timed by the
+ * caller, it gives the matrix-core rate the device sustains next to its published peak; the rate
+ * depends on the operand values through power and clock, hence random_operands: 0 = all-zero
+ * operands, non-zero = pseudo-random values in [-1, 1).  sink: device, 16-byte aligned, at least
+ * 2 KiB per compute unit (HA_ERR_WORKSPACE otherwise), overwritten.  *flops_per_launch (host)
+ * receives the flop count of one launch.  Returns once everything is enqueued on `hip_stream`. */
+ha_status hybrid_attn_mfma_probe(int random_operands, int iters, int launches, void *sink, size_t sink_bytes,
+                                 double *flops_per_launch, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *hybrid_attn_status_string(ha_status s);
 

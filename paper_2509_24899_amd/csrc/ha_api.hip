@@ -234,6 +234,26 @@ ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const voi
   return HA_OK;
 }
 
+ha_status hybrid_attn_mfma_probe(int random_operands, int iters, int launches, void *sink, size_t sink_bytes,
+                                 double *flops_per_launch, void *hip_stream) {
+  if (!sink || !flops_per_launch) return HA_ERR_NULL;
+  if (iters < 1 || launches < 1 || iters > (1 << 24) || launches > (1 << 16)) return HA_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(sink) & 15u) return HA_ERR_ALIGN;
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return ha::device_error(e);
+  if (sink_bytes < (size_t)cus * 512 * sizeof(float)) return HA_ERR_WORKSPACE;
+  // per wave and iteration: 16 instructions of 2 * 32 * 32 * 16 flops
+  *flops_per_launch = (double)cus * 8.0 * (double)iters * 16.0 * 32768.0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  for (int l = 0; l < launches; ++l) {
+    e = ha::launch_mfma_probe(static_cast<float *>(sink), cus, iters, random_operands != 0, st);
+    if (e != hipSuccess) return ha::device_error(e);
+  }
+  return HA_OK;
+}
+
 const char *hybrid_attn_status_string(ha_status s) {
   switch (s) {
     case HA_OK: return "ok";

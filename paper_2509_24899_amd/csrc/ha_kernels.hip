@@ -333,4 +333,50 @@ hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Measurement aid, not a step of the method: nothing but dense bf16 32x32x16 matrix instructions on
+// register operands (four independent accumulators per wave, eight waves per workgroup, one workgroup
+// per compute unit).  Timed by a caller, it gives the matrix-core rate this device sustains, which
+// depends on the operand values: all-zero operands toggle few wires and keep the clock at its
+// ceiling, pseudo-random ones draw more power and the clock drops.
+__global__ __launch_bounds__(512, 1) void mfma_probe_kernel(float *sink, int iters, int random_operands) {
+  const unsigned tid = threadIdx.x + blockIdx.x * 512u;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      // integer hash -> value in [-1, 1) with a full 8-bit bf16 significand
+      unsigned ha_ = (tid * 8u + i * 64u + t) * 2654435761u, hb_ = ha_ ^ 0x9e3779b9u;
+      ha_ ^= ha_ >> 15; ha_ *= 2246822519u; ha_ ^= ha_ >> 13;
+      hb_ ^= hb_ >> 15; hb_ *= 3266489917u; hb_ ^= hb_ >> 13;
+      const float fa = random_operands ? (float)(int)(ha_ >> 16) * (1.0f / 32768.0f) - 1.0f : 0.0f;
+      const float fb = random_operands ? (float)(int)(hb_ >> 16) * (1.0f / 32768.0f) - 1.0f : 0.0f;
+      a[i][t] = static_cast<__bf16>(fa);
+      b[i][t] = static_cast<__bf16>(fb);
+    }
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = mfma32(a[(i + u) & 3], b[i], acc[i]);
+  }
+  float r = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) r += acc[i][v];
+  sink[tid] = r;
+}
+
+hipError_t launch_mfma_probe(float *sink, int workgroups, int iters, int random_operands, hipStream_t st) {
+  mfma_probe_kernel<<<workgroups, 512, 0, st>>>(sink, iters, random_operands);
+  return hipGetLastError();
+}
+
 }  // namespace ha

@@ -75,6 +75,9 @@ def _lib():
         lib.hybrid_attn_profile_read.restype = ctypes.c_int
         lib.hybrid_attn_profile_count.argtypes = []
         lib.hybrid_attn_profile_count.restype = ctypes.c_int
+        lib.hybrid_attn_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                               ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+        lib.hybrid_attn_mfma_probe.restype = ctypes.c_int
         lib.hybrid_attn_abi_version.argtypes = []
         lib.hybrid_attn_abi_version.restype = ctypes.c_int
         _LIB = lib
@@ -160,6 +163,19 @@ def hybrid_attn_profile_enable(n_records: int) -> None:
 
 def hybrid_attn_profile_count() -> int:
     return _lib().hybrid_attn_profile_count()
+
+
+
+def hybrid_attn_mfma_probe(random_operands: bool, iters: int, launches: int, sink: torch.Tensor) -> float:
+    """Enqueue the matrix-core probe on the current stream (see the header); returns the flops of one
+    launch.  `sink`: device tensor of at least 2 KiB per compute unit."""
+    flops = ctypes.c_double(0.0)
+    st = _lib().hybrid_attn_mfma_probe(int(bool(random_operands)), iters, launches, sink.data_ptr(),
+                                       sink.numel() * sink.element_size(), ctypes.byref(flops),
+                                       torch.cuda.current_stream(sink.device).cuda_stream)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_mfma_probe")
+    return flops.value
 
 
 def hybrid_attn_profile_read(index: int):

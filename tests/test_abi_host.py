@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(lib):
     text = open(os.path.join(ROOT, "include", "hybrid_attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(hybrid_attn_\w+)\s*\(", text)
-    assert len(set(names)) == 10
+    assert len(set(names)) == 11
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
     assert ha.hybrid_attn_abi_version() == 1
@@ -145,3 +145,13 @@ def test_flop_and_byte_counts():
     assert abs(W.algorithmic_flops(W.TINY) / 1e9 - 0.223) < 1e-3
     assert abs(W.algorithmic_flops(W.with_rate(W.WAN_480P_81F, 0)) / 1e9 - 77.4) < 0.1
     assert W.WAN_480P_81F.n_softmax == 8190 and W.WAN_480P_161F.n_softmax == 7995
+
+
+def test_mfma_probe_rejects_bad_arguments_on_the_host(lib):
+    flops = ctypes.c_double(0.0)
+    f = lib.hybrid_attn_mfma_probe
+    assert f(1, 100, 1, None, 1 << 20, ctypes.byref(flops), None) == ha.HA_ERR_NULL
+    assert f(1, 100, 1, FAKE, 1 << 20, None, None) == ha.HA_ERR_NULL
+    assert f(1, 0, 1, FAKE, 1 << 20, ctypes.byref(flops), None) == ha.HA_ERR_SHAPE
+    assert f(1, 100, 0, FAKE, 1 << 20, ctypes.byref(flops), None) == ha.HA_ERR_SHAPE
+    assert f(1, 100, 1, FAKE + 4, 1 << 20, ctypes.byref(flops), None) == ha.HA_ERR_ALIGN

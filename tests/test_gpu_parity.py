@@ -258,3 +258,20 @@ def test_config5_stack_layer_sampled(layer):
         ma, rl = metrics(y, ref)
         record(f"cfg5_layer{layer}_R{w.R}_b{b}h{h}", ma, rl)
         assert ma <= MAX_ABS and rl <= REL_L2
+
+
+def test_mfma_probe_runs_and_reports_its_flops():
+    """The matrix-core probe (a measurement aid, not part of the method) enqueues, finishes, and its
+    flop count is 16 instructions x 32768 flops x 8 waves x compute units per iteration; its result
+    with zero operands is exactly zero, with random operands finite and non-zero."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.full((cus * 512,), float("nan"), device="cuda", dtype=torch.float32)
+    flops = ha.hybrid_attn_mfma_probe(False, 50, 2, sink)
+    torch.cuda.synchronize()
+    assert flops == cus * 8 * 50 * 16 * 32768
+    assert bool((sink == 0).all())
+    ha.hybrid_attn_mfma_probe(True, 50, 1, sink)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all()) and bool((sink != 0).any())
+    with pytest.raises(ha.HybridAttnError):
+        ha.hybrid_attn_mfma_probe(True, 50, 1, sink[:128])
