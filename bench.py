@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--rate", type=int, default=None, help="override the hybrid rate R (0 = pure linear, 1 = full softmax)")
     ap.add_argument("--block-size", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="all-zero q, k, v: NOT a benchmark, a power / clock experiment (same instruction stream, idle data wires)")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the matrix-core probe (sustained MFMA-only rate of this device, zero and random operands)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -78,6 +80,8 @@ def main():
     gen = torch.Generator(device=dev).manual_seed(w.seed)
     s = w.d ** -0.5
     q, k, v = ((torch.randn(w.B, w.H, w.N, w.d, generator=gen, device=dev) * s).to(dt) for _ in range(3))
+    if args.zero_inputs:
+        q.zero_(), k.zero_(), v.zero_()
 
     def dmap():
         return ha.FeatureMap((torch.randn(w.H, w.d_hidden, w.d, generator=gen, device=dev) * w.d ** -0.5).to(dt),
@@ -162,7 +166,8 @@ def main():
     rec = {
         "metric": "hybrid-attention fwd tokens/s", "value": w.B * w.N / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic" if not args.zero_inputs else "all-zero q, k, v (clock experiment, not a benchmark)",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype,
                    "hybrid_rate_R": w.R, "r": (1.0 / w.R if w.R else 0.0), "block_size": w.block_size,
                    "feature_map": f"{w.d}->{w.d_hidden}->{w.d_feat}, P={w.poly_degree}"},
