@@ -41,6 +41,67 @@ def cpu_baseline(w, heads=12):
                       f"pairs: {t_sample:.1f} s, scaled to all pairs: {t_full:.1f} s per forward"}
 
 
+def rate_selection_mode(args, w, ha, W, torch, q, k, v, fq, fk, out):
+    """Sec. 3.3 on measured costs: c_R = time of one layer of this shape at rate R (equal for all layers,
+    the shape being equal), e_{l,R} synthetic (the real ones come out of distillation, which needs the
+    model's weights): e_{l,1} = 0 and e_{l,R} = a_l (1 - 1/R)^2 with a_l log-normal, seed 0."""
+    import numpy as np
+    rates, n_layers = (1, 2, 4, 8), 30
+    dev = q.device
+
+    def run_layer(R, ws):
+        ha.hybrid_attn_forward(q, k, v, None if R == 1 else fq, None if R == 1 else fk, R, w.block_size, w.scale,
+                               out=out, workspace=ws)
+
+    ws_bytes = max(ha.hybrid_attn_workspace_bytes(ha.make_problem(q, R, w.block_size, w.scale),
+                                                  None if R == 1 else fq, None if R == 1 else fk) for R in rates)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    cost_ms = []
+    for R in rates:
+        for _ in range(2):
+            run_layer(R, ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            run_layer(R, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        cost_ms.append(e0.elapsed_time(e1) / args.steps)
+    rng = np.random.default_rng(0)
+    a = rng.lognormal(0.0, 1.0, size=n_layers)
+    err = [[float(a[l] * (1.0 - 1.0 / R) ** 2) for R in rates] for l in range(n_layers)]
+    cost = [list(cost_ms) for _ in range(n_layers)]
+    budget = args.select_rates * n_layers * cost_ms[0]
+    t0 = time.perf_counter()
+    sel = ha.hybrid_attn_select_rates(cost, err, budget)
+    solve_ms = (time.perf_counter() - t0) * 1e3
+    rec = {"metric": "hybrid-attention 30-layer stack with selected block rates", "unit": "ms", "n_gpus": 1,
+           "higher_is_better": False, "data": "synthetic", "dtype": "bf16",
+           "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "layers": n_layers,
+                      "candidate_rates": list(rates), "beta": args.select_rates},
+           "layer_cost_ms": dict(zip(map(str, rates), cost_ms)), "budget_ms": budget, "solve_ms": solve_ms}
+    if sel is None:
+        rec.update({"value": None, "note": "no assignment fits the budget"})
+        print(json.dumps(rec), flush=True)
+        return
+    choice, total_cost, total_err = sel
+    layer_rates = [rates[c] for c in choice]
+    for R in layer_rates[:3]:
+        run_layer(R, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for R in layer_rates:
+        run_layer(R, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    homog = {str(R): {"cost_ms": n_layers * cost_ms[i], "error": sum(e[i] for e in err)} for i, R in enumerate(rates)}
+    rec.update({"value": e0.elapsed_time(e1), "predicted_ms": total_cost, "selected_rates": layer_rates,
+                "selected_error": total_err, "homogeneous": homog,
+                "rate_histogram": {str(R): layer_rates.count(R) for R in rates}})
+    print(json.dumps(rec), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +111,10 @@ def main():
     ap.add_argument("--rate", type=int, default=None, help="override the hybrid rate R (0 = pure linear, 1 = full softmax)")
     ap.add_argument("--block-size", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
+                    help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
+                         "synthetic per-layer errors, solve the knapsack for a budget of BETA x the all-softmax stack, "
+                         "run the selected 30-layer stack and print one JSON line about it instead of the headline line")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="all-zero q, k, v: NOT a benchmark, a power / clock experiment (same instruction stream, idle data wires)")
     ap.add_argument("--no-mfma-probe", action="store_true",
@@ -97,6 +162,9 @@ def main():
     def step():
         ha.hybrid_attn_forward(q, k, v, fq, fk, w.R, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
 
+    if args.select_rates is not None:
+        rate_selection_mode(args, w, ha, W, torch, q, k, v, fq if fq else dmap(), fk if fk else dmap(), out)
+        return
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)

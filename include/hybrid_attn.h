@@ -40,7 +40,8 @@ typedef enum {
   HA_ERR_UNSUPPORTED = 3, /* a valid problem this build has no kernel for */
   HA_ERR_ALIGN = 4,       /* a device pointer or stride breaks the 16-byte rule */
   HA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than hybrid_attn_workspace_bytes() */
-  HA_ERR_DEVICE = 6       /* a HIP call failed; see hybrid_attn_last_device_error() */
+  HA_ERR_DEVICE = 6,      /* a HIP call failed; see hybrid_attn_last_device_error() */
+  HA_ERR_INFEASIBLE = 7   /* hybrid_attn_select_rates: no assignment fits the budget */
 } ha_status;
 
 typedef enum { HA_BF16 = 0, HA_F32 = 1 } ha_dtype;
@@ -137,6 +138,19 @@ int hybrid_attn_profile_count(void);   /* forwards recorded since the last enabl
  * receives the flop count of one launch.  Returns once everything is enqueued on `hip_stream`. */
 ha_status hybrid_attn_mfma_probe(int random_operands, int iters, int launches, void *sink, size_t sink_bytes,
                                  double *flops_per_launch, void *hip_stream);
+
+/* Block-rate selection (Sec. 3.3, "Heterogeneous Block-Rate Optimization"; host memory only, no GPU
+ * involved).  A model has n_blocks attention blocks and n_rates candidate hybrid rates; cost[i * n_rates + r]
+ * and error[i * n_rates + r] (both >= 0, finite) are the pre-computed cost c_ir (flops or measured
+ * latency) and error e_ir of giving block i candidate r.  Writes to choice[i] the candidate of block i in
+ * the assignment that minimises the summed error subject to summed cost <= budget (the multiple-choice
+ * knapsack of that section, solved exactly), and its sums to *total_cost / *total_error, formed in
+ * block order.  Among assignments of equal error the cheapest is returned, among those the
+ * lexicographically smallest choice vector.  HA_ERR_INFEASIBLE when even the cheapest assignment exceeds
+ * the budget; HA_ERR_SHAPE for sizes < 1 or negative / non-finite entries; HA_ERR_UNSUPPORTED when the
+ * search would need more than 2^22 undominated (cost, error) states. */
+ha_status hybrid_attn_select_rates(int n_blocks, int n_rates, const double *cost, const double *error,
+                                   double budget, int *choice, double *total_cost, double *total_error);
 
 /* Static, NUL-terminated description of a status code. */
 const char *hybrid_attn_status_string(ha_status s);

@@ -263,6 +263,7 @@ const char *hybrid_attn_status_string(ha_status s) {
     case HA_ERR_ALIGN: return "pointer or stride breaks the 16-byte alignment rule";
     case HA_ERR_WORKSPACE: return "workspace missing or too small";
     case HA_ERR_DEVICE: return "a HIP call failed (see hybrid_attn_last_device_error)";
+    case HA_ERR_INFEASIBLE: return "no assignment of rates fits the budget";
   }
   return "unknown status";
 }

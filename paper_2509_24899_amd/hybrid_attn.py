@@ -16,7 +16,7 @@ import torch  # imported before the library so that both share torch's HIP runti
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("HYBRID_ATTN_LIB", os.path.join(_HERE, "lib", "libhybridattn.so"))
 
-HA_OK, HA_ERR_NULL, HA_ERR_SHAPE, HA_ERR_UNSUPPORTED, HA_ERR_ALIGN, HA_ERR_WORKSPACE, HA_ERR_DEVICE = range(7)
+HA_OK, HA_ERR_NULL, HA_ERR_SHAPE, HA_ERR_UNSUPPORTED, HA_ERR_ALIGN, HA_ERR_WORKSPACE, HA_ERR_DEVICE, HA_ERR_INFEASIBLE = range(8)
 HA_BF16, HA_F32 = 0, 1
 HA_ACT_SOFTMAX, HA_ACT_EXP, HA_ACT_RELU = 0, 1, 2
 
@@ -78,6 +78,10 @@ def _lib():
         lib.hybrid_attn_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
                                                ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
         lib.hybrid_attn_mfma_probe.restype = ctypes.c_int
+        dp = ctypes.POINTER(ctypes.c_double)
+        lib.hybrid_attn_select_rates.argtypes = [ctypes.c_int, ctypes.c_int, dp, dp, ctypes.c_double,
+                                                 ctypes.POINTER(ctypes.c_int), dp, dp]
+        lib.hybrid_attn_select_rates.restype = ctypes.c_int
         lib.hybrid_attn_abi_version.argtypes = []
         lib.hybrid_attn_abi_version.restype = ctypes.c_int
         _LIB = lib
@@ -176,6 +180,27 @@ def hybrid_attn_mfma_probe(random_operands: bool, iters: int, launches: int, sin
     if st != HA_OK:
         raise HybridAttnError(st, "hybrid_attn_mfma_probe")
     return flops.value
+
+
+
+def hybrid_attn_select_rates(cost, error, budget: float):
+    """Block-rate selection (Sec. 3.3): cost[i][r], error[i][r] per block i and candidate r (host
+    numbers); returns (choice per block, total cost, total error) of the minimum-error assignment
+    within the budget, or None when nothing fits."""
+    n_blocks, n_rates = len(cost), len(cost[0])
+    if any(len(c) != n_rates for c in cost) or len(error) != n_blocks or any(len(e) != n_rates for e in error):
+        raise ValueError("cost and error must be n_blocks x n_rates tables of one shape")
+    arr = ctypes.c_double * (n_blocks * n_rates)
+    c = arr(*[float(x) for row in cost for x in row])
+    e = arr(*[float(x) for row in error for x in row])
+    choice = (ctypes.c_int * n_blocks)()
+    tc, te = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    st = _lib().hybrid_attn_select_rates(n_blocks, n_rates, c, e, float(budget), choice, ctypes.byref(tc), ctypes.byref(te))
+    if st == HA_ERR_INFEASIBLE:
+        return None
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_select_rates")
+    return tuple(choice), tc.value, te.value
 
 
 def hybrid_attn_profile_read(index: int):
