@@ -34,8 +34,9 @@ All arithmetic is float64; nothing is rounded inside.  Inputs are whatever the c
 Pins (tests/test_oracle_pins.py): R=1 against library softmax attention; the feature map against
 torch's grouped conv1d; closed forms for constant feature maps and for the two-token case; the
 explicit N x N loop form `hybrid_attn_dense_loops`; convexity / permutation / row-independence
-invariants; planted-mistake variants that the pins must reject.  No function here is
-"parity unpinned".
+invariants; planted-mistake variants that the pins must reject.  `value_distill_loss` is pinned
+in tests/test_value_distill_oracle.py (zero at R = 1, a closed form, the loop form, scaling).  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -173,6 +174,21 @@ def hybrid_attn(q, k, v, phi_q, phi_k, R, scale, rows=None):
         for h in range(H):
             y[b, h] = hybrid_attn_head(q[b, h], k[b, h], v[b, h], phi_q, phi_k, h, R, scale, rows)
     return y
+
+
+def value_distill_loss(q, k, v, phi_q, phi_k, R, scale):
+    """Value-distillation objective of Sec. 3.3 (Eq. "vd_loss"): || y - y_hat ||_1 with y the softmax
+    attention of Eq. "softmax" (the teacher: every token a softmax token) and y_hat the hybrid
+    attention of Eq. "hybrid" at rate R (the student), summed over every batch entry, head, token
+    and channel of q, k, v [B, H, N, d].  (Alg. 1 averages this over the samples of a batch: divide
+    by B.)  Returns a float."""
+    y = hybrid_attn(q, k, v, None, None, 1, scale)
+    y_hat = hybrid_attn(q, k, v, phi_q, phi_k, R, scale)
+    total = 0.0
+    for b in range(y.shape[0]):
+        for h in range(y.shape[1]):
+            total += float(np.abs(y[b, h] - y_hat[b, h]).sum())
+    return total
 
 
 def hybrid_attn_dense_loops(q, k, v, phi_q, phi_k, head, R, scale):
