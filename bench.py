@@ -67,9 +67,37 @@ def rate_selection_mode(args, w, ha, W, torch, q, k, v, fq, fk, out):
         e1.record()
         torch.cuda.synchronize()
         cost_ms.append(e0.elapsed_time(e1) / args.steps)
-    rng = np.random.default_rng(0)
-    a = rng.lognormal(0.0, 1.0, size=n_layers)
-    err = [[float(a[l] * (1.0 - 1.0 / R) ** 2) for R in rates] for l in range(n_layers)]
+    if args.measured_errors:
+        # e_{l,R} = || y - y_hat ||_1 / numel with the teacher output cached once (the inputs are shared) and
+        # layer l's own feature maps (untrained, seed 1000 + l): the pipeline of Alg. 1's loss line, not its values
+        s_ = w.d ** -0.5
+        dt = q.dtype
+        y_t = torch.empty_like(q)
+        y_s = torch.empty_like(q)
+        ha.hybrid_attn_forward(q, k, v, None, None, 1, w.block_size, w.scale, out=y_t, workspace=ws)
+        ws_vd = None
+        err, loss_ms = [], []
+        for l in range(n_layers):
+            g = torch.Generator(device=dev).manual_seed(1000 + l)
+            maps = [ha.FeatureMap((torch.randn(w.H, w.d_hidden, w.d, generator=g, device=dev) * s_).to(dt),
+                                  torch.randn(w.H, w.d_hidden, generator=g, device=dev) * 0.1,
+                                  (torch.randn(w.H, w.d_feat, w.d_hidden, generator=g, device=dev) * w.d_hidden ** -0.5).to(dt),
+                                  torch.randn(w.H, w.d_feat, generator=g, device=dev) * 0.1, w.poly_degree) for _ in range(2)]
+            row = [0.0]
+            for R in rates[1:]:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                loss, _, _ = ha.hybrid_attn_value_distill_loss(q, k, v, maps[0], maps[1], R, w.block_size, w.scale,
+                                                               y_teacher=y_t, teacher_is_cached=True, y_student=y_s)
+                e1.record()
+                torch.cuda.synchronize()
+                row.append(float(loss[0].item()) / q.numel())
+                loss_ms.append(e0.elapsed_time(e1))
+            err.append(row)
+    else:
+        rng = np.random.default_rng(0)
+        a = rng.lognormal(0.0, 1.0, size=n_layers)
+        err = [[float(a[l] * (1.0 - 1.0 / R) ** 2) for R in rates] for l in range(n_layers)]
     cost = [list(cost_ms) for _ in range(n_layers)]
     budget = args.select_rates * n_layers * cost_ms[0]
     t0 = time.perf_counter()
@@ -79,7 +107,11 @@ def rate_selection_mode(args, w, ha, W, torch, q, k, v, fq, fk, out):
            "higher_is_better": False, "data": "synthetic", "dtype": "bf16",
            "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "layers": n_layers,
                       "candidate_rates": list(rates), "beta": args.select_rates},
-           "layer_cost_ms": dict(zip(map(str, rates), cost_ms)), "budget_ms": budget, "solve_ms": solve_ms}
+           "layer_cost_ms": dict(zip(map(str, rates), cost_ms)), "budget_ms": budget, "solve_ms": solve_ms,
+           "errors": "value-distillation loss per element, untrained per-layer feature maps" if args.measured_errors
+                     else "synthetic: a_l (1 - 1/R)^2, a_l log-normal, seed 0"}
+    if args.measured_errors:
+        rec["loss_eval_ms_mean"] = sum(loss_ms) / len(loss_ms)
     if sel is None:
         rec.update({"value": None, "note": "no assignment fits the budget"})
         print(json.dumps(rec), flush=True)
@@ -115,6 +147,9 @@ def main():
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
                          "synthetic per-layer errors, solve the knapsack for a budget of BETA x the all-softmax stack, "
                          "run the selected 30-layer stack and print one JSON line about it instead of the headline line")
+    ap.add_argument("--measured-errors", action="store_true",
+                    help="with --select-rates: take e_{l,R} from the value-distillation loss (Eq. vd_loss) of layer l's own "
+                         "seeded random feature maps on the shared synthetic q, k, v instead of drawing it")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="all-zero q, k, v: NOT a benchmark, a power / clock experiment (same instruction stream, idle data wires)")
     ap.add_argument("--no-mfma-probe", action="store_true",

@@ -139,6 +139,24 @@ int hybrid_attn_profile_count(void);   /* forwards recorded since the last enabl
 ha_status hybrid_attn_mfma_probe(int random_operands, int iters, int launches, void *sink, size_t sink_bytes,
                                  double *flops_per_launch, void *hip_stream);
 
+/* Value-distillation objective (Sec. 3.3, Eq. "vd_loss"; the loss line of Alg. 1 for one sample batch):
+ * || y - y_hat ||_1, y the softmax attention of q, k, v (Eq. "softmax": the forward at rate 1, feature maps
+ * unused) and y_hat the hybrid attention at p->hybrid_rate (Eq. "hybrid"), summed over every batch entry,
+ * head, token and channel (Alg. 1 averages over samples: divide by B).  Enqueues the teacher forward
+ * (skipped when teacher_is_cached != 0: y_teacher then already holds it, as Alg. 1 caches the teacher's
+ * outputs for several student updates), the student forward and a two-stage reduction in a fixed order
+ * (bitwise reproducible).  y_teacher, y_student: device, [B, H, N, d_head] with p's strides and dtype,
+ * distinct buffers, both hold the two outputs afterwards.  loss: device double[1 + B * H]: loss[0] the
+ * total, loss[1 + b * H + h] the share of (batch b, head h).  workspace: device, 256-byte aligned, at
+ * least hybrid_attn_value_distill_workspace_bytes() bytes.  Other arguments and errors as for
+ * hybrid_attn_forward. */
+size_t hybrid_attn_value_distill_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q,
+                                                 const ha_feature_map *phi_k);
+ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, const void *k, const void *v,
+                                         const ha_feature_map *phi_q, const ha_feature_map *phi_k,
+                                         int teacher_is_cached, void *y_teacher, void *y_student, double *loss,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Block-rate selection (Sec. 3.3, "Heterogeneous Block-Rate Optimization"; host memory only, no GPU
  * involved).  A model has n_blocks attention blocks and n_rates candidate hybrid rates; cost[i * n_rates + r]
  * and error[i * n_rates + r] (both >= 0, finite) are the pre-computed cost c_ir (flops or measured

@@ -254,6 +254,52 @@ ha_status hybrid_attn_mfma_probe(int random_operands, int iters, int launches, v
   return HA_OK;
 }
 
+// Workspace of the loss: the larger of the two forwards' workspaces, then the reduction partials.
+static size_t distill_layout(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k,
+                             ha::Plan &teacher, ha::Plan &student, size_t &off_partial) {
+  ha_problem pt = p;
+  pt.hybrid_rate = 1;
+  ha::make_plan(pt, nullptr, nullptr, teacher);
+  ha::make_plan(p, phi_q, phi_k, student);
+  off_partial = ha::align256(teacher.total > student.total ? teacher.total : student.total);
+  return off_partial + ha::align256(ha::l1_partial_bytes(student));
+}
+
+size_t hybrid_attn_value_distill_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q,
+                                                 const ha_feature_map *phi_k) {
+  if (ha::validate(p, phi_q, phi_k) != HA_OK) return 0;
+  ha::Plan t, s;
+  size_t off;
+  return distill_layout(*p, phi_q, phi_k, t, s, off);
+}
+
+ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, const void *k, const void *v,
+                                         const ha_feature_map *phi_q, const ha_feature_map *phi_k,
+                                         int teacher_is_cached, void *y_teacher, void *y_student, double *loss,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+  ha_status s = ha::validate(p, phi_q, phi_k);
+  if (s != HA_OK) return s;
+  if (!q || !k || !v || !y_teacher || !y_student || !loss) return HA_ERR_NULL;
+  if (!ha::aligned16(y_teacher) || !ha::aligned16(y_student) || (reinterpret_cast<uintptr_t>(loss) & 7u)) return HA_ERR_ALIGN;
+  if (y_teacher == y_student) return HA_ERR_SHAPE;
+  ha::Plan pt, ps;
+  size_t off_partial;
+  const size_t need = distill_layout(*p, phi_q, phi_k, pt, ps, off_partial);
+  if (!workspace || workspace_bytes < need) return HA_ERR_WORKSPACE;
+  if (!teacher_is_cached) {
+    ha_problem teacher = *p;
+    teacher.hybrid_rate = 1;     // Eq. "softmax": every token is a softmax token
+    s = hybrid_attn_forward(&teacher, q, k, v, nullptr, nullptr, y_teacher, workspace, workspace_bytes, hip_stream);
+    if (s != HA_OK) return s;
+  }
+  s = hybrid_attn_forward(p, q, k, v, phi_q, phi_k, y_student, workspace, workspace_bytes, hip_stream);
+  if (s != HA_OK) return s;
+  double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + off_partial);
+  hipError_t e = ha::launch_l1_distance(ps, y_teacher, y_student, partial, loss, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return ha::device_error(e);
+  return HA_OK;
+}
+
 const char *hybrid_attn_status_string(ha_status s) {
   switch (s) {
     case HA_OK: return "ok";

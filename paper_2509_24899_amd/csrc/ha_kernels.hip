@@ -334,6 +334,82 @@ hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Value-distillation loss (Sec. 3.3, Eq. "vd_loss"): sum |y - y_hat| over two [B, H, N, d] tensors.
+// l1_partial_kernel: grid (L1_PARTS, B*H), 256 threads; workgroup (part, bh) walks a contiguous range of
+// rows in 16-byte pieces, each thread adds its absolute differences in fp32 (a few hundred terms), the
+// workgroup total is formed in fp64 in a fixed order.  l1_final_kernel adds the partials of every
+// (batch, head) in part order, then the (batch, head) totals in order: bitwise reproducible.
+constexpr int L1_PARTS = 64;
+
+template <bool F32>
+__global__ __launch_bounds__(256) void l1_partial_kernel(const void *__restrict__ ya, const void *__restrict__ yb,
+                                                         double *__restrict__ partial, int H, int N, int D,
+                                                         int64_t sb, int64_t sh, int64_t sn) {
+  constexpr int EPP = F32 ? 4 : 8;                    // elements per 16-byte piece
+  const int part = blockIdx.x, bh = blockIdx.y;
+  const int64_t base = (int64_t)(bh / H) * sb + (int64_t)(bh % H) * sh;
+  const int rows_per = (N + L1_PARTS - 1) / L1_PARTS;
+  const int r0 = part * rows_per, r1 = min(r0 + rows_per, N);
+  const int ppr = D / EPP;                            // pieces per row
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < (r1 - r0) * ppr; i += 256) {
+    const int64_t off = base + (int64_t)(r0 + i / ppr) * sn + (i % ppr) * EPP;
+    if constexpr (F32) {
+      const f32x4 a = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(ya) + off);
+      const f32x4 b = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(yb) + off);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc += fabsf(a[t] - b[t]);
+    } else {
+      const bf16x8 a = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(ya) + off);
+      const bf16x8 b = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(yb) + off);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc += fabsf(static_cast<float>(a[t]) - static_cast<float>(b[t]));
+    }
+  }
+  __shared__ double red[256];
+  red[threadIdx.x] = (double)acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[(int64_t)bh * L1_PARTS + part] = red[0];
+}
+
+// loss[0] = total, loss[1 + bh] = per (batch, head)
+__global__ __launch_bounds__(64) void l1_final_kernel(const double *__restrict__ partial, double *__restrict__ loss, int BH) {
+  __shared__ double tot[64];
+  double grand = 0.0;
+  for (int b0 = 0; b0 < BH; b0 += 64) {
+    const int bh = b0 + threadIdx.x;
+    double s = 0.0;
+    if (bh < BH) {
+      for (int p = 0; p < L1_PARTS; ++p) s += partial[(int64_t)bh * L1_PARTS + p];
+      loss[1 + bh] = s;
+    }
+    tot[threadIdx.x] = bh < BH ? s : 0.0;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      for (int i = 0; i < 64; ++i) grand += tot[i];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[0] = grand;
+}
+
+size_t l1_partial_bytes(const Plan &pl) { return (size_t)pl.B * pl.H * L1_PARTS * sizeof(double); }
+
+hipError_t launch_l1_distance(const Plan &pl, const void *ya, const void *yb, double *partial, double *loss,
+                              hipStream_t st) {
+  dim3 grid(L1_PARTS, pl.B * pl.H);
+  if (pl.f32) l1_partial_kernel<true><<<grid, 256, 0, st>>>(ya, yb, partial, pl.H, pl.N, pl.D, pl.sb, pl.sh, pl.sn);
+  else l1_partial_kernel<false><<<grid, 256, 0, st>>>(ya, yb, partial, pl.H, pl.N, pl.D, pl.sb, pl.sh, pl.sn);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  l1_final_kernel<<<1, 64, 0, st>>>(partial, loss, pl.B * pl.H);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Measurement aid, not a step of the method: nothing but dense bf16 32x32x16 matrix instructions on
 // register operands (four independent accumulators per wave, eight waves per workgroup, one workgroup
 // per compute unit).  Timed by a caller, it gives the matrix-core rate this device sustains, which

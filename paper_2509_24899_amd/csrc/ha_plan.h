@@ -33,6 +33,9 @@ hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_f
 hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st);
 hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
                         hipStream_t st);
+size_t l1_partial_bytes(const Plan &pl);
+hipError_t launch_l1_distance(const Plan &pl, const void *ya, const void *yb, double *partial, double *loss,
+                              hipStream_t st);
 hipError_t launch_mfma_probe(float *sink, int workgroups, int iters, int random_operands, hipStream_t st);
 
 }  // namespace ha

@@ -79,6 +79,11 @@ def _lib():
                                                ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
         lib.hybrid_attn_mfma_probe.restype = ctypes.c_int
         dp = ctypes.POINTER(ctypes.c_double)
+        lib.hybrid_attn_value_distill_workspace_bytes.argtypes = [P, FM, FM]
+        lib.hybrid_attn_value_distill_workspace_bytes.restype = ctypes.c_size_t
+        lib.hybrid_attn_value_distill_loss.argtypes = [P, vp, vp, vp, FM, FM, ctypes.c_int, vp, vp, vp, vp,
+                                                       ctypes.c_size_t, vp]
+        lib.hybrid_attn_value_distill_loss.restype = ctypes.c_int
         lib.hybrid_attn_select_rates.argtypes = [ctypes.c_int, ctypes.c_int, dp, dp, ctypes.c_double,
                                                  ctypes.POINTER(ctypes.c_int), dp, dp]
         lib.hybrid_attn_select_rates.restype = ctypes.c_int
@@ -253,6 +258,44 @@ def hybrid_attn_forward(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[Fe
     if st != HA_OK:
         raise HybridAttnError(st, "hybrid_attn_forward")
     return out
+
+
+
+def hybrid_attn_value_distill_loss(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[FeatureMap], hybrid_rate: int,
+                                   block_size: int = 128, softmax_scale: Optional[float] = None, y_teacher=None,
+                                   teacher_is_cached: bool = False, y_student=None, workspace=None, stream=None):
+    """Value-distillation loss of Sec. 3.3 (Eq. "vd_loss"): enqueues teacher forward (unless cached),
+    student forward and the reduction; returns (loss, y_teacher, y_student) with `loss` a device
+    float64 tensor [1 + B * H] (total, then per (batch, head)).  Does not synchronise."""
+    _require_gpu(q, k, v)
+    if softmax_scale is None:
+        softmax_scale = float(q.shape[-1]) ** -0.5
+    if y_teacher is None:
+        if teacher_is_cached:
+            raise ValueError("teacher_is_cached needs y_teacher")
+        y_teacher = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    if y_student is None:
+        y_student = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    _same_layout(q, k, v, y_teacher, y_student)
+    prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
+    sq, pq = _fm_ptr(phi_q)
+    sk, pk = _fm_ptr(phi_k)
+    lib = _lib()
+    st = lib.hybrid_attn_validate(ctypes.byref(prob), pq, pk)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_validate")
+    need = lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(prob), pq, pk)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    loss = torch.empty(1 + q.shape[0] * q.shape[1], dtype=torch.float64, device=q.device)
+    stream_handle = (stream if stream is not None else torch.cuda.current_stream(q.device)).cuda_stream
+    st = lib.hybrid_attn_value_distill_loss(ctypes.byref(prob), q.data_ptr(), k.data_ptr(), v.data_ptr(), pq, pk,
+                                            int(teacher_is_cached), y_teacher.data_ptr(), y_student.data_ptr(),
+                                            loss.data_ptr(), workspace.data_ptr(),
+                                            workspace.numel() * workspace.element_size(), stream_handle)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_value_distill_loss")
+    return loss, y_teacher, y_student
 
 
 def hybrid_attn_linear_state(k, v, phi_k: FeatureMap, hybrid_rate: int, block_size: int = 128, workspace=None,

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(lib):
     text = open(os.path.join(ROOT, "include", "hybrid_attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(hybrid_attn_\w+)\s*\(", text)
-    assert len(set(names)) == 12
+    assert len(set(names)) == 14
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
     assert ha.hybrid_attn_abi_version() == 1
@@ -155,3 +155,26 @@ def test_mfma_probe_rejects_bad_arguments_on_the_host(lib):
     assert f(1, 0, 1, FAKE, 1 << 20, ctypes.byref(flops), None) == ha.HA_ERR_SHAPE
     assert f(1, 100, 0, FAKE, 1 << 20, ctypes.byref(flops), None) == ha.HA_ERR_SHAPE
     assert f(1, 100, 1, FAKE + 4, 1 << 20, ctypes.byref(flops), None) == ha.HA_ERR_ALIGN
+
+
+def test_value_distill_workspace_and_errors(lib):
+    fm = _map()
+    p = _problem()
+    fwd = lib.hybrid_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(fm), ctypes.byref(fm))
+    both = lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(p), ctypes.byref(fm), ctypes.byref(fm))
+    teacher = _problem(R=1)
+    fwd_teacher = lib.hybrid_attn_workspace_bytes(ctypes.byref(teacher), None, None)
+    assert both >= max(fwd, fwd_teacher) + 12 * 64 * 8          # the larger forward plus the reduction partials
+    assert lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(_problem(N=0)), ctypes.byref(fm), ctypes.byref(fm)) == 0
+    f = lib.hybrid_attn_value_distill_loss
+    A = [FAKE + i * 0x10000000 for i in range(8)]
+    args = lambda **kw: [ctypes.byref(kw.get("p", p)), A[0], A[1], A[2], ctypes.byref(fm), ctypes.byref(fm), 0,
+                         kw.get("yt", A[3]), kw.get("ys", A[4]), kw.get("loss", A[5]), kw.get("ws", A[6]),
+                         kw.get("wsb", both), None]
+    assert f(*args(yt=None)) == ha.HA_ERR_NULL
+    assert f(*args(loss=None)) == ha.HA_ERR_NULL
+    assert f(*args(ys=A[3])) == ha.HA_ERR_SHAPE               # teacher and student outputs must be distinct
+    assert f(*args(loss=A[5] + 4)) == ha.HA_ERR_ALIGN
+    assert f(*args(wsb=both - 1)) == ha.HA_ERR_WORKSPACE
+    assert f(*args(ws=None)) == ha.HA_ERR_WORKSPACE
+    assert f(*args(p=_problem(d=96))) == ha.HA_ERR_UNSUPPORTED
