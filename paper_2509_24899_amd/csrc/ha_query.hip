@@ -129,7 +129,7 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
 // is first read (as K(j+2)) at least one barrier after it was requested.
 template <int D, int HD, int F, int QB, int NW, int NB, int G, bool F32>
 __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(QueryArgs a) {
-  static_assert(NB >= 2 * G + 2 && (NB & (NB - 1)) == 0, "ring too short for the barrier period");
+  static_assert(G <= 2 && NB >= 2 * G + 2 && (NB & (NB - 1)) == 0, "ring too short for the barrier period");
   constexpr int KS = D / 16, RB = D / 32;
   constexpr int FRAG = D * 4;                 // bf16x8 per 32-key block per tensor
   constexpr int LEAD = NB - G, QT = 32 * QB * NW;
@@ -139,11 +139,6 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   static_assert(32 * ((D / (F32 ? 2 : 1)) * (F32 ? 4 : 2) + 16) <= 2 * NB * FRAG * 16 / NW, "staging tile too large");
   bf16x8 (*ring_k)[FRAG] = reinterpret_cast<bf16x8 (*)[FRAG]>(&ring[0]);
   bf16x8 (*ring_v)[FRAG] = reinterpret_cast<bf16x8 (*)[FRAG]>(&ring[NB * FRAG]);
-  // The first QL of the KS Q fragments of every wave live in LDS instead of registers: with two waves per
-  // SIMD the loop is a few registers over budget otherwise, and a register spilled to scratch would make
-  // every step wait on the vector-memory counter, i.e. on the direct-to-LDS loads just issued.
-  constexpr int QL = (D == 128 && QB == 1) ? 4 : 0;
-  __shared__ bf16x8 q_lds[QL > 0 ? NW * QL * 64 : 1];
 
   const int per_xcd = (a.total_wg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -161,10 +156,6 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
     const int qi = min(q0 + 32 * qb + r, a.N - 1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = load8<F32>(a.q, base + (int64_t)qi * a.sn + 16 * ks + 8 * g);
-  }
-  if constexpr (QL > 0) {
-#pragma unroll
-    for (int ks = 0; ks < QL; ++ks) q_lds[(w * QL + ks) * 64 + lane] = qf[0][ks];
   }
   f32x16 o[QB][RB];
   // m_true: exact running maximum c_i.  m: the (possibly older) maximum the accumulators are currently
@@ -225,15 +216,18 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
       }
       __syncthreads();
     };
-    for (int b = 0; b < LEAD && b < nblk; ++b) request(b);
+    // Every step of the loop below runs the same code, also past the last block (its logits are masked
+    // and its weights are zero), so every ring slot must hold finite data before it is read: requests past
+    // the end re-fetch the last block of the (zero padded) fragment arrays.
+    for (int b = 0; b < LEAD; ++b) request(min(b, a.n_kblocks - 1));
     ring_barrier(std::false_type{});
 
     const float c = a.scale_log2e;
-    bf16x8 kf[KS], vf[RB][2];
+    bf16x8 k_a[KS], k_b[KS], vf[RB][2];
     f32x16 s_a[QB], s_b[QB];
-    auto load_k = [&](int b) {
+    auto load_k = [&](int b, bf16x8 (&dst)[KS]) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[ks] = ring_k[b & (NB - 1)][ks * 64 + lane];
+      for (int ks = 0; ks < KS; ++ks) dst[ks] = ring_k[b & (NB - 1)][ks * 64 + lane];
     };
     // logits of block b that are zero padding (keys >= NS) must not take part
     auto mask_tail = [&](f32x16 (&s)[QB], int b) {
@@ -276,7 +270,7 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
     };
 
     // prologue: S(0), its maximum, and the K fragments of block 1
-    load_k(0);
+    load_k(0, k_b);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -284,30 +278,25 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) s_a[qb] = mfma32(kf[ks], qf[qb][ks], s_a[qb]);
+      for (int qb = 0; qb < QB; ++qb) s_a[qb] = mfma32(k_b[ks], qf[qb][ks], s_a[qb]);
     mask_tail(s_a, 0);
     {
       float mx[QB];
       col_max(s_a, mx);
       fold_max(mx);
     }
-    if (nblk > 1) load_k(1);
+    load_k(1, k_a);
 
-    // One step.  On entry s_cur = S(j)^T (masked), m already covers block j, kf holds K(j+1).
-    // NEXT: block j+1 exists; NEXT2: block j+2 exists; MASK: block j+1 may hold padding keys.
-    auto step = [&](int j, f32x16 (&s_cur)[QB], f32x16 (&s_nxt)[QB], auto next_c, auto next2_c, auto mask_c) {
-      constexpr bool NEXT = decltype(next_c)::value, NEXT2 = decltype(next2_c)::value, MASK = decltype(mask_c)::value;
-      if constexpr (NEXT2) request(min(j + LEAD, a.n_kblocks - 1));
-      // V(j) fragments come in as two halves (keys 0..15 and 16..31 of the block) to keep fewer
-      // registers live: the first now, the second once half of the K fragments have been consumed
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) vf[rb][0] = ring_v[j & (NB - 1)][(rb * 2 + 0) * 64 + lane];
-      bf16x8 ql[QL > 0 ? QL : 1];
-      if constexpr (QL > 0 && NEXT) {
-#pragma unroll
-        for (int ks = 0; ks < QL; ++ks) ql[ks] = q_lds[(w * QL + ks) * 64 + lane];
-      }
-      __builtin_amdgcn_sched_barrier(0);   // keep these reads up here so their latency hides under phase 1
+    // One step.  On entry s_cur = S(j)^T (masked), m already covers block j, k_cur holds K(j+1).  Blocks past
+    // the last real one are processed like any other: their logits are masked to -inf (weights exactly 0).
+    // All LDS reads of a step are issued during phase 1, a phase or more ahead of their use: V(j) for
+    // phase 2 of this step, K(j+2) (into the other K buffer) for phase 1 of the next.
+    // MASK: block j + 1 may hold padding keys (or lie past the end).
+    auto step = [&](int j, f32x16 (&s_cur)[QB], f32x16 (&s_nxt)[QB], bf16x8 (&k_cur)[KS], bf16x8 (&k_nxt)[KS],
+                    auto mask_c) {
+      constexpr bool MASK = decltype(mask_c)::value;
+      request(min(j + LEAD, a.n_kblocks - 1));
+      const bf16x8 *vsrc_lds = ring_v[j & (NB - 1)], *ksrc_lds = ring_k[(j + 2) & (NB - 1)];
       // phase 1: S(j+1)^T on the matrix cores, exponentials of S(j)^T on the VALU
       float mc[QB], ps[QB];
       bf16x8 pb[2][QB];
@@ -315,21 +304,30 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
       for (int qb = 0; qb < QB; ++qb) {
         mc[qb] = m[qb] * c;
         ps[qb] = 0.f;
-        if constexpr (NEXT) {
 #pragma unroll
-          for (int x = 0; x < 16; ++x) s_nxt[qb][x] = 0.f;
-        }
+        for (int x = 0; x < 16; ++x) s_nxt[qb][x] = 0.f;
       }
       constexpr int PER = 16 / KS;   // logits per (ks, qb) slot: 2 for d = 128, 4 for d = 64
+      constexpr int QTR = KS / 4 > 0 ? KS / 4 : 1;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        if (ks == KS / 2) {
+        // LDS reads, a quarter of the step's sixteen fragments at a time
+        if (ks == 0) {
 #pragma unroll
-          for (int rb = 0; rb < RB; ++rb) vf[rb][1] = ring_v[j & (NB - 1)][(rb * 2 + 1) * 64 + lane];
+          for (int rb = 0; rb < RB; ++rb) vf[rb][0] = vsrc_lds[(rb * 2 + 0) * 64 + lane];
+        } else if (ks == QTR) {
+#pragma unroll
+          for (int t = 0; t < KS / 2; ++t) k_nxt[t] = ksrc_lds[t * 64 + lane];
+        } else if (ks == 2 * QTR) {
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) vf[rb][1] = vsrc_lds[(rb * 2 + 1) * 64 + lane];
+        } else if (ks == 3 * QTR) {
+#pragma unroll
+          for (int t = KS / 2; t < KS; ++t) k_nxt[t] = ksrc_lds[t * 64 + lane];
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-          if constexpr (NEXT) s_nxt[qb] = mfma32(kf[ks], (QL > 0 && ks < QL) ? ql[ks] : qf[qb][ks], s_nxt[qb]);
+          s_nxt[qb] = mfma32(k_cur[ks], qf[qb][ks], s_nxt[qb]);
           // a slice of the exponentials rides along with every matrix instruction
 #pragma unroll
           for (int i = 0; i < PER; ++i) {
@@ -360,50 +358,37 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
       }
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) lsum[qb] += ps[qb];
-      // phase 2: O^T += V(j)^T P(j)^T on the matrix cores; K(j+2) fragments come in from LDS (half after
-      // each half of the products) and the column maxima of S(j+1)^T are formed on the VALU
+      // phase 2: O^T += V(j)^T P(j)^T on the matrix cores; the column maxima of S(j+1)^T on the VALU
 #pragma unroll
-      for (int sp = 0; sp < 2; ++sp) {
+      for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) o[qb][rb] = mfma32(vf[rb][sp], pb[sp][qb], o[qb][rb]);
-        if constexpr (NEXT2) {
-#pragma unroll
-          for (int ks = sp * (KS / 2); ks < (sp + 1) * (KS / 2); ++ks)
-            kf[ks] = ring_k[(j + 2) & (NB - 1)][ks * 64 + lane];
-        }
-      }
-      if constexpr (NEXT) {
-        if constexpr (MASK) mask_tail(s_nxt, j + 1);
-        float mx[QB];
-        col_max(s_nxt, mx);
-        fold_max(mx);
-      }
+      if constexpr (MASK) mask_tail(s_nxt, j + 1);
+      float mx[QB];
+      col_max(s_nxt, mx);
+      fold_max(mx);
     };
     using T = std::true_type;
     using Fa = std::false_type;
-    // steady state: steps whose two successors exist run without any end-of-sequence checks
+    // two steps per trip (the two S buffers swap roles); an odd block count adds one all-masked step.
+    // Trips whose blocks j + 1, j + 2 consist of real keys only skip the padding mask.
+    const int n_full = a.NS >> 5;
     int j = 0;
-    for (; j + 3 < nblk; j += 2) {
-      step(j, s_a, s_b, T{}, T{}, Fa{});
+    for (; j + 2 < n_full; j += 2) {
+      step(j, s_a, s_b, k_a, k_b, Fa{});
       if (G == 1) ring_barrier(T{});
-      step(j + 1, s_b, s_a, T{}, T{}, Fa{});
-      if (G <= 2 || (j & 2)) ring_barrier(T{});
+      step(j + 1, s_b, s_a, k_b, k_a, Fa{});
+      ring_barrier(T{});
     }
-    // the last one to three steps (j is even here)
     for (; j < nblk; j += 2) {
-      if (j + 2 < nblk) step(j, s_a, s_b, T{}, T{}, T{});
-      else if (j + 1 < nblk) step(j, s_a, s_b, T{}, Fa{}, T{});
-      else step(j, s_a, s_b, Fa{}, Fa{}, Fa{});
-      ring_barrier(Fa{});
-      if (j + 1 < nblk) {
-        if (j + 3 < nblk) step(j + 1, s_b, s_a, T{}, T{}, T{});
-        else if (j + 2 < nblk) step(j + 1, s_b, s_a, T{}, Fa{}, T{});
-        else step(j + 1, s_b, s_a, Fa{}, Fa{}, Fa{});
-      }
-      ring_barrier(Fa{});
+      step(j, s_a, s_b, k_a, k_b, T{});
+      if (G == 1) ring_barrier(T{});
+      step(j + 1, s_b, s_a, k_b, k_a, T{});
+      ring_barrier(T{});
     }
+    ring_barrier(Fa{});   // everything landed and read: the ring is free for the epilogue
     // express the accumulators against the exact c_i (Eq. "hybrid": the largest softmax weight is 1)
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -414,10 +399,6 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
 #pragma unroll
         for (int x = 0; x < 16; ++x) o[qb][rb][x] *= alpha;
     }
-  }
-  if constexpr (QL > 0) {   // the epilogue wants all Q fragments in registers again
-#pragma unroll
-    for (int ks = 0; ks < QL; ++ks) qf[0][ks] = q_lds[(w * QL + ks) * 64 + lane];
   }
   // epilogue operands stay in global memory (L2-resident: 64 KiB of weights per head, 64 KiB of state
   // per (batch, head)); staging them through the idle ring was measured slower than reading them in place
