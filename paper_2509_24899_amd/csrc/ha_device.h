@@ -143,8 +143,9 @@ static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g
 //   w1f/w2f : A-operand fragments of the weights, w1 in natural order, w2 in chained order
 // Layer 1 leaves relu(W1 x + b1) as hi + lo bf16 pairs in chained order: a peaky output softmax
 // amplifies errors in u = W2 h + b2, so h is not allowed to lose its low mantissa bits.
-template <int D, int HD>
-static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D / 16], const bf16x8 *__restrict__ w1f,
+// (WP: pointer to the weight fragments, global / generic `const bf16x8 *` or an LDS-qualified one)
+template <int D, int HD, typename WP>
+static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D / 16], WP w1f,
                                                           const float *__restrict__ b1, int lane, int g,
                                                           bf16x8 (&h_hi)[HD / 32][2], bf16x8 (&h_lo)[HD / 32][2]) {
   constexpr int KS = D / 16, HB = HD / 32;
@@ -174,9 +175,9 @@ static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D /
 }
 
 // Layer 2: u[fb] = W2 h + b2 as C tiles (rows = channels, column = token).
-template <int HD, int F>
+template <int HD, int F, typename WP>
 static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[HD / 32][2], const bf16x8 (&h_lo)[HD / 32][2],
-                                                          const bf16x8 *__restrict__ w2f, const float *__restrict__ b2,
+                                                          WP w2f, const float *__restrict__ b2,
                                                           int lane, int g, f32x16 (&u)[F / 32]) {
   constexpr int HB = HD / 32, FB = F / 32;
 #pragma unroll
@@ -201,9 +202,9 @@ static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[H
   }
 }
 
-template <int D, int HD, int F>
-static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], const bf16x8 *__restrict__ w1f,
-                                                   const bf16x8 *__restrict__ w2f, const float *__restrict__ b1,
+template <int D, int HD, int F, typename WP>
+static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], WP w1f,
+                                                   WP w2f, const float *__restrict__ b1,
                                                    const float *__restrict__ b2, int lane, int g,
                                                    f32x16 (&u)[F / 32]) {
   bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];

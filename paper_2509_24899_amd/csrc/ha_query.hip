@@ -30,11 +30,10 @@ struct QueryArgs {
 // Linear part and merge for one 32-query column block (Eq. "hybrid"): g = phi_q(q), n = g S,
 // e = g.z, y = (a + n) / (l + e); `o` holds a^T (d x queries) as C tiles, `lsum` this lane's half of l.
 // w1f / w2f / sth / stl: this head's weight fragments and this (batch, head)'s S^T fragments (global or LDS).
-template <int D, int HD, int F, bool F32>
+template <int D, int HD, int F, bool F32, bool ELDS, typename WP>
 static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane, int qi,
                                                       const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum,
-                                                      const bf16x8 *w1f, const bf16x8 *w2f, const bf16x8 *sth,
-                                                      const bf16x8 *stl, char *stage, int q_first) {
+                                                      WP w1f, WP w2f, WP sth, WP stl, char *stage, int q_first) {
   constexpr int RB = D / 32, FB = F / 32;
   const int g = lane >> 5;
   float den = xhalf_sum(lsum);
@@ -42,7 +41,16 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
     const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
     const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
     f32x16 u[FB];
-    feature_mlp<D, HD, F>(qf, w1f, w2f, b1, b2, lane, g, u);
+    {
+      bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
+      feature_mlp_layer1<D, HD>(qf, w1f, b1, lane, g, h_hi, h_lo);
+      if constexpr (ELDS) {
+        // w2f / sth / stl were requested into the ring when the loop ended and land while layer 1 runs
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
+      feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
+    }
     feature_activation<FB>(u, g, a.act, a.P, F / a.P);
     bf16x8 gb[FB][2];
     float e = 0.f;
@@ -78,6 +86,9 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
   }
   const float inv = 1.0f / den;
   (void)qi;
+  if constexpr (ELDS) {
+    if (a.has_linear) __syncthreads();   // every wave is done with the operands in the ring: it becomes the staging area
+  }
   // Store.  The C layout has one query per lane with 4 consecutive channels per register group, i.e. 8-byte
   // pieces 256 bytes apart across lanes.  The tile goes through this wave's LDS staging area instead
   // ([32 queries][channels of one pass], rows padded by 16 bytes) and leaves as 16-byte pieces with
@@ -139,6 +150,13 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   static_assert(32 * ((D / (F32 ? 2 : 1)) * (F32 ? 4 : 2) + 16) <= 2 * NB * FRAG * 16 / NW, "staging tile too large");
   bf16x8 (*ring_k)[FRAG] = reinterpret_cast<bf16x8 (*)[FRAG]>(&ring[0]);
   bf16x8 (*ring_v)[FRAG] = reinterpret_cast<bf16x8 (*)[FRAG]>(&ring[NB * FRAG]);
+  // Epilogue operands through LDS (one fetch per workgroup instead of one per wave) where they fit: the
+  // layer-1 weights of phi_q in an area of their own, fetched at kernel start; the layer-2 weights and the
+  // state (hi + lo) in the ring once the loop has ended.
+  constexpr int NW1 = HD * D / 8, NW2 = F * HD / 8, NST = D * F / 8;   // bf16x8 per head / per (batch, head)
+  constexpr bool ELDS = NW == 8 && QB == 1 && NW1 * 16 <= 32 * 1024 && (NW2 + 2 * NST) <= 2 * NB * FRAG &&
+                        NW1 % (64 * NW) == 0 && NW2 % (64 * NW) == 0 && NST % (64 * NW) == 0;
+  __shared__ bf16x8 w1_lds[ELDS ? NW1 : 1];
 
   const int per_xcd = (a.total_wg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -149,6 +167,19 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept scalar
   const int q0 = qtile * QT + w * (32 * QB);
+  // n_chunks 1 KiB wave-chunks global -> LDS, dealt round-robin to the waves (direct-to-LDS loads, see below)
+  auto stage_in = [&](const bf16x8 *gsrc, bf16x8 *ldst, int n_chunks) {
+    const unsigned lane_off16 = lane * 16;
+    for (int ch = w; ch < n_chunks; ch += NW) {
+      const unsigned l = __builtin_amdgcn_readfirstlane(
+          (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(ldst + ch * 64));
+      const bf16x8 *gp = gsrc + ch * 64;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(l), "v"(lane_off16), "s"(gp) : "memory");
+    }
+  };
+  if constexpr (ELDS) {
+    if (a.has_linear) stage_in(a.w1f + (int64_t)h * NW1, w1_lds, NW1 / 64);
+  }
 
   bf16x8 qf[QB][KS];
 #pragma unroll
@@ -400,17 +431,30 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
         for (int x = 0; x < 16; ++x) o[qb][rb][x] *= alpha;
     }
   }
-  // epilogue operands stay in global memory (L2-resident: 64 KiB of weights per head, 64 KiB of state
-  // per (batch, head)); staging them through the idle ring was measured slower than reading them in place
-  constexpr int NW1 = HD * D / 8, NW2 = F * HD / 8, NST = D * F / 8;
-  const bf16x8 *w1f = a.w1f + (int64_t)h * NW1;
-  const bf16x8 *w2f = a.w2f + (int64_t)h * NW2;
-  const bf16x8 *sth = a.st_hi + (int64_t)bh * NST;
-  const bf16x8 *stl = a.st_lo + (int64_t)bh * NST;
+  char *stage = reinterpret_cast<char *>(&ring[0]) + w * (2 * NB * FRAG * 16 / NW);
+  const bf16x8 *w1g = a.w1f + (int64_t)h * NW1;
+  const bf16x8 *w2g = a.w2f + (int64_t)h * NW2;
+  const bf16x8 *sthg = a.st_hi + (int64_t)bh * NST;
+  const bf16x8 *stlg = a.st_lo + (int64_t)bh * NST;
+  if constexpr (ELDS) {
+    typedef const __attribute__((address_space(3))) bf16x8 *lds_ptr;
+    if (a.has_linear) {
+      stage_in(w2g, &ring[0], NW2 / 64);
+      stage_in(sthg, &ring[NW2], NST / 64);
+      stage_in(stlg, &ring[NW2 + NST], NST / 64);
+      // the layer-1 weights were requested at kernel start; with no key block at all nothing has waited for them yet
+      asm volatile("s_waitcnt vmcnt(%0)" :: "n"((NW2 + 2 * NST) / 64 / NW) : "memory");
+      __syncthreads();
+    }
+    query_epilogue<D, HD, F, F32, true>(a, bh, h, base, lane, q0 + r, qf[0], o[0], lsum[0], (lds_ptr)&w1_lds[0],
+                                        (lds_ptr)&ring[0], (lds_ptr)&ring[NW2], (lds_ptr)&ring[NW2 + NST], stage, q0);
+  } else {
+    // the operands do not fit next to the ring: read in place (L2-resident, per head / per (batch, head))
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-    query_epilogue<D, HD, F, F32>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb], w1f, w2f, sth, stl,
-                                  reinterpret_cast<char *>(&ring[0]) + w * (2 * NB * FRAG * 16 / NW), q0 + 32 * qb);
+    for (int qb = 0; qb < QB; ++qb)
+      query_epilogue<D, HD, F, F32, false>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb], w1g, w2g, sthg,
+                                           stlg, stage, q0 + 32 * qb);
+  }
 }
 
 hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
