@@ -131,9 +131,10 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
 //
 // K_S / V_S fragments travel global -> LDS with direct-to-LDS loads into a ring of NB 32-key blocks
 // (no staging registers).  Loop step j handles key block j:
-//   phase 1   S(j+1)^T = K(j+1) Q^T on the matrix cores   ||   softmax of S(j) on the vector ALU,
-//             V(j) fragments LDS -> registers
-//   phase 2   O^T += V(j)^T P(j)^T                          ||   K(j+2) fragments LDS -> registers
+//   phase 1   S(j+1)^T = K(j+1) Q^T on the matrix cores   ||   softmax of S(j) on the vector ALU;
+//             V(j) and K(j+2) fragments LDS -> registers (two K buffers alternate)
+//   phase 2   O^T += V(j)^T P(j)^T                          ||   column maxima of S(j+1)
+// Every block runs the same step, also the (at most one) step past the last block, whose logits are masked.
 // The block for step j + LEAD (LEAD = NB - G) is requested at the top of step j; a barrier (after
 // waiting for this wave's outstanding loads) closes every G-th step.  NB >= 2 G + 2 makes this safe:
 // the slot being refilled was last read before the latest barrier every wave has passed, and a block
