@@ -275,3 +275,42 @@ def test_mfma_probe_runs_and_reports_its_flops():
     assert bool(torch.isfinite(sink).all()) and bool((sink != 0).any())
     with pytest.raises(ha.HybridAttnError):
         ha.hybrid_attn_mfma_probe(True, 50, 1, sink[:128])
+
+
+def test_long_sequence_sampled():
+    """Half a million tokens in one head (the largest N this suite runs): index arithmetic, chunking of the
+    state pass and the masked tail at a size far beyond the video shapes; oracle on sampled rows."""
+    w = W.Workload("long_bf16_d64", 1, 1, 500_009, 64, "bf16", 128, 256, 64, 64, seed=21)
+    inp = W.make_inputs(w)
+    rows = W.sample_rows(w, 48)
+    check("long_sequence_R256", inp, rows=rows)
+
+
+def test_forward_under_hip_graph_capture():
+    """The forward is a fixed sequence of kernel launches on the caller's stream (no allocation, no host
+    synchronisation, no memset), so it can be captured into a HIP graph; three replays with eager work and
+    synchronisations in between must each reproduce the eager result bit for bit."""
+    inp = W.make_inputs(SMALL)
+    q, k, v, fq, fk = ha.to_device(inp)
+    prob = ha.make_problem(q, 4, SMALL.block_size, SMALL.scale)
+    ws = torch.empty(ha.hybrid_attn_workspace_bytes(prob, fq, fk), dtype=torch.uint8, device="cuda")
+    eager = ha.hybrid_attn_forward(q, k, v, fq, fk, 4, SMALL.block_size, SMALL.scale, workspace=ws).clone()
+    torch.cuda.synchronize()
+    out = torch.empty_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ha.hybrid_attn_forward(q, k, v, fq, fk, 4, SMALL.block_size, SMALL.scale, out=out, workspace=ws)   # warm-up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ha.hybrid_attn_forward(q, k, v, fq, fk, 4, SMALL.block_size, SMALL.scale, out=out, workspace=ws,
+                               stream=torch.cuda.current_stream())
+    for rep in range(3):
+        out.zero_()
+        ws.random_(0, 255)                     # eager work between replays: the workspace holds garbage
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
