@@ -142,6 +142,9 @@ def main():
     ap.add_argument("--workload", default="wan_480p_81f", choices=["tiny", "wan_480p_81f", "wan_480p_161f", "wan_720p_81f_cfg"])
     ap.add_argument("--rate", type=int, default=None, help="override the hybrid rate R (0 = pure linear, 1 = full softmax)")
     ap.add_argument("--block-size", type=int, default=None)
+    ap.add_argument("--phi-width", type=int, default=None,
+                    help="hidden and output width of both feature maps (default: the workload's d -> d -> d; 256 is the "
+                         "paper's default map at d = 128, Tab. phi row P = 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
@@ -171,6 +174,8 @@ def main():
         w = W.with_rate(w, args.rate)
     if args.block_size is not None:
         w = W.replace(w, block_size=args.block_size)
+    if args.phi_width is not None:
+        w = W.replace(w, d_hidden=args.phi_width, d_feat=args.phi_width)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
