@@ -187,11 +187,11 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
       f32x16 u[FB];
       {
         bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
-        feature_mlp_layer1<D, HD>(xf, w1f, b1, lane, g, h_hi, h_lo);
+        feature_mlp_layer1<D, HD, true>(xf, w1f, b1, lane, g, h_hi, h_lo);
         __builtin_amdgcn_sched_barrier(0);
         load_k(t0 + TOK, xf);
         __builtin_amdgcn_sched_barrier(0);
-        feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
+        feature_mlp_layer2<HD, F, true>(h_hi, h_lo, w2f, b2, lane, g, u);
       }
       feature_activation<FB>(u, g, act, P, Dp);
       if (t0 + TOK > NL) {                                 // ragged end of T_L: padded tokens add nothing
