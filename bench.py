@@ -155,6 +155,7 @@ def main():
                          "seeded random feature maps on the shared synthetic q, k, v instead of drawing it")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="all-zero q, k, v: NOT a benchmark, a power / clock experiment (same instruction stream, idle data wires)")
+    ap.add_argument("--no-cold-cache", action="store_true", help="skip the extra forwards with flushed caches")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the matrix-core probe (sustained MFMA-only rate of this device, zero and random operands)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -228,16 +229,18 @@ def main():
     # cold-cache forwards: a 512 MiB fill between forwards evicts L2 and the 256 MiB Infinity Cache, so inputs,
     # weights and workspace come from HBM (matters for the HBM-bound r = 0 point; the timing is the forward's
     # own event pair, the fill lies outside it)
-    n_cold = min(10, args.steps)
-    flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
-    ha.hybrid_attn_profile_enable(n_cold)
-    for i in range(n_cold):
-        flush.fill_(i & 0xFF)
-        step()
-    torch.cuda.synchronize()
-    cold_sorted = sorted(ha.hybrid_attn_profile_read(i)[4] for i in range(n_cold))
-    ha.hybrid_attn_profile_enable(0)
-    del flush
+    cold_sorted = None
+    if not args.no_cold_cache:
+        n_cold = min(10, args.steps)
+        flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        ha.hybrid_attn_profile_enable(n_cold)
+        for i in range(n_cold):
+            flush.fill_(i & 0xFF)
+            step()
+        torch.cuda.synchronize()
+        cold_sorted = sorted(ha.hybrid_attn_profile_read(i)[4] for i in range(n_cold))
+        ha.hybrid_attn_profile_enable(0)
+        del flush
 
     # sustained matrix-core rate of this device next to the published peak: a kernel of nothing but MFMA
     # instructions, run for a few hundred ms so that power management settles; operand values matter
@@ -296,7 +299,7 @@ def main():
         "tflops": flops / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "forward_ms_median": fwd_sorted[len(fwd_sorted) // 2], "forward_ms_min": fwd_sorted[0],
-        "forward_ms_cold_cache_median": cold_sorted[len(cold_sorted) // 2],
+        "forward_ms_cold_cache_median": cold_sorted[len(cold_sorted) // 2] if cold_sorted else None,
         "stage_ms": {"compact": mean[0], "state": mean[1], "wprep_q": mean[2], "query": mean[3], "forward": mean[4]},
         "roofline": roofline,
     }
