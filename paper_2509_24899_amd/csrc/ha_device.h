@@ -48,13 +48,6 @@ static __device__ __forceinline__ float xhalf_sum(float x) {
 
 static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Read-only fp32 table entry at a wave-uniform index (bias vectors, z): addressed through the constant
-// address space so that the load goes through the scalar unit into an SGPR instead of costing every lane a
-// vector-memory load.  Only for data no kernel writes while this one runs.
-static __device__ __forceinline__ float uniform_load(const float *table, int idx) {
-  return reinterpret_cast<const __attribute__((address_space(4))) float *>(reinterpret_cast<uintptr_t>(table))[idx];
-}
-
 // 8 consecutive elements of a row in the io dtype -> 8 bf16 (fp32 is rounded to nearest even).
 template <bool F32>
 static __device__ __forceinline__ bf16x8 load8(const void *base, int64_t elem_off) {
@@ -151,11 +144,12 @@ static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g
 // Layer 1 leaves relu(W1 x + b1) as hi + lo bf16 pairs in chained order: a peaky output softmax
 // amplifies errors in u = W2 h + b2, so h is not allowed to lose its low mantissa bits.
 // (WP: pointer to the weight fragments, global / generic `const bf16x8 *` or an LDS-qualified one)
-// SB: fetch the bias through the scalar unit (two wave-uniform candidates per register and a select) instead of
-// one vector load per register; pays where vector-memory latency is exposed (one wave per SIMD).
-template <int D, int HD, bool SB = false, typename WP>
+// BATCH: request all weight fragments of a block before its chain of matrix instructions starts, so the chain
+// waits for LDS once instead of before every instruction; pays with one wave per SIMD, where nothing else
+// hides the latency.  BP: pointer to the bias (global, or LDS-resident in the state pass).
+template <int D, int HD, bool BATCH = false, typename WP, typename BP>
 static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D / 16], WP w1f,
-                                                          const float *__restrict__ b1, int lane, int g,
+                                                          BP b1, int lane, int g,
                                                           bf16x8 (&h_hi)[HD / 32][2], bf16x8 (&h_lo)[HD / 32][2]) {
   constexpr int KS = D / 16, HB = HD / 32;
 #pragma unroll
@@ -163,20 +157,24 @@ static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D /
     f32x16 h;
     if (b1) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        if constexpr (SB) {
-          const float lo = uniform_load(b1, 32 * hb + crow(v, 0)), hi = uniform_load(b1, 32 * hb + crow(v, 1));
-          h[v] = g ? hi : lo;
-        } else {
-          h[v] = b1[32 * hb + crow(v, g)];
-        }
-      }
+      for (int v = 0; v < 16; ++v) h[v] = b1[32 * hb + crow(v, g)];
     } else {
 #pragma unroll
       for (int v = 0; v < 16; ++v) h[v] = 0.f;
     }
+    if constexpr (BATCH) {
+      // one wave per SIMD: all fragments of the block are requested before the chain starts, so the chain
+      // waits for LDS once instead of before every instruction
+      bf16x8 wf[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) h = mfma32(w1f[(hb * KS + ks) * 64 + lane], xf[ks], h);
+      for (int ks = 0; ks < KS; ++ks) wf[ks] = w1f[(hb * KS + ks) * 64 + lane];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) h = mfma32(wf[ks], xf[ks], h);
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) h = mfma32(w1f[(hb * KS + ks) * 64 + lane], xf[ks], h);
+    }
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       f32x8 t, lo;
@@ -191,9 +189,9 @@ static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D /
 }
 
 // Layer 2: u[fb] = W2 h + b2 as C tiles (rows = channels, column = token).
-template <int HD, int F, bool SB = false, typename WP>
+template <int HD, int F, bool BATCH = false, typename WP, typename BP>
 static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[HD / 32][2], const bf16x8 (&h_lo)[HD / 32][2],
-                                                          WP w2f, const float *__restrict__ b2,
+                                                          WP w2f, BP b2,
                                                           int lane, int g, f32x16 (&u)[F / 32]) {
   constexpr int HB = HD / 32, FB = F / 32;
 #pragma unroll
@@ -201,34 +199,43 @@ static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[H
     f32x16 acc;
     if (b2) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        if constexpr (SB) {
-          const float lo = uniform_load(b2, 32 * fb + crow(v, 0)), hi = uniform_load(b2, 32 * fb + crow(v, 1));
-          acc[v] = g ? hi : lo;
-        } else {
-          acc[v] = b2[32 * fb + crow(v, g)];
-        }
-      }
+      for (int v = 0; v < 16; ++v) acc[v] = b2[32 * fb + crow(v, g)];
     } else {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     }
+    if constexpr (BATCH) {
+      bf16x8 wf[HB][2];
 #pragma unroll
-    for (int hb = 0; hb < HB; ++hb)
+      for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const bf16x8 wf = w2f[((fb * HB + hb) * 2 + s) * 64 + lane];
-        acc = mfma32(wf, h_lo[hb][s], acc);
-        acc = mfma32(wf, h_hi[hb][s], acc);
-      }
+        for (int s = 0; s < 2; ++s) wf[hb][s] = w2f[((fb * HB + hb) * 2 + s) * 64 + lane];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          acc = mfma32(wf[hb][s], h_lo[hb][s], acc);
+          acc = mfma32(wf[hb][s], h_hi[hb][s], acc);
+        }
+    } else {
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          const bf16x8 wf = w2f[((fb * HB + hb) * 2 + s) * 64 + lane];
+          acc = mfma32(wf, h_lo[hb][s], acc);
+          acc = mfma32(wf, h_hi[hb][s], acc);
+        }
+    }
     u[fb] = acc;
   }
 }
 
 template <int D, int HD, int F, typename WP>
 static __device__ __forceinline__ void feature_mlp(const bf16x8 (&xf)[D / 16], WP w1f,
-                                                   WP w2f, const float *__restrict__ b1,
-                                                   const float *__restrict__ b2, int lane, int g,
+                                                   WP w2f, const float *b1,
+                                                   const float *b2, int lane, int g,
                                                    f32x16 (&u)[F / 32]) {
   bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
   feature_mlp_layer1<D, HD>(xf, w1f, b1, lane, g, h_hi, h_lo);

@@ -131,8 +131,14 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   }
   const bf16x8 *w1f = WLDS ? &wlds[0] : w1g;
   const bf16x8 *w2f = WLDS ? &wlds[HD * D / 8] : w2g;
-  const float *b1 = b1_all ? b1_all + (int64_t)h * HD : nullptr;
-  const float *b2 = b2_all ? b2_all + (int64_t)h * F : nullptr;
+  // the biases of this head sit in LDS (zeros when absent): their reads queue up with the weight reads
+  // instead of exposing a vector-memory round trip in front of every chain of matrix instructions
+  __shared__ float blds[HD + F];
+  for (int i = tid; i < HD; i += 256) blds[i] = b1_all ? b1_all[(int64_t)h * HD + i] : 0.f;
+  for (int i = tid; i < F; i += 256) blds[HD + i] = b2_all ? b2_all[(int64_t)h * F + i] : 0.f;
+  __syncthreads();
+  const float *b1 = &blds[0];
+  const float *b2 = &blds[HD];
   const int Dp = F / P;
   const LinearMap lmap(R);
 
