@@ -227,24 +227,32 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
     }
     __syncthreads();
     if (w < GW) {
+      const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);     // the "1" column that yields z
+      const bf16x8 ones = bf16x8{one, one, one, one, one, one, one, one};
+      // two 16-token slices at a time: all their fragments are requested before the matrix instructions that
+      // use them (one wave per SIMD: nothing else hides the LDS latency)
+      constexpr int KB = 2;
 #pragma unroll
-      for (int ks = 0; ks < TOK / 16; ++ks) {
-        const int col = ((2 * ks + g) ^ rsw) << 3;
+      for (int ks0 = 0; ks0 < TOK / 16; ks0 += KB) {
+        bf16x8 af[KB][RPW], bfr[KB][D / 32];
 #pragma unroll
-        for (int rp = 0; rp < RPW; ++rp) {
-          const bf16x8 af = *reinterpret_cast<const bf16x8 *>(&ftp[(32 * (w * RPW + rp) + r) * PITCH + col]);
+        for (int kk = 0; kk < KB; ++kk) {
+          const int col = ((2 * (ks0 + kk) + g) ^ rsw) << 3;
 #pragma unroll
-          for (int cb = 0; cb < NCB; ++cb) {
-            bf16x8 bfr;
-            if (cb < D / 32) {
-              bfr = *reinterpret_cast<const bf16x8 *>(&vtp[(32 * cb + r) * PITCH + col]);
-            } else {
-              const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);   // the "1" column that yields z
-              bfr = bf16x8{one, one, one, one, one, one, one, one};
-            }
-            acc[rp * NCB + cb] = mfma32(af, bfr, acc[rp * NCB + cb]);
-          }
+          for (int rp = 0; rp < RPW; ++rp)
+            af[kk][rp] = *reinterpret_cast<const bf16x8 *>(&ftp[(32 * (w * RPW + rp) + r) * PITCH + col]);
+#pragma unroll
+          for (int cb = 0; cb < D / 32; ++cb)
+            bfr[kk][cb] = *reinterpret_cast<const bf16x8 *>(&vtp[(32 * cb + r) * PITCH + col]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+          for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+              acc[rp * NCB + cb] = mfma32(af[kk][rp], cb < D / 32 ? bfr[kk][cb] : ones, acc[rp * NCB + cb]);
       }
     }
     __syncthreads();
