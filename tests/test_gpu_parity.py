@@ -314,3 +314,24 @@ def test_forward_under_hip_graph_capture():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+
+
+@pytest.mark.parametrize("which", ("b1", "b2", "both"))
+def test_null_biases(which):
+    """The ABI allows NULL for either bias vector (= zero bias); the oracle gets explicit zeros."""
+    inp = W.make_inputs(SMALL)
+    q, k, v, fq, fk = ha.to_device(inp)
+    oq, ok = oracle_map(inp.phi_q), oracle_map(inp.phi_k)
+    for gm, om in ((fq, oq), (fk, ok)):
+        if which in ("b1", "both"):
+            gm.b1 = None
+            om.b1 = np.zeros_like(om.b1)
+        if which in ("b2", "both"):
+            gm.b2 = None
+            om.b2 = np.zeros_like(om.b2)
+    out = ha.hybrid_attn_forward(q, k, v, fq, fk, 4, SMALL.block_size, SMALL.scale)
+    torch.cuda.synchronize()
+    ref = O.hybrid_attn(inp.q, inp.k, inp.v, oq, ok, 4, SMALL.scale)
+    ma, rl = metrics(out.float().cpu().numpy(), ref)
+    record(f"null_bias_{which}", ma, rl)
+    assert ma <= MAX_ABS and rl <= REL_L2
