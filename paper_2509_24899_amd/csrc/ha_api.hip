@@ -77,7 +77,6 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.act_q = has_linear ? phi_q->out_act : 0;
   pl.act_k = has_linear ? phi_k->out_act : 0;
   pl.KT = p.block_size;
-  pl.QB = p.block_size / 64;
   pl.QT = 2 * p.block_size;
   pl.n_qtiles = (pl.N + pl.QT - 1) / pl.QT;
   pl.n_ktiles = (pl.NS + pl.KT - 1) / pl.KT;

@@ -14,8 +14,9 @@ struct Plan {
   bool f32;
   int64_t sb, sh, sn;
   float scale;
-  // softmax part: KT keys per LDS tile, QB 32-query column blocks per wave, 4 waves per workgroup
-  int KT, QB, QT, n_qtiles, n_ktiles, n_kblocks;
+  // softmax part: KT = block_size (the key fragments are padded to whole multiples of it), QT queries per
+  // workgroup of the query kernel (2 x block_size: block_size / 16 waves of 32 queries), 32-key blocks
+  int KT, QT, n_qtiles, n_ktiles, n_kblocks;
   // state pass: CH linear tokens per workgroup, partial tiles per chunk
   int CH, n_chunks, n_state_tiles;
   // workspace byte offsets (all multiples of 256)

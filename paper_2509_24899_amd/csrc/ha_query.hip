@@ -10,9 +10,8 @@ template <typename T>
 static inline T *ws_ptr(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
 
 // ------------------------------------------------------------------------------------------------
-// query_kernel: 4 waves; wave w owns QB column blocks of 32 queries.  Workgroups are numbered so that
-// consecutive ids on one XCD (id % 8) walk the query tiles of one (batch, head) together and share its
-// K_S / V_S in that XCD's L2.
+// Arguments of the query kernel.  Workgroups are numbered so that consecutive ids on one XCD (id % 8) walk the
+// query tiles of one (batch, head) together and share its K_S / V_S in that XCD's L2.
 struct QueryArgs {
   const void *q;
   void *out;
@@ -31,7 +30,7 @@ struct QueryArgs {
 // e = g.z, y = (a + n) / (l + e); `o` holds a^T (d x queries) as C tiles, `lsum` this lane's half of l.
 // w1f / w2f / sth / stl: this head's weight fragments and this (batch, head)'s S^T fragments (global or LDS).
 template <int D, int HD, int F, bool F32, bool ELDS, typename WP>
-static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane, int qi,
+static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane,
                                                       const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum,
                                                       WP w1f, WP w2f, WP sth, WP stl, char *stage, int q_first) {
   constexpr int RB = D / 32, FB = F / 32;
@@ -85,7 +84,6 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
     }
   }
   const float inv = 1.0f / den;
-  (void)qi;
   if constexpr (ELDS) {
     if (a.has_linear) __syncthreads();   // every wave is done with the operands in the ring: it becomes the staging area
   }
@@ -126,8 +124,8 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
 }
 
 // ------------------------------------------------------------------------------------------------
-// query_kernel_ring: the softmax tile loop as a software pipeline.  NW waves, each owning QB column
-// blocks of 32 queries (every K / V fragment read from LDS feeds QB matrix instructions).
+// query_kernel_ring: the softmax tile loop as a software pipeline.  NW waves, each owning one column block
+// of 32 queries.
 //
 // K_S / V_S fragments travel global -> LDS with direct-to-LDS loads into a ring of NB 32-key blocks
 // (no staging registers).  Loop step j handles key block j:
@@ -139,12 +137,12 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
 // waiting for this wave's outstanding loads) closes every G-th step.  NB >= 2 G + 2 makes this safe:
 // the slot being refilled was last read before the latest barrier every wave has passed, and a block
 // is first read (as K(j+2)) at least one barrier after it was requested.
-template <int D, int HD, int F, int QB, int NW, int NB, int G, bool F32>
-__global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(QueryArgs a) {
+template <int D, int HD, int F, int NW, int NB, int G, bool F32>
+__global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   static_assert(G <= 2 && NB >= 2 * G + 2 && (NB & (NB - 1)) == 0, "ring too short for the barrier period");
   constexpr int KS = D / 16, RB = D / 32;
   constexpr int FRAG = D * 4;                 // bf16x8 per 32-key block per tensor
-  constexpr int LEAD = NB - G, QT = 32 * QB * NW;
+  constexpr int LEAD = NB - G, QT = 32 * NW;
   constexpr int WCH = FRAG / 64;              // 1 KiB wave-chunks per block per tensor
   __shared__ bf16x8 ring[2 * NB * FRAG];
   // after the loop each wave stages its 32-query output tile in its share of the ring
@@ -155,7 +153,7 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   // layer-1 weights of phi_q in an area of their own, fetched at kernel start; the layer-2 weights and the
   // state (hi + lo) in the ring once the loop has ended.
   constexpr int NW1 = HD * D / 8, NW2 = F * HD / 8, NST = D * F / 8;   // bf16x8 per head / per (batch, head)
-  constexpr bool ELDS = NW == 8 && QB == 1 && NW1 * 16 <= 32 * 1024 && (NW2 + 2 * NST) <= 2 * NB * FRAG &&
+  constexpr bool ELDS = NW == 8 && NW1 * 16 <= 32 * 1024 && (NW2 + 2 * NST) <= 2 * NB * FRAG &&
                         NW1 % (64 * NW) == 0 && NW2 % (64 * NW) == 0 && NST % (64 * NW) == 0;
   __shared__ bf16x8 w1_lds[ELDS ? NW1 : 1];
 
@@ -167,7 +165,7 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept scalar
-  const int q0 = qtile * QT + w * (32 * QB);
+  const int q0 = qtile * QT + w * 32;
   // n_chunks 1 KiB wave-chunks global -> LDS, dealt round-robin to the waves (direct-to-LDS loads, see below)
   auto stage_in = [&](const bf16x8 *gsrc, bf16x8 *ldst, int n_chunks) {
     const unsigned lane_off16 = lane * 16;
@@ -182,28 +180,21 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
     if (a.has_linear) stage_in(a.w1f + (int64_t)h * NW1, w1_lds, NW1 / 64);
   }
 
-  bf16x8 qf[QB][KS];
+  bf16x8 qf[KS];
+  {
+    const int qi = min(q0 + r, a.N - 1);   // rows past the end repeat the last query and are not stored
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int qi = min(q0 + 32 * qb + r, a.N - 1);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = load8<F32>(a.q, base + (int64_t)qi * a.sn + 16 * ks + 8 * g);
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = load8<F32>(a.q, base + (int64_t)qi * a.sn + 16 * ks + 8 * g);
   }
-  f32x16 o[QB][RB];
+  f32x16 o[RB];
   // m_true: exact running maximum c_i.  m: the (possibly older) maximum the accumulators are currently
   // expressed against; it follows m_true only when the gap would let exponentials exceed 2^kLazy.
   constexpr float kLazy = 8.0f;
-  float m[QB], m_true[QB], lsum[QB];
+  float m = -INFINITY, m_true = -INFINITY, lsum = 0.f;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m[qb] = -INFINITY;
-    m_true[qb] = -INFINITY;
-    lsum[qb] = 0.f;
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int x = 0; x < 16; ++x) o[qb][rb][x] = 0.f;
-  }
+    for (int x = 0; x < 16; ++x) o[rb][x] = 0.f;
 
   const int nblk = (a.NS + 31) >> 5;     // key blocks that hold at least one real key
   if (nblk > 0) {
@@ -256,67 +247,46 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
 
     const float c = a.scale_log2e;
     bf16x8 k_a[KS], k_b[KS], vf[RB][2];
-    f32x16 s_a[QB], s_b[QB];
+    f32x16 s_a, s_b;
     auto load_k = [&](int b, bf16x8 (&dst)[KS]) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) dst[ks] = ring_k[b & (NB - 1)][ks * 64 + lane];
     };
     // logits of block b that are zero padding (keys >= NS) must not take part
-    auto mask_tail = [&](f32x16 (&s)[QB], int b) {
+    auto mask_tail = [&](f32x16 &s, int b) {
       if ((b + 1) * 32 > a.NS) {
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          const bool dead = b * 32 + crow(x, g) >= a.NS;
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) s[qb][x] = dead ? -INFINITY : s[qb][x];
-        }
+        for (int x = 0; x < 16; ++x) s[x] = (b * 32 + crow(x, g) >= a.NS) ? -INFINITY : s[x];
       }
     };
     // Running maximum c_i over the blocks seen so far.  The accumulators follow it lazily: they are
     // rescaled only when some row's maximum has moved more than kLazy (in log2 units) past the reference
     // they are expressed against, which keeps every exponential below 2^kLazy; the exact c_i is restored
     // once after the loop.
-    auto fold_max = [&](const float (&mx)[QB]) {
+    auto fold_max = [&](const f32x16 &s) {
+      float t = s[0];
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        m_true[qb] = fmaxf(m_true[qb], mx[qb]);
-        if (__any((m_true[qb] - m[qb]) * c > kLazy)) {
-          const float alpha = fast_exp2((m[qb] - m_true[qb]) * c);
-          lsum[qb] *= alpha;
+      for (int x = 1; x < 16; ++x) t = fmaxf(t, s[x]);
+      m_true = fmaxf(m_true, xhalf_max(t));
+      if (__any((m_true - m) * c > kLazy)) {
+        const float alpha = fast_exp2((m - m_true) * c);
+        lsum *= alpha;
 #pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int x = 0; x < 16; ++x) o[qb][rb][x] *= alpha;
-          m[qb] = m_true[qb];
-        }
-      }
-    };
-    auto col_max = [&](const f32x16 (&s)[QB], float (&mx)[QB]) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float t = s[qb][0];
-#pragma unroll
-        for (int x = 1; x < 16; ++x) t = fmaxf(t, s[qb][x]);
-        mx[qb] = xhalf_max(t);
+          for (int x = 0; x < 16; ++x) o[rb][x] *= alpha;
+        m = m_true;
       }
     };
 
     // prologue: S(0), its maximum, and the K fragments of block 1
     load_k(0, k_b);
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+    for (int x = 0; x < 16; ++x) s_a[x] = 0.f;
 #pragma unroll
-      for (int x = 0; x < 16; ++x) s_a[qb][x] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) s_a[qb] = mfma32(k_b[ks], qf[qb][ks], s_a[qb]);
+    for (int ks = 0; ks < KS; ++ks) s_a = mfma32(k_b[ks], qf[ks], s_a);
     mask_tail(s_a, 0);
-    {
-      float mx[QB];
-      col_max(s_a, mx);
-      fold_max(mx);
-    }
+    fold_max(s_a);
     load_k(1, k_a);
 
     // One step.  On entry s_cur = S(j)^T (masked), m already covers block j, k_cur holds K(j+1).  Blocks past
@@ -324,22 +294,17 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
     // All LDS reads of a step are issued during phase 1, a phase or more ahead of their use: V(j) for
     // phase 2 of this step, K(j+2) (into the other K buffer) for phase 1 of the next.
     // MASK: block j + 1 may hold padding keys (or lie past the end).
-    auto step = [&](int j, f32x16 (&s_cur)[QB], f32x16 (&s_nxt)[QB], bf16x8 (&k_cur)[KS], bf16x8 (&k_nxt)[KS],
-                    auto mask_c) {
+    auto step = [&](int j, f32x16 &s_cur, f32x16 &s_nxt, bf16x8 (&k_cur)[KS], bf16x8 (&k_nxt)[KS], auto mask_c) {
       constexpr bool MASK = decltype(mask_c)::value;
       request(min(j + LEAD, a.n_kblocks - 1));
       const bf16x8 *vsrc_lds = ring_v[j & (NB - 1)], *ksrc_lds = ring_k[(j + 2) & (NB - 1)];
       // phase 1: S(j+1)^T on the matrix cores, exponentials of S(j)^T on the VALU
-      float mc[QB], ps[QB];
-      bf16x8 pb[2][QB];
+      const float mc = m * c;
+      float ps = 0.f;
+      bf16x8 pb[2];
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        mc[qb] = m[qb] * c;
-        ps[qb] = 0.f;
-#pragma unroll
-        for (int x = 0; x < 16; ++x) s_nxt[qb][x] = 0.f;
-      }
-      constexpr int PER = 16 / KS;   // logits per (ks, qb) slot: 2 for d = 128, 4 for d = 64
+      for (int x = 0; x < 16; ++x) s_nxt[x] = 0.f;
+      constexpr int PER = 16 / KS;   // logits per matrix instruction: 2 for d = 128, 4 for d = 64
       constexpr int QTR = KS / 4 > 0 ? KS / 4 : 1;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -357,50 +322,39 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
 #pragma unroll
           for (int t = KS / 2; t < KS; ++t) k_nxt[t] = ksrc_lds[t * 64 + lane];
         }
+        s_nxt = mfma32(k_cur[ks], qf[ks], s_nxt);
+        // a slice of the exponentials rides along with every matrix instruction
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          s_nxt[qb] = mfma32(k_cur[ks], qf[qb][ks], s_nxt[qb]);
-          // a slice of the exponentials rides along with every matrix instruction
-#pragma unroll
-          for (int i = 0; i < PER; ++i) {
-            const int x = ks * PER + i;
-            s_cur[qb][x] = fast_exp2(__builtin_fmaf(s_cur[qb][x], c, -mc[qb]));
-          }
+        for (int i = 0; i < PER; ++i) {
+          const int x = ks * PER + i;
+          s_cur[x] = fast_exp2(__builtin_fmaf(s_cur[x], c, -mc));
         }
         // once a half of the block is exponentiated it is rounded to bf16 (the B operand of P V) and its
         // row-sum contribution is taken from the rounded values, two per v_dot2, so that numerator and
         // denominator see the same weights
         if (ks == KS / 2 - 1 || ks == KS - 1) {
           const int sp = ks == KS - 1;
+          f32x8 p8;
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb) {
-            f32x8 p8;
+          for (int i = 0; i < 8; ++i) p8[i] = s_cur[8 * sp + i];
+          pb[sp] = __builtin_convertvector(p8, bf16x8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) p8[i] = s_cur[qb][8 * sp + i];
-            pb[sp][qb] = __builtin_convertvector(p8, bf16x8);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-              const bf16x2 pr = {pb[sp][qb][2 * i], pb[sp][qb][2 * i + 1]};
-              const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-              ps[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, ps[qb], false);
-            }
+          for (int i = 0; i < 4; ++i) {
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            const bf16x2 pr = {pb[sp][2 * i], pb[sp][2 * i + 1]};
+            const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+            ps = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, ps, false);
           }
         }
       }
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) lsum[qb] += ps[qb];
+      lsum += ps;
       // phase 2: O^T += V(j)^T P(j)^T on the matrix cores; the column maxima of S(j+1)^T on the VALU
 #pragma unroll
       for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) o[qb][rb] = mfma32(vf[rb][sp], pb[sp][qb], o[qb][rb]);
+        for (int rb = 0; rb < RB; ++rb) o[rb] = mfma32(vf[rb][sp], pb[sp], o[rb]);
       if constexpr (MASK) mask_tail(s_nxt, j + 1);
-      float mx[QB];
-      col_max(s_nxt, mx);
-      fold_max(mx);
+      fold_max(s_nxt);
     };
     using T = std::true_type;
     using Fa = std::false_type;
@@ -422,15 +376,12 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
     }
     ring_barrier(Fa{});   // everything landed and read: the ring is free for the epilogue
     // express the accumulators against the exact c_i (Eq. "hybrid": the largest softmax weight is 1)
+    const float alpha = fast_exp2((m - m_true) * c);
+    lsum *= alpha;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      const float alpha = fast_exp2((m[qb] - m_true[qb]) * c);
-      lsum[qb] *= alpha;
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) o[qb][rb][x] *= alpha;
-    }
+      for (int x = 0; x < 16; ++x) o[rb][x] *= alpha;
   }
   char *stage = reinterpret_cast<char *>(&ring[0]) + w * (2 * NB * FRAG * 16 / NW);
   const bf16x8 *w1g = a.w1f + (int64_t)h * NW1;
@@ -447,14 +398,11 @@ __global__ __launch_bounds__(64 * NW, (QB == 1 ? 2 : 1)) void query_kernel_ring(
       asm volatile("s_waitcnt vmcnt(%0)" :: "n"((NW2 + 2 * NST) / 64 / NW) : "memory");
       __syncthreads();
     }
-    query_epilogue<D, HD, F, F32, true>(a, bh, h, base, lane, q0 + r, qf[0], o[0], lsum[0], (lds_ptr)&w1_lds[0],
-                                        (lds_ptr)&ring[0], (lds_ptr)&ring[NW2], (lds_ptr)&ring[NW2 + NST], stage, q0);
+    query_epilogue<D, HD, F, F32, true>(a, bh, h, base, lane, qf, o, lsum, (lds_ptr)&w1_lds[0], (lds_ptr)&ring[0],
+                                        (lds_ptr)&ring[NW2], (lds_ptr)&ring[NW2 + NST], stage, q0);
   } else {
     // the operands do not fit next to the ring: read in place (L2-resident, per head / per (batch, head))
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-      query_epilogue<D, HD, F, F32, false>(a, bh, h, base, lane, q0 + 32 * qb + r, qf[qb], o[qb], lsum[qb], w1g, w2g, sthg,
-                                           stlg, stage, q0 + 32 * qb);
+    query_epilogue<D, HD, F, F32, false>(a, bh, h, base, lane, qf, o, lsum, w1g, w2g, sthg, stlg, stage, q0);
   }
 }
 
@@ -480,14 +428,13 @@ hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi
   // block_size 128: 8 waves x 32 queries, ring of 8 key blocks, barrier every 64 keys (one workgroup per CU);
   // block_size 64: 4 waves x 32 queries, ring of 4 key blocks, barrier every 32 keys (two workgroups per CU).
   const bool big = pl.KT == 128;
-  const int QT = big ? 256 : 128;
-  a.n_qtiles = (pl.N + QT - 1) / QT;
+  a.n_qtiles = pl.n_qtiles;
   a.total_wg = a.n_qtiles * pl.B * pl.H;
   dim3 grid(((a.total_wg + 7) / 8) * 8);
 #define HA_QUERY(DD, HH, FF, F32) \
   do { \
-    if (big) query_kernel_ring<DD, HH, FF, 1, 8, 8, 2, F32><<<grid, 512, 0, st>>>(a); \
-    else query_kernel_ring<DD, HH, FF, 1, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \
+    if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32><<<grid, 512, 0, st>>>(a); \
+    else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \
   } while (0)
   if (pl.D == 64) { if (pl.f32) HA_QUERY(64, 64, 64, true); else HA_QUERY(64, 64, 64, false); }
   else if (pl.HD == 128) { if (pl.f32) HA_QUERY(128, 128, 128, true); else HA_QUERY(128, 128, 128, false); }
