@@ -6,9 +6,11 @@
 //   state_kernel         linear tokens T_L: phi_k(k_j), then partial S = sum phi_k(k_j)^T v_j and
 //                        z = sum phi_k(k_j) per chunk of tokens (Sec. 3.1: the two cached sums)
 //   state_reduce_kernel  fixed-order sum of the partials -> S, z (fp32) and S^T as hi/lo bf16 fragments
-//   query_kernel         per 32-query column block: flash-style loop over K_S/V_S with online
-//                        maximum c_i, then phi_q(q_i), phi_q(q_i).S, phi_q(q_i).z and the merge
+//   (ha_query.hip)       query kernel, per 32-query column block: flash-style loop over K_S/V_S with
+//                        online maximum c_i, then phi_q(q_i), phi_q(q_i).S, phi_q(q_i).z and the merge
 //                        (a_i + n_i) / (l_i + e_i) of Eq. "hybrid"
+//   l1_partial_kernel, l1_final_kernel   || y - y_hat ||_1 of the value-distillation loss (Sec. 3.3)
+//   mfma_probe_kernel    measurement aid: matrix instructions only
 //
 // All products are computed transposed (keys x queries, channels x tokens) so that one lane owns one
 // query / token column: row maxima and sums are in-lane plus one exchange with lane ^ 32.
