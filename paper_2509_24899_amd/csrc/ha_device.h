@@ -144,6 +144,25 @@ static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g
 // Layer 1 leaves relu(W1 x + b1) as hi + lo bf16 pairs in chained order: a peaky output softmax
 // amplifies errors in u = W2 h + b2, so h is not allowed to lose its low mantissa bits.
 // (WP: pointer to the weight fragments, global / generic `const bf16x8 *` or an LDS-qualified one)
+// Fragment `idx` (64 lanes x 16 bytes) of an operand array: lane's piece.
+//  - LDS-resident array: plain indexed read.
+//  - array in global memory: read through a buffer descriptor, lane offset in one VGPR and the fragment offset in
+//    a scalar register.  (With plain pointers the compiler precomputes one 64-bit per-lane address for every
+//    fragment of a weight matrix, hoists them out of the loops and spills them.)  Reads past `bytes` return 0.
+typedef const __attribute__((address_space(3))) bf16x8 *lds_frag_ptr;
+struct GlobalFrags {
+  __amdgpu_buffer_rsrc_t rsrc;
+};
+static __device__ __forceinline__ GlobalFrags global_frags(const bf16x8 *base, int bytes) {
+  // word 3 of the descriptor: raw 32-bit data format of gfx9-family buffers
+  return GlobalFrags{__builtin_amdgcn_make_buffer_rsrc(const_cast<bf16x8 *>(base), 0, bytes, 0x00020000)};
+}
+static __device__ __forceinline__ bf16x8 frag_at(lds_frag_ptr base, int idx, int lane) { return base[idx * 64 + lane]; }
+static __device__ __forceinline__ bf16x8 frag_at(const GlobalFrags &f, int idx, int lane) {
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(f.rsrc, lane * 16, idx * 1024, 0));
+}
+
 // BATCH: request all weight fragments of a block before its chain of matrix instructions starts, so the chain
 // waits for LDS once instead of before every instruction; pays with one wave per SIMD, where nothing else
 // hides the latency.  BP: pointer to the bias (global, or LDS-resident in the state pass).
@@ -167,13 +186,13 @@ static __device__ __forceinline__ void feature_mlp_layer1(const bf16x8 (&xf)[D /
       // waits for LDS once instead of before every instruction
       bf16x8 wf[KS];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) wf[ks] = w1f[(hb * KS + ks) * 64 + lane];
+      for (int ks = 0; ks < KS; ++ks) wf[ks] = frag_at(w1f, hb * KS + ks, lane);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) h = mfma32(wf[ks], xf[ks], h);
     } else {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) h = mfma32(w1f[(hb * KS + ks) * 64 + lane], xf[ks], h);
+      for (int ks = 0; ks < KS; ++ks) h = mfma32(frag_at(w1f, hb * KS + ks, lane), xf[ks], h);
     }
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
@@ -209,7 +228,7 @@ static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[H
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
-        for (int s = 0; s < 2; ++s) wf[hb][s] = w2f[((fb * HB + hb) * 2 + s) * 64 + lane];
+        for (int s = 0; s < 2; ++s) wf[hb][s] = frag_at(w2f, (fb * HB + hb) * 2 + s, lane);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
@@ -223,12 +242,122 @@ static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[H
       for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-          const bf16x8 wf = w2f[((fb * HB + hb) * 2 + s) * 64 + lane];
+          const bf16x8 wf = frag_at(w2f, (fb * HB + hb) * 2 + s, lane);
           acc = mfma32(wf, h_lo[hb][s], acc);
           acc = mfma32(wf, h_hi[hb][s], acc);
         }
     }
     u[fb] = acc;
+  }
+}
+
+// Layer 2 and the output stage fused, for wide maps (F > 128) where the fp32 pre-activations of all F
+// channels of a token do not fit in registers next to everything else: every 32-channel tile is reduced
+// to bf16 right after its chain of matrix instructions.  For the softmax activation this is an online
+// softmax over the tiles: tile fb is exponentiated against the running maximum m_fb known so far and kept
+// as bf16, and once all tiles are done it is rescaled by exp(m_fb - m) / sum, raised to its slice power and
+// rounded again (two bf16 roundings instead of one; both are of the size the single rounding of the narrow
+// path has).  phi[fb][s][i] is channel 32 fb + crow(8 s + i, g) of this lane's token: the B operand
+// ("chained" order) of a product contracted over the channels.
+template <int HD, int F, bool BATCH, typename WP, typename BP>
+static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[HD / 32][2], const bf16x8 (&h_lo)[HD / 32][2],
+                                                          WP w2f, BP b2, int lane, int g, int act, int P, int Dp,
+                                                          bf16x8 (&phi)[F / 32][2]) {
+  constexpr int HB = HD / 32, FB = F / 32;
+  float m_run = -INFINITY, sum = 0.f, mref[FB];
+#pragma unroll
+  for (int fb = 0; fb < FB; ++fb) {
+    f32x16 acc;
+    if (b2) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = b2[32 * fb + crow(v, g)];
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    }
+    if constexpr (BATCH) {
+      bf16x8 wf[HB][2];
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) wf[hb][s] = frag_at(w2f, (fb * HB + hb) * 2 + s, lane);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          acc = mfma32(wf[hb][s], h_lo[hb][s], acc);
+          acc = mfma32(wf[hb][s], h_hi[hb][s], acc);
+        }
+    } else {
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          const bf16x8 wf = frag_at(w2f, (fb * HB + hb) * 2 + s, lane);
+          acc = mfma32(wf, h_lo[hb][s], acc);
+          acc = mfma32(wf, h_hi[hb][s], acc);
+        }
+    }
+    if (act == 0) {
+      float t = acc[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) t = fmaxf(t, acc[v]);
+      const float m_new = fmaxf(m_run, xhalf_max(t));
+      sum *= fast_exp2((m_run - m_new) * kLog2e);          // exp2(-inf) = 0 on the first tile
+      const float off = -m_new * kLog2e;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        acc[v] = fast_exp2(__builtin_fmaf(acc[v], kLog2e, off));
+        sum += acc[v];
+      }
+      mref[fb] = m_new;
+      m_run = m_new;
+    } else if (act == 1) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = fast_exp2(acc[v] * kLog2e);
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = fmaxf(acc[v], 0.f);
+    }
+    if (act != 0 && P > 1) {   // no normalisation to wait for: the slice power can be applied right away
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int extra = (32 * fb + 8 * q) / Dp;            // wave-uniform
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float t0 = acc[4 * q + j];
+          for (int i = 0; i < extra; ++i) acc[4 * q + j] *= t0;
+        }
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      f32x8 t8;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t8[i] = acc[8 * s + i];
+      phi[fb][s] = __builtin_convertvector(t8, bf16x8);
+    }
+  }
+  if (act == 0) {
+    const float inv = 1.0f / xhalf_sum(sum);
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb) {
+      const float factor = fast_exp2((mref[fb] - m_run) * kLog2e) * inv;
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        f32x8 t8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float t0 = static_cast<float>(phi[fb][s][i]) * factor;
+          const int extra = P > 1 ? (32 * fb + 8 * (2 * s + i / 4)) / Dp : 0;   // wave-uniform
+          float t = t0;
+          for (int k = 0; k < extra; ++k) t *= t0;
+          t8[i] = t;
+        }
+        phi[fb][s] = __builtin_convertvector(t8, bf16x8);
+      }
+    }
   }
 }
 

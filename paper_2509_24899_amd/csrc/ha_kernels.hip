@@ -14,6 +14,8 @@
 //
 // All products are computed transposed (keys x queries, channels x tokens) so that one lane owns one
 // query / token column: row maxima and sums are in-lane plus one exchange with lane ^ 32.
+#include <type_traits>
+
 #include "ha_device.h"
 #include "ha_plan.h"
 
@@ -101,8 +103,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const void *__restrict__ k
 // and the 16-byte operand reads over all banks.
 template <int D, int HD, int F, bool F32>
 __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ k, const void *__restrict__ v,
-                                                       const bf16x8 *__restrict__ w1f_all,
-                                                       const bf16x8 *__restrict__ w2f_all,
+                                                       const bf16x8 *w1f_all, const bf16x8 *w2f_all,
                                                        const float *__restrict__ b1_all, const float *__restrict__ b2_all,
                                                        float *__restrict__ part, int H, int NL, int R, int CH, int P,
                                                        int act, int64_t sb, int64_t sh, int64_t sn) {
@@ -131,8 +132,14 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
     // must not start before that, so synchronise once here
     __syncthreads();
   }
-  const bf16x8 *w1f = WLDS ? &wlds[0] : w1g;
-  const bf16x8 *w2f = WLDS ? &wlds[HD * D / 8] : w2g;
+  std::conditional_t<WLDS, lds_frag_ptr, GlobalFrags> w1f, w2f;
+  if constexpr (WLDS) {
+    w1f = (lds_frag_ptr)&wlds[0];
+    w2f = (lds_frag_ptr)&wlds[HD * D / 8];
+  } else {
+    w1f = global_frags(w1g, HD * D * 2);
+    w2f = global_frags(w2g, F * HD * 2);
+  }
   // the biases of this head sit in LDS (zeros when absent): their reads queue up with the weight reads
   // instead of exposing a vector-memory round trip in front of every chain of matrix instructions
   __shared__ float blds[HD + F];
@@ -181,44 +188,61 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
     // V rows of this tile: pass p of wave w covers tokens 16 ((4p + w) % 8) .. + 15 and the four
     // 16-byte chunks 4 (p / 2) .. + 3 of each (64 contiguous bytes per row)
+    // (wide maps: the MLP needs the registers, so V is requested only once the hidden activations are dead)
+    constexpr bool WIDE = F > 128;
     bf16x8 vreg[VPT];
+    auto load_v = [&]() {
 #pragma unroll
-    for (int p = 0; p < VPT; ++p) {
-      const int trow = 16 * ((4 * p + w) & 7) + (lane & 15), c8 = 4 * (p >> 1) + (lane >> 4);
-      const int tok = lmap.token(min(t0 + trow, NL - 1));
-      vreg[p] = load8<F32>(v, base + (int64_t)tok * sn + c8 * 8);
-    }
+      for (int p = 0; p < VPT; ++p) {
+        const int trow = 16 * ((4 * p + w) & 7) + (lane & 15), c8 = 4 * (p >> 1) + (lane >> 4);
+        const int tok = lmap.token(min(t0 + trow, NL - 1));
+        vreg[p] = load8<F32>(v, base + (int64_t)tok * sn + c8 * 8);
+      }
+    };
+    if constexpr (!WIDE) load_v();
     __builtin_amdgcn_sched_barrier(0);
     // phi_k on this wave's 32 tokens; the K rows of the next tile are requested as soon as layer 1
     // has consumed the current ones
     {
-      f32x16 u[FB];
+      bf16x8 phi[FB][2];
       {
         bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
         feature_mlp_layer1<D, HD, true>(xf, w1f, b1, lane, g, h_hi, h_lo);
         __builtin_amdgcn_sched_barrier(0);
         load_k(t0 + TOK, xf);
         __builtin_amdgcn_sched_barrier(0);
-        feature_mlp_layer2<HD, F, true>(h_hi, h_lo, w2f, b2, lane, g, u);
+        if constexpr (WIDE) {
+          feature_layer2_phi<HD, F, false>(h_hi, h_lo, w2f, b2, lane, g, act, P, Dp, phi);
+        } else {
+          f32x16 u[FB];
+          feature_mlp_layer2<HD, F, true>(h_hi, h_lo, w2f, b2, lane, g, u);
+          feature_activation<FB>(u, g, act, P, Dp);
+#pragma unroll
+          for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {
+              f32x8 t8;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
+              phi[fb][sp] = __builtin_convertvector(t8, bf16x8);
+            }
+        }
       }
-      feature_activation<FB>(u, g, act, P, Dp);
+      if constexpr (WIDE) load_v();
       if (t0 + TOK > NL) {                                 // ragged end of T_L: padded tokens add nothing
         const bool valid = t0 + tf < NL;
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-          for (int x = 0; x < 16; ++x) u[fb][x] = valid ? u[fb][x] : 0.f;
+          for (int sp = 0; sp < 2; ++sp) phi[fb][sp] = valid ? phi[fb][sp] : zero;
       }
+      // element (sp, i) of a tile is register x = 8 sp + i, i.e. row 32 fb + crow(x, g)
 #pragma unroll
       for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-        for (int x = 0; x < 16; x += 2) {
-          typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-          typedef float f32x2 __attribute__((ext_vector_type(2)));
-          const bf16x2 pr = __builtin_convertvector(f32x2{u[fb][x], u[fb][x + 1]}, bf16x2);
-          ftp[(32 * fb + 8 * (x >> 2) + (x & 3)) * PITCH + fcol[x >> 2]] = pr[0];
-          ftp[(32 * fb + 8 * (x >> 2) + (x & 3) + 1) * PITCH + fcol[x >> 2]] = pr[1];
-        }
+        for (int x = 0; x < 16; ++x)
+          ftp[(32 * fb + 8 * (x >> 2) + (x & 3)) * PITCH + fcol[x >> 2]] = phi[fb][x >> 3][x & 7];
     }
 #pragma unroll
     for (int p = 0; p < VPT; ++p) {

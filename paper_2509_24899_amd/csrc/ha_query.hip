@@ -39,7 +39,7 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
   if (a.has_linear) {
     const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
     const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
-    f32x16 u[FB];
+    bf16x8 gb[FB][2];
     {
       bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
       feature_mlp_layer1<D, HD>(qf, w1f, b1, lane, g, h_hi, h_lo);
@@ -48,23 +48,32 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
       }
-      feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
+      if constexpr (F > 128) {
+        feature_layer2_phi<HD, F, false>(h_hi, h_lo, w2f, b2, lane, g, a.act, a.P, F / a.P, gb);
+      } else {
+        f32x16 u[FB];
+        feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
+        feature_activation<FB>(u, g, a.act, a.P, F / a.P);
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int sp = 0; sp < 2; ++sp) {
+            f32x8 t8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
+            gb[fb][sp] = __builtin_convertvector(t8, bf16x8);
+          }
+      }
     }
-    feature_activation<FB>(u, g, a.act, a.P, F / a.P);
-    bf16x8 gb[FB][2];
+    // e = g.z with the bf16-rounded g, so that numerator and denominator see the same g
     float e = 0.f;
     const float *zz = a.z + (int64_t)bh * F;
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-      for (int sp = 0; sp < 2; ++sp) {
-        f32x8 t8;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
-        gb[fb][sp] = __builtin_convertvector(t8, bf16x8);
+      for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
         for (int i = 0; i < 8; ++i) e += static_cast<float>(gb[fb][sp][i]) * zz[32 * fb + crow(8 * sp + i, g)];
-      }
     den += xhalf_sum(e);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -75,9 +84,9 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
       for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp) {
-          const int idx = ((rb * FB + fb) * 2 + sp) * 64 + lane;
-          n = mfma32(stl[idx], gb[fb][sp], n);
-          n = mfma32(sth[idx], gb[fb][sp], n);
+          const int idx = (rb * FB + fb) * 2 + sp;
+          n = mfma32(frag_at(stl, idx, lane), gb[fb][sp], n);
+          n = mfma32(frag_at(sth, idx, lane), gb[fb][sp], n);
         }
 #pragma unroll
       for (int x = 0; x < 16; ++x) o[rb][x] += n[x];
@@ -389,7 +398,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   const bf16x8 *sthg = a.st_hi + (int64_t)bh * NST;
   const bf16x8 *stlg = a.st_lo + (int64_t)bh * NST;
   if constexpr (ELDS) {
-    typedef const __attribute__((address_space(3))) bf16x8 *lds_ptr;
+    typedef lds_frag_ptr lds_ptr;
     if (a.has_linear) {
       stage_in(w2g, &ring[0], NW2 / 64);
       stage_in(sthg, &ring[NW2], NST / 64);
@@ -402,7 +411,9 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
                                         (lds_ptr)&ring[NW2], (lds_ptr)&ring[NW2 + NST], stage, q0);
   } else {
     // the operands do not fit next to the ring: read in place (L2-resident, per head / per (batch, head))
-    query_epilogue<D, HD, F, F32, false>(a, bh, h, base, lane, qf, o, lsum, w1g, w2g, sthg, stlg, stage, q0);
+    query_epilogue<D, HD, F, F32, false>(a, bh, h, base, lane, qf, o, lsum, global_frags(w1g, NW1 * 16),
+                                         global_frags(w2g, NW2 * 16), global_frags(sthg, NST * 16),
+                                         global_frags(stlg, NST * 16), stage, q0);
   }
 }
 
