@@ -259,14 +259,21 @@ static __device__ __forceinline__ void feature_mlp_layer2(const bf16x8 (&h_hi)[H
 // rounded again (two bf16 roundings instead of one; both are of the size the single rounding of the narrow
 // path has).  phi[fb][s][i] is channel 32 fb + crow(8 s + i, g) of this lane's token: the B operand
 // ("chained" order) of a product contracted over the channels.
-template <int HD, int F, bool BATCH, typename WP, typename BP>
-static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[HD / 32][2], const bf16x8 (&h_lo)[HD / 32][2],
-                                                          WP w2f, BP b2, int lane, int g, int act, int P, int Dp,
-                                                          bf16x8 (&phi)[F / 32][2]) {
-  constexpr int HB = HD / 32, FB = F / 32;
+template <int FB>
+struct PhiState {
   float m_run = -INFINITY, sum = 0.f, mref[FB];
+};
+
+// Tiles FB0 .. FB1 - 1.  Fragment (fb, hb, s) of W2 is read at index (fb * HB + hb) * 2 + s - frag_bias, so a
+// caller that stages W2 through LDS in pieces can hand in the piece that holds these tiles.
+template <int HD, int F, int FB0, int FB1, bool BATCH, typename WP, typename BP>
+static __device__ __forceinline__ void feature_layer2_phi_tiles(const bf16x8 (&h_hi)[HD / 32][2],
+                                                                const bf16x8 (&h_lo)[HD / 32][2], WP w2f, int frag_bias,
+                                                                BP b2, int lane, int g, int act, int P, int Dp,
+                                                                PhiState<F / 32> &st, bf16x8 (&phi)[F / 32][2]) {
+  constexpr int HB = HD / 32;
 #pragma unroll
-  for (int fb = 0; fb < FB; ++fb) {
+  for (int fb = FB0; fb < FB1; ++fb) {
     f32x16 acc;
     if (b2) {
 #pragma unroll
@@ -280,7 +287,7 @@ static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[H
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
-        for (int s = 0; s < 2; ++s) wf[hb][s] = frag_at(w2f, (fb * HB + hb) * 2 + s, lane);
+        for (int s = 0; s < 2; ++s) wf[hb][s] = frag_at(w2f, (fb * HB + hb) * 2 + s - frag_bias, lane);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
@@ -294,7 +301,7 @@ static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[H
       for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-          const bf16x8 wf = frag_at(w2f, (fb * HB + hb) * 2 + s, lane);
+          const bf16x8 wf = frag_at(w2f, (fb * HB + hb) * 2 + s - frag_bias, lane);
           acc = mfma32(wf, h_lo[hb][s], acc);
           acc = mfma32(wf, h_hi[hb][s], acc);
         }
@@ -303,16 +310,16 @@ static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[H
       float t = acc[0];
 #pragma unroll
       for (int v = 1; v < 16; ++v) t = fmaxf(t, acc[v]);
-      const float m_new = fmaxf(m_run, xhalf_max(t));
-      sum *= fast_exp2((m_run - m_new) * kLog2e);          // exp2(-inf) = 0 on the first tile
+      const float m_new = fmaxf(st.m_run, xhalf_max(t));
+      st.sum *= fast_exp2((st.m_run - m_new) * kLog2e);          // exp2(-inf) = 0 on the first tile
       const float off = -m_new * kLog2e;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         acc[v] = fast_exp2(__builtin_fmaf(acc[v], kLog2e, off));
-        sum += acc[v];
+        st.sum += acc[v];
       }
-      mref[fb] = m_new;
-      m_run = m_new;
+      st.mref[fb] = m_new;
+      st.m_run = m_new;
     } else if (act == 1) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[v] = fast_exp2(acc[v] * kLog2e);
@@ -339,11 +346,18 @@ static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[H
       phi[fb][s] = __builtin_convertvector(t8, bf16x8);
     }
   }
+}
+
+// After the last tile: the softmax normalisation and slice powers (nothing to do for the other activations).
+template <int F>
+static __device__ __forceinline__ void feature_phi_finish(const PhiState<F / 32> &st, int act, int P, int Dp,
+                                                          bf16x8 (&phi)[F / 32][2]) {
+  constexpr int FB = F / 32;
   if (act == 0) {
-    const float inv = 1.0f / xhalf_sum(sum);
+    const float inv = 1.0f / xhalf_sum(st.sum);
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb) {
-      const float factor = fast_exp2((mref[fb] - m_run) * kLog2e) * inv;
+      const float factor = fast_exp2((st.mref[fb] - st.m_run) * kLog2e) * inv;
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
         f32x8 t8;
@@ -359,6 +373,15 @@ static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[H
       }
     }
   }
+}
+
+template <int HD, int F, bool BATCH, typename WP, typename BP>
+static __device__ __forceinline__ void feature_layer2_phi(const bf16x8 (&h_hi)[HD / 32][2], const bf16x8 (&h_lo)[HD / 32][2],
+                                                          WP w2f, BP b2, int lane, int g, int act, int P, int Dp,
+                                                          bf16x8 (&phi)[F / 32][2]) {
+  PhiState<F / 32> st;
+  feature_layer2_phi_tiles<HD, F, 0, F / 32, BATCH>(h_hi, h_lo, w2f, 0, b2, lane, g, act, P, Dp, st, phi);
+  feature_phi_finish<F>(st, act, P, Dp, phi);
 }
 
 template <int D, int HD, int F, typename WP>

@@ -26,85 +26,72 @@ struct QueryArgs {
   float scale_log2e;
 };
 
-// Linear part and merge for one 32-query column block (Eq. "hybrid"): g = phi_q(q), n = g S,
-// e = g.z, y = (a + n) / (l + e); `o` holds a^T (d x queries) as C tiles, `lsum` this lane's half of l.
-// w1f / w2f / sth / stl: this head's weight fragments and this (batch, head)'s S^T fragments (global or LDS).
-template <int D, int HD, int F, bool F32, bool ELDS, typename WP>
-static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane,
-                                                      const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum,
-                                                      WP w1f, WP w2f, WP sth, WP stl, char *stage, int q_first) {
-  constexpr int RB = D / 32, FB = F / 32;
-  const int g = lane >> 5;
-  float den = xhalf_sum(lsum);
-  if (a.has_linear) {
-    const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
-    const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
-    bf16x8 gb[FB][2];
-    {
-      bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
-      feature_mlp_layer1<D, HD>(qf, w1f, b1, lane, g, h_hi, h_lo);
-      if constexpr (ELDS) {
-        // w2f / sth / stl were requested into the ring when the loop ended and land while layer 1 runs
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-      }
-      if constexpr (F > 128) {
-        feature_layer2_phi<HD, F, false>(h_hi, h_lo, w2f, b2, lane, g, a.act, a.P, F / a.P, gb);
-      } else {
-        f32x16 u[FB];
-        feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
-        feature_activation<FB>(u, g, a.act, a.P, F / a.P);
+// Pieces of the epilogue of one 32-query column block (Eq. "hybrid"): g = phi_q(q), n = g S, e = g.z,
+// y = (a + n) / (l + e); `o` holds a^T (d x queries) as C tiles, `lsum` this lane's half of l.
+
+// bf16 copy of the activated tiles: the B operand ("chained" order) of the contraction with the state
+template <int FB>
+static __device__ __forceinline__ void round_tiles(const f32x16 (&u)[FB], bf16x8 (&gb)[FB][2]) {
 #pragma unroll
-        for (int fb = 0; fb < FB; ++fb)
+  for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-          for (int sp = 0; sp < 2; ++sp) {
-            f32x8 t8;
+    for (int sp = 0; sp < 2; ++sp) {
+      f32x8 t8;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
-            gb[fb][sp] = __builtin_convertvector(t8, bf16x8);
-          }
-      }
+      for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
+      gb[fb][sp] = __builtin_convertvector(t8, bf16x8);
     }
-    // e = g.z with the bf16-rounded g, so that numerator and denominator see the same g
-    float e = 0.f;
-    const float *zz = a.z + (int64_t)bh * F;
+}
+
+// e = g.z with the bf16-rounded g, so that numerator and denominator see the same g (this lane's half)
+template <int FB>
+static __device__ __forceinline__ float dot_z(const bf16x8 (&gb)[FB][2], const float *zz, int g) {
+  float e = 0.f;
+#pragma unroll
+  for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+    for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) e += static_cast<float>(gb[fb][sp][i]) * zz[32 * fb + crow(8 * sp + i, g)];
+  return e;
+}
+
+// o^T += S^T g^T with S^T as hi + lo bf16 fragments (sth / stl: global through a descriptor, or LDS)
+template <int D, int F, typename WP>
+static __device__ __forceinline__ void contract_state(const bf16x8 (&gb)[F / 32][2], WP sth, WP stl, int lane,
+                                                      f32x16 (&o)[D / 32]) {
+  constexpr int RB = D / 32, FB = F / 32;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    f32x16 n;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) n[x] = 0.f;
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-      for (int sp = 0; sp < 2; ++sp)
+      for (int sp = 0; sp < 2; ++sp) {
+        const int idx = (rb * FB + fb) * 2 + sp;
+        n = mfma32(frag_at(stl, idx, lane), gb[fb][sp], n);
+        n = mfma32(frag_at(sth, idx, lane), gb[fb][sp], n);
+      }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) e += static_cast<float>(gb[fb][sp][i]) * zz[32 * fb + crow(8 * sp + i, g)];
-    den += xhalf_sum(e);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      f32x16 n;
-#pragma unroll
-      for (int x = 0; x < 16; ++x) n[x] = 0.f;
-#pragma unroll
-      for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
-          const int idx = (rb * FB + fb) * 2 + sp;
-          n = mfma32(frag_at(stl, idx, lane), gb[fb][sp], n);
-          n = mfma32(frag_at(sth, idx, lane), gb[fb][sp], n);
-        }
-#pragma unroll
-      for (int x = 0; x < 16; ++x) o[rb][x] += n[x];
-    }
+    for (int x = 0; x < 16; ++x) o[rb][x] += n[x];
   }
-  const float inv = 1.0f / den;
-  if constexpr (ELDS) {
-    if (a.has_linear) __syncthreads();   // every wave is done with the operands in the ring: it becomes the staging area
-  }
-  // Store.  The C layout has one query per lane with 4 consecutive channels per register group, i.e. 8-byte
-  // pieces 256 bytes apart across lanes.  The tile goes through this wave's LDS staging area instead
-  // ([32 queries][channels of one pass], rows padded by 16 bytes) and leaves as 16-byte pieces with
-  // consecutive lanes on consecutive addresses of a row.
+}
+
+// Store y = o * inv.  The C layout has one query per lane with 4 consecutive channels per register group, i.e.
+// 8-byte pieces 256 bytes apart across lanes.  The tile goes through this wave's LDS staging area instead
+// ([32 queries][channels of one pass], rows padded by 16 bytes) and leaves as 16-byte pieces with
+// consecutive lanes on consecutive addresses of a row.
+template <int D, bool F32>
+static __device__ __forceinline__ void store_tile(const QueryArgs &a, int64_t base, int lane, const f32x16 (&o)[D / 32],
+                                                  float inv, char *stage, int q_first) {
+  constexpr int RB = D / 32;
   constexpr int PASSES = F32 ? 2 : 1;               // fp32 output is staged half a row at a time
   constexpr int DP = D / PASSES, ESZ = F32 ? 4 : 2;
   constexpr int PITCH = DP * ESZ + 16;              // bytes
   constexpr int CPR = DP * ESZ / 16;                // 16-byte pieces per staged row
-  const int r = lane & 31;
+  const int r = lane & 31, g = lane >> 5;
 #pragma unroll
   for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
@@ -130,6 +117,44 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
     }
     if (PASSES > 1) __syncthreads();
   }
+}
+
+// The whole epilogue with every operand array in one place for its whole duration.
+// ELDS: w2f / sth / stl sit in the ring and were requested when the loop ended (they land while layer 1 runs).
+template <int D, int HD, int F, bool F32, bool ELDS, typename WP>
+static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh, int h, int64_t base, int lane,
+                                                      const bf16x8 (&qf)[D / 16], f32x16 (&o)[D / 32], float lsum,
+                                                      WP w1f, WP w2f, WP sth, WP stl, char *stage, int q_first) {
+  constexpr int FB = F / 32;
+  const int g = lane >> 5;
+  float den = xhalf_sum(lsum);
+  if (a.has_linear) {
+    const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
+    const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
+    bf16x8 gb[FB][2];
+    {
+      bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
+      feature_mlp_layer1<D, HD>(qf, w1f, b1, lane, g, h_hi, h_lo);
+      if constexpr (ELDS) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
+      if constexpr (F > 128) {
+        feature_layer2_phi<HD, F, false>(h_hi, h_lo, w2f, b2, lane, g, a.act, a.P, F / a.P, gb);
+      } else {
+        f32x16 u[FB];
+        feature_mlp_layer2<HD, F>(h_hi, h_lo, w2f, b2, lane, g, u);
+        feature_activation<FB>(u, g, a.act, a.P, F / a.P);
+        round_tiles<FB>(u, gb);
+      }
+    }
+    den += xhalf_sum(dot_z<FB>(gb, a.z + (int64_t)bh * F, g));
+    contract_state<D, F>(gb, sth, stl, lane, o);
+  }
+  if constexpr (ELDS) {
+    if (a.has_linear) __syncthreads();   // every wave is done with the operands in the ring: it becomes the staging area
+  }
+  store_tile<D, F32>(a, base, lane, o, 1.0f / den, stage, q_first);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -165,6 +190,10 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   constexpr bool ELDS = NW == 8 && NW1 * 16 <= 32 * 1024 && (NW2 + 2 * NST) <= 2 * NB * FRAG &&
                         NW1 % (64 * NW) == 0 && NW2 % (64 * NW) == 0 && NST % (64 * NW) == 0;
   __shared__ bf16x8 w1_lds[ELDS ? NW1 : 1];
+  // Wider maps: the operands do not fit at once, but the ring takes them in three rounds after the loop
+  // (layer-1 weights + first half of the layer-2 weights, second half, state hi + lo).
+  constexpr bool PHASED = NW == 8 && !ELDS && NW1 <= NB * FRAG && NW2 / 2 <= NB * FRAG && NST <= NB * FRAG &&
+                          NW1 % 64 == 0 && (NW2 / 2) % 64 == 0 && NST % 64 == 0 && (F / 32) % 2 == 0;
 
   const int per_xcd = (a.total_wg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -409,6 +438,44 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     }
     query_epilogue<D, HD, F, F32, true>(a, bh, h, base, lane, qf, o, lsum, (lds_ptr)&w1_lds[0], (lds_ptr)&ring[0],
                                         (lds_ptr)&ring[NW2], (lds_ptr)&ring[NW2 + NST], stage, q0);
+  } else if constexpr (PHASED) {
+    typedef lds_frag_ptr lds_ptr;
+    constexpr int FB = F / 32, HB = HD / 32, HALF = NB * FRAG;
+    const int g = lane >> 5;
+    float den = xhalf_sum(lsum);
+    auto landed = [&]() {                       // this wave's requests have landed, and so have everybody's
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    };
+    if (a.has_linear) {
+      const float *b1 = a.b1 ? a.b1 + (int64_t)h * HD : nullptr;
+      const float *b2 = a.b2 ? a.b2 + (int64_t)h * F : nullptr;
+      bf16x8 gb[FB][2];
+      stage_in(w1g, &ring[0], NW1 / 64);
+      stage_in(w2g, &ring[HALF], NW2 / 2 / 64);
+      landed();
+      {
+        PhiState<FB> st;
+        bf16x8 h_hi[HB][2], h_lo[HB][2];
+        feature_mlp_layer1<D, HD>(qf, (lds_ptr)&ring[0], b1, lane, g, h_hi, h_lo);
+        feature_layer2_phi_tiles<HD, F, 0, FB / 2, false>(h_hi, h_lo, (lds_ptr)&ring[HALF], 0, b2, lane, g, a.act, a.P,
+                                                          F / a.P, st, gb);
+        __syncthreads();                        // every wave is done with W1 and the first half of W2
+        stage_in(w2g + NW2 / 2, &ring[0], NW2 / 2 / 64);
+        landed();
+        feature_layer2_phi_tiles<HD, F, FB / 2, FB, false>(h_hi, h_lo, (lds_ptr)&ring[0], (FB / 2) * HB * 2, b2, lane, g,
+                                                           a.act, a.P, F / a.P, st, gb);
+        feature_phi_finish<F>(st, a.act, a.P, F / a.P, gb);
+      }
+      den += xhalf_sum(dot_z<FB>(gb, a.z + (int64_t)bh * F, g));
+      __syncthreads();                          // second half of W2 no longer needed
+      stage_in(sthg, &ring[0], NST / 64);
+      stage_in(stlg, &ring[HALF], NST / 64);
+      landed();
+      contract_state<D, F>(gb, (lds_ptr)&ring[0], (lds_ptr)&ring[HALF], lane, o);
+      __syncthreads();                          // the ring becomes the staging area of the stores
+    }
+    store_tile<D, F32>(a, base, lane, o, 1.0f / den, stage, q0);
   } else {
     // the operands do not fit next to the ring: read in place (L2-resident, per head / per (batch, head))
     query_epilogue<D, HD, F, F32, false>(a, bh, h, base, lane, qf, o, lsum, global_frags(w1g, NW1 * 16),
