@@ -1,0 +1,142 @@
+"""fp64 CPU oracle for the gradient of the value-distillation objective with respect to the
+feature maps (Sec. 3.3: Alg. "distil", the update of phi = (phi_q, phi_k); Eq. "vd_loss").
+
+TEST INFRASTRUCTURE ONLY.  Plain chain rule, written out step by step in float64.  It shares no
+code with the GPU library and must never be imported by the product path.
+
+What it computes.  With q, k, v fixed (in the distillation stage everything but phi is frozen, so
+the attention inputs of the isolated layer are constants), the loss is
+
+    L = sum_{b,h,i,c} | y_i,c - y_hat_i,c |,     y = softmax attention (Eq. "softmax"),
+                                                  y_hat = hybrid attention (Eq. "hybrid")
+
+and y_hat_i = num_i / den_i with num_i = a_i + phi_q(q_i) S, den_i = l_i + phi_q(q_i) . z,
+S = sum_{T_L} phi_k(k_j)^T v_j, z = sum_{T_L} phi_k(k_j); a_i, l_i (the softmax-token sums) do
+not depend on phi.  The derivative is taken where it exists; at y_hat = y the subgradient 0 is
+used (sign(0) = 0).  Returned are dL/dW1, dL/db1, dL/dW2, dL/db2 of phi_q and of phi_k per head,
+summed over the batch (the parameters are shared by the batch; Alg. "distil" then divides by the
+number of samples, which is left to the caller).
+
+Readings taken: the loss is the plain sum (no mean); phi_q and phi_k are separate parameter sets;
+the sign pattern may be handed in (`sign_from`) as the pair of tensors both sides of a parity test
+look at, so that the one discontinuous decision of the gradient is taken from the same numbers.
+
+Pins (tests/test_value_distill_grad_oracle.py): reverse-mode automatic differentiation of an
+independent torch expression of the loss; central finite differences of the pinned loss oracle;
+exact zeros at R = 1; the shift invariance of the channel softmax (the b2 gradient sums to zero
+per head); planted mistakes that these must reject.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import hybrid_attn_oracle as O
+
+
+def feature_map_with_trace(x, fm: O.FeatureMap, head: int):
+    """phi(x) of Sec. 3.2 together with what its derivative needs: rows x [n, d] ->
+    (phi [n, F], hidden [n, Hd], pre-activation u [n, F], positive output t [n, F])."""
+    x = np.asarray(x, dtype=np.float64)
+    pre = x @ fm.w1[head].T + fm.b1[head]
+    hidden = np.maximum(pre, 0.0)
+    u = hidden @ fm.w2[head].T + fm.b2[head]
+    if fm.act == O.ACT_SOFTMAX:
+        e = np.exp(u - u.max(axis=-1, keepdims=True))
+        t = e / e.sum(axis=-1, keepdims=True)
+    elif fm.act == O.ACT_EXP:
+        t = np.exp(u)
+    elif fm.act == O.ACT_RELU:
+        t = np.maximum(u, 0.0)
+    else:
+        raise ValueError("unknown activation")
+    Dp = fm.F // fm.P
+    phi = np.empty_like(t)
+    for p in range(1, fm.P + 1):
+        sl = slice((p - 1) * Dp, p * Dp)
+        phi[:, sl] = t[:, sl] ** p
+    return phi, hidden, u, t
+
+
+def feature_map_backward(x, fm: O.FeatureMap, head: int, dphi):
+    """Given dL/dphi [n, F] for rows x [n, d], the gradient with respect to the parameters of the
+    map of this head: (dW1 [Hd, d], db1 [Hd], dW2 [F, Hd], db2 [F])."""
+    x = np.asarray(x, dtype=np.float64)
+    _, hidden, u, t = feature_map_with_trace(x, fm, head)
+    Dp = fm.F // fm.P
+    dt = np.empty_like(t)
+    for p in range(1, fm.P + 1):                         # phi_c = t_c ** p on slice p
+        sl = slice((p - 1) * Dp, p * Dp)
+        dt[:, sl] = dphi[:, sl] * p * t[:, sl] ** (p - 1)
+    if fm.act == O.ACT_SOFTMAX:                           # t = softmax(u) over the F channels
+        du = t * (dt - (t * dt).sum(axis=-1, keepdims=True))
+    elif fm.act == O.ACT_EXP:
+        du = dt * t
+    else:                                                 # ReLU
+        du = dt * (u > 0.0)
+    dw2 = du.T @ hidden
+    db2 = du.sum(axis=0)
+    dhidden = du @ fm.w2[head]
+    dpre = dhidden * (hidden > 0.0)
+    dw1 = dpre.T @ x
+    db1 = dpre.sum(axis=0)
+    return dw1, db1, dw2, db2
+
+
+def head_gradients(q, k, v, phi_q, phi_k, head, R, scale, sign=None):
+    """One (batch, head): q, k, v [N, d] -> (grads of phi_q, grads of phi_k, loss), each grads a tuple
+    (dW1, db1, dW2, db2).  `sign` [N, d], if given, replaces sign(y_hat - y)."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    N, d = q.shape
+    _, idx_l = O.token_split(N, R)
+    a_t, l_t, _ = O.softmax_part(q, k, v, 1, scale)                 # teacher: every token a softmax token
+    y = a_t / l_t[:, None]
+    a, l, _ = O.softmax_part(q, k, v, R, scale)                     # student's softmax-token sums
+    if idx_l.size == 0:                                             # no linear tokens: phi is unused
+        zq = tuple(np.zeros_like(t) for t in (phi_q.w1[head], phi_q.b1[head], phi_q.w2[head], phi_q.b2[head]))
+        zk = tuple(np.zeros_like(t) for t in (phi_k.w1[head], phi_k.b1[head], phi_k.w2[head], phi_k.b2[head]))
+        return zq, zk, float(np.abs(y - a / l[:, None]).sum())
+    fk = O.feature_map(k[idx_l], phi_k, head)                       # [N_L, F]
+    S = fk.T @ v[idx_l]
+    z = fk.sum(axis=0)
+    fq = O.feature_map(q, phi_q, head)                              # [N, F]
+    num = a + fq @ S
+    den = l + fq @ z
+    y_hat = num / den[:, None]
+    g = np.sign(y_hat - y) if sign is None else np.asarray(sign, dtype=np.float64)   # dL/dy_hat
+    dnum = g / den[:, None]                                         # y_hat = num / den
+    dden = -(g * y_hat).sum(axis=1) / den
+    dfq = dnum @ S.T + dden[:, None] * z[None, :]                   # through num and den to phi_q(q_i)
+    dS = fq.T @ dnum
+    dz = fq.T @ dden
+    dfk = v[idx_l] @ dS.T + dz[None, :]                             # through S and z to phi_k(k_j), j in T_L
+    gq = feature_map_backward(q, phi_q, head, dfq)
+    gk = feature_map_backward(k[idx_l], phi_k, head, dfk)
+    return gq, gk, float(np.abs(y - y_hat).sum())
+
+
+def value_distill_grad(q, k, v, phi_q, phi_k, R, scale, sign_from=None):
+    """Gradient of the value-distillation loss for q, k, v [B, H, N, d].
+
+    `sign_from` = (y_teacher, y_student), both [B, H, N, d]: when given, dL/dy_hat is the sign of
+    their difference (student minus teacher) instead of the sign of the float64 values computed here.
+    Returns (grads_q, grads_k, loss): grads_* is a dict with w1 [H, Hd, d], b1 [H, Hd], w2 [H, F, Hd],
+    b2 [H, F], summed over the batch."""
+    B, H, N, d = q.shape
+
+    def zeros(fm):
+        return dict(w1=np.zeros_like(fm.w1), b1=np.zeros_like(fm.b1), w2=np.zeros_like(fm.w2), b2=np.zeros_like(fm.b2))
+
+    out_q, out_k, loss = zeros(phi_q), zeros(phi_k), 0.0
+    for b in range(B):
+        for h in range(H):
+            sign = None
+            if sign_from is not None:
+                sign = np.sign(np.asarray(sign_from[1][b, h], dtype=np.float64) - np.asarray(sign_from[0][b, h], dtype=np.float64))
+            gq, gk, l_bh = head_gradients(q[b, h], k[b, h], v[b, h], phi_q, phi_k, h, R, scale, sign)
+            for out, g in ((out_q, gq), (out_k, gk)):
+                for name, t in zip(("w1", "b1", "w2", "b2"), g):
+                    out[name][h] += t
+            loss += l_bh
+    return out_q, out_k, loss

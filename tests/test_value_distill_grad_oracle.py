@@ -1,0 +1,179 @@
+"""Pins for the oracle's gradient of the value-distillation loss with respect to the feature maps
+(Sec. 3.3, Alg. "distil": phi <- phi - eta grad_phi L with L of Eq. "vd_loss")."""
+import importlib.util
+import inspect
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hybrid_attn_oracle as O
+from oracle import value_distill_grad_oracle as G
+from tests.test_oracle_pins import _rand_map
+
+NAMES = ("w1", "b1", "w2", "b2")
+
+
+def _inputs(seed, B=2, H=2, N=13, d=6):
+    rng = np.random.default_rng(seed)
+    return rng, tuple(rng.standard_normal((B, H, N, d)) for _ in range(3))
+
+
+def _torch_loss_and_grads(q, k, v, fq, fk, R, scale):
+    """The loss written once more with torch ops on float64 tensors (library softmax for the teacher, one
+    concatenated weight matrix for the student) and differentiated by torch's reverse-mode autograd."""
+    tq, tk, tv = (torch.tensor(t, dtype=torch.float64) for t in (q, k, v))
+    B, H, N, d = q.shape
+    par = {}
+    for tag, fm in (("q", fq), ("k", fk)):
+        par[tag] = [torch.tensor(getattr(fm, n), dtype=torch.float64, requires_grad=True) for n in NAMES]
+
+    def phi(x, tag, fm, h):
+        w1, b1, w2, b2 = par[tag]
+        u = torch.relu(x @ w1[h].T + b1[h]) @ w2[h].T + b2[h]
+        if fm.act == O.ACT_SOFTMAX:
+            t = torch.softmax(u, dim=-1)
+        elif fm.act == O.ACT_EXP:
+            t = torch.exp(u)
+        else:
+            t = torch.relu(u)
+        parts = torch.chunk(t, fm.P, dim=-1)
+        return torch.cat([c ** (i + 1) for i, c in enumerate(parts)], dim=-1)
+
+    is_s = torch.zeros(N, dtype=torch.bool) if R == 0 else (torch.arange(N) % R == 0)
+    loss = torch.zeros((), dtype=torch.float64)
+    for b in range(B):
+        for h in range(H):
+            logits = scale * tq[b, h] @ tk[b, h].T                              # [N, N]
+            teacher = torch.softmax(logits, dim=-1) @ tv[b, h]
+            w = torch.zeros(N, N, dtype=torch.float64)
+            if is_s.any():
+                ls = logits[:, is_s]
+                w[:, is_s] = torch.exp(ls - ls.max(dim=1, keepdim=True).values)
+            if (~is_s).any():
+                w[:, ~is_s] = phi(tq[b, h], "q", fq, h) @ phi(tk[b, h][~is_s], "k", fk, h).T
+            student = (w @ tv[b, h]) / w.sum(dim=1, keepdim=True)
+            loss = loss + (teacher - student).abs().sum()
+    if loss.requires_grad:
+        loss.backward()
+    grads = {tag: {n: (p.grad.numpy() if p.grad is not None else np.zeros(p.shape)) for n, p in zip(NAMES, par[tag])}
+             for tag in ("q", "k")}
+    return float(loss.detach()), grads
+
+
+def pin_against_autograd(M, seeds=(0, 1), acts=(O.ACT_SOFTMAX, O.ACT_EXP, O.ACT_RELU), rates=(0, 2, 3)):
+    for seed in seeds:
+        for act in acts:
+            for R in rates:
+                rng, (q, k, v) = _inputs(seed)
+                fq, fk = _rand_map(rng, 2, 6, 8, 6, 3, act), _rand_map(rng, 2, 6, 8, 6, 2, act)
+                gq, gk, loss = M.value_distill_grad(q, k, v, fq, fk, R, 0.45)
+                want_loss, want = _torch_loss_and_grads(q, k, v, fq, fk, R, 0.45)
+                np.testing.assert_allclose(loss, want_loss, rtol=1e-11)
+                for got, tag in ((gq, "q"), (gk, "k")):
+                    for n in NAMES:
+                        scale_ = np.abs(want[tag][n]).max() + 1e-30
+                        np.testing.assert_allclose(got[n], want[tag][n], rtol=1e-8, atol=1e-9 * scale_,
+                                                   err_msg=f"seed {seed} act {act} R {R} phi_{tag}.{n}")
+
+
+def test_matches_reverse_mode_autograd():
+    pin_against_autograd(G)
+
+
+def test_matches_central_finite_differences_of_the_loss():
+    """d loss / d theta for a handful of single parameters, from the loss oracle alone (which has its own
+    pins).  The loss is piecewise smooth; the step is small enough that no |.| changes branch."""
+    rng, (q, k, v) = _inputs(5, B=1)
+    fq, fk = _rand_map(rng, 2, 6, 8, 6, 2), _rand_map(rng, 2, 6, 8, 6, 2)
+    R, scale, eps = 3, 0.5, 1e-6
+    gq, gk, loss = G.value_distill_grad(q, k, v, fq, fk, R, scale)
+    np.testing.assert_allclose(loss, O.value_distill_loss(q, k, v, fq, fk, R, scale), rtol=1e-12)
+    pick = np.random.default_rng(9)
+    for fm, grads in ((fq, gq), (fk, gk)):
+        for n in NAMES:
+            arr = getattr(fm, n)
+            for _ in range(3):
+                idx = tuple(int(pick.integers(s)) for s in arr.shape)
+                keep = arr[idx]
+                arr[idx] = keep + eps
+                up = O.value_distill_loss(q, k, v, fq, fk, R, scale)
+                arr[idx] = keep - eps
+                dn = O.value_distill_loss(q, k, v, fq, fk, R, scale)
+                arr[idx] = keep
+                fd = (up - dn) / (2 * eps)
+                assert abs(fd - grads[n][idx]) <= 2e-5 * max(1.0, abs(fd)), (n, idx, fd, grads[n][idx])
+
+
+def test_no_linear_tokens_no_gradient():
+    """R = 1: T_L is empty, the student never evaluates phi, every gradient is exactly zero."""
+    rng, (q, k, v) = _inputs(2)
+    fq, fk = _rand_map(rng, 2, 6, 8, 6, 2), _rand_map(rng, 2, 6, 8, 6, 2)
+    gq, gk, loss = G.value_distill_grad(q, k, v, fq, fk, 1, 0.4)
+    assert loss == 0.0
+    for g in (gq, gk):
+        for n in NAMES:
+            assert g[n].shape == getattr(fq, n).shape and not g[n].any()
+
+
+def test_softmax_shift_invariance():
+    """Adding one constant to all F second-layer biases of a head leaves a softmax map unchanged, so the b2
+    gradient of every head sums to zero; phi_k's first-layer gradient vanishes for heads whose hidden units are
+    all switched off (b1 very negative)."""
+    rng, (q, k, v) = _inputs(3)
+    fq, fk = _rand_map(rng, 2, 6, 8, 6, 2), _rand_map(rng, 2, 6, 8, 6, 3)
+    fk.b1[1] = -1e3
+    gq, gk, _ = G.value_distill_grad(q, k, v, fq, fk, 2, 0.4)
+    for g in (gq, gk):
+        assert np.abs(g["b2"].sum(axis=1)).max() <= 1e-12 * np.abs(g["b2"]).max()
+    assert not gk["w1"][1].any() and not gk["b1"][1].any() and not gk["w2"][1].any()
+    assert gk["b2"][1].any() and gk["w1"][0].any()
+
+
+def test_batch_additivity_and_sign_override():
+    """Parameters are shared over the batch: the gradient is the sum of per-sample gradients.  Handing in the
+    exact outputs as `sign_from` changes nothing; flipping them flips every gradient."""
+    rng, (q, k, v) = _inputs(4, B=2)
+    fq, fk = _rand_map(rng, 2, 6, 8, 6, 2), _rand_map(rng, 2, 6, 8, 6, 2)
+    R, scale = 4, 0.4
+    gq, gk, loss = G.value_distill_grad(q, k, v, fq, fk, R, scale)
+    parts = [G.value_distill_grad(q[b:b + 1], k[b:b + 1], v[b:b + 1], fq, fk, R, scale) for b in range(2)]
+    y = O.hybrid_attn(q, k, v, None, None, 1, scale)
+    y_hat = O.hybrid_attn(q, k, v, fq, fk, R, scale)
+    same = G.value_distill_grad(q, k, v, fq, fk, R, scale, sign_from=(y, y_hat))
+    flipped = G.value_distill_grad(q, k, v, fq, fk, R, scale, sign_from=(y_hat, y))
+    for i, g in enumerate((gq, gk)):
+        for n in NAMES:
+            np.testing.assert_allclose(parts[0][i][n] + parts[1][i][n], g[n], rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(same[i][n], g[n], rtol=1e-13, atol=0)
+            np.testing.assert_allclose(flipped[i][n], -g[n], rtol=1e-13, atol=0)
+
+
+MUTATIONS = [
+    ("dden = -(g * y_hat).sum(axis=1) / den", "dden = (g * y_hat).sum(axis=1) / den"),                 # sign of the denominator path
+    ("dfq = dnum @ S.T + dden[:, None] * z[None, :]", "dfq = dnum @ S.T"),                             # dropped term
+    ("dfk = v[idx_l] @ dS.T + dz[None, :]", "dfk = v[idx_l] @ dS + dz[None, :]"),                      # transposed operand
+    ("du = t * (dt - (t * dt).sum(axis=-1, keepdims=True))", "du = t * dt"),                           # softmax Jacobian without its rank-one part
+    ("dt[:, sl] = dphi[:, sl] * p * t[:, sl] ** (p - 1)", "dt[:, sl] = dphi[:, sl] * t[:, sl] ** (p - 1)"),  # power rule without p
+    ("dpre = dhidden * (hidden > 0.0)", "dpre = dhidden"),                                             # ReLU gate
+    ("dw2 = du.T @ hidden", "dw2 = du.T @ np.maximum(hidden, 0.1)"),                                   # wrong activations
+    ("dS = fq.T @ dnum", "dS = fq.T @ g"),                                                             # missing 1/den
+]
+
+
+@pytest.mark.parametrize("old,new", MUTATIONS)
+def test_planted_mistakes_are_caught(old, new):
+    """A copy of the oracle's source with one mistake must fail the autograd pin."""
+    src = inspect.getsource(G)
+    assert src.count(old) == 1, "mutation target not found: " + old
+    spec = importlib.util.spec_from_loader("oracle._mutant_grad", loader=None)
+    mod = importlib.util.module_from_spec(spec)
+    mod.__package__ = "oracle"
+    sys.modules["oracle._mutant_grad"] = mod
+    try:
+        exec(compile(src.replace(old, new), "<mutant>", "exec"), mod.__dict__)
+        with pytest.raises((AssertionError, ValueError)):
+            pin_against_autograd(mod, seeds=(0,), acts=(O.ACT_SOFTMAX,), rates=(2,))
+    finally:
+        del sys.modules["oracle._mutant_grad"]
