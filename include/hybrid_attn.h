@@ -157,6 +157,35 @@ ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, con
                                          int teacher_is_cached, void *y_teacher, void *y_student, double *loss,
                                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Gradient of the value-distillation objective with respect to the two feature maps (Sec. 3.3: the update
+ * line of Alg. 1, phi <- phi - eta grad_phi L, with L of Eq. "vd_loss"; everything but phi_q, phi_k is frozen in
+ * that stage, so q, k, v are constants).  Buffers of one map's gradient, all device fp32, overwritten in full,
+ * summed over the batch (the parameters are shared by it): w1 [H, d_hidden, d_head], b1 [H, d_hidden],
+ * w2 [H, d_out, d_hidden], b2 [H, d_out].  All four are required, also for a map given without biases. */
+typedef struct ha_feature_map_grad {
+  float *w1, *b1, *w2, *b2;
+} ha_feature_map_grad;
+
+/* Enqueues: the teacher forward (unless teacher_is_cached), the student forward, which also leaves the
+ * denominator l_i + phi_q(q_i).z of every row of Eq. "hybrid" in row_den (unless student_is_cached: y_student
+ * and row_den are then inputs, e.g. kept from an earlier call with the same phi), the loss as in
+ * hybrid_attn_value_distill_loss, and the backward pass: d loss / d y_hat = sign(y_hat - y) taken from the two
+ * stored outputs (0 where they are equal), then the chain rule through Eq. "hybrid" and the feature maps
+ * (Sec. 3.2) down to the eight parameter tensors.  The loss is the plain sum, so is the gradient; Alg. 1's
+ * 1 / (m |T|) is the caller's.  row_den: device fp32 [B, H, N].  At hybrid_rate == 1 the gradients are zero.
+ * Supported here: feature maps with d_hidden == d_out == d_head (HA_ERR_UNSUPPORTED otherwise).  Matrix products
+ * run in bf16 with fp32 accumulation; the sums over tokens are formed in a fixed order (bitwise reproducible).
+ * workspace: device, 256-byte aligned, at least hybrid_attn_value_distill_grad_workspace_bytes() bytes.  Other
+ * arguments and errors as for hybrid_attn_value_distill_loss. */
+size_t hybrid_attn_value_distill_grad_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q,
+                                                      const ha_feature_map *phi_k);
+ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, const void *k, const void *v,
+                                         const ha_feature_map *phi_q, const ha_feature_map *phi_k,
+                                         int teacher_is_cached, int student_is_cached, void *y_teacher,
+                                         void *y_student, float *row_den, double *loss,
+                                         const ha_feature_map_grad *grad_q, const ha_feature_map_grad *grad_k,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Block-rate selection (Sec. 3.3, "Heterogeneous Block-Rate Optimization"; host memory only, no GPU
  * involved).  A model has n_blocks attention blocks and n_rates candidate hybrid rates; cost[i * n_rates + r]
  * and error[i * n_rates + r] (both >= 0, finite) are the pre-computed cost c_ir (flops or measured

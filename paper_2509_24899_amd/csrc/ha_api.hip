@@ -145,9 +145,9 @@ size_t hybrid_attn_workspace_bytes(const ha_problem *p, const ha_feature_map *ph
   return pl.total;
 }
 
-ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k, const void *v,
-                              const ha_feature_map *phi_q, const ha_feature_map *phi_k, void *out, void *workspace,
-                              size_t workspace_bytes, void *hip_stream) {
+static ha_status forward_impl(const ha_problem *p, const void *q, const void *k, const void *v,
+                              const ha_feature_map *phi_q, const ha_feature_map *phi_k, void *out, float *row_den,
+                              void *workspace, size_t workspace_bytes, void *hip_stream) {
   ha_status s = ha::validate(p, phi_q, phi_k);
   if (s != HA_OK) return s;
   if (!q || !k || !v || !out) return HA_ERR_NULL;
@@ -163,12 +163,18 @@ ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k,
   hipError_t e;
   if (pl.NL > 0 && (e = ha::launch_weight_prep(pl, *phi_q, true, workspace, st)) != hipSuccess) return ha::device_error(e);
   if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return ha::device_error(e);
-  if ((e = ha::launch_query(pl, q, phi_q, out, workspace, st)) != hipSuccess) return ha::device_error(e);
+  if ((e = ha::launch_query(pl, q, phi_q, out, row_den, workspace, st)) != hipSuccess) return ha::device_error(e);
   if (ev) {
     if ((e = hipEventRecord(ev[4], st)) != hipSuccess) return ha::device_error(e);
     ++ha::g_prof.count;
   }
   return HA_OK;
+}
+
+ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k, const void *v,
+                              const ha_feature_map *phi_q, const ha_feature_map *phi_k, void *out, void *workspace,
+                              size_t workspace_bytes, void *hip_stream) {
+  return forward_impl(p, q, k, v, phi_q, phi_k, out, nullptr, workspace, workspace_bytes, hip_stream);
 }
 
 ha_status hybrid_attn_profile_enable(int n_records) {
@@ -299,6 +305,96 @@ ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, con
   return HA_OK;
 }
 
+// Workspace of the gradient: the loss's layout, then the backward pass's buffers.
+static size_t grad_layout(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, ha::Plan &teacher,
+                          ha::Plan &student, size_t &off_partial, ha::GradPlan &gp) {
+  const size_t base = distill_layout(p, phi_q, phi_k, teacher, student, off_partial);
+  if (student.NL == 0) return base;
+  ha::make_grad_plan(student, base, gp);
+  return gp.total;
+}
+
+static ha_status check_grad_maps(const ha_problem *p, const ha_feature_map *phi_q, const ha_feature_map *phi_k) {
+  ha_status s = ha::validate(p, phi_q, phi_k);
+  if (s != HA_OK) return s;
+  if (!phi_q || !phi_k) return HA_ERR_NULL;      // also at rate 1: the shapes of the gradients come from the maps
+  if (p->hybrid_rate == 1) {
+    s = ha::check_map(phi_q, *p);
+    if (s == HA_OK) s = ha::check_map(phi_k, *p);
+    if (s != HA_OK) return s;
+  }
+  for (const ha_feature_map *fm : {phi_q, phi_k})
+    if (fm->d_hidden != p->d_head || fm->d_out != p->d_head) return HA_ERR_UNSUPPORTED;
+  return HA_OK;
+}
+
+size_t hybrid_attn_value_distill_grad_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q,
+                                                      const ha_feature_map *phi_k) {
+  if (check_grad_maps(p, phi_q, phi_k) != HA_OK) return 0;
+  ha::Plan t, s;
+  ha::GradPlan gp;
+  size_t off;
+  return grad_layout(*p, phi_q, phi_k, t, s, off, gp);
+}
+
+ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, const void *k, const void *v,
+                                         const ha_feature_map *phi_q, const ha_feature_map *phi_k,
+                                         int teacher_is_cached, int student_is_cached, void *y_teacher,
+                                         void *y_student, float *row_den, double *loss,
+                                         const ha_feature_map_grad *grad_q, const ha_feature_map_grad *grad_k,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+  ha_status s = check_grad_maps(p, phi_q, phi_k);
+  if (s != HA_OK) return s;
+  if (!q || !k || !v || !y_teacher || !y_student || !row_den || !loss || !grad_q || !grad_k) return HA_ERR_NULL;
+  for (const ha_feature_map_grad *gm : {grad_q, grad_k}) {
+    if (!gm->w1 || !gm->b1 || !gm->w2 || !gm->b2) return HA_ERR_NULL;
+    for (const float *t : {gm->w1, gm->b1, gm->w2, gm->b2})
+      if (reinterpret_cast<uintptr_t>(t) & 3u) return HA_ERR_ALIGN;
+  }
+  if (!ha::aligned16(q) || !ha::aligned16(k) || !ha::aligned16(v) || !ha::aligned16(y_teacher) ||
+      !ha::aligned16(y_student) || (reinterpret_cast<uintptr_t>(row_den) & 3u) || (reinterpret_cast<uintptr_t>(loss) & 7u))
+    return HA_ERR_ALIGN;
+  if (y_teacher == y_student) return HA_ERR_SHAPE;
+  ha::Plan pt, ps;
+  ha::GradPlan gp;
+  size_t off_partial;
+  const size_t need = grad_layout(*p, phi_q, phi_k, pt, ps, off_partial, gp);
+  if (!workspace || workspace_bytes < need) return HA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (!teacher_is_cached) {
+    ha_problem teacher = *p;
+    teacher.hybrid_rate = 1;
+    s = hybrid_attn_forward(&teacher, q, k, v, nullptr, nullptr, y_teacher, workspace, workspace_bytes, hip_stream);
+    if (s != HA_OK) return s;
+  }
+  hipError_t e;
+  if (!student_is_cached) {
+    s = forward_impl(p, q, k, v, phi_q, phi_k, y_student, row_den, workspace, workspace_bytes, hip_stream);
+    if (s != HA_OK) return s;
+  } else if (ps.NL > 0) {
+    // the backward pass needs S, z of the current phi_k in the workspace
+    s = ha::run_key_side(ps, k, v, phi_k, workspace, st);
+    if (s != HA_OK) return s;
+  }
+  double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + off_partial);
+  if ((e = ha::launch_l1_distance(ps, y_teacher, y_student, partial, loss, st)) != hipSuccess) return ha::device_error(e);
+  const size_t H = (size_t)p->H, D = (size_t)p->d_head;
+  if (ps.NL == 0) {
+    for (const ha_feature_map_grad *gm : {grad_q, grad_k}) {
+      if ((e = ha::launch_fill_zero(gm->w1, H * D * D, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->w2, H * D * D, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->b1, H * D, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->b2, H * D, st)) != hipSuccess) return ha::device_error(e);
+    }
+    return HA_OK;
+  }
+  e = ha::launch_value_distill_backward(ps, gp, q, k, v, *phi_q, *phi_k, y_teacher, y_student, row_den, *grad_q, *grad_k,
+                                        workspace, st);
+  if (e != hipSuccess) return ha::device_error(e);
+  return HA_OK;
+}
+
 const char *hybrid_attn_status_string(ha_status s) {
   switch (s) {
     case HA_OK: return "ok";
@@ -315,6 +411,6 @@ const char *hybrid_attn_status_string(ha_status s) {
 
 int hybrid_attn_last_device_error(void) { return ha::g_last_device_error; }
 
-int hybrid_attn_abi_version(void) { return 1; }
+int hybrid_attn_abi_version(void) { return 2; }
 
 }  // extern "C"

@@ -1,0 +1,551 @@
+// Gradient of the value-distillation loss (Attention Surgery, Sec. 3.3: Eq. "vd_loss" and the update line of
+// Alg. "distil") with respect to the two feature maps, gfx950.  q, k, v are constants of the isolated layer.
+//
+// With y_hat_i = num_i / den_i, num_i = a_i + phi_q(q_i) S, den_i = l_i + phi_q(q_i).z (Eq. "hybrid") and
+// g_i = sign(y_hat_i - y_i):
+//     dnum_i = g_i / den_i,   dden_i = -(g_i . y_hat_i) / den_i
+//     dphi_q(q_i) = S dnum_i + dden_i z          dS = sum_i phi_q(q_i)^T dnum_i,   dz = sum_i dden_i phi_q(q_i)
+//     dphi_k(k_j) = dS v_j + dz   (j in T_L)
+// and each dphi goes back through  phi = t^p (slice powers), t = softmax / exp / relu (u), u = W2 h + b2,
+// h = relu(W1 x + b1)  to  dW2 = sum du h^T, db2 = sum du, dW1 = sum dpre x^T, db1 = sum dpre.
+//
+//   grad_weight_prep_kernel   W2^T as A-operand fragments in chained order (for dh = W2^T du)
+//   natural_frags_kernel      an fp32 matrix (S or dS) as hi + lo bf16 A-operand fragments in natural order
+//   vd_rows_kernel            per row: the sign tensor g (bf16), 1 / den_i and -(g_i . y_hat_i)
+//   grad_kernel<QUERY>        one pass over the query tokens (QUERY) or the linear key tokens: recomputes the
+//                             map, forms dphi, du, dpre per 32-token column block in registers and contracts
+//                             over the tokens through LDS into per-chunk partial tiles of [dW2 | db2],
+//                             [dW1 | db1] and, for queries, [dS | dz]
+//   grad_reduce_kernel        fixed-order sum of the partial tiles over chunks (and over the batch for the
+//                             shared parameters) into plain row-major fp32
+//
+// As in the forward, every product is computed transposed (channels x tokens): one lane owns one token.
+#include "ha_device.h"
+#include "ha_plan.h"
+
+namespace ha {
+
+// ------------------------------------------------------------------------------------------------
+// grad_weight_prep_kernel: grid (ceil(HD*F / 256), H)
+//   w2tf[h][hb][fb][s][lane][t] = W2[h][32fb + crow(8s + t, g)][32hb + r]
+template <bool F32>
+__global__ __launch_bounds__(256) void grad_weight_prep_kernel(const void *__restrict__ w2, __bf16 *__restrict__ w2tf,
+                                                               int HD, int F) {
+  const int h = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= HD * F) return;
+  const int t = e & 7, lane = (e >> 3) & 63, rest = e >> 9;
+  const int r = lane & 31, g = lane >> 5;
+  const int FB = F / 32;
+  const int s = rest & 1, fb = (rest >> 1) % FB, hb = (rest >> 1) / FB;
+  const int64_t src = ((int64_t)h * F + 32 * fb + crow(8 * s + t, g)) * HD + 32 * hb + r;
+  float val;
+  if constexpr (F32) val = static_cast<const float *>(w2)[src];
+  else val = static_cast<float>(static_cast<const __bf16 *>(w2)[src]);
+  w2tf[(int64_t)h * HD * F + e] = static_cast<__bf16>(val);
+}
+
+// natural_frags_kernel: grid (ceil(rows*cols / 256), n_mat)
+//   hi/lo[m][rb][ks][lane][t] = M[m][32rb + r][16ks + 8g + t]
+__global__ __launch_bounds__(256) void natural_frags_kernel(const float *__restrict__ M, __bf16 *__restrict__ hi,
+                                                            __bf16 *__restrict__ lo, int rows, int cols) {
+  const int m = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= rows * cols) return;
+  const int t = e & 7, lane = (e >> 3) & 63, rest = e >> 9;
+  const int r = lane & 31, g = lane >> 5;
+  const int KS = cols / 16;
+  const int ks = rest % KS, rb = rest / KS;
+  const float val = M[((int64_t)m * rows + 32 * rb + r) * cols + 16 * ks + 8 * g + t];
+  const __bf16 h = static_cast<__bf16>(val);
+  hi[(int64_t)m * rows * cols + e] = h;
+  lo[(int64_t)m * rows * cols + e] = static_cast<__bf16>(val - static_cast<float>(h));
+}
+
+// ------------------------------------------------------------------------------------------------
+// vd_rows_kernel: grid (ceil(N / rows_per_block), B*H), 256 threads, D / 8 threads per row.
+//   gsign[bh][i][:] = sign(y_hat_i - y_i) (bf16, dense),  rs[bh][i] = 1 / den_i,  wp[bh][i] = -(g_i . y_hat_i)
+template <int D, bool F32>
+__global__ __launch_bounds__(256) void vd_rows_kernel(const void *__restrict__ y_teacher, const void *__restrict__ y_student,
+                                                      const float *__restrict__ row_den, bf16x8 *__restrict__ gsign,
+                                                      float *__restrict__ rs, float *__restrict__ wp, int H, int N,
+                                                      int64_t sb, int64_t sh, int64_t sn) {
+  constexpr int TPR = D / 8, RPB = 256 / TPR;
+  const int bh = blockIdx.y;
+  const int row = blockIdx.x * RPB + threadIdx.x / TPR, c8 = threadIdx.x % TPR;
+  const bool valid = row < N;
+  const int64_t base = (int64_t)(bh / H) * sb + (int64_t)(bh % H) * sh + (int64_t)(valid ? row : 0) * sn + c8 * 8;
+  float yt[8], ys[8];
+  if constexpr (F32) {
+    const float *a = static_cast<const float *>(y_teacher) + base, *b = static_cast<const float *>(y_student) + base;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) { yt[t] = a[t]; ys[t] = b[t]; }
+  } else {
+    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(y_teacher) + base);
+    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(y_student) + base);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) { yt[t] = static_cast<float>(a[t]); ys[t] = static_cast<float>(b[t]); }
+  }
+  bf16x8 gs;
+  float dot = 0.f;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const float diff = ys[t] - yt[t];
+    const float sg = diff > 0.f ? 1.f : (diff < 0.f ? -1.f : 0.f);
+    gs[t] = static_cast<__bf16>(sg);
+    dot += sg * ys[t];
+  }
+#pragma unroll
+  for (int m = 1; m < TPR; m <<= 1) dot += __shfl_xor(dot, m);
+  if (valid) {
+    gsign[((int64_t)bh * N + row) * TPR + c8] = gs;
+    if (c8 == 0) {
+      rs[(int64_t)bh * N + row] = 1.0f / row_den[(int64_t)bh * N + row];
+      wp[(int64_t)bh * N + row] = -dot;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// grad_kernel: grid (n_chunks, B*H), 4 waves; square maps (hidden width = feature width = D).  A chunk is CH
+// tokens of the pass's token set, walked in tiles of 128; wave w owns tokens 32 w .. 32 w + 31 of a tile.
+//
+// Per tile and wave, in registers (lane = token, registers = channels, as in the forward):
+//   h, t = activation(W2 h + b2)                       recomputed
+//   dphi = rs (M u) + wz zvec                          M = S, u = g_i, rs = 1/den_i, wz = dden_i   (queries)
+//                                                      M = dS, u = v_j, rs = wz = 1                 (keys)
+//   du   = activation'(t) (dphi p t^(p-1)),  dpre = (W2^T du) [h > 0]
+// then up to three contractions over the 128 tokens of the tile, each through the same two LDS arrays
+// (A side: rows x tokens, B side: columns x tokens, tokens contiguous, swizzled as in the state pass):
+//   queries only   [dS | dz]   += (rs phi) [g | wp]^T       wp = dden / rs in an extra hi + lo column pair
+//   always         [dW2 | db2] += du [h | 1]^T
+//                  [dW1 | db1] += dpre [x | 1]^T
+// Output row block w of each product belongs to wave w (waves >= T idle during the contractions).
+// Partial tiles go to part[bh][chunk][set][tile][v][lane], set order: dW2, dW1, dS.
+struct GradArgs {
+  const void *x;                    // q (queries) or k (keys): io dtype, strided
+  const void *u;                    // queries: sign tensor, bf16 dense [B*H][N][D]; keys: v, io dtype, strided
+  const float *rs, *wp;             // queries only: [B*H][N]
+  const bf16x8 *w1f, *w2f, *w2tf;   // per head
+  const float *b1, *b2;             // per head, may be null
+  const bf16x8 *m_hi, *m_lo;        // [B*H][D*D/8]: natural-order fragments of S (queries) or dS (keys)
+  const float *zvec;                // [B*H][D]: z (queries) or dz (keys)
+  float *part;
+  int H, N, NT, R, CH, P, act;
+  int64_t sb, sh, sn;
+};
+
+template <int D, bool F32, bool QUERY>
+__global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
+  constexpr int TOK = 128, PITCH = TOK + 8;
+  constexpr int KS = D / 16, T = D / 32, NCB = T + 1, NT2 = T * NCB;
+  constexpr int NSET = QUERY ? 3 : 2;
+  __shared__ __align__(16) __bf16 ft[D][PITCH];
+  __shared__ __align__(16) __bf16 vt[D][PITCH];
+  __shared__ __align__(16) __bf16 et[2][PITCH];
+  __shared__ bf16x8 wlds[2 * D * D / 8];
+  __shared__ float blds[3 * D];
+  const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % a.H;
+  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  {
+    const bf16x8 *w1g = a.w1f + (int64_t)h * (D * D / 8), *w2g = a.w2f + (int64_t)h * (D * D / 8);
+    for (int i = tid; i < D * D / 8; i += 256) {
+      wlds[i] = w1g[i];
+      wlds[D * D / 8 + i] = w2g[i];
+    }
+    for (int i = tid; i < D; i += 256) {
+      blds[i] = a.b1 ? a.b1[(int64_t)h * D + i] : 0.f;
+      blds[D + i] = a.b2 ? a.b2[(int64_t)h * D + i] : 0.f;
+      blds[2 * D + i] = a.zvec[(int64_t)bh * D + i];
+    }
+    __syncthreads();
+  }
+  const lds_frag_ptr w1f = (lds_frag_ptr)&wlds[0], w2f = (lds_frag_ptr)&wlds[D * D / 8];
+  const GlobalFrags w2tf = global_frags(a.w2tf + (int64_t)h * (D * D / 8), D * D * 2);
+  const GlobalFrags mhi = global_frags(a.m_hi + (int64_t)bh * (D * D / 8), D * D * 2);
+  const GlobalFrags mlo = global_frags(a.m_lo + (int64_t)bh * (D * D / 8), D * D * 2);
+  const float *b1 = &blds[0], *b2 = &blds[D], *zl = &blds[2 * D];
+  const int Dp = D / a.P;
+  const LinearMap lmap(QUERY ? 0 : a.R);
+
+  f32x16 acc2[NCB], acc1[NCB], accS[QUERY ? NCB : 1];
+#pragma unroll
+  for (int i = 0; i < NCB; ++i)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      acc2[i][x] = 0.f;
+      acc1[i][x] = 0.f;
+      if constexpr (QUERY) accS[i][x] = 0.f;
+    }
+
+  // LDS addressing (see the state pass): element (row, token) at row * PITCH + (((token / 8) ^ sw(row)) * 8 +
+  // token % 8), sw(row) = ((row / 8) % 4) * 2
+  const int tf = w * 32 + r;
+  int fcol[4];                                            // chained-order writes: rows 32 b + 8 q + 4 g + e
+#pragma unroll
+  for (int q = 0; q < 4; ++q) fcol[q] = (4 * g) * PITCH + ((((tf >> 3) ^ (2 * q)) << 3) | (tf & 7));
+  const int rsw = ((r >> 3) & 3) << 1;
+  __bf16 *ftp = &ft[0][0];
+  __bf16 *vtp = &vt[0][0];
+  auto park_chained = [&](__bf16 *arr, const bf16x8 (&val)[T][2]) {
+#pragma unroll
+    for (int b = 0; b < T; ++b)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) arr[(32 * b + 8 * (x >> 2) + (x & 3)) * PITCH + fcol[x >> 2]] = val[b][x >> 3][x & 7];
+  };
+  auto park_natural = [&](__bf16 *arr, const bf16x8 (&val)[KS]) {   // rows 16 ks + 8 g + i
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int sw = ((2 * ks + g) & 3) << 1;
+      const int col = (((tf >> 3) ^ sw) << 3) | (tf & 7);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) arr[(16 * ks + 8 * g + i) * PITCH + col] = val[ks][i];
+    }
+  };
+  // row block w of (A side) x all column blocks of (B side), plus the extra column block
+  auto contract = [&](f32x16 (&acc)[NCB], bool weighted) {
+    if (w < T) {
+      const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);
+      const bf16x8 ones = bf16x8{one, one, one, one, one, one, one, one};
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < TOK / 16; ++ks) {
+        const int col = ((2 * ks + g) ^ rsw) << 3;
+        const bf16x8 af = *reinterpret_cast<const bf16x8 *>(&ftp[(32 * w + r) * PITCH + col]);
+        bf16x8 bfr[NCB];
+#pragma unroll
+        for (int cb = 0; cb < T; ++cb) bfr[cb] = *reinterpret_cast<const bf16x8 *>(&vtp[(32 * cb + r) * PITCH + col]);
+        if (weighted) {
+          const bf16x8 ew = *reinterpret_cast<const bf16x8 *>(&et[r & 1][(2 * ks + g) << 3]);
+          bfr[T] = r < 2 ? ew : zero;
+        } else {
+          bfr[T] = ones;
+        }
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma32(af, bfr[cb], acc[cb]);
+      }
+    }
+  };
+
+  const int t_begin = chunk * a.CH;
+  const int t_end = min(t_begin + a.CH, a.NT);
+  for (int t0 = t_begin; t0 < t_end; t0 += TOK) {
+    const bool valid = t0 + tf < a.NT;
+    const int tok = lmap.token(min(t0 + tf, a.NT - 1));
+    bf16x8 xf[KS], uf[KS];
+    float rs_ = 1.f, wp_ = 1.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      xf[ks] = load8<F32>(a.x, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
+      if constexpr (QUERY) uf[ks] = static_cast<const bf16x8 *>(a.u)[((int64_t)bh * a.N + tok) * (D / 8) + 2 * ks + g];
+      else uf[ks] = load8<F32>(a.u, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
+    }
+    if constexpr (QUERY) {
+      rs_ = a.rs[(int64_t)bh * a.N + tok];
+      wp_ = a.wp[(int64_t)bh * a.N + tok];
+    }
+    const float wz_ = QUERY ? wp_ * rs_ : 1.f;             // dden_i = -(g_i . y_hat_i) / den_i
+
+    // the map, recomputed: h (hi + lo), t = positive output before the slice powers
+    bf16x8 h_hi[T][2];
+    f32x16 tt[T];
+    {
+      bf16x8 h_lo[T][2];
+      feature_mlp_layer1<D, D, true>(xf, w1f, b1, lane, g, h_hi, h_lo);
+      feature_mlp_layer2<D, D, true>(h_hi, h_lo, w2f, b2, lane, g, tt);
+      feature_activation<T>(tt, g, a.act, 1, D);
+    }
+    // dphi = rs (M u) + wz zvec
+    f32x16 dv[T];
+#pragma unroll
+    for (int fb = 0; fb < T; ++fb) {
+      f32x16 acc;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        acc = mfma32(frag_at(mlo, fb * KS + ks, lane), uf[ks], acc);
+        acc = mfma32(frag_at(mhi, fb * KS + ks, lane), uf[ks], acc);
+      }
+#pragma unroll
+      for (int x = 0; x < 16; ++x) dv[fb][x] = rs_ * acc[x] + wz_ * zl[32 * fb + crow(x, g)];
+    }
+
+    if constexpr (QUERY) {
+      // [dS | dz] += (rs phi) [g | wp]^T
+      bf16x8 a1[T][2];
+#pragma unroll
+      for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const int extra = (32 * fb + 8 * (x >> 2)) / Dp;      // wave-uniform
+          const float t0v = tt[fb][x];
+          float pw = t0v;
+          for (int i = 0; i < extra; ++i) pw *= t0v;
+          a1[fb][x >> 3][x & 7] = static_cast<__bf16>(valid ? rs_ * pw : 0.f);
+        }
+      park_chained(ftp, a1);
+      park_natural(vtp, uf);
+      if (g == 0) {
+        const __bf16 whi = static_cast<__bf16>(wp_);
+        et[0][tf] = whi;
+        et[1][tf] = static_cast<__bf16>(wp_ - static_cast<float>(whi));
+      }
+      __syncthreads();
+      contract(accS, true);
+      __syncthreads();
+    }
+
+    // back through the slice powers and the activation: dv becomes du
+    {
+      float dot = 0.f;
+#pragma unroll
+      for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const int extra = (32 * fb + 8 * (x >> 2)) / Dp;      // slice power p = extra + 1
+          const float t0v = tt[fb][x];
+          float pw = 1.f;
+          for (int i = 0; i < extra; ++i) pw *= t0v;
+          dv[fb][x] *= (float)(extra + 1) * pw;                 // d/dt of t^p
+          dot += t0v * dv[fb][x];
+        }
+      if (a.act == 0) {
+        dot = xhalf_sum(dot);
+#pragma unroll
+        for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) dv[fb][x] = tt[fb][x] * (dv[fb][x] - dot);
+      } else if (a.act == 1) {
+#pragma unroll
+        for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) dv[fb][x] *= tt[fb][x];
+      } else {
+#pragma unroll
+        for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) dv[fb][x] = tt[fb][x] > 0.f ? dv[fb][x] : 0.f;
+      }
+    }
+    bf16x8 dub[T][2];
+#pragma unroll
+    for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) dub[fb][x >> 3][x & 7] = static_cast<__bf16>(valid ? dv[fb][x] : 0.f);
+
+    // dpre = (W2^T du) [h > 0]
+    bf16x8 dpb[T][2];
+#pragma unroll
+    for (int hb = 0; hb < T; ++hb) {
+      f32x16 acc;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+#pragma unroll
+      for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) acc = mfma32(frag_at(w2tf, (hb * T + fb) * 2 + s, lane), dub[fb][s], acc);
+#pragma unroll
+      for (int x = 0; x < 16; ++x)
+        dpb[hb][x >> 3][x & 7] = static_cast<__bf16>(static_cast<float>(h_hi[hb][x >> 3][x & 7]) > 0.f ? acc[x] : 0.f);
+    }
+
+    // [dW2 | db2] += du [h | 1]^T
+    park_chained(ftp, dub);
+    park_chained(vtp, h_hi);
+    __syncthreads();
+    contract(acc2, false);
+    __syncthreads();
+    // [dW1 | db1] += dpre [x | 1]^T
+    park_chained(ftp, dpb);
+    park_natural(vtp, xf);
+    __syncthreads();
+    contract(acc1, false);
+    __syncthreads();
+  }
+  if (w < T) {
+    float *dst = a.part + (((int64_t)bh * gridDim.x + chunk) * NSET) * NT2 * 1024 + (int64_t)w * NCB * 1024;
+#pragma unroll
+    for (int i = 0; i < NCB; ++i)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        dst[i * 1024 + x * 64 + lane] = acc2[i][x];
+        dst[(NT2 + i) * 1024 + x * 64 + lane] = acc1[i][x];
+        if constexpr (QUERY) dst[(2 * NT2 + i) * 1024 + x * 64 + lane] = accS[i][x];
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// grad_reduce_kernel: grid (T*(T+1)*1024 / 256, n_out).  Output o sums set `set` of the partials over the
+// chunks of (batch b, head o) for every b (n_sum = B, shared parameters) or of (batch, head) pair o alone
+// (n_sum = 1), in a fixed order.  mat[o][row][col] row-major fp32, vec[o][row] = the extra column block
+// (columns 0 and 1: the hi and lo parts of a weighted sum, or the plain sum and zero).
+__global__ __launch_bounds__(256) void grad_reduce_kernel(const float *__restrict__ part, float *__restrict__ mat,
+                                                          float *__restrict__ vec, int D, int n_chunks, int n_sets,
+                                                          int set, int n_sum, int stride_sum) {
+  const int T = D / 32, NCB = T + 1, NT2 = T * NCB;
+  const int o = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= NT2 * 1024) return;
+  const int ti = e >> 10, x = (e >> 6) & 15, lane = e & 63, r = lane & 31, g = lane >> 5;
+  const int rb = ti / NCB, cb = ti % NCB;
+  if (cb == T && r != 0) return;
+  float sum = 0.f;
+  for (int b = 0; b < n_sum; ++b) {
+    const int64_t bh = (int64_t)b * stride_sum + o;
+    for (int c = 0; c < n_chunks; ++c) {
+      const float *src = part + ((bh * n_chunks + c) * n_sets + set) * (int64_t)NT2 * 1024 + e;
+      sum += src[0];
+      if (cb == T) sum += src[1];
+    }
+  }
+  const int row = 32 * rb + crow(x, g);
+  if (cb < T) mat[((int64_t)o * D + row) * D + 32 * cb + r] = sum;
+  else vec[(int64_t)o * D + row] = sum;
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+
+template <typename T>
+static inline T *ws_ptr(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
+static inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+void make_grad_plan(const Plan &pl, size_t base_off, GradPlan &gp) {
+  const size_t BH = (size_t)pl.B * pl.H;
+  const int D = pl.D, T = D / 32;
+  gp.tiles_per_set = T * (T + 1);
+  auto chunking = [&](int n_tok, int &CH, int &n_chunks) {
+    const int tiles = (n_tok + 127) / 128;
+    const int per_head = 256 / (int)BH > 0 ? 256 / (int)BH : 1;
+    const int want = tiles < per_head ? (tiles > 0 ? tiles : 1) : per_head;
+    CH = ((tiles + want - 1) / want) * 128;
+    if (CH < 128) CH = 128;
+    n_chunks = (n_tok + CH - 1) / CH;
+  };
+  chunking(pl.N, gp.CHq, gp.n_chunks_q);
+  chunking(pl.NL, gp.CHk, gp.n_chunks_k);
+  size_t off = base_off;
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+  gp.off_w2tq = take((size_t)pl.H * D * D * 2);
+  gp.off_w2tk = take((size_t)pl.H * D * D * 2);
+  gp.off_shi = take(BH * D * D * 2);
+  gp.off_slo = take(BH * D * D * 2);
+  gp.off_dS = take(BH * D * D * 4);
+  gp.off_dz = take(BH * D * 4);
+  gp.off_dshi = take(BH * D * D * 2);
+  gp.off_dslo = take(BH * D * D * 2);
+  gp.off_gsign = take(BH * pl.N * D * 2);
+  gp.off_rs = take(BH * pl.N * 4);
+  gp.off_wp = take(BH * pl.N * 4);
+  const size_t pq = BH * gp.n_chunks_q * 3 * gp.tiles_per_set * 1024 * 4;
+  const size_t pk = BH * gp.n_chunks_k * 2 * gp.tiles_per_set * 1024 * 4;
+  gp.off_part = take(pq > pk ? pq : pk);
+  gp.total = off;
+}
+
+hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  fill_zero_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, (int64_t)n);
+  return hipGetLastError();
+}
+
+// Everything after the student's forward: S, z are in the forward's workspace region (`pl` offsets), y_teacher,
+// y_student and row_den hold the two outputs and the student's row denominators.
+hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, const void *q, const void *k, const void *v,
+                                         const ha_feature_map &phi_q, const ha_feature_map &phi_k, const void *y_teacher,
+                                         const void *y_student, const float *row_den, const ha_feature_map_grad &gq,
+                                         const ha_feature_map_grad &gk, void *ws, hipStream_t st) {
+  const int D = pl.D, BH = pl.B * pl.H, T = D / 32;
+  hipError_t e;
+#define HA_CHECK() if ((e = hipGetLastError()) != hipSuccess) return e
+  // operand fragments: W1, W2 of both maps (forward order), W2^T (chained), S (natural, hi + lo)
+  if ((e = launch_weight_prep(pl, phi_q, true, ws, st)) != hipSuccess) return e;
+  if ((e = launch_weight_prep(pl, phi_k, false, ws, st)) != hipSuccess) return e;
+  {
+    dim3 grid((D * D + 255) / 256, pl.H);
+    if (pl.f32) {
+      grad_weight_prep_kernel<true><<<grid, 256, 0, st>>>(phi_q.w2, ws_ptr<__bf16>(ws, gp.off_w2tq), D, D);
+      grad_weight_prep_kernel<true><<<grid, 256, 0, st>>>(phi_k.w2, ws_ptr<__bf16>(ws, gp.off_w2tk), D, D);
+    } else {
+      grad_weight_prep_kernel<false><<<grid, 256, 0, st>>>(phi_q.w2, ws_ptr<__bf16>(ws, gp.off_w2tq), D, D);
+      grad_weight_prep_kernel<false><<<grid, 256, 0, st>>>(phi_k.w2, ws_ptr<__bf16>(ws, gp.off_w2tk), D, D);
+    }
+    HA_CHECK();
+    dim3 gridm((D * D + 255) / 256, BH);
+    natural_frags_kernel<<<gridm, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_S), ws_ptr<__bf16>(ws, gp.off_shi),
+                                                ws_ptr<__bf16>(ws, gp.off_slo), D, D);
+    HA_CHECK();
+  }
+  // per-row factors
+  {
+    const int rpb = 256 / (D / 8);
+    dim3 grid((pl.N + rpb - 1) / rpb, BH);
+#define HA_ROWS(DD, F32) \
+  vd_rows_kernel<DD, F32><<<grid, 256, 0, st>>>(y_teacher, y_student, row_den, ws_ptr<bf16x8>(ws, gp.off_gsign), \
+                                                ws_ptr<float>(ws, gp.off_rs), ws_ptr<float>(ws, gp.off_wp), pl.H, pl.N, \
+                                                pl.sb, pl.sh, pl.sn)
+    if (D == 64) { if (pl.f32) HA_ROWS(64, true); else HA_ROWS(64, false); }
+    else { if (pl.f32) HA_ROWS(128, true); else HA_ROWS(128, false); }
+#undef HA_ROWS
+    HA_CHECK();
+  }
+  GradArgs a;
+  a.H = pl.H; a.N = pl.N; a.R = pl.R; a.P = pl.P;
+  a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
+  a.part = ws_ptr<float>(ws, gp.off_part);
+  a.rs = ws_ptr<float>(ws, gp.off_rs);
+  a.wp = ws_ptr<float>(ws, gp.off_wp);
+  const dim3 rgrid(gp.tiles_per_set * 1024 / 256, pl.H), rgrid_bh(gp.tiles_per_set * 1024 / 256, BH);
+  // query pass: phi_q's gradient and [dS | dz]
+  {
+    a.x = q; a.u = ws_ptr<void>(ws, gp.off_gsign);
+    a.w1f = ws_ptr<bf16x8>(ws, pl.off_w1q); a.w2f = ws_ptr<bf16x8>(ws, pl.off_w2q); a.w2tf = ws_ptr<bf16x8>(ws, gp.off_w2tq);
+    a.b1 = phi_q.b1; a.b2 = phi_q.b2;
+    a.m_hi = ws_ptr<bf16x8>(ws, gp.off_shi); a.m_lo = ws_ptr<bf16x8>(ws, gp.off_slo);
+    a.zvec = ws_ptr<float>(ws, pl.off_z);
+    a.NT = pl.N; a.CH = gp.CHq; a.act = pl.act_q;
+    dim3 grid(gp.n_chunks_q, BH);
+    if (D == 64) { if (pl.f32) grad_kernel<64, true, true><<<grid, 256, 0, st>>>(a); else grad_kernel<64, false, true><<<grid, 256, 0, st>>>(a); }
+    else { if (pl.f32) grad_kernel<128, true, true><<<grid, 256, 0, st>>>(a); else grad_kernel<128, false, true><<<grid, 256, 0, st>>>(a); }
+    HA_CHECK();
+    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w2, gq.b2, D, gp.n_chunks_q, 3, 0, pl.B, pl.H);
+    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w1, gq.b1, D, gp.n_chunks_q, 3, 1, pl.B, pl.H);
+    grad_reduce_kernel<<<rgrid_bh, 256, 0, st>>>(a.part, ws_ptr<float>(ws, gp.off_dS), ws_ptr<float>(ws, gp.off_dz), D,
+                                                 gp.n_chunks_q, 3, 2, 1, 0);
+    HA_CHECK();
+    dim3 gridm((D * D + 255) / 256, BH);
+    natural_frags_kernel<<<gridm, 256, 0, st>>>(ws_ptr<float>(ws, gp.off_dS), ws_ptr<__bf16>(ws, gp.off_dshi),
+                                                ws_ptr<__bf16>(ws, gp.off_dslo), D, D);
+    HA_CHECK();
+  }
+  // key pass over the linear tokens: phi_k's gradient
+  {
+    a.x = k; a.u = v;
+    a.w1f = ws_ptr<bf16x8>(ws, pl.off_w1k); a.w2f = ws_ptr<bf16x8>(ws, pl.off_w2k); a.w2tf = ws_ptr<bf16x8>(ws, gp.off_w2tk);
+    a.b1 = phi_k.b1; a.b2 = phi_k.b2;
+    a.m_hi = ws_ptr<bf16x8>(ws, gp.off_dshi); a.m_lo = ws_ptr<bf16x8>(ws, gp.off_dslo);
+    a.zvec = ws_ptr<float>(ws, gp.off_dz);
+    a.NT = pl.NL; a.CH = gp.CHk; a.act = pl.act_k;
+    dim3 grid(gp.n_chunks_k, BH);
+    if (D == 64) { if (pl.f32) grad_kernel<64, true, false><<<grid, 256, 0, st>>>(a); else grad_kernel<64, false, false><<<grid, 256, 0, st>>>(a); }
+    else { if (pl.f32) grad_kernel<128, true, false><<<grid, 256, 0, st>>>(a); else grad_kernel<128, false, false><<<grid, 256, 0, st>>>(a); }
+    HA_CHECK();
+    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w2, gk.b2, D, gp.n_chunks_k, 2, 0, pl.B, pl.H);
+    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w1, gk.b1, D, gp.n_chunks_k, 2, 1, pl.B, pl.H);
+    HA_CHECK();
+  }
+#undef HA_CHECK
+  (void)T;
+  return hipSuccess;
+}
+
+}  // namespace ha

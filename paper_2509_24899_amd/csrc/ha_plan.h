@@ -23,6 +23,13 @@ struct Plan {
   size_t off_w1q, off_w2q, off_w1k, off_w2k, off_ks, off_vs, off_part, off_S, off_z, off_sthi, off_stlo, total;
 };
 
+// Workspace of the value-distillation gradient beyond the forward's: operand fragments of W2^T, S and dS, the
+// per-row factors, the sign tensor and the partial tiles of the two gradient passes.
+struct GradPlan {
+  int CHq, n_chunks_q, CHk, n_chunks_k, tiles_per_set;
+  size_t off_w2tq, off_w2tk, off_shi, off_slo, off_dS, off_dz, off_dshi, off_dslo, off_gsign, off_rs, off_wp, off_part, total;
+};
+
 // Fills `pl` from a validated problem.  Pure host arithmetic.
 void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, Plan &pl);
 
@@ -32,11 +39,18 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, void *ws
 hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_feature_map &phi_k, void *ws,
                         hipStream_t st);
 hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st);
-hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
+hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, float *row_den, void *ws,
                         hipStream_t st);
 size_t l1_partial_bytes(const Plan &pl);
 hipError_t launch_l1_distance(const Plan &pl, const void *ya, const void *yb, double *partial, double *loss,
                               hipStream_t st);
+// ha_grad.hip
+void make_grad_plan(const Plan &pl, size_t base_off, GradPlan &gp);
+hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
+hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, const void *q, const void *k, const void *v,
+                                         const ha_feature_map &phi_q, const ha_feature_map &phi_k, const void *y_teacher,
+                                         const void *y_student, const float *row_den, const ha_feature_map_grad &gq,
+                                         const ha_feature_map_grad &gk, void *ws, hipStream_t st);
 hipError_t launch_mfma_probe(float *sink, int workgroups, int iters, int random_operands, hipStream_t st);
 
 }  // namespace ha

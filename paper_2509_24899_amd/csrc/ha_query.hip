@@ -20,6 +20,7 @@ struct QueryArgs {
   const float *b1, *b2;                 // phi_q biases, per head (may be null)
   const bf16x8 *st_hi, *st_lo;           // [B*H][D/32][F/32][2][64]
   const float *z;                       // [B*H][F]
+  float *row_den;                       // optional [B*H][N]: the denominator l_i + phi_q(q_i).z of every row
   int H, N, NS, n_qtiles, n_ktiles, n_kblocks, total_wg;
   int has_linear, P, act;
   int64_t sb, sh, sn;
@@ -83,6 +84,12 @@ static __device__ __forceinline__ void contract_state(const bf16x8 (&gb)[F / 32]
 // 8-byte pieces 256 bytes apart across lanes.  The tile goes through this wave's LDS staging area instead
 // ([32 queries][channels of one pass], rows padded by 16 bytes) and leaves as 16-byte pieces with
 // consecutive lanes on consecutive addresses of a row.
+// Row denominators for a caller that differentiates the output (value distillation): lane r of the lower half
+// holds the denominator of query q_first + r.
+static __device__ __forceinline__ void store_den(const QueryArgs &a, int bh, int lane, float den, int q_first) {
+  if (a.row_den && lane < 32 && q_first + lane < a.N) a.row_den[(int64_t)bh * a.N + q_first + lane] = den;
+}
+
 template <int D, bool F32>
 static __device__ __forceinline__ void store_tile(const QueryArgs &a, int64_t base, int lane, const f32x16 (&o)[D / 32],
                                                   float inv, char *stage, int q_first) {
@@ -154,6 +161,7 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
   if constexpr (ELDS) {
     if (a.has_linear) __syncthreads();   // every wave is done with the operands in the ring: it becomes the staging area
   }
+  store_den(a, bh, lane, den, q_first);
   store_tile<D, F32>(a, base, lane, o, 1.0f / den, stage, q_first);
 }
 
@@ -475,6 +483,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
       contract_state<D, F>(gb, (lds_ptr)&ring[0], (lds_ptr)&ring[HALF], lane, o);
       __syncthreads();                          // the ring becomes the staging area of the stores
     }
+    store_den(a, bh, lane, den, q0);
     store_tile<D, F32>(a, base, lane, o, 1.0f / den, stage, q0);
   } else {
     // the operands do not fit next to the ring: read in place (L2-resident, per head / per (batch, head))
@@ -484,11 +493,12 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   }
 }
 
-hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, void *ws,
+hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, float *row_den, void *ws,
                         hipStream_t st) {
   QueryArgs a;
   a.q = q;
   a.out = out;
+  a.row_den = row_den;
   a.ks_frag = ws_ptr<bf16x8>(ws, pl.off_ks);
   a.vs_frag = ws_ptr<bf16x8>(ws, pl.off_vs);
   a.w1f = ws_ptr<bf16x8>(ws, pl.off_w1q);

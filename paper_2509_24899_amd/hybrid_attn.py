@@ -27,6 +27,10 @@ class ha_feature_map(ctypes.Structure):
                 ("out_act", ctypes.c_int32)]
 
 
+class ha_feature_map_grad(ctypes.Structure):
+    _fields_ = [("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
+
+
 class ha_problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d_head", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32), ("hybrid_rate", ctypes.c_int32),
@@ -87,6 +91,12 @@ def _lib():
         lib.hybrid_attn_select_rates.argtypes = [ctypes.c_int, ctypes.c_int, dp, dp, ctypes.c_double,
                                                  ctypes.POINTER(ctypes.c_int), dp, dp]
         lib.hybrid_attn_select_rates.restype = ctypes.c_int
+        lib.hybrid_attn_value_distill_grad_workspace_bytes.argtypes = [P, FM, FM]
+        lib.hybrid_attn_value_distill_grad_workspace_bytes.restype = ctypes.c_size_t
+        FMG = ctypes.POINTER(ha_feature_map_grad)
+        lib.hybrid_attn_value_distill_grad.argtypes = [P, vp, vp, vp, FM, FM, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp,
+                                                       FMG, FMG, vp, ctypes.c_size_t, vp]
+        lib.hybrid_attn_value_distill_grad.restype = ctypes.c_int
         lib.hybrid_attn_abi_version.argtypes = []
         lib.hybrid_attn_abi_version.restype = ctypes.c_int
         _LIB = lib
@@ -296,6 +306,59 @@ def hybrid_attn_value_distill_loss(q, k, v, phi_q: Optional[FeatureMap], phi_k: 
     if st != HA_OK:
         raise HybridAttnError(st, "hybrid_attn_value_distill_loss")
     return loss, y_teacher, y_student
+
+
+def hybrid_attn_value_distill_grad(q, k, v, phi_q: FeatureMap, phi_k: FeatureMap, hybrid_rate: int, block_size: int = 128,
+                                   softmax_scale: Optional[float] = None, y_teacher=None, teacher_is_cached: bool = False,
+                                   y_student=None, row_den=None, student_is_cached: bool = False, workspace=None,
+                                   stream=None):
+    """Loss and gradient of the value-distillation step (Sec. 3.3, Alg. 1): returns (loss, grads_q, grads_k, y_teacher,
+    y_student, row_den); grads_* is a dict of fp32 device tensors w1 [H, Hd, d], b1 [H, Hd], w2 [H, F, Hd], b2 [H, F]
+    summed over the batch.  Does not synchronise."""
+    _require_gpu(q, k, v)
+    if softmax_scale is None:
+        softmax_scale = float(q.shape[-1]) ** -0.5
+    if y_teacher is None:
+        if teacher_is_cached:
+            raise ValueError("teacher_is_cached needs y_teacher")
+        y_teacher = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    if student_is_cached and (y_student is None or row_den is None):
+        raise ValueError("student_is_cached needs y_student and row_den")
+    if y_student is None:
+        y_student = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    if row_den is None:
+        row_den = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    if row_den.dtype != torch.float32 or not row_den.is_contiguous() or tuple(row_den.shape) != tuple(q.shape[:3]):
+        raise ValueError("row_den must be a contiguous fp32 tensor [B, H, N]")
+    _same_layout(q, k, v, y_teacher, y_student)
+    prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
+    sq, pq = _fm_ptr(phi_q)
+    sk, pk = _fm_ptr(phi_k)
+    lib = _lib()
+    need = lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(prob), pq, pk)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    B, H = q.shape[0], q.shape[1]
+    loss = torch.empty(1 + B * H, dtype=torch.float64, device=q.device)
+
+    def grads_of(fm):
+        t = dict(w1=torch.empty(fm.w1.shape, dtype=torch.float32, device=q.device),
+                 b1=torch.empty(fm.w1.shape[:2], dtype=torch.float32, device=q.device),
+                 w2=torch.empty(fm.w2.shape, dtype=torch.float32, device=q.device),
+                 b2=torch.empty(fm.w2.shape[:2], dtype=torch.float32, device=q.device))
+        return t, ha_feature_map_grad(t["w1"].data_ptr(), t["b1"].data_ptr(), t["w2"].data_ptr(), t["b2"].data_ptr())
+
+    gq, cq = grads_of(phi_q)
+    gk, ck = grads_of(phi_k)
+    stream_handle = (stream if stream is not None else torch.cuda.current_stream(q.device)).cuda_stream
+    st = lib.hybrid_attn_value_distill_grad(ctypes.byref(prob), q.data_ptr(), k.data_ptr(), v.data_ptr(), pq, pk,
+                                            int(teacher_is_cached), int(student_is_cached), y_teacher.data_ptr(),
+                                            y_student.data_ptr(), row_den.data_ptr(), loss.data_ptr(), ctypes.byref(cq),
+                                            ctypes.byref(ck), workspace.data_ptr(),
+                                            workspace.numel() * workspace.element_size(), stream_handle)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_value_distill_grad")
+    return loss, gq, gk, y_teacher, y_student, row_den
 
 
 def hybrid_attn_linear_state(k, v, phi_k: FeatureMap, hybrid_rate: int, block_size: int = 128, workspace=None,
