@@ -134,6 +134,62 @@ def rate_selection_mode(args, w, ha, W, torch, q, k, v, fq, fk, out):
     print(json.dumps(rec), flush=True)
 
 
+def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
+    """One student update of the attention-distillation loop (Sec. 3.3, Alg. 1, inner loop) on the cached teacher
+    output: student forward, loss, gradient with respect to phi_q and phi_k.  Prints one JSON line."""
+    assert w.R != 1 and w.d_hidden == w.d and w.d_feat == w.d, "the gradient needs linear tokens and d -> d -> d maps"
+    prob = ha.make_problem(q, w.R, w.block_size, w.scale)
+    lib_ws = torch.empty(max(ha.hybrid_attn_value_distill_grad_workspace_bytes(prob, fq, fk), 256), dtype=torch.uint8,
+                         device=q.device)
+    loss, gq, gk, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale, workspace=lib_ws)
+    torch.cuda.synchronize()
+
+    def full_step():
+        ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
+                                          y_student=ys, row_den=rd, workspace=lib_ws)
+
+    def backward_only():
+        ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
+                                          y_student=ys, row_den=rd, student_is_cached=True, workspace=lib_ws)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
+
+    wall_full, ev_full = timed(full_step)
+    _, ev_bwd = timed(backward_only)          # state pass + loss + backward (no student query kernel)
+    n_l = w.n_linear
+    # algorithmic flops of the backward pass per token: map recomputed (d Hd + Hd F), dphi (F d), W2^T du (F Hd),
+    # dW2 (F Hd), dW1 (Hd d); queries also dS (F d); 2 flops per multiply-add
+    per_q = 2.0 * (w.d * w.d_hidden + w.d_hidden * w.d_feat + w.d_feat * w.d + 2 * w.d_feat * w.d_hidden + w.d_hidden * w.d + w.d_feat * w.d)
+    per_k = per_q - 2.0 * w.d_feat * w.d
+    bwd_flops = w.B * w.H * (w.N * per_q + n_l * per_k)
+    rec = {
+        "metric": "value-distillation step tokens/s", "value": w.B * w.N / (wall_full * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_full, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype, "hybrid_rate_R": w.R,
+                   "block_size": w.block_size, "feature_map": f"{w.d}->{w.d_hidden}->{w.d_feat}, P={w.poly_degree}",
+                   "step": "student forward + loss + gradient of phi_q, phi_k (teacher output cached)"},
+        "step_ms_events": ev_full, "backward_with_state_pass_and_loss_ms": ev_bwd,
+        "roofline": {"bound": "mfma", "kernel": "grad_kernel (query pass + key pass) with its small helpers", "achieved":
+                     bwd_flops / (ev_bwd * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": bwd_flops / (ev_bwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "kernel_ms": ev_bwd, "traffic": None},
+        "loss": float(loss[0].item()),
+        "grad_norms": {side + "." + n: float(g[n].double().norm().item()) for side, g in (("phi_q", gq), ("phi_k", gk)) for n in g},
+    }
+    print(json.dumps(rec), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +209,10 @@ def main():
     ap.add_argument("--measured-errors", action="store_true",
                     help="with --select-rates: take e_{l,R} from the value-distillation loss (Eq. vd_loss) of layer l's own "
                          "seeded random feature maps on the shared synthetic q, k, v instead of drawing it")
+    ap.add_argument("--distill-step", action="store_true",
+                    help="time one student update of the distillation loop (Sec. 3.3, Alg. 1: student forward, loss, gradient "
+                         "of the feature maps on the cached teacher output) and print one JSON line about it instead of the "
+                         "headline line")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="all-zero q, k, v: NOT a benchmark, a power / clock experiment (same instruction stream, idle data wires)")
     ap.add_argument("--no-cold-cache", action="store_true", help="skip the extra forwards with flushed caches")
@@ -203,6 +263,9 @@ def main():
     def step():
         ha.hybrid_attn_forward(q, k, v, fq, fk, w.R, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
 
+    if args.distill_step:
+        distill_step_mode(args, w, ha, torch, q, k, v, fq, fk)
+        return
     if args.select_rates is not None:
         rate_selection_mode(args, w, ha, W, torch, q, k, v, fq if fq else dmap(), fk if fk else dmap(), out)
         return

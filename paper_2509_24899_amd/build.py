@@ -17,6 +17,13 @@ HIPCC_FLAGS = [
 ]
 
 
+# Per-file additions.  ha_grad.hip: its kernels run one wave per SIMD with 512 registers; selecting the matrix
+# instructions in their vector-register form keeps the transient products of the feature-map recomputation out
+# of the accumulator file, which the persistent partial sums fill (otherwise those are spilled to scratch and
+# reloaded in every tile).
+FILE_FLAGS = {"ha_grad.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"], "ha_kernels.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PATH, tag: str = "") -> str:
     """Compile every source and link the shared library (libhybridattn.so by default); returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -24,7 +31,7 @@ def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PAT
     objs, procs = [], []
     for src in SOURCES:
         obj = os.path.join(LIB_DIR, src.replace(".hip", tag + ".o"))
-        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -151,16 +151,34 @@ static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g
 //    fragment of a weight matrix, hoists them out of the loops and spills them.)  Reads past `bytes` return 0.
 typedef const __attribute__((address_space(3))) bf16x8 *lds_frag_ptr;
 struct GlobalFrags {
-  __amdgpu_buffer_rsrc_t rsrc;
+  const bf16x8 *base;
+  int bytes;
 };
-static __device__ __forceinline__ GlobalFrags global_frags(const bf16x8 *base, int bytes) {
-  // word 3 of the descriptor: raw 32-bit data format of gfx9-family buffers
-  return GlobalFrags{__builtin_amdgcn_make_buffer_rsrc(const_cast<bf16x8 *>(base), 0, bytes, 0x00020000)};
+static __device__ __forceinline__ GlobalFrags global_frags(const bf16x8 *base, int bytes) { return GlobalFrags{base, bytes}; }
+// The descriptor is rebuilt at every use from a base address that is pinned to scalar registers: a descriptor
+// the compiler parks in vector registers turns every read into a loop over its distinct values with a full
+// wait behind it.  Word 3: raw 32-bit data format of gfx9-family buffers.
+static __device__ __forceinline__ __amdgpu_buffer_rsrc_t frag_rsrc(const GlobalFrags &f) {
+  const uint64_t p = reinterpret_cast<uint64_t>(f.base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(p));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(p >> 32));
+  void *q = reinterpret_cast<void *>((static_cast<uint64_t>(hi) << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(q, 0, __builtin_amdgcn_readfirstlane(f.bytes), 0x00020000);
 }
 static __device__ __forceinline__ bf16x8 frag_at(lds_frag_ptr base, int idx, int lane) { return base[idx * 64 + lane]; }
 static __device__ __forceinline__ bf16x8 frag_at(const GlobalFrags &f, int idx, int lane) {
-  typedef int i32x4 __attribute__((ext_vector_type(4)));
-  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(f.rsrc, lane * 16, idx * 1024, 0));
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(frag_rsrc(f), lane * 16, idx * 1024, 0));
+}
+// A zero the compiler cannot see through.  Added to the scalar offset of fragment reads inside a loop whose
+// fragments are the same in every iteration, it keeps those reads in the loop (hoisted, a whole operand matrix
+// would sit in registers, i.e. in scratch).
+static __device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+s"(z));
+  return z;
+}
+static __device__ __forceinline__ bf16x8 frag_at(const GlobalFrags &f, int idx, int lane, int soff) {
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(frag_rsrc(f), lane * 16, idx * 1024 + soff, 0));
 }
 
 // BATCH: request all weight fragments of a block before its chain of matrix instructions starts, so the chain

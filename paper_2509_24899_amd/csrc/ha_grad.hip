@@ -12,10 +12,11 @@
 //   grad_weight_prep_kernel   W2^T as A-operand fragments in chained order (for dh = W2^T du)
 //   natural_frags_kernel      an fp32 matrix (S or dS) as hi + lo bf16 A-operand fragments in natural order
 //   vd_rows_kernel            per row: the sign tensor g (bf16), 1 / den_i and -(g_i . y_hat_i)
+//   (state_kernel, weighted)  [dS | dz] over all query tokens: the forward's state pass with q in place of k, the
+//                             sign tensor in place of v, rows scaled by 1 / den_i and dden_i den_i in place of 1
 //   grad_kernel<QUERY>        one pass over the query tokens (QUERY) or the linear key tokens: recomputes the
 //                             map, forms dphi, du, dpre per 32-token column block in registers and contracts
-//                             over the tokens through LDS into per-chunk partial tiles of [dW2 | db2],
-//                             [dW1 | db1] and, for queries, [dS | dz]
+//                             over the tokens through LDS into per-chunk partial tiles of [dW2 | db2], [dW1 | db1]
 //   grad_reduce_kernel        fixed-order sum of the partial tiles over chunks (and over the batch for the
 //                             shared parameters) into plain row-major fp32
 //
@@ -120,13 +121,21 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, i
 //   dphi = rs (M u) + wz zvec                          M = S, u = g_i, rs = 1/den_i, wz = dden_i   (queries)
 //                                                      M = dS, u = v_j, rs = wz = 1                 (keys)
 //   du   = activation'(t) (dphi p t^(p-1)),  dpre = (W2^T du) [h > 0]
-// then up to three contractions over the 128 tokens of the tile, each through the same two LDS arrays
+// then two contractions over the 128 tokens of the tile, each through the same two LDS arrays
 // (A side: rows x tokens, B side: columns x tokens, tokens contiguous, swizzled as in the state pass):
-//   queries only   [dS | dz]   += (rs phi) [g | wp]^T       wp = dden / rs in an extra hi + lo column pair
-//   always         [dW2 | db2] += du [h | 1]^T
-//                  [dW1 | db1] += dpre [x | 1]^T
+//   [dW2 | db2] += du [h | 1]^T
+//   [dW1 | db1] += dpre [x | 1]^T
 // Output row block w of each product belongs to wave w (waves >= T idle during the contractions).
-// Partial tiles go to part[bh][chunk][set][tile][v][lane], set order: dW2, dW1, dS.
+// Partial tiles go to part[bh][chunk][set][tile][v][lane], set order: dW2, dW1.
+// t^e for a small wave-uniform exponent e in 0..7, branch-free
+static __device__ __forceinline__ float pow_small(float t, int e) {
+  const float t2 = t * t;
+  float r = (e & 1) ? t : 1.f;
+  r = (e & 2) ? r * t2 : r;
+  r = (e & 4) ? r * (t2 * t2) : r;
+  return r;
+}
+
 struct GradArgs {
   const void *x;                    // q (queries) or k (keys): io dtype, strided
   const void *u;                    // queries: sign tensor, bf16 dense [B*H][N][D]; keys: v, io dtype, strided
@@ -144,10 +153,9 @@ template <int D, bool F32, bool QUERY>
 __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
   constexpr int TOK = 128, PITCH = TOK + 8;
   constexpr int KS = D / 16, T = D / 32, NCB = T + 1, NT2 = T * NCB;
-  constexpr int NSET = QUERY ? 3 : 2;
+  constexpr int NSET = 2;
   __shared__ __align__(16) __bf16 ft[D][PITCH];
   __shared__ __align__(16) __bf16 vt[D][PITCH];
-  __shared__ __align__(16) __bf16 et[2][PITCH];
   __shared__ bf16x8 wlds[2 * D * D / 8];
   __shared__ float blds[3 * D];
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % a.H;
@@ -172,137 +180,170 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
   const GlobalFrags mhi = global_frags(a.m_hi + (int64_t)bh * (D * D / 8), D * D * 2);
   const GlobalFrags mlo = global_frags(a.m_lo + (int64_t)bh * (D * D / 8), D * D * 2);
   const float *b1 = &blds[0], *b2 = &blds[D], *zl = &blds[2 * D];
+
   const int Dp = D / a.P;
   const LinearMap lmap(QUERY ? 0 : a.R);
 
-  f32x16 acc2[NCB], acc1[NCB], accS[QUERY ? NCB : 1];
+  f32x16 acc2[NCB], acc1[NCB];
 #pragma unroll
   for (int i = 0; i < NCB; ++i)
 #pragma unroll
     for (int x = 0; x < 16; ++x) {
       acc2[i][x] = 0.f;
       acc1[i][x] = 0.f;
-      if constexpr (QUERY) accS[i][x] = 0.f;
     }
 
   // LDS addressing (see the state pass): element (row, token) at row * PITCH + (((token / 8) ^ sw(row)) * 8 +
   // token % 8), sw(row) = ((row / 8) % 4) * 2
+  // (the address pieces below are the same in every tile; they are formed from `zt`, a zero the compiler cannot
+  // see through that is refreshed per tile, so that they are recomputed with two or three instructions where
+  // they are used instead of living, i.e. being spilled, across the whole tile)
   const int tf = w * 32 + r;
-  int fcol[4];                                            // chained-order writes: rows 32 b + 8 q + 4 g + e
-#pragma unroll
-  for (int q = 0; q < 4; ++q) fcol[q] = (4 * g) * PITCH + ((((tf >> 3) ^ (2 * q)) << 3) | (tf & 7));
-  const int rsw = ((r >> 3) & 3) << 1;
+  int zt = 0;
   __bf16 *ftp = &ft[0][0];
   __bf16 *vtp = &vt[0][0];
   auto park_chained = [&](__bf16 *arr, const bf16x8 (&val)[T][2]) {
+    const int tfz = tf + zt;
+    int fcol[4];                                          // chained-order writes: rows 32 b + 8 q + 4 g + e
+#pragma unroll
+    for (int q = 0; q < 4; ++q) fcol[q] = (4 * g) * PITCH + ((((tfz >> 3) ^ (2 * q)) << 3) | (tfz & 7));
 #pragma unroll
     for (int b = 0; b < T; ++b)
 #pragma unroll
       for (int x = 0; x < 16; ++x) arr[(32 * b + 8 * (x >> 2) + (x & 3)) * PITCH + fcol[x >> 2]] = val[b][x >> 3][x & 7];
   };
   auto park_natural = [&](__bf16 *arr, const bf16x8 (&val)[KS]) {   // rows 16 ks + 8 g + i
+    const int tfz = tf + zt;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int sw = ((2 * ks + g) & 3) << 1;
-      const int col = (((tf >> 3) ^ sw) << 3) | (tf & 7);
+      const int col = (((tfz >> 3) ^ sw) << 3) | (tfz & 7);
 #pragma unroll
       for (int i = 0; i < 8; ++i) arr[(16 * ks + 8 * g + i) * PITCH + col] = val[ks][i];
     }
   };
   // row block w of (A side) x all column blocks of (B side), plus the extra column block
-  auto contract = [&](f32x16 (&acc)[NCB], bool weighted) {
+  auto contract = [&](f32x16 (&acc)[NCB]) {
     if (w < T) {
       const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);
       const bf16x8 ones = bf16x8{one, one, one, one, one, one, one, one};
-      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      const int rz = r + zt;
+      const int rsw = ((rz >> 3) & 3) << 1;
+      const int arow = (32 * w + rz) * PITCH, brow = rz * PITCH;
+      // four 16-token slices at a time: their fragments are requested before the matrix instructions that use them
+      constexpr int KB = 4;
 #pragma unroll
-      for (int ks = 0; ks < TOK / 16; ++ks) {
-        const int col = ((2 * ks + g) ^ rsw) << 3;
-        const bf16x8 af = *reinterpret_cast<const bf16x8 *>(&ftp[(32 * w + r) * PITCH + col]);
-        bf16x8 bfr[NCB];
+      for (int ks0 = 0; ks0 < TOK / 16; ks0 += KB) {
+        bf16x8 af[KB], bfr[KB][T];
 #pragma unroll
-        for (int cb = 0; cb < T; ++cb) bfr[cb] = *reinterpret_cast<const bf16x8 *>(&vtp[(32 * cb + r) * PITCH + col]);
-        if (weighted) {
-          const bf16x8 ew = *reinterpret_cast<const bf16x8 *>(&et[r & 1][(2 * ks + g) << 3]);
-          bfr[T] = r < 2 ? ew : zero;
-        } else {
-          bfr[T] = ones;
+        for (int kk = 0; kk < KB; ++kk) {
+          const int col = ((2 * (ks0 + kk) + g) ^ rsw) << 3;
+          af[kk] = *reinterpret_cast<const bf16x8 *>(&ftp[arow + col]);
+#pragma unroll
+          for (int cb = 0; cb < T; ++cb) bfr[kk][cb] = *reinterpret_cast<const bf16x8 *>(&vtp[brow + 32 * cb * PITCH + col]);
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma32(af, bfr[cb], acc[cb]);
+        for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma32(af[kk], cb < T ? bfr[kk][cb] : ones, acc[cb]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
 
   const int t_begin = chunk * a.CH;
   const int t_end = min(t_begin + a.CH, a.NT);
-  for (int t0 = t_begin; t0 < t_end; t0 += TOK) {
-    const bool valid = t0 + tf < a.NT;
+  // the rows of the next tile are requested while the current one is still being contracted
+  bf16x8 xf[KS], uf[KS];
+  auto request_x = [&](int t0) {
     const int tok = lmap.token(min(t0 + tf, a.NT - 1));
-    bf16x8 xf[KS], uf[KS];
-    float rs_ = 1.f, wp_ = 1.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) xf[ks] = load8<F32>(a.x, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
+  };
+  auto request_u = [&](int t0) {
+    const int tok = lmap.token(min(t0 + tf, a.NT - 1));
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      xf[ks] = load8<F32>(a.x, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
       if constexpr (QUERY) uf[ks] = static_cast<const bf16x8 *>(a.u)[((int64_t)bh * a.N + tok) * (D / 8) + 2 * ks + g];
       else uf[ks] = load8<F32>(a.u, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
     }
+  };
+  request_x(t_begin);
+  request_u(t_begin);
+  for (int t0 = t_begin; t0 < t_end; t0 += TOK) {
+    const bool valid = t0 + tf < a.NT;
+    const int tok = lmap.token(min(t0 + tf, a.NT - 1));
+    // weights, biases and the fragments of M are the same in every tile: reading them through an offset the
+    // compiler cannot see through keeps the reads in the loop (hoisted, they would fill the register file)
+    const int z0 = opaque_zero();
+    zt = z0;
+    const lds_frag_ptr w1t = w1f + z0, w2t = w2f + z0;
+    const float *b1t = b1 + z0, *b2t = b2 + z0, *zt = zl + z0;
+    __builtin_assume(b1t != nullptr);
+    __builtin_assume(b2t != nullptr);
+    float rs_ = 1.f, wp_ = 1.f;
     if constexpr (QUERY) {
       rs_ = a.rs[(int64_t)bh * a.N + tok];
       wp_ = a.wp[(int64_t)bh * a.N + tok];
     }
     const float wz_ = QUERY ? wp_ * rs_ : 1.f;             // dden_i = -(g_i . y_hat_i) / den_i
 
-    // the map, recomputed: h (hi + lo), t = positive output before the slice powers
-    bf16x8 h_hi[T][2];
+    // the map, recomputed: h (hi + lo), t = positive output before the slice powers.  h goes to the B side
+    // array right away; its ReLU gate is kept as one bit per hidden unit.
     f32x16 tt[T];
+    unsigned gate[(T + 1) / 2];
     {
-      bf16x8 h_lo[T][2];
-      feature_mlp_layer1<D, D, true>(xf, w1f, b1, lane, g, h_hi, h_lo);
-      feature_mlp_layer2<D, D, true>(h_hi, h_lo, w2f, b2, lane, g, tt);
+      bf16x8 h_hi[T][2], h_lo[T][2];
+      feature_mlp_layer1<D, D, true>(xf, w1t, b1t, lane, g, h_hi, h_lo);
+#pragma unroll
+      for (int i = 0; i < (T + 1) / 2; ++i) gate[i] = 0u;
+#pragma unroll
+      for (int hb = 0; hb < T; ++hb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x)
+          gate[hb >> 1] |= (static_cast<float>(h_hi[hb][x >> 3][x & 7]) > 0.f ? 1u : 0u) << (16 * (hb & 1) + x);
+      feature_mlp_layer2<D, D, true>(h_hi, h_lo, w2t, b2t, lane, g, tt);
+      // consumed by the vector ALU from here on: keep the tiles out of the accumulator file, which the persistent
+      // partial sums fill
+#pragma unroll
+      for (int fb = 0; fb < T; ++fb) asm volatile("" : "+v"(tt[fb]));
       feature_activation<T>(tt, g, a.act, 1, D);
+      park_chained(vtp, h_hi);
     }
     // dphi = rs (M u) + wz zvec
+    // (the fragments of M come from L2: those of channel block fb + 1 are requested before the chain of block fb
+    // starts, so that one round trip is exposed per tile instead of one per instruction)
     f32x16 dv[T];
+    bf16x8 mf[2][2 * KS];
+    auto request_m = [&](int fb, bf16x8 (&dst)[2 * KS]) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        dst[ks] = frag_at(mlo, fb * KS + ks, lane, z0);
+        dst[KS + ks] = frag_at(mhi, fb * KS + ks, lane, z0);
+      }
+    };
+    request_m(0, mf[0]);
 #pragma unroll
     for (int fb = 0; fb < T; ++fb) {
       f32x16 acc;
 #pragma unroll
       for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+      if (fb + 1 < T) request_m(fb + 1, mf[(fb + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        acc = mfma32(frag_at(mlo, fb * KS + ks, lane), uf[ks], acc);
-        acc = mfma32(frag_at(mhi, fb * KS + ks, lane), uf[ks], acc);
+        acc = mfma32(mf[fb & 1][ks], uf[ks], acc);
+        acc = mfma32(mf[fb & 1][KS + ks], uf[ks], acc);
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int x = 0; x < 16; ++x) dv[fb][x] = rs_ * acc[x] + wz_ * zl[32 * fb + crow(x, g)];
+      for (int x = 0; x < 16; ++x) dv[fb][x] = rs_ * acc[x] + wz_ * zt[32 * fb + crow(x, g)];
     }
 
-    if constexpr (QUERY) {
-      // [dS | dz] += (rs phi) [g | wp]^T
-      bf16x8 a1[T][2];
-#pragma unroll
-      for (int fb = 0; fb < T; ++fb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          const int extra = (32 * fb + 8 * (x >> 2)) / Dp;      // wave-uniform
-          const float t0v = tt[fb][x];
-          float pw = t0v;
-          for (int i = 0; i < extra; ++i) pw *= t0v;
-          a1[fb][x >> 3][x & 7] = static_cast<__bf16>(valid ? rs_ * pw : 0.f);
-        }
-      park_chained(ftp, a1);
-      park_natural(vtp, uf);
-      if (g == 0) {
-        const __bf16 whi = static_cast<__bf16>(wp_);
-        et[0][tf] = whi;
-        et[1][tf] = static_cast<__bf16>(wp_ - static_cast<float>(whi));
-      }
-      __syncthreads();
-      contract(accS, true);
-      __syncthreads();
-    }
-
+    __builtin_amdgcn_sched_barrier(0);
+    request_u(t0 + TOK);
+    __builtin_amdgcn_sched_barrier(0);
     // back through the slice powers and the activation: dv becomes du
     {
       float dot = 0.f;
@@ -310,11 +351,9 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
       for (int fb = 0; fb < T; ++fb)
 #pragma unroll
         for (int x = 0; x < 16; ++x) {
-          const int extra = (32 * fb + 8 * (x >> 2)) / Dp;      // slice power p = extra + 1
+          const int extra = (32 * fb + 8 * (x >> 2)) / Dp;      // slice power p = extra + 1 (wave-uniform)
           const float t0v = tt[fb][x];
-          float pw = 1.f;
-          for (int i = 0; i < extra; ++i) pw *= t0v;
-          dv[fb][x] *= (float)(extra + 1) * pw;                 // d/dt of t^p
+          dv[fb][x] *= (float)(extra + 1) * pow_small(t0v, extra);   // d/dt of t^p
           dot += t0v * dv[fb][x];
         }
       if (a.act == 0) {
@@ -341,33 +380,42 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
 #pragma unroll
       for (int x = 0; x < 16; ++x) dub[fb][x >> 3][x & 7] = static_cast<__bf16>(valid ? dv[fb][x] : 0.f);
 
-    // dpre = (W2^T du) [h > 0]
+    // [dW2 | db2] += du [h | 1]^T
+    park_chained(ftp, dub);
+    __syncthreads();
+    contract(acc2);
+    // dpre = (W2^T du) [h > 0]   (registers only: overlaps the other waves' contraction)
     bf16x8 dpb[T][2];
+    bf16x8 wt[2][2 * T];
+    auto request_w = [&](int hb, bf16x8 (&dst)[2 * T]) {
+#pragma unroll
+      for (int i = 0; i < 2 * T; ++i) dst[i] = frag_at(w2tf, hb * T * 2 + i, lane, z0);
+    };
+    request_w(0, wt[0]);
 #pragma unroll
     for (int hb = 0; hb < T; ++hb) {
       f32x16 acc;
 #pragma unroll
       for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+      if (hb + 1 < T) request_w(hb + 1, wt[(hb + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int fb = 0; fb < T; ++fb)
 #pragma unroll
-        for (int s = 0; s < 2; ++s) acc = mfma32(frag_at(w2tf, (hb * T + fb) * 2 + s, lane), dub[fb][s], acc);
+        for (int s = 0; s < 2; ++s) acc = mfma32(wt[hb & 1][fb * 2 + s], dub[fb][s], acc);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int x = 0; x < 16; ++x)
-        dpb[hb][x >> 3][x & 7] = static_cast<__bf16>(static_cast<float>(h_hi[hb][x >> 3][x & 7]) > 0.f ? acc[x] : 0.f);
+        dpb[hb][x >> 3][x & 7] = static_cast<__bf16>((gate[hb >> 1] >> (16 * (hb & 1) + x)) & 1u ? acc[x] : 0.f);
     }
-
-    // [dW2 | db2] += du [h | 1]^T
-    park_chained(ftp, dub);
-    park_chained(vtp, h_hi);
-    __syncthreads();
-    contract(acc2, false);
     __syncthreads();
     // [dW1 | db1] += dpre [x | 1]^T
     park_chained(ftp, dpb);
     park_natural(vtp, xf);
+    __builtin_amdgcn_sched_barrier(0);
+    request_x(t0 + TOK);
     __syncthreads();
-    contract(acc1, false);
+    contract(acc1);
     __syncthreads();
   }
   if (w < T) {
@@ -378,7 +426,6 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
       for (int x = 0; x < 16; ++x) {
         dst[i * 1024 + x * 64 + lane] = acc2[i][x];
         dst[(NT2 + i) * 1024 + x * 64 + lane] = acc1[i][x];
-        if constexpr (QUERY) dst[(2 * NT2 + i) * 1024 + x * 64 + lane] = accS[i][x];
       }
   }
 }
@@ -446,7 +493,7 @@ void make_grad_plan(const Plan &pl, size_t base_off, GradPlan &gp) {
   gp.off_gsign = take(BH * pl.N * D * 2);
   gp.off_rs = take(BH * pl.N * 4);
   gp.off_wp = take(BH * pl.N * 4);
-  const size_t pq = BH * gp.n_chunks_q * 3 * gp.tiles_per_set * 1024 * 4;
+  const size_t pq = BH * gp.n_chunks_q * 2 * gp.tiles_per_set * 1024 * 4;
   const size_t pk = BH * gp.n_chunks_k * 2 * gp.tiles_per_set * 1024 * 4;
   gp.off_part = take(pq > pk ? pq : pk);
   gp.total = off;
@@ -517,10 +564,15 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     if (D == 64) { if (pl.f32) grad_kernel<64, true, true><<<grid, 256, 0, st>>>(a); else grad_kernel<64, false, true><<<grid, 256, 0, st>>>(a); }
     else { if (pl.f32) grad_kernel<128, true, true><<<grid, 256, 0, st>>>(a); else grad_kernel<128, false, true><<<grid, 256, 0, st>>>(a); }
     HA_CHECK();
-    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w2, gq.b2, D, gp.n_chunks_q, 3, 0, pl.B, pl.H);
-    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w1, gq.b1, D, gp.n_chunks_q, 3, 1, pl.B, pl.H);
+    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w2, gq.b2, D, gp.n_chunks_q, 2, 0, pl.B, pl.H);
+    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w1, gq.b1, D, gp.n_chunks_q, 2, 1, pl.B, pl.H);
+    HA_CHECK();
+    // [dS | dz]: the weighted state pass over all query tokens, reduced per (batch, head)
+    if ((e = launch_weighted_state(pl, q, ws_ptr<void>(ws, gp.off_gsign), a.rs, a.wp, phi_q, a.w1f, a.w2f, a.part, gp.CHq,
+                                   gp.n_chunks_q, st)) != hipSuccess)
+      return e;
     grad_reduce_kernel<<<rgrid_bh, 256, 0, st>>>(a.part, ws_ptr<float>(ws, gp.off_dS), ws_ptr<float>(ws, gp.off_dz), D,
-                                                 gp.n_chunks_q, 3, 2, 1, 0);
+                                                 gp.n_chunks_q, 1, 0, 1, 0);
     HA_CHECK();
     dim3 gridm((D * D + 255) / 256, BH);
     natural_frags_kernel<<<gridm, 256, 0, st>>>(ws_ptr<float>(ws, gp.off_dS), ws_ptr<__bf16>(ws, gp.off_dshi),

@@ -101,12 +101,19 @@ __global__ __launch_bounds__(256) void compact_kernel(const void *__restrict__ k
 // the K rows of tile t+1 as soon as layer 1 of tile t is done with the current ones.  Both LDS arrays hold [feature row][token] with the 8-token (16 B)
 // blocks of a row XOR-swizzled by ((row / 8) % 4) * 2, which spreads the 2-byte transposing writes
 // and the 16-byte operand reads over all banks.
-template <int D, int HD, int F, bool F32>
+//
+// WEIGHTED (the value-distillation gradient reuses this pass for dS = sum_i phi_q(q_i)^T g_i / den_i and
+// dz = sum_i dden_i phi_q(q_i) over all query tokens): `k` holds the queries, `v` a dense bf16 [B*H][NL][D]
+// tensor, token i's feature row is multiplied by rs[i] before it is rounded, and the "1" column becomes the pair
+// of columns (hi, lo) of wp[i].
+template <int D, int HD, int F, bool F32, bool WEIGHTED = false>
 __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ k, const void *__restrict__ v,
                                                        const bf16x8 *w1f_all, const bf16x8 *w2f_all,
                                                        const float *__restrict__ b1_all, const float *__restrict__ b2_all,
                                                        float *__restrict__ part, int H, int NL, int R, int CH, int P,
-                                                       int act, int64_t sb, int64_t sh, int64_t sn) {
+                                                       int act, int64_t sb, int64_t sh, int64_t sn,
+                                                       const float *__restrict__ rs_all = nullptr,
+                                                       const float *__restrict__ wp_all = nullptr) {
   constexpr int TOK = 128, PITCH = TOK + 8;
   constexpr int KS = D / 16, FB = F / 32, NCB = D / 32 + 1, NT = FB * NCB;
   constexpr int RPW = FB >= 4 ? FB / 4 : 1;   // row blocks of [S | z] per wave
@@ -119,6 +126,8 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   __shared__ __align__(16) __bf16 ft[F][PITCH];
   __shared__ __align__(16) __bf16 vt[D][PITCH];
   __shared__ bf16x8 wlds[WLDS ? (HD * D + F * HD) / 8 : 1];
+  __shared__ __align__(16) __bf16 et[WEIGHTED ? 2 : 1][WEIGHTED ? PITCH : 8];
+  static_assert(!WEIGHTED || F <= 128, "the weighted pass is built for the narrow maps only");
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H;
   const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
@@ -196,7 +205,8 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
       for (int p = 0; p < VPT; ++p) {
         const int trow = 16 * ((4 * p + w) & 7) + (lane & 15), c8 = 4 * (p >> 1) + (lane >> 4);
         const int tok = lmap.token(min(t0 + trow, NL - 1));
-        vreg[p] = load8<F32>(v, base + (int64_t)tok * sn + c8 * 8);
+        if constexpr (WEIGHTED) vreg[p] = static_cast<const bf16x8 *>(v)[((int64_t)bh * NL + tok) * (D / 8) + c8];
+        else vreg[p] = load8<F32>(v, base + (int64_t)tok * sn + c8 * 8);
       }
     };
     if constexpr (!WIDE) load_v();
@@ -217,13 +227,15 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
           f32x16 u[FB];
           feature_mlp_layer2<HD, F, true>(h_hi, h_lo, w2f, b2, lane, g, u);
           feature_activation<FB>(u, g, act, P, Dp);
+          float rs = 1.f;
+          if constexpr (WEIGHTED) rs = rs_all[(int64_t)bh * NL + lmap.token(min(t0 + tf, NL - 1))];
 #pragma unroll
           for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
             for (int sp = 0; sp < 2; ++sp) {
               f32x8 t8;
 #pragma unroll
-              for (int i = 0; i < 8; ++i) t8[i] = u[fb][8 * sp + i];
+              for (int i = 0; i < 8; ++i) t8[i] = WEIGHTED ? u[fb][8 * sp + i] * rs : u[fb][8 * sp + i];
               phi[fb][sp] = __builtin_convertvector(t8, bf16x8);
             }
         }
@@ -251,6 +263,14 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
 #pragma unroll
       for (int i = 0; i < 8; ++i) vtp[(32 * (p >> 1) + i) * PITCH + vrow0 + col] = vreg[p][i];
     }
+    if constexpr (WEIGHTED) {
+      if (g == 0) {
+        const float wp = wp_all[(int64_t)bh * NL + lmap.token(min(t0 + tf, NL - 1))];
+        const __bf16 whi = static_cast<__bf16>(wp);
+        et[0][tf] = whi;
+        et[1][tf] = static_cast<__bf16>(wp - static_cast<float>(whi));
+      }
+    }
     __syncthreads();
     if (w < GW) {
       const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);     // the "1" column that yields z
@@ -260,10 +280,17 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
       constexpr int KB = 2;
 #pragma unroll
       for (int ks0 = 0; ks0 < TOK / 16; ks0 += KB) {
-        bf16x8 af[KB][RPW], bfr[KB][D / 32];
+        bf16x8 af[KB][RPW], bfr[KB][D / 32], ew[KB];
 #pragma unroll
         for (int kk = 0; kk < KB; ++kk) {
           const int col = ((2 * (ks0 + kk) + g) ^ rsw) << 3;
+          if constexpr (WEIGHTED) {
+            const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+            const bf16x8 e8 = *reinterpret_cast<const bf16x8 *>(&et[r & 1][(2 * (ks0 + kk) + g) << 3]);
+            ew[kk] = r < 2 ? e8 : zero;
+          } else {
+            ew[kk] = ones;
+          }
 #pragma unroll
           for (int rp = 0; rp < RPW; ++rp)
             af[kk][rp] = *reinterpret_cast<const bf16x8 *>(&ftp[(32 * (w * RPW + rp) + r) * PITCH + col]);
@@ -278,7 +305,7 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
           for (int rp = 0; rp < RPW; ++rp)
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb)
-              acc[rp * NCB + cb] = mfma32(af[kk][rp], cb < D / 32 ? bfr[kk][cb] : ones, acc[rp * NCB + cb]);
+              acc[rp * NCB + cb] = mfma32(af[kk][rp], cb < D / 32 ? bfr[kk][cb] : ew[kk], acc[rp * NCB + cb]);
       }
     }
     __syncthreads();
@@ -362,6 +389,21 @@ hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_f
   else if (pl.HD == 128) { if (pl.f32) HA_STATE(128, 128, 128, true); else HA_STATE(128, 128, 128, false); }
   else { if (pl.f32) HA_STATE(128, 256, 256, true); else HA_STATE(128, 256, 256, false); }
 #undef HA_STATE
+  return hipGetLastError();
+}
+
+// The weighted pass over all N query tokens (value-distillation gradient): partial tiles of [dS | dz] to `part`.
+hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsign, const float *rs, const float *wp,
+                                 const ha_feature_map &fm, const void *w1f_, const void *w2f_, float *part, int CH,
+                                 int n_chunks, hipStream_t st) {
+  dim3 grid(n_chunks, pl.B * pl.H);
+  const bf16x8 *w1f = static_cast<const bf16x8 *>(w1f_), *w2f = static_cast<const bf16x8 *>(w2f_);
+#define HA_WSTATE(DD, F32) \
+  state_kernel<DD, DD, DD, F32, true><<<grid, 256, 0, st>>>(q, gsign, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.N, 0, CH, pl.P, \
+                                                            pl.act_q, pl.sb, pl.sh, pl.sn, rs, wp)
+  if (pl.D == 64) { if (pl.f32) HA_WSTATE(64, true); else HA_WSTATE(64, false); }
+  else { if (pl.f32) HA_WSTATE(128, true); else HA_WSTATE(128, false); }
+#undef HA_WSTATE
   return hipGetLastError();
 }
 

@@ -162,6 +162,12 @@ def hybrid_attn_workspace_bytes(problem: ha_problem, phi_q=None, phi_k=None) -> 
     return _lib().hybrid_attn_workspace_bytes(ctypes.byref(problem), pq, pk)
 
 
+def hybrid_attn_value_distill_grad_workspace_bytes(problem: ha_problem, phi_q=None, phi_k=None) -> int:
+    sq, pq = _fm_ptr(phi_q)
+    sk, pk = _fm_ptr(phi_k)
+    return _lib().hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(problem), pq, pk)
+
+
 def hybrid_attn_status_string(status: int) -> str:
     return _lib().hybrid_attn_status_string(status).decode()
 
