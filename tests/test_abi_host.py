@@ -178,3 +178,39 @@ def test_value_distill_workspace_and_errors(lib):
     assert f(*args(wsb=both - 1)) == ha.HA_ERR_WORKSPACE
     assert f(*args(ws=None)) == ha.HA_ERR_WORKSPACE
     assert f(*args(p=_problem(d=96))) == ha.HA_ERR_UNSUPPORTED
+
+
+def test_value_distill_grad_workspace_and_errors(lib):
+    """Host-side checks of the gradient entry point: every error is reported before anything is enqueued."""
+    fm = _map()
+    p = _problem()
+    loss_ws = lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(p), ctypes.byref(fm), ctypes.byref(fm))
+    need = lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(fm), ctypes.byref(fm))
+    # beyond the loss's workspace: the sign tensor (one bf16 per element of q) and the partial tiles, at least
+    assert need >= loss_ws + 12 * 32760 * 128 * 2
+    wide = _map(256, 256)
+    assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(wide), ctypes.byref(wide)) == 0
+    f = lib.hybrid_attn_value_distill_grad
+    A = [FAKE + i * 0x10000000 for i in range(16)]
+    gq = ha.ha_feature_map_grad(A[8], A[9], A[10], A[11])
+    gk = ha.ha_feature_map_grad(A[12], A[13], A[14], A[15])
+
+    def args(**kw):
+        return [ctypes.byref(kw.get("p", p)), A[0], A[1], A[2], ctypes.byref(kw.get("fq", fm)), ctypes.byref(kw.get("fk", fm)),
+                0, 0, kw.get("yt", A[3]), kw.get("ys", A[4]), kw.get("den", A[5]), kw.get("loss", A[6]),
+                ctypes.byref(kw.get("gq", gq)), ctypes.byref(kw.get("gk", gk)), kw.get("ws", A[7]), kw.get("wsb", need), None]
+    assert f(*args(den=None)) == ha.HA_ERR_NULL
+    assert f(*args(loss=None)) == ha.HA_ERR_NULL
+    assert f(*args(gq=ha.ha_feature_map_grad(A[8], None, A[10], A[11]))) == ha.HA_ERR_NULL
+    assert f(*args(gk=ha.ha_feature_map_grad(A[12], A[13], A[14] + 2, A[15]))) == ha.HA_ERR_ALIGN
+    assert f(*args(ys=A[3])) == ha.HA_ERR_SHAPE
+    assert f(*args(den=A[5] + 2)) == ha.HA_ERR_ALIGN
+    assert f(*args(wsb=need - 1)) == ha.HA_ERR_WORKSPACE
+    assert f(*args(ws=None)) == ha.HA_ERR_WORKSPACE
+    assert f(*args(fq=wide, fk=wide)) == ha.HA_ERR_UNSUPPORTED      # only d -> d -> d maps have a gradient kernel
+    assert f(*args(p=_problem(d=96))) == ha.HA_ERR_UNSUPPORTED
+    # rate 1: the maps are still required (they give the gradients their shapes)
+    p1 = _problem(R=1)
+    a = args(p=p1)
+    a[4] = None
+    assert f(*a) == ha.HA_ERR_NULL

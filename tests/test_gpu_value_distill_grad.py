@@ -168,3 +168,51 @@ def test_other_activations_and_no_biases():
                                                               student_is_cached=True)
         torch.cuda.synchronize()
         assert compare(f"act{act}_bias{int(with_bias)}", (gq, gk), want) <= GRAD_REL_L2
+
+
+def test_headline_shape_properties():
+    """480p / 81 frames, R = 4, the launch configuration bench.py times.  The oracle cannot run a whole head at this
+    length, so the gradient is held to what must hold at any size: (a) the second-layer bias gradient of a softmax
+    map sums to zero over the channels of every head (shifting all logits of a token changes nothing); (b) the
+    gradient of one head computed alone, where the chunking of the token sums is different (256 chunks per head
+    instead of 21), equals that head's slice of the 12-head result up to fp32 summation order; (c) a second call
+    reproduces every tensor bit for bit."""
+    w = W.WAN_480P_81F
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    s = w.d ** -0.5
+    q, k, v = ((torch.randn(w.B, w.H, w.N, w.d, generator=gen, device="cuda") * s).to(torch.bfloat16) for _ in range(3))
+
+    def dmap():
+        return ha.FeatureMap((torch.randn(w.H, w.d_hidden, w.d, generator=gen, device="cuda") * s).to(torch.bfloat16),
+                             torch.randn(w.H, w.d_hidden, generator=gen, device="cuda") * 0.1,
+                             (torch.randn(w.H, w.d_feat, w.d_hidden, generator=gen, device="cuda") * s).to(torch.bfloat16),
+                             torch.randn(w.H, w.d_feat, generator=gen, device="cuda") * 0.1, w.poly_degree)
+    fq, fk = dmap(), dmap()
+    print("  case headline gradient, 12 heads", flush=True)
+    loss, gq, gk, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale)
+    torch.cuda.synchronize()
+    for g in (gq, gk):
+        for n in NAMES:
+            assert torch.isfinite(g[n]).all() and g[n].abs().max() > 0
+        assert (g["b2"].double().sum(dim=1).abs() <= 1e-4 * g["b2"].double().abs().sum(dim=1)).all()
+    print("  case headline gradient, second call", flush=True)
+    loss2, gq2, gk2, _, _, _ = ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale)
+    torch.cuda.synchronize()
+    for a, b in ((gq, gq2), (gk, gk2)):
+        for n in NAMES:
+            assert torch.equal(a[n], b[n])
+    h = 7
+
+    def one_head(fm):
+        return ha.FeatureMap(fm.w1[h:h + 1].contiguous(), fm.b1[h:h + 1].contiguous(), fm.w2[h:h + 1].contiguous(),
+                             fm.b2[h:h + 1].contiguous(), fm.poly_degree)
+    print("  case headline gradient, one head alone", flush=True)
+    _, gq1, gk1, _, _, _ = ha.hybrid_attn_value_distill_grad(q[:, h:h + 1], k[:, h:h + 1], v[:, h:h + 1], one_head(fq), one_head(fk),
+                                                           w.R, w.block_size, w.scale)
+    torch.cuda.synchronize()
+    for full, alone in ((gq, gq1), (gk, gk1)):
+        for n in NAMES:
+            a, b = full[n][h].double(), alone[n][0].double()
+            rel = float((a - b).norm() / b.norm())
+            record(f"vd_grad_headline_head{h}_{n}", float((a - b).abs().max()), rel)
+            assert rel <= 1e-4
