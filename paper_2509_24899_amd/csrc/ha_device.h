@@ -169,6 +169,18 @@ static __device__ __forceinline__ bf16x8 frag_at(lds_frag_ptr base, int idx, int
 static __device__ __forceinline__ bf16x8 frag_at(const GlobalFrags &f, int idx, int lane) {
   return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(frag_rsrc(f), lane * 16, idx * 1024, 0));
 }
+// n_chunks 1 KiB chunks global -> LDS with direct-to-LDS loads (no staging registers), dealt round-robin to the
+// nw waves of the workgroup; wave index w must be wave-uniform.  The caller waits (vmcnt) and synchronises.
+static __device__ __forceinline__ void dma_to_lds(const bf16x8 *gsrc, bf16x8 *ldst, int n_chunks, int w, int nw, int lane) {
+  const unsigned lane_off16 = lane * 16;
+  for (int ch = w; ch < n_chunks; ch += nw) {
+    const unsigned l = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(ldst + ch * 64));
+    const bf16x8 *gp = gsrc + ch * 64;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(lane_off16), "s"(gp) : "memory");
+  }
+}
+
 // A zero the compiler cannot see through.  Added to the scalar offset of fragment reads inside a loop whose
 // fragments are the same in every iteration, it keeps those reads in the loop (hoisted, a whole operand matrix
 // would sit in registers, i.e. in scratch).

@@ -123,8 +123,17 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   constexpr int VPT = (TOK / 16) * CG / 4;    // V chunks per thread per tile
   // the MLP weight fragments of this head live in LDS when they fit next to the two transposing arrays
   constexpr bool WLDS = (HD * D + F * HD) * 2 <= 64 * 1024;
-  __shared__ __align__(16) __bf16 ft[F][PITCH];
-  __shared__ __align__(16) __bf16 vt[D][PITCH];
+  // Wider maps: the weights do not fit next to the two transposing arrays, but those are idle while the MLP runs.
+  // One raw area serves both: per tile W1 and the first half of W2 are staged into it (direct-to-LDS, one fetch
+  // per workgroup instead of one per wave), the second half of W2 follows once layer 1 is done, and only then
+  // the area becomes phi^T and V^T.
+  constexpr bool WIDE = F > 128;
+  constexpr int NW1 = HD * D / 8, NW2 = F * HD / 8;            // bf16x8 per head
+  constexpr int RAW = WIDE ? (NW1 + NW2 / 2 > (F + D) * PITCH / 8 ? NW1 + NW2 / 2 : (F + D) * PITCH / 8) : 1;
+  static_assert(!WIDE || (NW2 / 2 <= NW1 && (F / 32) % 2 == 0 && RAW * 16 <= 150 * 1024), "staging plan does not fit");
+  __shared__ __align__(16) __bf16 ft_s[WIDE ? 1 : F][PITCH];
+  __shared__ __align__(16) __bf16 vt_s[WIDE ? 1 : D][PITCH];
+  __shared__ bf16x8 raw[RAW];
   __shared__ bf16x8 wlds[WLDS ? (HD * D + F * HD) / 8 : 1];
   __shared__ __align__(16) __bf16 et[WEIGHTED ? 2 : 1][WEIGHTED ? PITCH : 8];
   static_assert(!WEIGHTED || F <= 128, "the weighted pass is built for the narrow maps only");
@@ -181,8 +190,8 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   const int vsw = (lane >> 4) << 1;                       // sw of rows 8 c8 + i, c8 % 4 = lane / 16
   const int vrow0 = 8 * (lane >> 4) * PITCH;
   const int rsw = ((r >> 3) & 3) << 1;                    // sw of operand rows 32 blk + r
-  __bf16 *ftp = &ft[0][0];
-  __bf16 *vtp = &vt[0][0];
+  __bf16 *ftp = WIDE ? reinterpret_cast<__bf16 *>(&raw[0]) : &ft_s[0][0];
+  __bf16 *vtp = WIDE ? reinterpret_cast<__bf16 *>(&raw[0]) + F * PITCH : &vt_s[0][0];
 
   const int lt_begin = chunk * CH;
   const int lt_end = min(lt_begin + CH, NL);
@@ -198,7 +207,6 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
     // V rows of this tile: pass p of wave w covers tokens 16 ((4p + w) % 8) .. + 15 and the four
     // 16-byte chunks 4 (p / 2) .. + 3 of each (64 contiguous bytes per row)
     // (wide maps: the MLP needs the registers, so V is requested only once the hidden activations are dead)
-    constexpr bool WIDE = F > 128;
     bf16x8 vreg[VPT];
     auto load_v = [&]() {
 #pragma unroll
@@ -217,12 +225,30 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
       bf16x8 phi[FB][2];
       {
         bf16x8 h_hi[HD / 32][2], h_lo[HD / 32][2];
-        feature_mlp_layer1<D, HD, true>(xf, w1f, b1, lane, g, h_hi, h_lo);
+        if constexpr (WIDE) {
+          // the previous tile's contraction is over (barrier at the end of the loop body): the area is free
+          dma_to_lds(w1g, &raw[0], NW1 / 64, w, 4, lane);
+          dma_to_lds(w2g, &raw[NW1], NW2 / 2 / 64, w, 4, lane);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __syncthreads();
+          feature_mlp_layer1<D, HD, true>(xf, (lds_frag_ptr)&raw[0], b1, lane, g, h_hi, h_lo);
+        } else {
+          feature_mlp_layer1<D, HD, true>(xf, w1f, b1, lane, g, h_hi, h_lo);
+        }
         __builtin_amdgcn_sched_barrier(0);
         load_k(t0 + TOK, xf);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (WIDE) {
-          feature_layer2_phi<HD, F, false>(h_hi, h_lo, w2f, b2, lane, g, act, P, Dp, phi);
+          PhiState<FB> st;
+          feature_layer2_phi_tiles<HD, F, 0, FB / 2, true>(h_hi, h_lo, (lds_frag_ptr)&raw[NW1], 0, b2, lane, g, act, P, Dp, st,
+                                                           phi);
+          __syncthreads();                                  // every wave is done with W1: the second half of W2 replaces it
+          dma_to_lds(w2g + NW2 / 2, &raw[0], NW2 / 2 / 64, w, 4, lane);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __syncthreads();
+          feature_layer2_phi_tiles<HD, F, FB / 2, FB, true>(h_hi, h_lo, (lds_frag_ptr)&raw[0], (FB / 2) * (HD / 32) * 2, b2,
+                                                            lane, g, act, P, Dp, st, phi);
+          feature_phi_finish<F>(st, act, P, Dp, phi);
         } else {
           f32x16 u[FB];
           feature_mlp_layer2<HD, F, true>(h_hi, h_lo, w2f, b2, lane, g, u);
@@ -240,7 +266,10 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
             }
         }
       }
-      if constexpr (WIDE) load_v();
+      if constexpr (WIDE) {
+        load_v();
+        __syncthreads();                                    // the weights have been read by every wave: the area becomes phi^T | V^T
+      }
       if (t0 + TOK > NL) {                                 // ragged end of T_L: padded tokens add nothing
         const bool valid = t0 + tf < NL;
         const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
