@@ -240,13 +240,13 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (WIDE) {
           PhiState<FB> st;
-          feature_layer2_phi_tiles<HD, F, 0, FB / 2, true>(h_hi, h_lo, (lds_frag_ptr)&raw[NW1], 0, b2, lane, g, act, P, Dp, st,
+          feature_layer2_phi_tiles<HD, F, 0, FB / 2, false>(h_hi, h_lo, (lds_frag_ptr)&raw[NW1], 0, b2, lane, g, act, P, Dp, st,
                                                            phi);
           __syncthreads();                                  // every wave is done with W1: the second half of W2 replaces it
           dma_to_lds(w2g + NW2 / 2, &raw[0], NW2 / 2 / 64, w, 4, lane);
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           __syncthreads();
-          feature_layer2_phi_tiles<HD, F, FB / 2, FB, true>(h_hi, h_lo, (lds_frag_ptr)&raw[0], (FB / 2) * (HD / 32) * 2, b2,
+          feature_layer2_phi_tiles<HD, F, FB / 2, FB, false>(h_hi, h_lo, (lds_frag_ptr)&raw[0], (FB / 2) * (HD / 32) * 2, b2,
                                                             lane, g, act, P, Dp, st, phi);
           feature_phi_finish<F>(st, act, P, Dp, phi);
         } else {
