@@ -124,7 +124,7 @@ static __device__ __forceinline__ void feature_activation(f32x16 (&u)[NB], int g
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int extra = (32 * b + 8 * q) / Dp;       // wave-uniform
+        const int extra = ((32 * b + 8 * q) * P) / (32 * NB);   // = channel / Dp without a run-time division; wave-uniform
         if (extra > 0) {
           const float t0 = u[b][4 * q], t1 = u[b][4 * q + 1], t2 = u[b][4 * q + 2], t3 = u[b][4 * q + 3];
           for (int i = 0; i < extra; ++i) {
@@ -360,7 +360,7 @@ static __device__ __forceinline__ void feature_layer2_phi_tiles(const bf16x8 (&h
     if (act != 0 && P > 1) {   // no normalisation to wait for: the slice power can be applied right away
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int extra = (32 * fb + 8 * q) / Dp;            // wave-uniform
+        const int extra = ((32 * fb + 8 * q) * P) / F;        // = channel / Dp; wave-uniform
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const float t0 = acc[4 * q + j];
@@ -394,7 +394,7 @@ static __device__ __forceinline__ void feature_phi_finish(const PhiState<F / 32>
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float t0 = static_cast<float>(phi[fb][s][i]) * factor;
-          const int extra = P > 1 ? (32 * fb + 8 * (2 * s + i / 4)) / Dp : 0;   // wave-uniform
+          const int extra = ((32 * fb + 8 * (2 * s + i / 4)) * P) / F;          // = channel / Dp; wave-uniform
           float t = t0;
           for (int k = 0; k < extra; ++k) t *= t0;
           t8[i] = t;

@@ -181,7 +181,6 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
   const GlobalFrags mlo = global_frags(a.m_lo + (int64_t)bh * (D * D / 8), D * D * 2);
   const float *b1 = &blds[0], *b2 = &blds[D], *zl = &blds[2 * D];
 
-  const int Dp = D / a.P;
   const LinearMap lmap(QUERY ? 0 : a.R);
 
   f32x16 acc2[NCB], acc1[NCB];
@@ -312,16 +311,15 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
       park_chained(vtp, h_hi);
     }
     // dphi = rs (M u) + wz zvec
-    // (the fragments of M come from L2: those of channel block fb + 1 are requested before the chain of block fb
-    // starts, so that one round trip is exposed per tile instead of one per instruction)
+    // (the fragments of M come from L2: the next half block (lo or hi part of one channel block, 8 fragments) is
+    // requested before the chain of the current one starts, so that one round trip is exposed per tile instead
+    // of one per instruction; larger batches cost more in spilled registers than they save)
     f32x16 dv[T];
-    bf16x8 mf[2][2 * KS];
-    auto request_m = [&](int fb, bf16x8 (&dst)[2 * KS]) {
+    bf16x8 mf[2][KS];
+    auto request_m = [&](int step, bf16x8 (&dst)[KS]) {       // step = 2 fb + (0: lo part, 1: hi part)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        dst[ks] = frag_at(mlo, fb * KS + ks, lane, z0);
-        dst[KS + ks] = frag_at(mhi, fb * KS + ks, lane, z0);
-      }
+      for (int ks = 0; ks < KS; ++ks)
+        dst[ks] = (step & 1) ? frag_at(mhi, (step >> 1) * KS + ks, lane, z0) : frag_at(mlo, (step >> 1) * KS + ks, lane, z0);
     };
     request_m(0, mf[0]);
 #pragma unroll
@@ -329,14 +327,13 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
       f32x16 acc;
 #pragma unroll
       for (int x = 0; x < 16; ++x) acc[x] = 0.f;
-      if (fb + 1 < T) request_m(fb + 1, mf[(fb + 1) & 1]);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        acc = mfma32(mf[fb & 1][ks], uf[ks], acc);
-        acc = mfma32(mf[fb & 1][KS + ks], uf[ks], acc);
+      for (int half = 0; half < 2; ++half) {
+        const int step = 2 * fb + half;
+        if (step + 1 < 2 * T) request_m(step + 1, mf[(step + 1) & 1]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc = mfma32(mf[step & 1][ks], uf[ks], acc);
       }
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int x = 0; x < 16; ++x) dv[fb][x] = rs_ * acc[x] + wz_ * zt[32 * fb + crow(x, g)];
     }
@@ -351,7 +348,7 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
       for (int fb = 0; fb < T; ++fb)
 #pragma unroll
         for (int x = 0; x < 16; ++x) {
-          const int extra = (32 * fb + 8 * (x >> 2)) / Dp;      // slice power p = extra + 1 (wave-uniform)
+          const int extra = ((32 * fb + 8 * (x >> 2)) * a.P) / D;   // channel / Dp: slice power p = extra + 1 (wave-uniform)
           const float t0v = tt[fb][x];
           dv[fb][x] *= (float)(extra + 1) * pow_small(t0v, extra);   // d/dt of t^p
           dot += t0v * dv[fb][x];
