@@ -216,3 +216,39 @@ def test_headline_shape_properties():
             rel = float((a - b).norm() / b.norm())
             record(f"vd_grad_headline_head{h}_{n}", float((a - b).abs().max()), rel)
             assert rel <= 1e-4
+
+
+def _cached_run(inp, R, layout="bhnd"):
+    wl = inp.workload
+    fq, fk, y, yh, den = oracle_forward_pieces(inp, R)
+    y_r, yh_r = round_io(y, wl.dtype), round_io(yh, wl.dtype)
+    want = G.value_distill_grad(inp.q, inp.k, inp.v, fq, fk, R, wl.scale, sign_from=(y_r, yh_r))
+    q, k, v, dq, dk = ha.to_device(inp)
+    dt = q.dtype
+    yt_d = torch.from_numpy(y_r).to(device="cuda", dtype=dt).contiguous()
+    ys_d = torch.from_numpy(yh_r).to(device="cuda", dtype=dt).contiguous()
+    if layout == "bnhd":          # [B, N, H, d] memory behind [B, H, N, d] views
+        q, k, v, yt_d, ys_d = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v, yt_d, ys_d))
+    den_d = torch.from_numpy(den).to(device="cuda", dtype=torch.float32).contiguous()
+    _, gq, gk, _, _, _ = ha.hybrid_attn_value_distill_grad(q, k, v, dq, dk, R, wl.block_size, wl.scale, y_teacher=yt_d,
+                                                          teacher_is_cached=True, y_student=ys_d, row_den=den_d,
+                                                          student_is_cached=True)
+    torch.cuda.synchronize()
+    return (gq, gk), want
+
+
+@pytest.mark.parametrize("N,R", [(37, 4), (129, 2), (5, 0)])
+def test_short_sequences(N, R):
+    """Fewer tokens than one 128-token tile, one token past a tile, fewer than one wave's 32: every padded
+    token must contribute nothing."""
+    wl = W.replace(LOGIT_STD1, name=f"short_N{N}", B=1, H=2, N=N)
+    print(f"  case short N={N} R={R}", flush=True)
+    got, want = _cached_run(W.make_inputs(wl), R)
+    assert compare(f"short_N{N}_R{R}", got, want) <= GRAD_REL_L2
+
+
+def test_strided_layout():
+    """q, k, v and the two outputs as [B, H, N, d] views of [B, N, H, d] memory."""
+    print("  case strided layout", flush=True)
+    got, want = _cached_run(W.make_inputs(SMALL), 4, layout="bnhd")
+    assert compare("bnhd_R4", got, want) <= GRAD_REL_L2
