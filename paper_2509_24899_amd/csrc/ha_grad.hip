@@ -442,14 +442,26 @@ __global__ __launch_bounds__(256) void grad_reduce_kernel(const float *__restric
   const int ti = e >> 10, x = (e >> 6) & 15, lane = e & 63, r = lane & 31, g = lane >> 5;
   const int rb = ti / NCB, cb = ti % NCB;
   if (cb == T && r != 0) return;
+  // four chunks per step: the loads of a step do not depend on each other (a plain running sum exposes one
+  // memory round trip per chunk); the order of the additions is fixed all the same
   float sum = 0.f;
+  const int64_t cstride = (int64_t)n_sets * NT2 * 1024;
+  const bool two = cb == T;
   for (int b = 0; b < n_sum; ++b) {
     const int64_t bh = (int64_t)b * stride_sum + o;
-    for (int c = 0; c < n_chunks; ++c) {
-      const float *src = part + ((bh * n_chunks + c) * n_sets + set) * (int64_t)NT2 * 1024 + e;
-      sum += src[0];
-      if (cb == T) sum += src[1];
+    const float *src = part + ((bh * n_chunks) * n_sets + set) * (int64_t)NT2 * 1024 + e;
+    int c = 0;
+    for (; c + 4 <= n_chunks; c += 4) {
+      float v[4], u[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[i] = src[(c + i) * cstride];
+        u[i] = two ? src[(c + i) * cstride + 1] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sum += v[i] + u[i];
     }
+    for (; c < n_chunks; ++c) sum += src[c * cstride] + (two ? src[c * cstride + 1] : 0.f);
   }
   const int row = 32 * rb + crow(x, g);
   if (cb < T) mat[((int64_t)o * D + row) * D + 32 * cb + r] = sum;

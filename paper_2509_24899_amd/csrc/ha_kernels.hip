@@ -360,8 +360,18 @@ __global__ __launch_bounds__(256) void state_reduce_kernel(const float *__restri
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= NT * 1024) return;
   const int ti = e >> 10, x = (e >> 6) & 15, lane = e & 63, r = lane & 31, g = lane >> 5;
+  // four chunks per step so that their loads are in flight together; fixed order of additions
   float sum = 0.f;
-  for (int c = 0; c < n_chunks; ++c) sum += part[((int64_t)bh * n_chunks + c) * NT * 1024 + e];
+  const float *src = part + (int64_t)bh * n_chunks * NT * 1024 + e;
+  int c = 0;
+  for (; c + 4 <= n_chunks; c += 4) {
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = src[(int64_t)(c + i) * NT * 1024];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sum += v[i];
+  }
+  for (; c < n_chunks; ++c) sum += src[(int64_t)c * NT * 1024];
   const int fb = ti / NCB, cb = ti % NCB;
   const int ch = 32 * fb + crow(x, g);
   if (cb < D / 32) {
