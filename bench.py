@@ -343,7 +343,7 @@ def main():
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (null when this
     # workload has not been profiled)
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file):
+    if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d:   # profiled with the d -> d -> d maps
         t = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
         if t:
             roofline["traffic"] = t["read_bytes"] + t["written_bytes"]
