@@ -520,7 +520,7 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
                                          const ha_feature_map &phi_q, const ha_feature_map &phi_k, const void *y_teacher,
                                          const void *y_student, const float *row_den, const ha_feature_map_grad &gq,
                                          const ha_feature_map_grad &gk, void *ws, hipStream_t st) {
-  const int D = pl.D, BH = pl.B * pl.H, T = D / 32;
+  const int D = pl.D, BH = pl.B * pl.H;
   hipError_t e;
 #define HA_CHECK() if ((e = hipGetLastError()) != hipSuccess) return e
   // operand fragments: W1, W2 of both maps (forward order), W2^T (chained), S (natural, hi + lo)
@@ -605,7 +605,6 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     HA_CHECK();
   }
 #undef HA_CHECK
-  (void)T;
   return hipSuccess;
 }
 
