@@ -199,8 +199,8 @@ def main():
     ap.add_argument("--rate", type=int, default=None, help="override the hybrid rate R (0 = pure linear, 1 = full softmax)")
     ap.add_argument("--block-size", type=int, default=None)
     ap.add_argument("--phi-width", type=int, default=None,
-                    help="hidden and output width of both feature maps (default: the workload's d -> d -> d; 256 is the "
-                         "paper's default map at d = 128, Tab. phi row P = 2)")
+                    help="hidden and output width of both feature maps (default: the workload's d -> d -> d; 256, 384, 512 "
+                         "are the two-layer rows P = 2, 3, 4 of Tab. phi at d = 128, 768 the width of its P = 6 row)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
@@ -236,7 +236,9 @@ def main():
     if args.block_size is not None:
         w = W.replace(w, block_size=args.block_size)
     if args.phi_width is not None:
-        w = W.replace(w, d_hidden=args.phi_width, d_feat=args.phi_width)
+        # Tab. "phi": D' = d channels per slice, so a map of width P d has polynomial degree P
+        w = W.replace(w, d_hidden=args.phi_width, d_feat=args.phi_width,
+                      poly_degree=args.phi_width // w.d if args.phi_width % w.d == 0 else w.poly_degree)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"

@@ -30,7 +30,10 @@ static ha_status check_map(const ha_feature_map *fm, const ha_problem &p) {
   if (fm->out_act != HA_ACT_SOFTMAX && fm->out_act != HA_ACT_EXP && fm->out_act != HA_ACT_RELU) return HA_ERR_UNSUPPORTED;
   const bool square = fm->d_hidden == p.d_head && fm->d_out == p.d_head;
   const bool paper_width = p.d_head == 128 && fm->d_hidden == 256 && fm->d_out == 256;
-  if (!square && !paper_width) return HA_ERR_UNSUPPORTED;
+  // any other width goes layer by layer through HBM (ha_wide.hip): multiples of 128 up to 768 (Tab. "phi": P d, P <= 6)
+  const bool layered = p.d_head == 128 && fm->d_hidden % 128 == 0 && fm->d_out % 128 == 0 && fm->d_hidden <= 768 &&
+                       fm->d_out <= 768;
+  if (!square && !paper_width && !layered) return HA_ERR_UNSUPPORTED;
   if (!aligned16(fm->w1) || !aligned16(fm->w2)) return HA_ERR_ALIGN;
   if ((fm->b1 && (reinterpret_cast<uintptr_t>(fm->b1) & 3u)) || (fm->b2 && (reinterpret_cast<uintptr_t>(fm->b2) & 3u)))
     return HA_ERR_ALIGN;
@@ -109,6 +112,23 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.total = off;
 }
 
+// Feature maps outside the fused kernels' widths take the layer-by-layer path.
+static bool needs_wide_path(const Plan &pl) {
+  const bool square = pl.HD == pl.D && pl.F == pl.D;
+  const bool paper_width = pl.D == 128 && pl.HD == 256 && pl.F == 256;
+  return pl.NL > 0 && !square && !paper_width;
+}
+
+// Plan of the forward plus, where needed, the layer-by-layer path's buffers behind it; returns the workspace size.
+static size_t full_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, Plan &pl, WidePlan &wp,
+                        bool &wide) {
+  make_plan(p, phi_q, phi_k, pl);
+  wide = phi_q && phi_k && needs_wide_path(pl);
+  if (!wide) return pl.total;
+  make_wide_plan(pl, pl.total, wp);
+  return wp.total;
+}
+
 static ha_status device_error(hipError_t e) {
   g_last_device_error = static_cast<int>(e);
   return HA_ERR_DEVICE;
@@ -116,12 +136,14 @@ static ha_status device_error(hipError_t e) {
 
 // ev (optional): ev[0] before compaction, ev[1] after it, ev[2] after the state is reduced.
 static ha_status run_key_side(const Plan &pl, const void *k, const void *v, const ha_feature_map *phi_k, void *ws,
-                              hipStream_t st, hipEvent_t *ev = nullptr) {
+                              hipStream_t st, hipEvent_t *ev = nullptr, const WidePlan *wide = nullptr) {
   hipError_t e;
   if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return device_error(e);
   if (pl.NS > 0 && (e = launch_compact(pl, k, v, ws, st)) != hipSuccess) return device_error(e);
   if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return device_error(e);
-  if (pl.NL > 0) {
+  if (pl.NL > 0 && wide) {
+    if ((e = launch_wide_key_side(pl, *wide, k, v, *phi_k, ws, st)) != hipSuccess) return device_error(e);
+  } else if (pl.NL > 0) {
     if ((e = launch_weight_prep(pl, *phi_k, false, ws, st)) != hipSuccess) return device_error(e);
     if ((e = launch_state(pl, k, v, *phi_k, ws, st)) != hipSuccess) return device_error(e);
     if ((e = launch_state_reduce(pl, ws, st)) != hipSuccess) return device_error(e);
@@ -141,8 +163,9 @@ ha_status hybrid_attn_validate(const ha_problem *p, const ha_feature_map *phi_q,
 size_t hybrid_attn_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q, const ha_feature_map *phi_k) {
   if (ha::validate(p, phi_q, phi_k) != HA_OK) return 0;
   ha::Plan pl;
-  ha::make_plan(*p, phi_q, phi_k, pl);
-  return pl.total;
+  ha::WidePlan wp;
+  bool wide;
+  return ha::full_plan(*p, phi_q, phi_k, pl, wp, wide);
 }
 
 static ha_status forward_impl(const ha_problem *p, const void *q, const void *k, const void *v,
@@ -153,17 +176,24 @@ static ha_status forward_impl(const ha_problem *p, const void *q, const void *k,
   if (!q || !k || !v || !out) return HA_ERR_NULL;
   if (!ha::aligned16(q) || !ha::aligned16(k) || !ha::aligned16(v) || !ha::aligned16(out)) return HA_ERR_ALIGN;
   ha::Plan pl;
-  ha::make_plan(*p, phi_q, phi_k, pl);
-  if (!workspace || workspace_bytes < pl.total) return HA_ERR_WORKSPACE;
+  ha::WidePlan wp;
+  bool wide;
+  const size_t need = ha::full_plan(*p, phi_q, phi_k, pl, wp, wide);
+  if (!workspace || workspace_bytes < need) return HA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipEvent_t *ev = ha::prof_events();
-  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, ev);
+  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, ev, wide ? &wp : nullptr);
   if (s != HA_OK) return s;
   hipError_t e;
-  if (pl.NL > 0 && (e = ha::launch_weight_prep(pl, *phi_q, true, workspace, st)) != hipSuccess) return ha::device_error(e);
+  if (wide) {
+    if ((e = ha::launch_wide_query_side(pl, wp, q, *phi_q, workspace, st)) != hipSuccess) return ha::device_error(e);
+  } else if (pl.NL > 0 && (e = ha::launch_weight_prep(pl, *phi_q, true, workspace, st)) != hipSuccess) {
+    return ha::device_error(e);
+  }
   if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return ha::device_error(e);
-  if ((e = ha::launch_query(pl, q, phi_q, out, row_den, workspace, st)) != hipSuccess) return ha::device_error(e);
+  if ((e = ha::launch_query(pl, q, phi_q, out, row_den, workspace, st, wide ? &wp : nullptr)) != hipSuccess)
+    return ha::device_error(e);
   if (ev) {
     if ((e = hipEventRecord(ev[4], st)) != hipSuccess) return ha::device_error(e);
     ++ha::g_prof.count;
@@ -224,11 +254,13 @@ ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const voi
   if (p->hybrid_rate == 1) return HA_ERR_SHAPE;   // no linear tokens, no state
   if (!ha::aligned16(k) || !ha::aligned16(v)) return HA_ERR_ALIGN;
   ha::Plan pl;
-  ha::make_plan(*p, phi_k, phi_k, pl);
-  if (!workspace || workspace_bytes < pl.total) return HA_ERR_WORKSPACE;
+  ha::WidePlan wp;
+  bool wide;
+  const size_t need = ha::full_plan(*p, phi_k, phi_k, pl, wp, wide);
+  if (!workspace || workspace_bytes < need) return HA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  s = ha::run_key_side(pl, k, v, phi_k, workspace, st);
+  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, nullptr, wide ? &wp : nullptr);
   if (s != HA_OK) return s;
   const size_t BH = (size_t)pl.B * pl.H;
   char *ws = static_cast<char *>(workspace);
@@ -265,8 +297,10 @@ static size_t distill_layout(const ha_problem &p, const ha_feature_map *phi_q, c
   ha_problem pt = p;
   pt.hybrid_rate = 1;
   ha::make_plan(pt, nullptr, nullptr, teacher);
-  ha::make_plan(p, phi_q, phi_k, student);
-  off_partial = ha::align256(teacher.total > student.total ? teacher.total : student.total);
+  ha::WidePlan wp;
+  bool wide;
+  const size_t student_total = ha::full_plan(p, phi_q, phi_k, student, wp, wide);
+  off_partial = ha::align256(teacher.total > student_total ? teacher.total : student_total);
   return off_partial + ha::align256(ha::l1_partial_bytes(student));
 }
 

@@ -30,6 +30,13 @@ struct GradPlan {
   size_t off_w2tq, off_w2tk, off_shi, off_slo, off_dS, off_dz, off_dshi, off_dslo, off_gsign, off_rs, off_wp, off_part, total;
 };
 
+// Workspace of the layer-by-layer path for feature maps beyond the fused kernels' widths (beyond the forward's):
+// hidden activations (hi + lo), fp32 pre-activations, phi, and for the queries n = phi_q S and e = phi_q . z.
+struct WidePlan {
+  int n_tb_q, n_tb_k;      // 32-token blocks of the query tokens / the linear key tokens
+  size_t off_hhi, off_hlo, off_u, off_phi, off_lin, off_e, total;
+};
+
 // Fills `pl` from a validated problem.  Pure host arithmetic.
 void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, Plan &pl);
 
@@ -43,7 +50,13 @@ hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsig
                                  int n_chunks, hipStream_t st);
 hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st);
 hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, float *row_den, void *ws,
-                        hipStream_t st);
+                        hipStream_t st, const WidePlan *wide = nullptr);
+// ha_wide.hip
+void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp);
+hipError_t launch_wide_key_side(const Plan &pl, const WidePlan &wp, const void *k, const void *v, const ha_feature_map &phi_k,
+                                void *ws, hipStream_t st);
+hipError_t launch_wide_query_side(const Plan &pl, const WidePlan &wp, const void *q, const ha_feature_map &phi_q, void *ws,
+                                  hipStream_t st);
 size_t l1_partial_bytes(const Plan &pl);
 hipError_t launch_l1_distance(const Plan &pl, const void *ya, const void *yb, double *partial, double *loss,
                               hipStream_t st);

@@ -21,6 +21,10 @@ struct QueryArgs {
   const bf16x8 *st_hi, *st_lo;           // [B*H][D/32][F/32][2][64]
   const float *z;                       // [B*H][F]
   float *row_den;                       // optional [B*H][N]: the denominator l_i + phi_q(q_i).z of every row
+  // maps too wide for the fused epilogue: n_i = phi_q(q_i) S and e_i = phi_q(q_i).z arrive precomputed
+  const f32x4 *lin;                     // [B*H][n_tb][D/32][4][64]: fp32 register image of n^T per 32-query block, or null
+  const float *lin_e;                   // [B*H][N]
+  int n_tb;
   int H, N, NS, n_qtiles, n_ktiles, n_kblocks, total_wg;
   int has_linear, P, act;
   int64_t sb, sh, sn;
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     }
   };
   if constexpr (ELDS) {
-    if (a.has_linear) stage_in(a.w1f + (int64_t)h * NW1, w1_lds, NW1 / 64);
+    if (a.has_linear && !a.lin) stage_in(a.w1f + (int64_t)h * NW1, w1_lds, NW1 / 64);
   }
 
   bf16x8 qf[KS];
@@ -430,6 +434,25 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
       for (int x = 0; x < 16; ++x) o[rb][x] *= alpha;
   }
   char *stage = reinterpret_cast<char *>(&ring[0]) + w * (2 * NB * FRAG * 16 / NW);
+  if (a.lin) {
+    // linear part computed by the wide-map passes: add it to the accumulators, which share its register layout
+    float den = xhalf_sum(lsum);
+    const int tb = q0 >> 5;
+    if (tb < a.n_tb) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int x4 = 0; x4 < 4; ++x4) {
+          const f32x4 t = a.lin[((((int64_t)bh * a.n_tb + tb) * RB + rb) * 4 + x4) * 64 + lane];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o[rb][4 * x4 + j] += t[j];
+        }
+      den += a.lin_e[(int64_t)bh * a.N + min(q0 + (lane & 31), a.N - 1)];
+    }
+    store_den(a, bh, lane, den, q0);
+    store_tile<D, F32>(a, base, lane, o, 1.0f / den, stage, q0);
+    return;
+  }
   const bf16x8 *w1g = a.w1f + (int64_t)h * NW1;
   const bf16x8 *w2g = a.w2f + (int64_t)h * NW2;
   const bf16x8 *sthg = a.st_hi + (int64_t)bh * NST;
@@ -494,11 +517,14 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
 }
 
 hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, float *row_den, void *ws,
-                        hipStream_t st) {
+                        hipStream_t st, const WidePlan *wide) {
   QueryArgs a;
   a.q = q;
   a.out = out;
   a.row_den = row_den;
+  a.lin = wide ? ws_ptr<f32x4>(ws, wide->off_lin) : nullptr;
+  a.lin_e = wide ? ws_ptr<float>(ws, wide->off_e) : nullptr;
+  a.n_tb = wide ? wide->n_tb_q : 0;
   a.ks_frag = ws_ptr<bf16x8>(ws, pl.off_ks);
   a.vs_frag = ws_ptr<bf16x8>(ws, pl.off_vs);
   a.w1f = ws_ptr<bf16x8>(ws, pl.off_w1q);
@@ -525,7 +551,7 @@ hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi
     else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \
   } while (0)
   if (pl.D == 64) { if (pl.f32) HA_QUERY(64, 64, 64, true); else HA_QUERY(64, 64, 64, false); }
-  else if (pl.HD == 128) { if (pl.f32) HA_QUERY(128, 128, 128, true); else HA_QUERY(128, 128, 128, false); }
+  else if (pl.HD == 128 || wide) { if (pl.f32) HA_QUERY(128, 128, 128, true); else HA_QUERY(128, 128, 128, false); }
   else { if (pl.f32) HA_QUERY(128, 256, 256, true); else HA_QUERY(128, 256, 256, false); }
 #undef HA_QUERY
   return hipGetLastError();

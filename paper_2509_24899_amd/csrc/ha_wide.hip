@@ -1,0 +1,473 @@
+// Feature maps of any width (Attention Surgery, Sec. 3.2 "Characterization of phi"; Tab. "phi": d -> P d -> P d
+// for P = 2, 3, 4 and the three-layer P = 6 map), gfx950.  The fused kernels keep a token's hidden activations and
+// all its output channels in registers, which ends at 256 channels.  Here every layer is a pass of its own and
+// activations travel through HBM, in exactly the register image the next product wants:
+//
+//   wide_layer1_kernel     h^T = relu(W1 x^T + b1)                     x from q / k, h as hi + lo bf16
+//   wide_layer_kernel      h'^T = relu(W h^T + b)  or  u^T = W h^T + b  (last layer: fp32 pre-activations)
+//   wide_phi_finish_kernel softmax / exp / relu over all channels of a token, slice powers, bf16; for the queries
+//                          also e_i = phi_q(q_i).z
+//   wide_state_kernel      [S | z] += phi_k^T [V | 1], one 128-channel slab of S per workgroup
+//   wide_lin_kernel        n_i = phi_q(q_i) S   (fp32, in the layout of the query kernel's accumulators)
+// The query kernel then adds n_i and e_i in its epilogue instead of evaluating phi_q itself.
+//
+// Register images ("C image" of a 32-token block tb of (batch, head) bh; lane = 32 g + r owns token 32 tb + r):
+//   activations   bf16x8 [bh][tb][W/32][2][64]   piece (block c, half s) = channels 32 c + crow(8 s + t, g), t = 0..7,
+//                                                i.e. the B operand ("chained" order) of the next product
+//   fp32 tiles    f32x4  [bh][tb][W/32][4][64]   piece (block c, quad x) = channels 32 c + crow(4 x + j, g), j = 0..3
+#include "ha_device.h"
+#include "ha_plan.h"
+
+namespace ha {
+
+struct WideArgs {
+  const void *x;                 // layer 1: q or k (io dtype, strided)
+  const bf16x8 *in_hi, *in_lo;   // later layers / consumers: activations of the previous pass
+  const bf16x8 *wf;              // weight fragments of this layer, all heads
+  const float *bias;             // [H][NOUT] or null
+  bf16x8 *out_hi, *out_lo;       // hidden layers
+  f32x4 *out_u;                  // last layer
+  int H, K, NOUT, n_tok, n_tb, R;
+  int64_t sb, sh, sn;
+};
+
+// ------------------------------------------------------------------------------------------------
+// wide_layer1_kernel: grid (ceil(n_tb / 4), NOUT / 128, B*H), 4 waves, one 32-token block per wave and four
+// 32-channel output blocks per workgroup row.  W1 fragments in natural order (weight_prep_kernel).
+template <int D, bool F32>
+__global__ __launch_bounds__(256) void wide_layer1_kernel(WideArgs a) {
+  constexpr int KS = D / 16;
+  const int bh = blockIdx.z, h = bh % a.H;
+  const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
+  const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tb >= a.n_tb) return;
+  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
+  const LinearMap lmap(a.R);
+  const int tok = lmap.token(min(32 * tb + r, a.n_tok - 1));
+  bf16x8 xf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) xf[ks] = load8<F32>(a.x, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
+  const GlobalFrags wf = global_frags(a.wf + (int64_t)h * (a.NOUT * D / 8), a.NOUT * D * 2);
+  const int HB = a.NOUT / 32;
+  for (int j = 0; j < 4; ++j) {
+    const int hb = blockIdx.y * 4 + j;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = a.bias ? a.bias[(int64_t)h * a.NOUT + 32 * hb + crow(v, g)] : 0.f;
+    bf16x8 w8[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) w8[ks] = frag_at(wf, hb * KS + ks, lane);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) acc = mfma32(w8[ks], xf[ks], acc);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      f32x8 t, lo;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = fmaxf(acc[8 * s + i], 0.f);
+      const bf16x8 hi = __builtin_convertvector(t, bf16x8);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) lo[i] = t[i] - static_cast<float>(hi[i]);
+      const int64_t o = ((((int64_t)bh * a.n_tb + tb) * HB + hb) * 2 + s) * 64 + lane;
+      a.out_hi[o] = hi;
+      a.out_lo[o] = __builtin_convertvector(lo, bf16x8);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// wide_layer_kernel: grid (ceil(n_tb / 4), NOUT / 128, B*H).  Input activations as hi + lo C images (width K),
+// weights [NOUT x K] as fragments in chained order (weight_prep_kernel's second layout).  LAST: fp32
+// pre-activations out; otherwise relu and hi + lo bf16.  The fragments of the next 32 input channels are
+// requested before the 16 matrix instructions of the current ones.
+template <bool LAST>
+__global__ __launch_bounds__(256) void wide_layer_kernel(WideArgs a) {
+  const int bh = blockIdx.z, h = bh % a.H;
+  const int lane = threadIdx.x & 63, g = lane >> 5;
+  const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tb >= a.n_tb) return;
+  const int KB = a.K / 32, OB = a.NOUT / 32;
+  const GlobalFrags wf = global_frags(a.wf + (int64_t)h * ((int64_t)a.NOUT * a.K / 8), a.NOUT * a.K * 2);
+  const bf16x8 *bhi = a.in_hi + ((int64_t)bh * a.n_tb + tb) * KB * 128 + lane;
+  const bf16x8 *blo = a.in_lo + ((int64_t)bh * a.n_tb + tb) * KB * 128 + lane;
+  const int ob0 = blockIdx.y * 4;
+  f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = a.bias ? a.bias[(int64_t)h * a.NOUT + 32 * (ob0 + j) + crow(v, g)] : 0.f;
+  bf16x8 cb_hi[2], cb_lo[2], ca[4][2], nb_hi[2], nb_lo[2], na[4][2];
+  auto request = [&](int kb, bf16x8 (&hi)[2], bf16x8 (&lo)[2], bf16x8 (&wa)[4][2]) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      hi[s] = bhi[(kb * 2 + s) * 64];
+      lo[s] = blo[(kb * 2 + s) * 64];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) wa[j][s] = frag_at(wf, ((ob0 + j) * KB + kb) * 2 + s, lane);
+    }
+  };
+  request(0, cb_hi, cb_lo, ca);
+  for (int kb = 0; kb < KB; ++kb) {
+    if (kb + 1 < KB) request(kb + 1, nb_hi, nb_lo, na);
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        acc[j] = mfma32(ca[j][s], cb_lo[s], acc[j]);
+        acc[j] = mfma32(ca[j][s], cb_hi[s], acc[j]);
+      }
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      cb_hi[s] = nb_hi[s];
+      cb_lo[s] = nb_lo[s];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ca[j][s] = na[j][s];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int64_t blk = ((int64_t)bh * a.n_tb + tb) * OB + ob0 + j;
+    if constexpr (LAST) {
+#pragma unroll
+      for (int x4 = 0; x4 < 4; ++x4)
+        a.out_u[(blk * 4 + x4) * 64 + lane] = f32x4{acc[j][4 * x4], acc[j][4 * x4 + 1], acc[j][4 * x4 + 2], acc[j][4 * x4 + 3]};
+    } else {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        f32x8 t, lo;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = fmaxf(acc[j][8 * s + i], 0.f);
+        const bf16x8 hi = __builtin_convertvector(t, bf16x8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lo[i] = t[i] - static_cast<float>(hi[i]);
+        a.out_hi[(blk * 2 + s) * 64 + lane] = hi;
+        a.out_lo[(blk * 2 + s) * 64 + lane] = __builtin_convertvector(lo, bf16x8);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// wide_phi_finish_kernel: grid (ceil(n_tb / 4), B*H), one 32-token block per wave, all F <= 32 * FBMAX
+// pre-activations of a token in registers (one wave per SIMD).  Output: phi as bf16 C image (zero for tokens
+// past the end); QUERY: e[bh][token] = phi . z with the rounded phi, as the numerator will use it.
+constexpr int WIDE_FBMAX = 24;
+
+template <bool QUERY>
+__global__ __launch_bounds__(256, 1) void wide_phi_finish_kernel(const f32x4 *__restrict__ u_in, bf16x8 *__restrict__ phi_out,
+                                                                 const float *__restrict__ z, float *__restrict__ e_out,
+                                                                 int F, int n_tok, int n_tb, int act, int P) {
+  __shared__ float zl[QUERY ? 32 * WIDE_FBMAX : 1];
+  const int bh = blockIdx.y;
+  if constexpr (QUERY) {
+    for (int i = threadIdx.x; i < F; i += 256) zl[i] = z[(int64_t)bh * F + i];
+    __syncthreads();
+  }
+  const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
+  const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tb >= n_tb) return;
+  const int FB = F / 32, Dp = F / P;
+  const bool valid = 32 * tb + r < n_tok;
+  f32x16 u[WIDE_FBMAX];
+#pragma unroll
+  for (int fb = 0; fb < WIDE_FBMAX; ++fb)
+    if (fb < FB) {
+#pragma unroll
+      for (int x4 = 0; x4 < 4; ++x4) {
+        const f32x4 t = u_in[((((int64_t)bh * n_tb + tb) * FB + fb) * 4 + x4) * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) u[fb][4 * x4 + j] = t[j];
+      }
+    }
+  if (act == 0) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
+      if (fb < FB)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, u[fb][v]);
+    mx = xhalf_max(mx);
+    const float off = -mx * kLog2e;
+    float sum = 0.f;
+#pragma unroll
+    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
+      if (fb < FB)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          u[fb][v] = fast_exp2(__builtin_fmaf(u[fb][v], kLog2e, off));
+          sum += u[fb][v];
+        }
+    const float inv = 1.0f / xhalf_sum(sum);
+#pragma unroll
+    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
+      if (fb < FB)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) u[fb][v] *= inv;
+  } else {
+#pragma unroll
+    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
+      if (fb < FB)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) u[fb][v] = act == 1 ? fast_exp2(u[fb][v] * kLog2e) : fmaxf(u[fb][v], 0.f);
+  }
+  float dot = 0.f;
+#pragma unroll
+  for (int fb = 0; fb < WIDE_FBMAX; ++fb)
+    if (fb < FB) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        f32x8 t8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int extra = (32 * fb + 8 * (2 * s + i / 4)) / Dp;      // slice power - 1, wave-uniform
+          const float t0 = u[fb][8 * s + i];
+          float t = t0;
+          for (int k = 0; k < extra; ++k) t *= t0;
+          t8[i] = valid ? t : 0.f;
+        }
+        const bf16x8 p8 = __builtin_convertvector(t8, bf16x8);
+        phi_out[((((int64_t)bh * n_tb + tb) * FB + fb) * 2 + s) * 64 + lane] = p8;
+        if constexpr (QUERY) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) dot += static_cast<float>(p8[i]) * zl[32 * fb + crow(8 * s + i, g)];
+        }
+      }
+    }
+  if constexpr (QUERY) {
+    dot = xhalf_sum(dot);
+    if (g == 0 && valid) e_out[(int64_t)bh * n_tok + 32 * tb + r] = dot;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// wide_state_kernel: grid (n_chunks, B*H, F / 128), 4 waves.  As the contraction half of state_kernel, with
+// phi_k read back from its C image instead of being computed in place; workgroup z owns feature rows
+// 128 z .. 128 z + 127 of [S | z], wave w row block w of those.  Partial tiles go where state_kernel puts them
+// (part[bh][chunk][row block * NCB + column block][v][lane]), so state_reduce_kernel serves both.
+template <int D, bool F32>
+__global__ __launch_bounds__(256, 1) void wide_state_kernel(const bf16x8 *__restrict__ phi, const void *__restrict__ v,
+                                                            float *__restrict__ part, int H, int NL, int R, int CH,
+                                                            int F, int n_tb, int64_t sb, int64_t sh, int64_t sn) {
+  constexpr int TOK = 128, PITCH = TOK + 8, NCB = D / 32 + 1;
+  constexpr int CG = D / 32, VPT = (TOK / 16) * CG / 4;
+  __shared__ __align__(16) __bf16 ft[128][PITCH];
+  __shared__ __align__(16) __bf16 vt[D][PITCH];
+  const int chunk = blockIdx.x, bh = blockIdx.y, zb = blockIdx.z, h = bh % H;
+  const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int FB = F / 32;
+  const LinearMap lmap(R);
+  f32x16 acc[NCB];
+#pragma unroll
+  for (int i = 0; i < NCB; ++i)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) acc[i][x] = 0.f;
+  const int tf = w * 32 + r;
+  int fcol[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) fcol[q] = (4 * g) * PITCH + ((((tf >> 3) ^ (2 * q)) << 3) | (tf & 7));
+  const int vsw = (lane >> 4) << 1;
+  const int vrow0 = 8 * (lane >> 4) * PITCH;
+  const int rsw = ((r >> 3) & 3) << 1;
+  __bf16 *ftp = &ft[0][0];
+  __bf16 *vtp = &vt[0][0];
+  const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);
+  const bf16x8 ones = bf16x8{one, one, one, one, one, one, one, one};
+  const int lt_begin = chunk * CH, lt_end = min(lt_begin + CH, NL);
+  for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
+    bf16x8 vreg[VPT];
+#pragma unroll
+    for (int p = 0; p < VPT; ++p) {
+      const int trow = 16 * ((4 * p + w) & 7) + (lane & 15), c8 = 4 * (p >> 1) + (lane >> 4);
+      const int tok = lmap.token(min(t0 + trow, NL - 1));
+      vreg[p] = load8<F32>(v, base + (int64_t)tok * sn + c8 * 8);
+    }
+    const int tb = t0 / 32 + w;
+    bf16x8 ph[4][2];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        ph[fb][s] = tb < n_tb ? phi[((((int64_t)bh * n_tb + tb) * FB + 4 * zb + fb) * 2 + s) * 64 + lane] : zero;
+      }
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) ftp[(32 * fb + 8 * (x >> 2) + (x & 3)) * PITCH + fcol[x >> 2]] = ph[fb][x >> 3][x & 7];
+#pragma unroll
+    for (int p = 0; p < VPT; ++p) {
+      const int trow = 16 * ((4 * p + w) & 7) + (lane & 15);
+      const int col = (((trow >> 3) ^ vsw) << 3) | (trow & 7);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) vtp[(32 * (p >> 1) + i) * PITCH + vrow0 + col] = vreg[p][i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < TOK / 16; ++ks) {
+      const int col = ((2 * ks + g) ^ rsw) << 3;
+      const bf16x8 af = *reinterpret_cast<const bf16x8 *>(&ftp[(32 * w + r) * PITCH + col]);
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const bf16x8 bfr = cb < D / 32 ? *reinterpret_cast<const bf16x8 *>(&vtp[(32 * cb + r) * PITCH + col]) : ones;
+        acc[cb] = mfma32(af, bfr, acc[cb]);
+      }
+    }
+    __syncthreads();
+  }
+  float *dst = part + (((int64_t)bh * gridDim.x + chunk) * FB + 4 * zb + w) * NCB * 1024;
+#pragma unroll
+  for (int i = 0; i < NCB; ++i)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) dst[i * 1024 + x * 64 + lane] = acc[i][x];
+}
+
+// ------------------------------------------------------------------------------------------------
+// wide_lin_kernel: grid (ceil(n_tb / 4), B*H).  n^T = S^T phi_q^T per 32-query block: A operand = S^T as hi + lo
+// fragments in chained order (state_reduce_kernel's layout), B operand = the C image of phi_q.  Output: fp32 C
+// image of width D, i.e. the layout of the query kernel's accumulators.
+template <int D>
+__global__ __launch_bounds__(256) void wide_lin_kernel(const bf16x8 *__restrict__ phi, const bf16x8 *__restrict__ st_hi,
+                                                       const bf16x8 *__restrict__ st_lo, f32x4 *__restrict__ lin, int F,
+                                                       int n_tb) {
+  constexpr int RB = D / 32;
+  const int bh = blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tb >= n_tb) return;
+  const int FB = F / 32;
+  const GlobalFrags shi = global_frags(st_hi + (int64_t)bh * (D * F / 8), D * F * 2);
+  const GlobalFrags slo = global_frags(st_lo + (int64_t)bh * (D * F / 8), D * F * 2);
+  const bf16x8 *pb = phi + ((int64_t)bh * n_tb + tb) * FB * 128 + lane;
+  f32x16 acc[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
+  for (int fb = 0; fb < FB; ++fb) {
+    bf16x8 b[2], ahi[RB][2], alo[RB][2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      b[s] = pb[(fb * 2 + s) * 64];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        ahi[rb][s] = frag_at(shi, (rb * FB + fb) * 2 + s, lane);
+        alo[rb][s] = frag_at(slo, (rb * FB + fb) * 2 + s, lane);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        acc[rb] = mfma32(alo[rb][s], b[s], acc[rb]);
+        acc[rb] = mfma32(ahi[rb][s], b[s], acc[rb]);
+      }
+  }
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int x4 = 0; x4 < 4; ++x4)
+      lin[((((int64_t)bh * n_tb + tb) * RB + rb) * 4 + x4) * 64 + lane] =
+          f32x4{acc[rb][4 * x4], acc[rb][4 * x4 + 1], acc[rb][4 * x4 + 2], acc[rb][4 * x4 + 3]};
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+
+template <typename T>
+static inline T *ws_ptr(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
+static inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp) {
+  const size_t BH = (size_t)pl.B * pl.H;
+  wp.n_tb_q = (pl.N + 31) / 32;
+  wp.n_tb_k = (pl.NL + 31) / 32;
+  const size_t n_tb = wp.n_tb_q;                      // the key side (fewer tokens) reuses the query side's buffers
+  size_t off = base_off;
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+  wp.off_hhi = take(BH * n_tb * 32 * pl.HD * 2);
+  wp.off_hlo = take(BH * n_tb * 32 * pl.HD * 2);
+  wp.off_u = take(BH * n_tb * 32 * (size_t)pl.F * 4);
+  wp.off_phi = take(BH * n_tb * 32 * (size_t)pl.F * 2);
+  wp.off_lin = take(BH * n_tb * 32 * (size_t)pl.D * 4);
+  wp.off_e = take(BH * (size_t)pl.N * 4);
+  wp.total = off;
+}
+
+// One feature map over one token set: layer 1, last layer, output stage.  is_query: all N tokens of q, and
+// phi.z is formed; otherwise the linear tokens of k.
+static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query,
+                               void *ws, hipStream_t st) {
+  const int BH = pl.B * pl.H;
+  const int n_tok = is_query ? pl.N : pl.NL, n_tb = is_query ? wp.n_tb_q : wp.n_tb_k;
+  hipError_t e;
+  if ((e = launch_weight_prep(pl, fm, is_query, ws, st)) != hipSuccess) return e;
+  WideArgs a;
+  a.x = x;
+  a.H = pl.H; a.n_tok = n_tok; a.n_tb = n_tb; a.R = is_query ? 0 : pl.R;
+  a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
+  a.in_hi = a.in_lo = nullptr;
+  a.out_u = nullptr;
+  // layer 1: d -> HD
+  a.wf = ws_ptr<bf16x8>(ws, is_query ? pl.off_w1q : pl.off_w1k);
+  a.bias = fm.b1; a.K = pl.D; a.NOUT = pl.HD;
+  a.out_hi = ws_ptr<bf16x8>(ws, wp.off_hhi); a.out_lo = ws_ptr<bf16x8>(ws, wp.off_hlo);
+  {
+    dim3 grid((n_tb + 3) / 4, pl.HD / 128, BH);
+    if (pl.f32) wide_layer1_kernel<128, true><<<grid, 256, 0, st>>>(a);
+    else wide_layer1_kernel<128, false><<<grid, 256, 0, st>>>(a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  // last layer: HD -> F, fp32 pre-activations
+  a.in_hi = ws_ptr<bf16x8>(ws, wp.off_hhi); a.in_lo = ws_ptr<bf16x8>(ws, wp.off_hlo);
+  a.wf = ws_ptr<bf16x8>(ws, is_query ? pl.off_w2q : pl.off_w2k);
+  a.bias = fm.b2; a.K = pl.HD; a.NOUT = pl.F;
+  a.out_hi = a.out_lo = nullptr;
+  a.out_u = ws_ptr<f32x4>(ws, wp.off_u);
+  {
+    dim3 grid((n_tb + 3) / 4, pl.F / 128, BH);
+    wide_layer_kernel<true><<<grid, 256, 0, st>>>(a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
+    dim3 grid((n_tb + 3) / 4, BH);
+    if (is_query)
+      wide_phi_finish_kernel<true><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<bf16x8>(ws, wp.off_phi),
+                                                         ws_ptr<float>(ws, pl.off_z), ws_ptr<float>(ws, wp.off_e), pl.F, n_tok,
+                                                         n_tb, pl.act_q, pl.P);
+    else
+      wide_phi_finish_kernel<false><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<bf16x8>(ws, wp.off_phi), nullptr,
+                                                          nullptr, pl.F, n_tok, n_tb, pl.act_k, pl.P);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// Key side: phi_k over the linear tokens, then [S | z] (partials + the forward's reduction).
+hipError_t launch_wide_key_side(const Plan &pl, const WidePlan &wp, const void *k, const void *v, const ha_feature_map &phi_k,
+                                void *ws, hipStream_t st) {
+  hipError_t e = run_wide_map(pl, wp, k, phi_k, false, ws, st);
+  if (e != hipSuccess) return e;
+  dim3 grid(pl.n_chunks, pl.B * pl.H, pl.F / 128);
+  if (pl.f32)
+    wide_state_kernel<128, true><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), v, ws_ptr<float>(ws, pl.off_part), pl.H,
+                                                       pl.NL, pl.R, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
+  else
+    wide_state_kernel<128, false><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), v, ws_ptr<float>(ws, pl.off_part), pl.H,
+                                                        pl.NL, pl.R, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  return launch_state_reduce(pl, ws, st);
+}
+
+// Query side: phi_q over all tokens, e = phi_q . z, n = phi_q S; the query kernel picks both up in its epilogue.
+hipError_t launch_wide_query_side(const Plan &pl, const WidePlan &wp, const void *q, const ha_feature_map &phi_q, void *ws,
+                                  hipStream_t st) {
+  hipError_t e = run_wide_map(pl, wp, q, phi_q, true, ws, st);
+  if (e != hipSuccess) return e;
+  dim3 grid((wp.n_tb_q + 3) / 4, pl.B * pl.H);
+  wide_lin_kernel<128><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), ws_ptr<bf16x8>(ws, pl.off_sthi),
+                                             ws_ptr<bf16x8>(ws, pl.off_stlo), ws_ptr<f32x4>(ws, wp.off_lin), pl.F, wp.n_tb_q);
+  return hipGetLastError();
+}
+
+}  // namespace ha

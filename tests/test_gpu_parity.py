@@ -159,6 +159,33 @@ def test_paper_width_feature_map():
     check("paper_width_R0", W.make_inputs(w), R=0, block_size=64)
 
 
+@pytest.mark.parametrize("P", (3, 4, 6))
+def test_wider_feature_maps(P):
+    """Tab. "phi": d -> P d -> P d per head for P = 3, 4 and the width of its P = 6 row (F = 384, 512, 768); these go
+    layer by layer through HBM instead of through the fused kernels.  Hybrid, purely linear, and the state tap."""
+    w = W.replace(SMALL, name=f"phi_P{P}", B=1, H=2, d_hidden=128 * P, d_feat=128 * P, poly_degree=P, seed=60 + P)
+    inp = W.make_inputs(w)
+    print(f"  case wider maps P={P}", flush=True)
+    check(f"phi_P{P}_R4", inp, R=4)
+    check(f"phi_P{P}_R0", inp, R=0, block_size=64)
+    _, k, v, _, fk = ha.to_device(inp)
+    S, z = ha.hybrid_attn_linear_state(k, v, fk, 3)
+    torch.cuda.synchronize()
+    for h in range(w.H):
+        Sr, zr = O.linear_state(inp.k[0, h], inp.v[0, h], oracle_map(inp.phi_k), h, 3)
+        assert metrics(S.cpu().numpy()[0, h], Sr)[1] <= REL_L2 and metrics(z.cpu().numpy()[0, h], zr)[1] <= REL_L2
+
+
+def test_wider_feature_maps_mixed_widths_and_short_input():
+    """Hidden width different from the output width, other activations, fewer tokens than one 32-token block."""
+    w = W.replace(SMALL, name="phi_384_512", B=2, H=2, d_hidden=384, d_feat=512, poly_degree=2, seed=70)
+    check("phi_384_512_R4", W.make_inputs(w), R=4)
+    check("phi_384_512_exp", W.make_inputs(w), R=2, act=ha.HA_ACT_EXP)
+    w = W.replace(SMALL, name="phi_512_short", B=1, H=2, N=19, d_hidden=512, d_feat=512, poly_degree=4, seed=71)
+    check("phi_512_N19_R4", W.make_inputs(w), R=4)
+    check("phi_512_N19_R0", W.make_inputs(w), R=0)
+
+
 def test_linear_state_tap():
     inp = W.make_inputs(SMALL)
     w = inp.workload
