@@ -23,8 +23,8 @@ Readings of the paper taken here (each is a decision, listed again in the design
     the linear terms are NOT multiplied by exp(-c_i).  The maximum runs over T_S only.
   * Attention is per head; scale is passed in (1/sqrt(d_head) for the paper's operator);
     the feature maps see the unscaled q and k.
-  * phi: per-head 2-layer MLP (a grouped 1x1 convolution per layer) with ReLU between the
-    layers; the output is made positive by a softmax over all F output channels of the token,
+  * phi: per-head 2-layer MLP (a grouped 1x1 convolution per layer; optionally 3 layers, as in
+    the P = 6 row of Tab. "phi") with ReLU between the layers; the output is made positive by a softmax over all F output channels of the token,
     then split into P contiguous slices and slice p (1-based) is raised elementwise to the
     power p and the slices are concatenated in channel order.
 
@@ -52,16 +52,23 @@ class FeatureMap:
 
     w1: [H, Hd, d]   b1: [H, Hd]   w2: [H, F, Hd]   b2: [H, F]   (Sec. 3.2: per-head embedding
     network realised as grouped 1x1 convolutions), P = polynomial degree, act = output
-    positivity (softmax over the F channels by default).
+    positivity (softmax over the F channels by default).  Tab. "phi" also has a three-layer map
+    (its P = 6 row): then w_mid [H, Dm, Hd], b_mid [H, Dm] sit between the two, with a ReLU after
+    each hidden layer, and w2 is [H, F, Dm].
     """
 
-    def __init__(self, w1, b1, w2, b2, poly_degree=2, act=ACT_SOFTMAX):
+    def __init__(self, w1, b1, w2, b2, poly_degree=2, act=ACT_SOFTMAX, w_mid=None, b_mid=None):
         self.w1 = np.asarray(w1, dtype=np.float64)
         self.w2 = np.asarray(w2, dtype=np.float64)
         H, Hd, _ = self.w1.shape
         F = self.w2.shape[1]
         self.b1 = np.zeros((H, Hd)) if b1 is None else np.asarray(b1, dtype=np.float64)
         self.b2 = np.zeros((H, F)) if b2 is None else np.asarray(b2, dtype=np.float64)
+        self.w_mid = None if w_mid is None else np.asarray(w_mid, dtype=np.float64)
+        self.b_mid = None
+        if self.w_mid is not None:
+            Dm = self.w_mid.shape[1]
+            self.b_mid = np.zeros((H, Dm)) if b_mid is None else np.asarray(b_mid, dtype=np.float64)
         self.P = int(poly_degree)
         self.act = int(act)
         if F % self.P != 0:
@@ -73,7 +80,10 @@ class FeatureMap:
 
     def n_params(self):
         """Learnable parameter count of this one map over all heads (weights and biases)."""
-        return self.w1.size + self.b1.size + self.w2.size + self.b2.size
+        n = self.w1.size + self.b1.size + self.w2.size + self.b2.size
+        if self.w_mid is not None:
+            n += self.w_mid.size + self.b_mid.size
+        return n
 
 
 def token_split(N: int, R: int):
@@ -92,6 +102,8 @@ def feature_map(x, fm: FeatureMap, head: int):
     """phi(x) for rows x [n, d] of one head -> [n, F]  (Sec. 3.2, "Characterization of phi")."""
     x = np.asarray(x, dtype=np.float64)
     hidden = np.maximum(x @ fm.w1[head].T + fm.b1[head], 0.0)        # [n, Hd], ReLU
+    if fm.w_mid is not None:                                         # three-layer map: one more hidden layer
+        hidden = np.maximum(hidden @ fm.w_mid[head].T + fm.b_mid[head], 0.0)
     u = hidden @ fm.w2[head].T + fm.b2[head]                         # [n, F]
     if fm.act == ACT_SOFTMAX:
         u = u - u.max(axis=-1, keepdims=True)

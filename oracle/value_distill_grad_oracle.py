@@ -36,6 +36,8 @@ from . import hybrid_attn_oracle as O
 def feature_map_with_trace(x, fm: O.FeatureMap, head: int):
     """phi(x) of Sec. 3.2 together with what its derivative needs: rows x [n, d] ->
     (phi [n, F], hidden [n, Hd], pre-activation u [n, F], positive output t [n, F])."""
+    if fm.w_mid is not None:
+        raise ValueError("the gradient oracle covers the two-layer map only")
     x = np.asarray(x, dtype=np.float64)
     pre = x @ fm.w1[head].T + fm.b1[head]
     hidden = np.maximum(pre, 0.0)

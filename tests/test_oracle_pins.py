@@ -68,6 +68,32 @@ def pin_feature_map_is_grouped_conv(M):
             assert (got > 0).all()                        # phi must be non-negative (Sec. 3.1)
 
 
+def test_three_layer_feature_map_is_grouped_conv():
+    """The three-layer map of Tab. "phi" (its P = 6 row): three grouped 1x1 convolutions with a ReLU after the
+    first two, same output stage; and its parameter count through n_params() (15.4 M at d = 128, 12 heads)."""
+    rng = np.random.default_rng(12)
+    H, d, Hd, Dm, F, P, n = 3, 6, 10, 7, 9, 3, 17
+    fm = O.FeatureMap(rng.standard_normal((H, Hd, d)) / np.sqrt(d), rng.standard_normal((H, Hd)) * 0.3,
+                      rng.standard_normal((H, F, Dm)) / np.sqrt(Dm), rng.standard_normal((H, F)) * 0.3, P,
+                      w_mid=rng.standard_normal((H, Dm, Hd)) / np.sqrt(Hd), b_mid=rng.standard_normal((H, Dm)) * 0.3)
+    x = rng.standard_normal((H, n, d))
+    xt = torch.from_numpy(x).permute(0, 2, 1).reshape(1, H * d, n)
+    conv = torch.nn.functional.conv1d
+    h1 = torch.relu(conv(xt, torch.from_numpy(fm.w1).reshape(H * Hd, d, 1), torch.from_numpy(fm.b1).reshape(-1), groups=H))
+    h2 = torch.relu(conv(h1, torch.from_numpy(fm.w_mid).reshape(H * Dm, Hd, 1), torch.from_numpy(fm.b_mid).reshape(-1), groups=H))
+    u = conv(h2, torch.from_numpy(fm.w2).reshape(H * F, Dm, 1), torch.from_numpy(fm.b2).reshape(-1), groups=H)
+    t = torch.softmax(u.reshape(H, F, n), dim=1)
+    ref = torch.cat([torch.pow(part, p + 1) for p, part in enumerate(torch.chunk(t, P, dim=1))], dim=1)
+    for h in range(H):
+        np.testing.assert_allclose(O.feature_map(x[h], fm, h), ref[h].T.numpy(), rtol=1e-11, atol=1e-300)
+    # dropping the middle layer must change the result (the pin is sensitive to it)
+    two = O.FeatureMap(fm.w1, fm.b1, rng.standard_normal((H, F, Hd)), fm.b2, P)
+    assert not np.allclose(O.feature_map(x[0], two, 0), ref[0].T.numpy())
+    big = O.FeatureMap(np.zeros((12, 768, 128)), np.zeros((12, 768)), np.zeros((12, 768, 768)), np.zeros((12, 768)), 6,
+                       w_mid=np.zeros((12, 768, 768)), b_mid=np.zeros((12, 768)))
+    assert round(big.n_params() / 1e6, 1) == 15.4
+
+
 # ----------------------------------------------------------------------------- closed forms
 
 def pin_two_token_golden(M):
