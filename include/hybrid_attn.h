@@ -53,7 +53,10 @@ typedef enum { HA_ACT_SOFTMAX = 0, HA_ACT_EXP = 1, HA_ACT_RELU = 2 } ha_act;
 /* One feature map (phi_q or phi_k).  Weights are per head and shared over the batch
  * (Sec. 3.2: "per-head embedding network ... grouped 1x1 convolutions").
  *   hidden = relu(W1 x + b1),  u = W2 hidden + b2,  t = act(u),
- *   phi(x)[c] = t[c] ^ (1 + c / (F / P))          (integer division: slice p gets power p). */
+ *   phi(x)[c] = t[c] ^ (1 + c / (F / P))          (integer division: slice p gets power p).
+ * Three-layer map (Tab. "phi", the P = 6 row): with w_mid != NULL, hidden2 = relu(W_mid hidden + b_mid) sits
+ * between the two and W2 is [H, d_out, d_mid].  A caller that only knows the two-layer struct leaves the
+ * trailing fields zero. */
 typedef struct {
   const void  *w1;        /* device [H, d_hidden, d_head], io dtype, row-major, contiguous */
   const float *b1;        /* device [H, d_hidden] fp32, or NULL for zero bias */
@@ -63,6 +66,10 @@ typedef struct {
   int32_t d_out;          /* F = P * D': multiple of 32 */
   int32_t poly_degree;    /* P in 1..8, must divide d_out */
   int32_t out_act;        /* ha_act */
+  const void  *w_mid;     /* device [H, d_mid, d_hidden], io dtype, or NULL: two-layer map */
+  const float *b_mid;     /* device [H, d_mid] fp32, or NULL for zero bias */
+  int32_t d_mid;          /* width of the second hidden layer (ignored when w_mid is NULL) */
+  int32_t reserved;       /* 0 */
 } ha_feature_map;
 
 /* One forward problem.  q, k, v and out are [B, H, N, d_head] views: element (b, h, n, c) lives at
@@ -90,7 +97,10 @@ typedef struct {
  * linear tokens (hybrid_rate == 1); otherwise both are required and must agree in d_out.
  * Pointers inside the feature maps are checked for NULL and alignment but never dereferenced.
  * Supported here: d_head in {64, 128} with d_hidden == d_out == d_head, or d_head == 128 with
- * d_hidden == d_out == 256 (the paper's default widths, Tab. "phi"). */
+ * d_hidden == d_out == 256 (the paper's default widths, Tab. "phi"), both through kernels that keep a token's
+ * activations in registers; at d_head == 128 also any d_hidden, d_mid, d_out that are multiples of 128 up to 768,
+ * with two or three layers (the other rows of Tab. "phi"), layer by layer through HBM.  phi_q and phi_k must have
+ * the same widths and depth. */
 ha_status hybrid_attn_validate(const ha_problem *p, const ha_feature_map *phi_q,
                                const ha_feature_map *phi_k);
 

@@ -33,6 +33,11 @@ static ha_status check_map(const ha_feature_map *fm, const ha_problem &p) {
   // any other width goes layer by layer through HBM (ha_wide.hip): multiples of 128 up to 768 (Tab. "phi": P d, P <= 6)
   const bool layered = p.d_head == 128 && fm->d_hidden % 128 == 0 && fm->d_out % 128 == 0 && fm->d_hidden <= 768 &&
                        fm->d_out <= 768;
+  if (fm->w_mid) {   // three layers: always layer by layer
+    if (fm->d_mid <= 0) return HA_ERR_SHAPE;
+    if (!layered || fm->d_mid % 128 != 0 || fm->d_mid > 768) return HA_ERR_UNSUPPORTED;
+    if (!aligned16(fm->w_mid) || (fm->b_mid && (reinterpret_cast<uintptr_t>(fm->b_mid) & 3u))) return HA_ERR_ALIGN;
+  }
   if (!square && !paper_width && !layered) return HA_ERR_UNSUPPORTED;
   if (!aligned16(fm->w1) || !aligned16(fm->w2)) return HA_ERR_ALIGN;
   if ((fm->b1 && (reinterpret_cast<uintptr_t>(fm->b1) & 3u)) || (fm->b2 && (reinterpret_cast<uintptr_t>(fm->b2) & 3u)))
@@ -61,6 +66,8 @@ static ha_status validate(const ha_problem *p, const ha_feature_map *phi_q, cons
     if (s != HA_OK) return s;
     if (phi_q->d_out != phi_k->d_out || phi_q->d_hidden != phi_k->d_hidden) return HA_ERR_SHAPE;
     if (phi_q->poly_degree != phi_k->poly_degree) return HA_ERR_SHAPE;
+    if ((phi_q->w_mid != nullptr) != (phi_k->w_mid != nullptr)) return HA_ERR_SHAPE;
+    if (phi_q->w_mid && phi_q->d_mid != phi_k->d_mid) return HA_ERR_SHAPE;
   }
   return HA_OK;
 }
@@ -77,6 +84,7 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.HD = has_linear ? phi_k->d_hidden : pl.D;
   pl.F = has_linear ? phi_k->d_out : pl.D;
   pl.P = has_linear ? phi_k->poly_degree : 1;
+  pl.DM = has_linear && phi_k->w_mid ? phi_k->d_mid : 0;
   pl.act_q = has_linear ? phi_q->out_act : 0;
   pl.act_k = has_linear ? phi_k->out_act : 0;
   pl.KT = p.block_size;
@@ -116,7 +124,7 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
 static bool needs_wide_path(const Plan &pl) {
   const bool square = pl.HD == pl.D && pl.F == pl.D;
   const bool paper_width = pl.D == 128 && pl.HD == 256 && pl.F == 256;
-  return pl.NL > 0 && !square && !paper_width;
+  return pl.NL > 0 && ((!square && !paper_width) || pl.DM > 0);
 }
 
 // Plan of the forward plus, where needed, the layer-by-layer path's buffers behind it; returns the workspace size.
@@ -358,7 +366,7 @@ static ha_status check_grad_maps(const ha_problem *p, const ha_feature_map *phi_
     if (s != HA_OK) return s;
   }
   for (const ha_feature_map *fm : {phi_q, phi_k})
-    if (fm->d_hidden != p->d_head || fm->d_out != p->d_head) return HA_ERR_UNSUPPORTED;
+    if (fm->d_hidden != p->d_head || fm->d_out != p->d_head || fm->w_mid) return HA_ERR_UNSUPPORTED;
   return HA_OK;
 }
 
@@ -445,6 +453,6 @@ const char *hybrid_attn_status_string(ha_status s) {
 
 int hybrid_attn_last_device_error(void) { return ha::g_last_device_error; }
 
-int hybrid_attn_abi_version(void) { return 2; }
+int hybrid_attn_abi_version(void) { return 3; }
 
 }  // extern "C"

@@ -11,6 +11,7 @@ namespace ha {
 struct Plan {
   // problem
   int B, H, N, D, HD, F, R, NS, NL, P, act_q, act_k;
+  int DM;   // width of the second hidden layer of a three-layer feature map, 0 for two layers
   bool f32;
   int64_t sb, sh, sn;
   float scale;
@@ -34,7 +35,8 @@ struct GradPlan {
 // hidden activations (hi + lo), fp32 pre-activations, phi, and for the queries n = phi_q S and e = phi_q . z.
 struct WidePlan {
   int n_tb_q, n_tb_k;      // 32-token blocks of the query tokens / the linear key tokens
-  size_t off_hhi, off_hlo, off_u, off_phi, off_lin, off_e, total;
+  size_t off_w1, off_wm, off_w2;   // weight fragments of the map being evaluated (key side, then query side)
+  size_t off_hhi, off_hlo, off_h2hi, off_h2lo, off_u, off_phi, off_lin, off_e, total;
 };
 
 // Fills `pl` from a validated problem.  Pure host arithmetic.

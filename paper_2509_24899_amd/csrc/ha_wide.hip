@@ -3,6 +3,7 @@
 // all its output channels in registers, which ends at 256 channels.  Here every layer is a pass of its own and
 // activations travel through HBM, in exactly the register image the next product wants:
 //
+//   wide_prep_kernel       one weight matrix -> A-operand fragments (natural order for layer 1, chained after it)
 //   wide_layer1_kernel     h^T = relu(W1 x^T + b1)                     x from q / k, h as hi + lo bf16
 //   wide_layer_kernel      h'^T = relu(W h^T + b)  or  u^T = W h^T + b  (last layer: fp32 pre-activations)
 //   wide_phi_finish_kernel softmax / exp / relu over all channels of a token, slice powers, bf16; for the queries
@@ -30,6 +31,36 @@ struct WideArgs {
   int H, K, NOUT, n_tok, n_tb, R;
   int64_t sb, sh, sn;
 };
+
+// ------------------------------------------------------------------------------------------------
+// wide_prep_kernel: grid (ceil(NOUT*K / 256), H).  W [H][NOUT][K] (io dtype) ->
+//   natural:  wf[h][ob][ks][lane][t]    = W[h][32 ob + r][16 ks + 8 g + t]
+//   chained:  wf[h][ob][kb][s][lane][t] = W[h][32 ob + r][32 kb + crow(8 s + t, g)]
+template <bool F32, bool CHAINED>
+__global__ __launch_bounds__(256) void wide_prep_kernel(const void *__restrict__ wsrc, __bf16 *__restrict__ wf, int NOUT, int K) {
+  const int h = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= NOUT * K) return;
+  const int t = e & 7, lane = (e >> 3) & 63, rest = e >> 9;
+  const int r = lane & 31, g = lane >> 5;
+  int row, col;
+  if constexpr (CHAINED) {
+    const int KB = K / 32;
+    const int s = rest & 1, kb = (rest >> 1) % KB, ob = (rest >> 1) / KB;
+    row = 32 * ob + r;
+    col = 32 * kb + crow(8 * s + t, g);
+  } else {
+    const int KS = K / 16;
+    const int ks = rest % KS, ob = rest / KS;
+    row = 32 * ob + r;
+    col = 16 * ks + 8 * g + t;
+  }
+  const int64_t src = ((int64_t)h * NOUT + row) * K + col;
+  float val;
+  if constexpr (F32) val = static_cast<const float *>(wsrc)[src];
+  else val = static_cast<float>(static_cast<const __bf16 *>(wsrc)[src]);
+  wf[(int64_t)h * NOUT * K + e] = static_cast<__bf16>(val);
+}
 
 // ------------------------------------------------------------------------------------------------
 // wide_layer1_kernel: grid (ceil(n_tb / 4), NOUT / 128, B*H), 4 waves, one 32-token block per wave and four
@@ -385,8 +416,14 @@ void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp) {
   const size_t n_tb = wp.n_tb_q;                      // the key side (fewer tokens) reuses the query side's buffers
   size_t off = base_off;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+  const int KL = pl.DM > 0 ? pl.DM : pl.HD;            // input width of the last layer
+  wp.off_w1 = take((size_t)pl.H * pl.HD * pl.D * 2);
+  wp.off_wm = take((size_t)pl.H * pl.DM * pl.HD * 2);
+  wp.off_w2 = take((size_t)pl.H * pl.F * KL * 2);
   wp.off_hhi = take(BH * n_tb * 32 * pl.HD * 2);
   wp.off_hlo = take(BH * n_tb * 32 * pl.HD * 2);
+  wp.off_h2hi = take(BH * n_tb * 32 * pl.DM * 2);
+  wp.off_h2lo = take(BH * n_tb * 32 * pl.DM * 2);
   wp.off_u = take(BH * n_tb * 32 * (size_t)pl.F * 4);
   wp.off_phi = take(BH * n_tb * 32 * (size_t)pl.F * 2);
   wp.off_lin = take(BH * n_tb * 32 * (size_t)pl.D * 4);
@@ -394,14 +431,32 @@ void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp) {
   wp.total = off;
 }
 
-// One feature map over one token set: layer 1, last layer, output stage.  is_query: all N tokens of q, and
+// One feature map over one token set: weight fragments, layer 1, (middle layer,) last layer, output stage.  is_query: all N tokens of q, and
 // phi.z is formed; otherwise the linear tokens of k.
 static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query,
                                void *ws, hipStream_t st) {
   const int BH = pl.B * pl.H;
   const int n_tok = is_query ? pl.N : pl.NL, n_tb = is_query ? wp.n_tb_q : wp.n_tb_k;
   hipError_t e;
-  if ((e = launch_weight_prep(pl, fm, is_query, ws, st)) != hipSuccess) return e;
+  const int KL = pl.DM > 0 ? pl.DM : pl.HD;
+  // weight fragments of this map
+  {
+    auto prep = [&](const void *wsrc, size_t off, int nout, int kdim, bool chained) {
+      dim3 grid((nout * kdim + 255) / 256, pl.H);
+      __bf16 *dst = ws_ptr<__bf16>(ws, off);
+      if (pl.f32) {
+        if (chained) wide_prep_kernel<true, true><<<grid, 256, 0, st>>>(wsrc, dst, nout, kdim);
+        else wide_prep_kernel<true, false><<<grid, 256, 0, st>>>(wsrc, dst, nout, kdim);
+      } else {
+        if (chained) wide_prep_kernel<false, true><<<grid, 256, 0, st>>>(wsrc, dst, nout, kdim);
+        else wide_prep_kernel<false, false><<<grid, 256, 0, st>>>(wsrc, dst, nout, kdim);
+      }
+    };
+    prep(fm.w1, wp.off_w1, pl.HD, pl.D, false);
+    if (pl.DM > 0) prep(fm.w_mid, wp.off_wm, pl.DM, pl.HD, true);
+    prep(fm.w2, wp.off_w2, pl.F, KL, true);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   WideArgs a;
   a.x = x;
   a.H = pl.H; a.n_tok = n_tok; a.n_tb = n_tb; a.R = is_query ? 0 : pl.R;
@@ -409,7 +464,7 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
   a.in_hi = a.in_lo = nullptr;
   a.out_u = nullptr;
   // layer 1: d -> HD
-  a.wf = ws_ptr<bf16x8>(ws, is_query ? pl.off_w1q : pl.off_w1k);
+  a.wf = ws_ptr<bf16x8>(ws, wp.off_w1);
   a.bias = fm.b1; a.K = pl.D; a.NOUT = pl.HD;
   a.out_hi = ws_ptr<bf16x8>(ws, wp.off_hhi); a.out_lo = ws_ptr<bf16x8>(ws, wp.off_hlo);
   {
@@ -418,10 +473,20 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
     else wide_layer1_kernel<128, false><<<grid, 256, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  // last layer: HD -> F, fp32 pre-activations
   a.in_hi = ws_ptr<bf16x8>(ws, wp.off_hhi); a.in_lo = ws_ptr<bf16x8>(ws, wp.off_hlo);
-  a.wf = ws_ptr<bf16x8>(ws, is_query ? pl.off_w2q : pl.off_w2k);
-  a.bias = fm.b2; a.K = pl.HD; a.NOUT = pl.F;
+  if (pl.DM > 0) {
+    // middle layer of a three-layer map: HD -> DM, relu, hi + lo
+    a.wf = ws_ptr<bf16x8>(ws, wp.off_wm);
+    a.bias = fm.b_mid; a.K = pl.HD; a.NOUT = pl.DM;
+    a.out_hi = ws_ptr<bf16x8>(ws, wp.off_h2hi); a.out_lo = ws_ptr<bf16x8>(ws, wp.off_h2lo);
+    dim3 grid((n_tb + 3) / 4, pl.DM / 128, BH);
+    wide_layer_kernel<false><<<grid, 256, 0, st>>>(a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    a.in_hi = ws_ptr<bf16x8>(ws, wp.off_h2hi); a.in_lo = ws_ptr<bf16x8>(ws, wp.off_h2lo);
+  }
+  // last layer: -> F, fp32 pre-activations
+  a.wf = ws_ptr<bf16x8>(ws, wp.off_w2);
+  a.bias = fm.b2; a.K = KL; a.NOUT = pl.F;
   a.out_hi = a.out_lo = nullptr;
   a.out_u = ws_ptr<f32x4>(ws, wp.off_u);
   {

@@ -24,7 +24,8 @@ HA_ACT_SOFTMAX, HA_ACT_EXP, HA_ACT_RELU = 0, 1, 2
 class ha_feature_map(ctypes.Structure):
     _fields_ = [("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
                 ("d_hidden", ctypes.c_int32), ("d_out", ctypes.c_int32), ("poly_degree", ctypes.c_int32),
-                ("out_act", ctypes.c_int32)]
+                ("out_act", ctypes.c_int32),
+                ("w_mid", ctypes.c_void_p), ("b_mid", ctypes.c_void_p), ("d_mid", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class ha_feature_map_grad(ctypes.Structure):
@@ -106,24 +107,30 @@ def _lib():
 @dataclass
 class FeatureMap:
     """Device tensors of one feature map: w1 [H, Hd, d], b1 [H, Hd] fp32 or None, w2 [H, F, Hd],
-    b2 [H, F] fp32 or None; weights in the io dtype of q, k, v."""
+    b2 [H, F] fp32 or None; weights in the io dtype of q, k, v.  Three-layer map: w_mid [H, Dm, Hd],
+    b_mid [H, Dm] fp32 or None, and w2 is [H, F, Dm]."""
     w1: torch.Tensor
     b1: Optional[torch.Tensor]
     w2: torch.Tensor
     b2: Optional[torch.Tensor]
     poly_degree: int = 2
     out_act: int = HA_ACT_SOFTMAX
+    w_mid: Optional[torch.Tensor] = None
+    b_mid: Optional[torch.Tensor] = None
 
     def c_struct(self) -> ha_feature_map:
-        for t in (self.w1, self.w2):
-            if not t.is_contiguous():
+        for t in (self.w1, self.w2, self.w_mid):
+            if t is not None and not t.is_contiguous():
                 raise ValueError("feature-map weights must be contiguous")
-        for b in (self.b1, self.b2):
+        for b in (self.b1, self.b2, self.b_mid):
             if b is not None and (b.dtype != torch.float32 or not b.is_contiguous()):
                 raise ValueError("feature-map biases must be contiguous fp32")
         return ha_feature_map(self.w1.data_ptr(), self.b1.data_ptr() if self.b1 is not None else None,
                               self.w2.data_ptr(), self.b2.data_ptr() if self.b2 is not None else None,
-                              self.w1.shape[1], self.w2.shape[1], self.poly_degree, self.out_act)
+                              self.w1.shape[1], self.w2.shape[1], self.poly_degree, self.out_act,
+                              self.w_mid.data_ptr() if self.w_mid is not None else None,
+                              self.b_mid.data_ptr() if self.b_mid is not None else None,
+                              self.w_mid.shape[1] if self.w_mid is not None else 0, 0)
 
 
 def _dtype_code(t: torch.Tensor) -> int:
@@ -400,6 +407,8 @@ def to_device(inputs, device="cuda"):
         return torch.from_numpy(a).to(device=device, dtype=dtype).contiguous()
 
     def fm(p):
+        mid = getattr(p, "w_mid", None)
         return FeatureMap(dev(p.w1, dt), dev(p.b1, torch.float32), dev(p.w2, dt), dev(p.b2, torch.float32),
-                          p.poly_degree)
+                          p.poly_degree, w_mid=dev(mid, dt) if mid is not None else None,
+                          b_mid=dev(p.b_mid, torch.float32) if mid is not None else None)
     return dev(inputs.q, dt), dev(inputs.k, dt), dev(inputs.v, dt), fm(inputs.phi_q), fm(inputs.phi_k)

@@ -34,6 +34,7 @@ class Workload:
     grid: tuple = ()      # (frames, rows, cols) of the latent grid, metadata only
     qk_gain: float = 1.0  # stress sets multiply q and k by this
     w_gain: float = 1.0   # stress sets multiply the MLP weights by this
+    d_mid: int = 0        # width of the second hidden layer of a three-layer feature map (0: two layers)
 
     @property
     def n_softmax(self):
@@ -80,6 +81,8 @@ class FeatureMapParams:
     w2: np.ndarray   # [H, F, Hd]
     b2: np.ndarray   # [H, F]
     poly_degree: int
+    w_mid: Optional[np.ndarray] = None   # [H, Dm, Hd]: three-layer map (then w2 is [H, F, Dm])
+    b_mid: Optional[np.ndarray] = None   # [H, Dm]
 
 
 @dataclass
@@ -92,11 +95,16 @@ class Inputs:
     workload: Workload = field(repr=False, default=None)
 
 
-def _draw_map(rng, H, d, Hd, F, P, io_round, w_gain):
+def _draw_map(rng, H, d, Hd, F, P, io_round, w_gain, Dm=0):
     w1 = rng.standard_normal((H, Hd, d), dtype=np.float32) * np.float32(w_gain / np.sqrt(d))
     b1 = rng.standard_normal((H, Hd), dtype=np.float32) * np.float32(0.1)
-    w2 = rng.standard_normal((H, F, Hd), dtype=np.float32) * np.float32(w_gain / np.sqrt(Hd))
+    kl = Dm if Dm > 0 else Hd
+    w2 = rng.standard_normal((H, F, kl), dtype=np.float32) * np.float32(w_gain / np.sqrt(kl))
     b2 = rng.standard_normal((H, F), dtype=np.float32) * np.float32(0.1)
+    if Dm > 0:
+        w_mid = rng.standard_normal((H, Dm, Hd), dtype=np.float32) * np.float32(w_gain / np.sqrt(Hd))
+        b_mid = rng.standard_normal((H, Dm), dtype=np.float32) * np.float32(0.1)
+        return FeatureMapParams(io_round(w1), b1, io_round(w2), b2, P, io_round(w_mid), b_mid)
     return FeatureMapParams(io_round(w1), b1, io_round(w2), b2, P)
 
 
@@ -111,8 +119,8 @@ def make_inputs(w: Workload, heads: Optional[int] = None) -> Inputs:
     q = io_round(rng.standard_normal(shape, dtype=np.float32) * s)
     k = io_round(rng.standard_normal(shape, dtype=np.float32) * s)
     v = io_round(rng.standard_normal(shape, dtype=np.float32) * np.float32(1.0 / np.sqrt(w.d)))
-    phi_q = _draw_map(rng, H, w.d, w.d_hidden, w.d_feat, w.poly_degree, io_round, w.w_gain)
-    phi_k = _draw_map(rng, H, w.d, w.d_hidden, w.d_feat, w.poly_degree, io_round, w.w_gain)
+    phi_q = _draw_map(rng, H, w.d, w.d_hidden, w.d_feat, w.poly_degree, io_round, w.w_gain, w.d_mid)
+    phi_k = _draw_map(rng, H, w.d, w.d_hidden, w.d_feat, w.poly_degree, io_round, w.w_gain, w.d_mid)
     return Inputs(q, k, v, phi_q, phi_k, replace(w, H=H))
 
 

@@ -37,13 +37,13 @@ def test_header_symbols_are_exported(lib):
     assert len(set(names)) == 16
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert ha.hybrid_attn_abi_version() == 2
+    assert ha.hybrid_attn_abi_version() == 3
 
 
 def test_struct_layout_matches_header():
-    # 7 int32 + float, then three int64 at offset 32; four pointers then four int32
+    # 7 int32 + float, then three int64 at offset 32; four pointers, four int32, two pointers, two int32
     assert ha.ha_problem.stride_b.offset == 32 and ctypes.sizeof(ha.ha_problem) == 56
-    assert ha.ha_feature_map.d_hidden.offset == 32 and ctypes.sizeof(ha.ha_feature_map) == 48
+    assert ha.ha_feature_map.d_hidden.offset == 32 and ha.ha_feature_map.w_mid.offset == 48 and ctypes.sizeof(ha.ha_feature_map) == 72
 
 
 def test_valid_problems(lib):
@@ -214,3 +214,28 @@ def test_value_distill_grad_workspace_and_errors(lib):
     a = args(p=p1)
     a[4] = None
     assert f(*a) == ha.HA_ERR_NULL
+
+
+def test_wider_and_three_layer_maps_validate(lib):
+    """Host checks of the layer-by-layer path's shapes (Tab. "phi" rows beyond P = 2)."""
+    p = _problem()
+    for width in (384, 512, 768):
+        fm = _map(width, width, width // 128)
+        assert ha.hybrid_attn_validate(p, fm, fm) == ha.HA_OK
+        assert lib.hybrid_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(fm), ctypes.byref(fm)) > \
+            lib.hybrid_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(_map()), ctypes.byref(_map()))
+    mixed = _map(384, 512)
+    assert ha.hybrid_attn_validate(p, mixed, mixed) == ha.HA_OK
+    assert ha.hybrid_attn_validate(p, _map(896, 896), _map(896, 896)) == ha.HA_ERR_UNSUPPORTED     # beyond 768
+    assert ha.hybrid_attn_validate(p, _map(320, 320), _map(320, 320)) == ha.HA_ERR_UNSUPPORTED     # not a multiple of 128
+    assert ha.hybrid_attn_validate(_problem(H=2, N=1024, d=64, dtype=ha.HA_F32, bs=64), _map(128, 128), _map(128, 128)) == \
+        ha.HA_ERR_UNSUPPORTED                                                                      # wide maps need d_head = 128
+    three = ha.ha_feature_map(FAKE, None, FAKE + 0x100000, None, 768, 768, 6, ha.HA_ACT_SOFTMAX, FAKE + 0x200000, None, 768, 0)
+    assert ha.hybrid_attn_validate(p, three, three) == ha.HA_OK
+    assert ha.hybrid_attn_validate(p, three, _map(768, 768, 6)) == ha.HA_ERR_SHAPE                 # depths differ
+    bad = ha.ha_feature_map(FAKE, None, FAKE + 0x100000, None, 768, 768, 6, ha.HA_ACT_SOFTMAX, FAKE + 0x200000, None, 0, 0)
+    assert ha.hybrid_attn_validate(p, bad, bad) == ha.HA_ERR_SHAPE
+    odd = ha.ha_feature_map(FAKE, None, FAKE + 0x100000, None, 768, 768, 6, ha.HA_ACT_SOFTMAX, FAKE + 0x200000, None, 192, 0)
+    assert ha.hybrid_attn_validate(p, odd, odd) == ha.HA_ERR_UNSUPPORTED
+    # the gradient entry point has kernels for the d -> d -> d map only
+    assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(three), ctypes.byref(three)) == 0

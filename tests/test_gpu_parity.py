@@ -22,7 +22,7 @@ LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), 
 
 
 def oracle_map(p, act=O.ACT_SOFTMAX):
-    return O.FeatureMap(p.w1, p.b1, p.w2, p.b2, p.poly_degree, act)
+    return O.FeatureMap(p.w1, p.b1, p.w2, p.b2, p.poly_degree, act, w_mid=p.w_mid, b_mid=p.b_mid)
 
 
 def metrics(y_gpu, y_ref):
@@ -184,6 +184,19 @@ def test_wider_feature_maps_mixed_widths_and_short_input():
     w = W.replace(SMALL, name="phi_512_short", B=1, H=2, N=19, d_hidden=512, d_feat=512, poly_degree=4, seed=71)
     check("phi_512_N19_R4", W.make_inputs(w), R=4)
     check("phi_512_N19_R0", W.make_inputs(w), R=0)
+
+
+def test_three_layer_feature_map():
+    """Tab. "phi", P = 6 row: d -> 6d -> 6d -> 6d with three layers; and a small three-layer map whose widths
+    (128 -> 256 -> 128 -> 128) would otherwise go through the fused kernels."""
+    w = W.replace(SMALL, name="phi_P6_3layer", B=1, H=2, d_hidden=768, d_mid=768, d_feat=768, poly_degree=6, seed=80)
+    inp = W.make_inputs(w)
+    print("  case three layers 768", flush=True)
+    check("phi_P6_3layer_R4", inp, R=4)
+    check("phi_P6_3layer_R0", inp, R=0)
+    w = W.replace(SMALL, name="phi_3layer_small", B=2, H=2, d_hidden=256, d_mid=128, d_feat=128, poly_degree=2, seed=81)
+    print("  case three layers 256-128-128", flush=True)
+    check("phi_3layer_small_R3", W.make_inputs(w), R=3)
 
 
 def test_linear_state_tap():
