@@ -201,6 +201,8 @@ def main():
     ap.add_argument("--phi-width", type=int, default=None,
                     help="hidden and output width of both feature maps (default: the workload's d -> d -> d; 256, 384, 512 "
                          "are the two-layer rows P = 2, 3, 4 of Tab. phi at d = 128, 768 the width of its P = 6 row)")
+    ap.add_argument("--phi-layers", type=int, default=2, choices=[2, 3],
+                    help="MLP depth of both feature maps; 3 adds a hidden layer of the same width (Tab. phi, P = 6 row)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
@@ -239,6 +241,8 @@ def main():
         # Tab. "phi": D' = d channels per slice, so a map of width P d has polynomial degree P
         w = W.replace(w, d_hidden=args.phi_width, d_feat=args.phi_width,
                       poly_degree=args.phi_width // w.d if args.phi_width % w.d == 0 else w.poly_degree)
+    if args.phi_layers == 3:
+        w = W.replace(w, d_mid=w.d_hidden)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
@@ -252,10 +256,14 @@ def main():
         q.zero_(), k.zero_(), v.zero_()
 
     def dmap():
-        return ha.FeatureMap((torch.randn(w.H, w.d_hidden, w.d, generator=gen, device=dev) * w.d ** -0.5).to(dt),
-                             torch.randn(w.H, w.d_hidden, generator=gen, device=dev) * 0.1,
-                             (torch.randn(w.H, w.d_feat, w.d_hidden, generator=gen, device=dev) * w.d_hidden ** -0.5).to(dt),
-                             torch.randn(w.H, w.d_feat, generator=gen, device=dev) * 0.1, w.poly_degree)
+        fm = ha.FeatureMap((torch.randn(w.H, w.d_hidden, w.d, generator=gen, device=dev) * w.d ** -0.5).to(dt),
+                           torch.randn(w.H, w.d_hidden, generator=gen, device=dev) * 0.1,
+                           (torch.randn(w.H, w.d_feat, w.d_hidden, generator=gen, device=dev) * w.d_hidden ** -0.5).to(dt),
+                           torch.randn(w.H, w.d_feat, generator=gen, device=dev) * 0.1, w.poly_degree)
+        if w.d_mid:
+            fm.w_mid = (torch.randn(w.H, w.d_mid, w.d_hidden, generator=gen, device=dev) * w.d_hidden ** -0.5).to(dt)
+            fm.b_mid = torch.randn(w.H, w.d_mid, generator=gen, device=dev) * 0.1
+        return fm
     fq, fk = (dmap(), dmap()) if w.R != 1 else (None, None)
     prob = ha.make_problem(q, w.R, w.block_size, w.scale)
     ws = torch.empty(ha.hybrid_attn_workspace_bytes(prob, fq, fk), dtype=torch.uint8, device=dev)
@@ -332,8 +340,11 @@ def main():
     if n_s > 0:
         # dominant kernel: the fused query kernel; its algorithmic flops are everything except the
         # key-side feature map and state (4 N N_S d + phi_q MLP + g.S, g.z)
+        layered = n_l > 0 and (w.d_mid or not ((w.d_hidden == w.d and w.d_feat == w.d) or (w.d_hidden == 256 and w.d_feat == 256)))
+        # (maps that go layer by layer through HBM leave only the softmax loop and the merge to the query kernel)
         k_flops = w.B * w.H * (4.0 * w.N * n_s * w.d + (2.0 * w.N * (w.d * w.d_hidden + w.d_hidden * w.d_feat)
-                                                         + 2.0 * w.N * w.d_feat * w.d + 2.0 * w.N * w.d_feat if n_l > 0 else 0.0))
+                                                         + 2.0 * w.N * w.d_feat * w.d + 2.0 * w.N * w.d_feat
+                                                         if n_l > 0 and not layered else 0.0))
         achieved = k_flops / (mean[3] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "query_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_TFLOPS, "kernel_ms": mean[3], "traffic": None}
@@ -360,7 +371,8 @@ def main():
         "data": "synthetic" if not args.zero_inputs else "all-zero q, k, v (clock experiment, not a benchmark)",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype,
                    "hybrid_rate_R": w.R, "r": (1.0 / w.R if w.R else 0.0), "block_size": w.block_size,
-                   "feature_map": f"{w.d}->{w.d_hidden}->{w.d_feat}, P={w.poly_degree}"},
+                   "feature_map": (f"{w.d}->{w.d_hidden}->{w.d_mid}->{w.d_feat}" if w.d_mid else f"{w.d}->{w.d_hidden}->{w.d_feat}")
+                   + f", P={w.poly_degree}"},
         "tflops": flops / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "forward_ms_median": fwd_sorted[len(fwd_sorted) // 2], "forward_ms_min": fwd_sorted[0],

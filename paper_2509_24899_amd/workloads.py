@@ -144,7 +144,8 @@ def algorithmic_flops(w: Workload) -> float:
     n_s, n_l, N, d, Hd, F = w.n_softmax, w.n_linear, w.N, w.d, w.d_hidden, w.d_feat
     per_head = 4.0 * N * n_s * d
     if n_l > 0:
-        per_head += 2.0 * (N + n_l) * (d * Hd + Hd * F)
+        mlp = d * Hd + (Hd * w.d_mid + w.d_mid * F if w.d_mid else Hd * F)       # multiply-adds per token
+        per_head += 2.0 * (N + n_l) * mlp
         per_head += 2.0 * n_l * F * d + n_l * F
         per_head += 2.0 * N * F * d + 2.0 * N * F
     return w.B * w.H * per_head

@@ -262,6 +262,16 @@ def test_config2_shape_other_rates_sampled(R):
     _sampled(f"cfg2_shape_R{R}", W.with_rate(W.WAN_480P_81F, R), n_random=64)
 
 
+@pytest.mark.parametrize("P,layers", [(4, 2), (6, 3)])
+def test_config2_shape_tab_phi_rows_sampled(P, layers):
+    """480p / 81 frames with the P = 4 (two layers) and P = 6 (three layers) maps of Tab. "phi", three heads:
+    the layer-by-layer path at full sequence length, oracle on sampled rows."""
+    w = W.replace(W.WAN_480P_81F, name=f"cfg2_phi_P{P}", H=3, d_hidden=128 * P, d_feat=128 * P, poly_degree=P,
+                  d_mid=128 * P if layers == 3 else 0, seed=90 + P)
+    print(f"  case full length P={P} layers={layers}", flush=True)
+    _sampled(f"cfg2_N32760_phi_P{P}_L{layers}", w, n_random=64)
+
+
 def test_config4_wan_480p_161f_sampled():
     _sampled("cfg4_N63960_R8", W.WAN_480P_161F, n_random=128)
 
