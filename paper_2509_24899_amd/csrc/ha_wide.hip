@@ -106,56 +106,78 @@ __global__ __launch_bounds__(256) void wide_layer1_kernel(WideArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// wide_layer_kernel: grid (ceil(n_tb / 4), NOUT / 128, B*H).  Input activations as hi + lo C images (width K),
-// weights [NOUT x K] as fragments in chained order (weight_prep_kernel's second layout).  LAST: fp32
-// pre-activations out; otherwise relu and hi + lo bf16.  The fragments of the next 32 input channels are
-// requested before the 16 matrix instructions of the current ones.
+// wide_layer_kernel: grid (ceil(n_tb / 4), ceil(NOUT / 256), B*H), 4 waves.  Input activations as hi + lo C images
+// (width K), weights [NOUT x K] as fragments in chained order.  LAST: fp32 pre-activations out; otherwise relu
+// and hi + lo bf16.  Every wave owns one 32-token block and all (up to eight) 32-channel output tiles of the
+// workgroup, so an activation fragment is read once per 256 output channels; the weight fragments are the same
+// for the four waves and pass through LDS, two 32-channel input blocks per stage, the next stage in flight
+// (direct-to-LDS) while the 64 matrix instructions of the current one run.
 template <bool LAST>
-__global__ __launch_bounds__(256) void wide_layer_kernel(WideArgs a) {
+__global__ __launch_bounds__(256, 2) void wide_layer_kernel(WideArgs a) {
+  constexpr int NT = 8, KCH = 2, STG = NT * KCH * 2 * 64;       // bf16x8 per stage buffer (32 KiB)
+  __shared__ bf16x8 wl[2][STG];
   const int bh = blockIdx.z, h = bh % a.H;
   const int lane = threadIdx.x & 63, g = lane >> 5;
-  const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (tb >= a.n_tb) return;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool live = blockIdx.x * 4 + w < a.n_tb;                 // idle waves keep staging and synchronising
+  const int tb = live ? blockIdx.x * 4 + w : a.n_tb - 1;
   const int KB = a.K / 32, OB = a.NOUT / 32;
-  const GlobalFrags wf = global_frags(a.wf + (int64_t)h * ((int64_t)a.NOUT * a.K / 8), a.NOUT * a.K * 2);
+  const int ob0 = blockIdx.y * NT;
+  const int nt = min(NT, OB - ob0);
+  const bf16x8 *wg = a.wf + (int64_t)h * ((int64_t)a.NOUT * a.K / 8);
   const bf16x8 *bhi = a.in_hi + ((int64_t)bh * a.n_tb + tb) * KB * 128 + lane;
   const bf16x8 *blo = a.in_lo + ((int64_t)bh * a.n_tb + tb) * KB * 128 + lane;
-  const int ob0 = blockIdx.y * 4;
-  f32x16 acc[4];
+  f32x16 acc[NT];
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+  for (int j = 0; j < NT; ++j)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[j][v] = a.bias ? a.bias[(int64_t)h * a.NOUT + 32 * (ob0 + j) + crow(v, g)] : 0.f;
-  bf16x8 cb_hi[2], cb_lo[2], ca[4][2], nb_hi[2], nb_lo[2], na[4][2];
-  auto request = [&](int kb, bf16x8 (&hi)[2], bf16x8 (&lo)[2], bf16x8 (&wa)[4][2]) {
+    for (int v = 0; v < 16; ++v) acc[j][v] = (a.bias && j < nt) ? a.bias[(int64_t)h * a.NOUT + 32 * (ob0 + j) + crow(v, g)] : 0.f;
+  auto stage = [&](int c, int buf) {              // input blocks c KCH .. c KCH + KCH - 1 of every output tile
+    for (int j = 0; j < nt; ++j)
+      dma_to_lds(wg + (((int64_t)(ob0 + j) * KB + c * KCH) * 2) * 64, &wl[buf][j * KCH * 2 * 64], KCH * 2, w, 4, lane);
+  };
+  bf16x8 cb_hi[2], cb_lo[2], nb_hi[2], nb_lo[2];
+  auto request_b = [&](int kb, bf16x8 (&hi)[2], bf16x8 (&lo)[2]) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       hi[s] = bhi[(kb * 2 + s) * 64];
       lo[s] = blo[(kb * 2 + s) * 64];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) wa[j][s] = frag_at(wf, ((ob0 + j) * KB + kb) * 2 + s, lane);
     }
   };
-  request(0, cb_hi, cb_lo, ca);
-  for (int kb = 0; kb < KB; ++kb) {
-    if (kb + 1 < KB) request(kb + 1, nb_hi, nb_lo, na);
+  stage(0, 0);
+  request_b(0, cb_hi, cb_lo);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  const int n_stages = KB / KCH;
+  for (int c = 0; c < n_stages; ++c) {
+    if (c + 1 < n_stages) stage(c + 1, (c + 1) & 1);
+    const bf16x8 *wbuf = &wl[c & 1][lane];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int kbl = 0; kbl < KCH; ++kbl) {
+      const int kb = c * KCH + kbl;
+      if (kb + 1 < KB) request_b(kb + 1, nb_hi, nb_lo);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        acc[j] = mfma32(ca[j][s], cb_lo[s], acc[j]);
-        acc[j] = mfma32(ca[j][s], cb_hi[s], acc[j]);
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          if (j < nt) {
+            const bf16x8 af = wbuf[(j * KCH * 2 + kbl * 2 + s) * 64];
+            acc[j] = mfma32(af, cb_lo[s], acc[j]);
+            acc[j] = mfma32(af, cb_hi[s], acc[j]);
+          }
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        cb_hi[s] = nb_hi[s];
+        cb_lo[s] = nb_lo[s];
       }
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      cb_hi[s] = nb_hi[s];
-      cb_lo[s] = nb_lo[s];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) ca[j][s] = na[j][s];
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                               // the next stage has landed; this one may be overwritten
   }
+  if (!live) return;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NT; ++j) {
+    if (j >= nt) break;
     const int64_t blk = ((int64_t)bh * a.n_tb + tb) * OB + ob0 + j;
     if constexpr (LAST) {
 #pragma unroll
@@ -178,16 +200,17 @@ __global__ __launch_bounds__(256) void wide_layer_kernel(WideArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// wide_phi_finish_kernel: grid (ceil(n_tb / 4), B*H), one 32-token block per wave, all F <= 32 * FBMAX
-// pre-activations of a token in registers (one wave per SIMD).  Output: phi as bf16 C image (zero for tokens
-// past the end); QUERY: e[bh][token] = phi . z with the rounded phi, as the numerator will use it.
-constexpr int WIDE_FBMAX = 24;
+// wide_phi_finish_kernel: grid (ceil(n_tb / 4), B*H), one 32-token block per wave.  Two sweeps over the fp32
+// pre-activations of the block, one 32-channel tile in registers at a time: running maximum and sum of
+// exponentials first (softmax only), then normalisation, slice powers and rounding.  Output: phi as bf16 C image
+// (zero for tokens past the end); QUERY: e[bh][token] = phi . z with the rounded phi, as the numerator uses it.
+constexpr int WIDE_FMAX = 768;
 
 template <bool QUERY>
-__global__ __launch_bounds__(256, 1) void wide_phi_finish_kernel(const f32x4 *__restrict__ u_in, bf16x8 *__restrict__ phi_out,
-                                                                 const float *__restrict__ z, float *__restrict__ e_out,
-                                                                 int F, int n_tok, int n_tb, int act, int P) {
-  __shared__ float zl[QUERY ? 32 * WIDE_FBMAX : 1];
+__global__ __launch_bounds__(256) void wide_phi_finish_kernel(const f32x4 *__restrict__ u_in, bf16x8 *__restrict__ phi_out,
+                                                              const float *__restrict__ z, float *__restrict__ e_out,
+                                                              int F, int n_tok, int n_tb, int act, int P) {
+  __shared__ float zl[QUERY ? WIDE_FMAX : 1];
   const int bh = blockIdx.y;
   if constexpr (QUERY) {
     for (int i = threadIdx.x; i < F; i += 256) zl[i] = z[(int64_t)bh * F + i];
@@ -196,73 +219,67 @@ __global__ __launch_bounds__(256, 1) void wide_phi_finish_kernel(const f32x4 *__
   const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
   const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tb >= n_tb) return;
-  const int FB = F / 32, Dp = F / P;
+  const int FB = F / 32;
+  const float inv_groups = 8.0f * (float)P / (float)F;        // 1 / (8-channel groups per slice)
   const bool valid = 32 * tb + r < n_tok;
-  f32x16 u[WIDE_FBMAX];
+  const f32x4 *src = u_in + ((int64_t)bh * n_tb + tb) * FB * 256 + lane;
+  auto load_tile = [&](int fb, f32x16 &u) {
 #pragma unroll
-  for (int fb = 0; fb < WIDE_FBMAX; ++fb)
-    if (fb < FB) {
+    for (int x4 = 0; x4 < 4; ++x4) {
+      const f32x4 t = src[(fb * 4 + x4) * 64];
 #pragma unroll
-      for (int x4 = 0; x4 < 4; ++x4) {
-        const f32x4 t = u_in[((((int64_t)bh * n_tb + tb) * FB + fb) * 4 + x4) * 64 + lane];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) u[fb][4 * x4 + j] = t[j];
-      }
+      for (int j = 0; j < 4; ++j) u[4 * x4 + j] = t[j];
     }
+  };
+  float off = 0.f, inv = 1.f;
   if (act == 0) {
-    float mx = -INFINITY;
+    float m = -INFINITY, sum = 0.f;
+    for (int fb = 0; fb < FB; ++fb) {
+      f32x16 u;
+      load_tile(fb, u);
+      float t = u[0];
 #pragma unroll
-    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
-      if (fb < FB)
+      for (int v = 1; v < 16; ++v) t = fmaxf(t, u[v]);
+      const float m_new = fmaxf(m, xhalf_max(t));
+      sum *= fast_exp2((m - m_new) * kLog2e);                  // exp2(-inf) = 0 on the first tile
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, u[fb][v]);
-    mx = xhalf_max(mx);
-    const float off = -mx * kLog2e;
-    float sum = 0.f;
-#pragma unroll
-    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
-      if (fb < FB)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          u[fb][v] = fast_exp2(__builtin_fmaf(u[fb][v], kLog2e, off));
-          sum += u[fb][v];
-        }
-    const float inv = 1.0f / xhalf_sum(sum);
-#pragma unroll
-    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
-      if (fb < FB)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) u[fb][v] *= inv;
-  } else {
-#pragma unroll
-    for (int fb = 0; fb < WIDE_FBMAX; ++fb)
-      if (fb < FB)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) u[fb][v] = act == 1 ? fast_exp2(u[fb][v] * kLog2e) : fmaxf(u[fb][v], 0.f);
+      for (int v = 0; v < 16; ++v) sum += fast_exp2((u[v] - m_new) * kLog2e);
+      m = m_new;
+    }
+    off = -m * kLog2e;
+    inv = 1.0f / xhalf_sum(sum);
   }
   float dot = 0.f;
+  for (int fb = 0; fb < FB; ++fb) {
+    f32x16 u;
+    load_tile(fb, u);
 #pragma unroll
-  for (int fb = 0; fb < WIDE_FBMAX; ++fb)
-    if (fb < FB) {
+    for (int v = 0; v < 16; ++v) {
+      if (act == 0) u[v] = fast_exp2(__builtin_fmaf(u[v], kLog2e, off)) * inv;
+      else if (act == 1) u[v] = fast_exp2(u[v] * kLog2e);
+      else u[v] = fmaxf(u[v], 0.f);
+    }
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        f32x8 t8;
+    for (int s = 0; s < 2; ++s) {
+      f32x8 t8;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int extra = (32 * fb + 8 * (2 * s + i / 4)) / Dp;      // slice power - 1, wave-uniform
-          const float t0 = u[fb][8 * s + i];
-          float t = t0;
-          for (int k = 0; k < extra; ++k) t *= t0;
-          t8[i] = valid ? t : 0.f;
-        }
-        const bf16x8 p8 = __builtin_convertvector(t8, bf16x8);
-        phi_out[((((int64_t)bh * n_tb + tb) * FB + fb) * 2 + s) * 64 + lane] = p8;
-        if constexpr (QUERY) {
+      for (int i = 0; i < 8; ++i) {
+        // slice power - 1 = (8-channel group index) / (groups per slice), wave-uniform; exact in fp32 for these sizes
+        const int extra = (int)(((float)(4 * fb + 2 * s + i / 4) + 0.5f) * inv_groups);
+        const float t0 = u[8 * s + i], t2 = t0 * t0;
+        float t = (extra & 1) ? t2 : t0;                           // t0^(extra + 1), extra in 0..7
+        t = (extra & 2) ? t * t2 : t;
+        t = (extra & 4) ? t * (t2 * t2) : t;
+        t8[i] = valid ? t : 0.f;
+      }
+      const bf16x8 p8 = __builtin_convertvector(t8, bf16x8);
+      phi_out[((((int64_t)bh * n_tb + tb) * FB + fb) * 2 + s) * 64 + lane] = p8;
+      if constexpr (QUERY) {
 #pragma unroll
-          for (int i = 0; i < 8; ++i) dot += static_cast<float>(p8[i]) * zl[32 * fb + crow(8 * s + i, g)];
-        }
+        for (int i = 0; i < 8; ++i) dot += static_cast<float>(p8[i]) * zl[32 * fb + crow(8 * s + i, g)];
       }
     }
+  }
   if constexpr (QUERY) {
     dot = xhalf_sum(dot);
     if (g == 0 && valid) e_out[(int64_t)bh * n_tok + 32 * tb + r] = dot;
@@ -479,7 +496,7 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
     a.wf = ws_ptr<bf16x8>(ws, wp.off_wm);
     a.bias = fm.b_mid; a.K = pl.HD; a.NOUT = pl.DM;
     a.out_hi = ws_ptr<bf16x8>(ws, wp.off_h2hi); a.out_lo = ws_ptr<bf16x8>(ws, wp.off_h2lo);
-    dim3 grid((n_tb + 3) / 4, pl.DM / 128, BH);
+    dim3 grid((n_tb + 3) / 4, (pl.DM + 255) / 256, BH);
     wide_layer_kernel<false><<<grid, 256, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     a.in_hi = ws_ptr<bf16x8>(ws, wp.off_h2hi); a.in_lo = ws_ptr<bf16x8>(ws, wp.off_h2lo);
@@ -490,7 +507,7 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
   a.out_hi = a.out_lo = nullptr;
   a.out_u = ws_ptr<f32x4>(ws, wp.off_u);
   {
-    dim3 grid((n_tb + 3) / 4, pl.F / 128, BH);
+    dim3 grid((n_tb + 3) / 4, (pl.F + 255) / 256, BH);
     wide_layer_kernel<true><<<grid, 256, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
