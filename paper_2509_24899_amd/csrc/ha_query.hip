@@ -183,7 +183,9 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
 // waiting for this wave's outstanding loads) closes every G-th step.  NB >= 2 G + 2 makes this safe:
 // the slot being refilled was last read before the latest barrier every wave has passed, and a block
 // is first read (as K(j+2)) at least one barrier after it was requested.
-template <int D, int HD, int F, int NW, int NB, int G, bool F32>
+// LIN: the linear part arrives precomputed (maps too wide for the epilogue below); a variant of its own so that
+// the usual kernel carries none of it.
+template <int D, int HD, int F, int NW, int NB, int G, bool F32, bool LIN = false>
 __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   static_assert(G <= 2 && NB >= 2 * G + 2 && (NB & (NB - 1)) == 0, "ring too short for the barrier period");
   constexpr int KS = D / 16, RB = D / 32;
@@ -199,12 +201,12 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   // layer-1 weights of phi_q in an area of their own, fetched at kernel start; the layer-2 weights and the
   // state (hi + lo) in the ring once the loop has ended.
   constexpr int NW1 = HD * D / 8, NW2 = F * HD / 8, NST = D * F / 8;   // bf16x8 per head / per (batch, head)
-  constexpr bool ELDS = NW == 8 && NW1 * 16 <= 32 * 1024 && (NW2 + 2 * NST) <= 2 * NB * FRAG &&
+  constexpr bool ELDS = !LIN && NW == 8 && NW1 * 16 <= 32 * 1024 && (NW2 + 2 * NST) <= 2 * NB * FRAG &&
                         NW1 % (64 * NW) == 0 && NW2 % (64 * NW) == 0 && NST % (64 * NW) == 0;
   __shared__ bf16x8 w1_lds[ELDS ? NW1 : 1];
   // Wider maps: the operands do not fit at once, but the ring takes them in three rounds after the loop
   // (layer-1 weights + first half of the layer-2 weights, second half, state hi + lo).
-  constexpr bool PHASED = NW == 8 && !ELDS && NW1 <= NB * FRAG && NW2 / 2 <= NB * FRAG && NST <= NB * FRAG &&
+  constexpr bool PHASED = !LIN && NW == 8 && !ELDS && NW1 <= NB * FRAG && NW2 / 2 <= NB * FRAG && NST <= NB * FRAG &&
                           NW1 % 64 == 0 && (NW2 / 2) % 64 == 0 && NST % 64 == 0 && (F / 32) % 2 == 0;
 
   const int per_xcd = (a.total_wg + 7) >> 3;
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     }
   };
   if constexpr (ELDS) {
-    if (a.has_linear && !a.lin) stage_in(a.w1f + (int64_t)h * NW1, w1_lds, NW1 / 64);
+    if (a.has_linear) stage_in(a.w1f + (int64_t)h * NW1, w1_lds, NW1 / 64);
   }
 
   bf16x8 qf[KS];
@@ -434,7 +436,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
       for (int x = 0; x < 16; ++x) o[rb][x] *= alpha;
   }
   char *stage = reinterpret_cast<char *>(&ring[0]) + w * (2 * NB * FRAG * 16 / NW);
-  if (a.lin) {
+  if constexpr (LIN) {
     // linear part computed by the wide-map passes: add it to the accumulators, which share its register layout
     float den = xhalf_sum(lsum);
     const int tb = q0 >> 5;
@@ -550,8 +552,17 @@ hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi
     if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32><<<grid, 512, 0, st>>>(a); \
     else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \
   } while (0)
-  if (pl.D == 64) { if (pl.f32) HA_QUERY(64, 64, 64, true); else HA_QUERY(64, 64, 64, false); }
-  else if (pl.HD == 128 || wide) { if (pl.f32) HA_QUERY(128, 128, 128, true); else HA_QUERY(128, 128, 128, false); }
+  if (wide) {
+    if (big) {
+      if (pl.f32) query_kernel_ring<128, 128, 128, 8, 8, 2, true, true><<<grid, 512, 0, st>>>(a);
+      else query_kernel_ring<128, 128, 128, 8, 8, 2, false, true><<<grid, 512, 0, st>>>(a);
+    } else {
+      if (pl.f32) query_kernel_ring<128, 128, 128, 4, 4, 1, true, true><<<grid, 256, 0, st>>>(a);
+      else query_kernel_ring<128, 128, 128, 4, 4, 1, false, true><<<grid, 256, 0, st>>>(a);
+    }
+  }
+  else if (pl.D == 64) { if (pl.f32) HA_QUERY(64, 64, 64, true); else HA_QUERY(64, 64, 64, false); }
+  else if (pl.HD == 128) { if (pl.f32) HA_QUERY(128, 128, 128, true); else HA_QUERY(128, 128, 128, false); }
   else { if (pl.f32) HA_QUERY(128, 256, 256, true); else HA_QUERY(128, 256, 256, false); }
 #undef HA_QUERY
   return hipGetLastError();
