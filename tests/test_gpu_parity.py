@@ -186,6 +186,15 @@ def test_wider_feature_maps_mixed_widths_and_short_input():
     check("phi_512_N19_R0", W.make_inputs(w), R=0)
 
 
+def test_wider_feature_maps_fp32_io_and_strided_layout():
+    """The layer-by-layer path with fp32 q, k, v and weights (rounded to bf16 on load, fp32 output) and with
+    [B, N, H, d] memory behind the [B, H, N, d] views."""
+    w = W.replace(SMALL, name="phi_384_f32", B=1, H=2, dtype="f32", d_hidden=384, d_feat=384, poly_degree=3, seed=72)
+    check("phi_384_f32_R4", W.make_inputs(w), R=4)
+    w = W.replace(SMALL, name="phi_512_bnhd", B=2, H=3, d_hidden=512, d_feat=512, poly_degree=4, seed=73)
+    check("phi_512_bnhd_R3", W.make_inputs(w), R=3, layout="bnhd")
+
+
 def test_three_layer_feature_map():
     """Tab. "phi", P = 6 row: d -> 6d -> 6d -> 6d with three layers; and a small three-layer map whose widths
     (128 -> 256 -> 128 -> 128) would otherwise go through the fused kernels."""
