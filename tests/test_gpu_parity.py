@@ -394,3 +394,23 @@ def test_null_biases(which):
     ma, rl = metrics(out.float().cpu().numpy(), ref)
     record(f"null_bias_{which}", ma, rl)
     assert ma <= MAX_ABS and rl <= REL_L2
+
+
+@pytest.mark.parametrize("seed", range(18))
+def test_mixed_small_configurations(seed):
+    """Everything the ABI lets a caller vary, changed at once along a fixed schedule: head size, io dtype, batch and
+    head counts, sequence length (from a single token to several tiles with a ragged tail), rate (0, 1, powers of
+    two and not), block size, memory layout, feature-map shape (square, 256 wide, the wider and three-layer ones),
+    polynomial degree and output activation."""
+    d = (64, 128, 128)[seed % 3]
+    N = (1, 2, 31, 33, 127, 129, 300, 517, 700)[seed % 9]
+    R = min((0, 4, 1, 3, 2, 8, 5, 16, 7)[(seed * 5 + 1) % 9], N)
+    shapes = [(64, 64, 0)] if d == 64 else [(128, 128, 0), (256, 256, 0), (384, 384, 0), (128, 256, 0), (256, 128, 128), (384, 256, 128)]
+    Hd, F, Dm = shapes[(seed // 3) % len(shapes)]
+    P = (1, 2, 4)[seed % 3] if F % 4 == 0 else 1
+    w = W.Workload(f"mix{seed}", 1 + seed % 2, 1 + seed % 3, N, d, ("bf16", "f32")[(seed // 2) % 2], (64, 128)[(seed // 3) % 2], R,
+                   Hd, F, poly_degree=P, seed=2000 + seed, d_mid=Dm, qk_gain=(1.0, float(d ** 0.5))[seed % 2])
+    act = (ha.HA_ACT_SOFTMAX, ha.HA_ACT_SOFTMAX, ha.HA_ACT_EXP, ha.HA_ACT_RELU)[seed % 4]
+    layout = ("bhnd", "bnhd")[(seed // 4) % 2]
+    print(f"  case {w} act={act} layout={layout}", flush=True)
+    check(f"mix{seed}", W.make_inputs(w), act=act, layout=layout)
