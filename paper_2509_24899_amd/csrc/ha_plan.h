@@ -36,7 +36,7 @@ struct GradPlan {
 struct WidePlan {
   int n_tb_q, n_tb_k;      // 32-token blocks of the query tokens / the linear key tokens
   size_t off_w1, off_wm, off_w2;   // weight fragments of the map being evaluated (key side, then query side)
-  size_t off_hhi, off_hlo, off_h2hi, off_h2lo, off_u, off_phi, off_lin, off_e, total;
+  size_t off_hhi, off_hlo, off_h2hi, off_h2lo, off_u, off_stat, off_phi, off_lin, off_e, total;
 };
 
 // Fills `pl` from a validated problem.  Pure host arithmetic.

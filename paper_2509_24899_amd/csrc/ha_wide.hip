@@ -28,6 +28,7 @@ struct WideArgs {
   const float *bias;             // [H][NOUT] or null
   bf16x8 *out_hi, *out_lo;       // hidden layers
   f32x4 *out_u;                  // last layer
+  float *out_stat;               // last layer: [bh][tb][256-channel block][2][64] running maximum and sum of exponentials
   int H, K, NOUT, n_tok, n_tb, R;
   int64_t sb, sh, sn;
 };
@@ -175,6 +176,27 @@ __global__ __launch_bounds__(256, 2) void wide_layer_kernel(WideArgs a) {
     __syncthreads();                               // the next stage has landed; this one may be overwritten
   }
   if (!live) return;
+  if constexpr (LAST) {
+    // per token: maximum of this workgroup's channels and the sum of exponentials against it, so that the output
+    // stage can form the softmax over all channels with a single sweep over the pre-activations
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+      if (j < nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m = fmaxf(m, acc[j][v]);
+    m = xhalf_max(m);
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+      if (j < nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += fast_exp2((acc[j][v] - m) * kLog2e);
+    sum = xhalf_sum(sum);
+    float *st = a.out_stat + ((((int64_t)bh * a.n_tb + tb) * gridDim.y + blockIdx.y) * 2) * 64 + lane;
+    st[0] = m;
+    st[64] = sum;
+  }
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     if (j >= nt) break;
@@ -200,16 +222,17 @@ __global__ __launch_bounds__(256, 2) void wide_layer_kernel(WideArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// wide_phi_finish_kernel: grid (ceil(n_tb / 4), B*H), one 32-token block per wave.  Two sweeps over the fp32
-// pre-activations of the block, one 32-channel tile in registers at a time: running maximum and sum of
-// exponentials first (softmax only), then normalisation, slice powers and rounding.  Output: phi as bf16 C image
+// wide_phi_finish_kernel: grid (ceil(n_tb / 4), B*H), one 32-token block per wave.  One sweep over the fp32
+// pre-activations of the block, one 32-channel tile in registers at a time: normalisation (softmax: against the
+// maximum and sum combined from the last layer's per-block values), slice powers and rounding.  Output: phi as bf16 C image
 // (zero for tokens past the end); QUERY: e[bh][token] = phi . z with the rounded phi, as the numerator uses it.
 constexpr int WIDE_FMAX = 768;
 
 template <bool QUERY>
-__global__ __launch_bounds__(256) void wide_phi_finish_kernel(const f32x4 *__restrict__ u_in, bf16x8 *__restrict__ phi_out,
-                                                              const float *__restrict__ z, float *__restrict__ e_out,
-                                                              int F, int n_tok, int n_tb, int act, int P) {
+__global__ __launch_bounds__(256) void wide_phi_finish_kernel(const f32x4 *__restrict__ u_in, const float *__restrict__ stat,
+                                                              bf16x8 *__restrict__ phi_out, const float *__restrict__ z,
+                                                              float *__restrict__ e_out, int F, int n_tok, int n_tb, int act,
+                                                              int P) {
   __shared__ float zl[QUERY ? WIDE_FMAX : 1];
   const int bh = blockIdx.y;
   if constexpr (QUERY) {
@@ -233,21 +256,15 @@ __global__ __launch_bounds__(256) void wide_phi_finish_kernel(const f32x4 *__res
   };
   float off = 0.f, inv = 1.f;
   if (act == 0) {
-    float m = -INFINITY, sum = 0.f;
-    for (int fb = 0; fb < FB; ++fb) {
-      f32x16 u;
-      load_tile(fb, u);
-      float t = u[0];
-#pragma unroll
-      for (int v = 1; v < 16; ++v) t = fmaxf(t, u[v]);
-      const float m_new = fmaxf(m, xhalf_max(t));
-      sum *= fast_exp2((m - m_new) * kLog2e);                  // exp2(-inf) = 0 on the first tile
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sum += fast_exp2((u[v] - m_new) * kLog2e);
-      m = m_new;
-    }
+    // softmax over all channels from the per-block maxima and sums the last layer left behind
+    const int nblk = (F + 255) / 256;
+    const float *st = stat + (((int64_t)bh * n_tb + tb) * nblk * 2) * 64 + lane;
+    float m = -INFINITY;
+    for (int b = 0; b < nblk; ++b) m = fmaxf(m, st[b * 128]);
+    float sum = 0.f;
+    for (int b = 0; b < nblk; ++b) sum += st[b * 128 + 64] * fast_exp2((st[b * 128] - m) * kLog2e);
     off = -m * kLog2e;
-    inv = 1.0f / xhalf_sum(sum);
+    inv = 1.0f / sum;
   }
   float dot = 0.f;
   for (int fb = 0; fb < FB; ++fb) {
@@ -442,6 +459,7 @@ void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp) {
   wp.off_h2hi = take(BH * n_tb * 32 * pl.DM * 2);
   wp.off_h2lo = take(BH * n_tb * 32 * pl.DM * 2);
   wp.off_u = take(BH * n_tb * 32 * (size_t)pl.F * 4);
+  wp.off_stat = take(BH * n_tb * ((pl.F + 255) / 256) * 2 * 64 * sizeof(float));
   wp.off_phi = take(BH * n_tb * 32 * (size_t)pl.F * 2);
   wp.off_lin = take(BH * n_tb * 32 * (size_t)pl.D * 4);
   wp.off_e = take(BH * (size_t)pl.N * 4);
@@ -480,6 +498,7 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
   a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
   a.in_hi = a.in_lo = nullptr;
   a.out_u = nullptr;
+  a.out_stat = nullptr;
   // layer 1: d -> HD
   a.wf = ws_ptr<bf16x8>(ws, wp.off_w1);
   a.bias = fm.b1; a.K = pl.D; a.NOUT = pl.HD;
@@ -506,6 +525,7 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
   a.bias = fm.b2; a.K = KL; a.NOUT = pl.F;
   a.out_hi = a.out_lo = nullptr;
   a.out_u = ws_ptr<f32x4>(ws, wp.off_u);
+  a.out_stat = ws_ptr<float>(ws, wp.off_stat);
   {
     dim3 grid((n_tb + 3) / 4, (pl.F + 255) / 256, BH);
     wide_layer_kernel<true><<<grid, 256, 0, st>>>(a);
@@ -514,11 +534,13 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
   {
     dim3 grid((n_tb + 3) / 4, BH);
     if (is_query)
-      wide_phi_finish_kernel<true><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<bf16x8>(ws, wp.off_phi),
+      wide_phi_finish_kernel<true><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat),
+                                                         ws_ptr<bf16x8>(ws, wp.off_phi),
                                                          ws_ptr<float>(ws, pl.off_z), ws_ptr<float>(ws, wp.off_e), pl.F, n_tok,
                                                          n_tb, pl.act_q, pl.P);
     else
-      wide_phi_finish_kernel<false><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<bf16x8>(ws, wp.off_phi), nullptr,
+      wide_phi_finish_kernel<false><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat),
+                                                          ws_ptr<bf16x8>(ws, wp.off_phi), nullptr,
                                                           nullptr, pl.F, n_tok, n_tb, pl.act_k, pl.P);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
