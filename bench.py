@@ -137,7 +137,7 @@ def rate_selection_mode(args, w, ha, W, torch, q, k, v, fq, fk, out):
 def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
     """One student update of the attention-distillation loop (Sec. 3.3, Alg. 1, inner loop) on the cached teacher
     output: student forward, loss, gradient with respect to phi_q and phi_k.  Prints one JSON line."""
-    assert w.R != 1 and w.d_hidden == w.d and w.d_feat == w.d, "the gradient needs linear tokens and d -> d -> d maps"
+    assert w.R != 1 and w.d_mid == 0, "the gradient needs linear tokens and two-layer maps"
     prob = ha.make_problem(q, w.R, w.block_size, w.scale)
     lib_ws = torch.empty(max(ha.hybrid_attn_value_distill_grad_workspace_bytes(prob, fq, fk), 256), dtype=torch.uint8,
                          device=q.device)
@@ -181,7 +181,8 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
                    "block_size": w.block_size, "feature_map": f"{w.d}->{w.d_hidden}->{w.d_feat}, P={w.poly_degree}",
                    "step": "student forward + loss + gradient of phi_q, phi_k (teacher output cached)"},
         "step_ms_events": ev_full, "backward_with_state_pass_and_loss_ms": ev_bwd,
-        "roofline": {"bound": "mfma", "kernel": "grad_kernel (query pass + key pass) with its small helpers", "achieved":
+        "roofline": {"bound": "mfma", "kernel": ("grad_kernel (query pass + key pass) with its small helpers" if w.d_hidden == w.d and w.d_feat == w.d
+                                                    else "the pass-per-step backward of wider maps, all kernels"), "achieved":
                      bwd_flops / (ev_bwd * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": bwd_flops / (ev_bwd * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "kernel_ms": ev_bwd, "traffic": None},
         "loss": float(loss[0].item()),

@@ -183,7 +183,9 @@ typedef struct ha_feature_map_grad {
  * stored outputs (0 where they are equal), then the chain rule through Eq. "hybrid" and the feature maps
  * (Sec. 3.2) down to the eight parameter tensors.  The loss is the plain sum, so is the gradient; Alg. 1's
  * 1 / (m |T|) is the caller's.  row_den: device fp32 [B, H, N].  At hybrid_rate == 1 the gradients are zero.
- * Supported here: feature maps with d_hidden == d_out == d_head (HA_ERR_UNSUPPORTED otherwise).  Matrix products
+ * Supported here: two-layer feature maps, d_hidden == d_out == d_head, or at d_head == 128 any d_hidden, d_out
+ * that the forward takes (multiples of 128 up to 768; both maps of one shape); HA_ERR_UNSUPPORTED otherwise, also
+ * for three-layer maps.  Matrix products
  * run in bf16 with fp32 accumulation; the sums over tokens are formed in a fixed order (bitwise reproducible).
  * workspace: device, 256-byte aligned, at least hybrid_attn_value_distill_grad_workspace_bytes() bytes.  Other
  * arguments and errors as for hybrid_attn_value_distill_loss. */

@@ -347,13 +347,30 @@ ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, con
   return HA_OK;
 }
 
-// Workspace of the gradient: the loss's layout, then the backward pass's buffers.
-static size_t grad_layout(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, ha::Plan &teacher,
-                          ha::Plan &student, size_t &off_partial, ha::GradPlan &gp) {
-  const size_t base = distill_layout(p, phi_q, phi_k, teacher, student, off_partial);
-  if (student.NL == 0) return base;
-  ha::make_grad_plan(student, base, gp);
-  return gp.total;
+// Workspace of the gradient: the loss's layout, then the backward pass's buffers.  Maps other than d -> d -> d take
+// the pass-per-step backward, which brings image buffers of its own (`layered`).
+struct GradLayout {
+  ha::Plan teacher, student;
+  ha::GradPlan gp;
+  ha::WidePlan wp;
+  ha::WideGradPlan wgp;
+  size_t off_partial, total;
+  bool layered;
+};
+
+static void grad_layout(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, GradLayout &gl) {
+  const size_t base = distill_layout(p, phi_q, phi_k, gl.teacher, gl.student, gl.off_partial);
+  gl.layered = phi_q->d_hidden != p.d_head || phi_q->d_out != p.d_head;
+  gl.total = base;
+  if (gl.student.NL == 0) return;
+  if (gl.layered) {
+    ha::make_wide_plan(gl.student, base, gl.wp);
+    ha::make_wide_grad_plan(gl.student, gl.wp, gl.wp.total, gl.wgp);
+    gl.total = gl.wgp.total;
+  } else {
+    ha::make_grad_plan(gl.student, base, gl.gp);
+    gl.total = gl.gp.total;
+  }
 }
 
 static ha_status check_grad_maps(const ha_problem *p, const ha_feature_map *phi_q, const ha_feature_map *phi_k) {
@@ -365,18 +382,22 @@ static ha_status check_grad_maps(const ha_problem *p, const ha_feature_map *phi_
     if (s == HA_OK) s = ha::check_map(phi_k, *p);
     if (s != HA_OK) return s;
   }
-  for (const ha_feature_map *fm : {phi_q, phi_k})
-    if (fm->d_hidden != p->d_head || fm->d_out != p->d_head || fm->w_mid) return HA_ERR_UNSUPPORTED;
+  if (phi_q->d_out != phi_k->d_out || phi_q->d_hidden != phi_k->d_hidden) return HA_ERR_SHAPE;
+  for (const ha_feature_map *fm : {phi_q, phi_k}) {
+    if (fm->w_mid) return HA_ERR_UNSUPPORTED;                        // two-layer maps only
+    const bool square = fm->d_hidden == p->d_head && fm->d_out == p->d_head;
+    const bool layered = p->d_head == 128 && fm->d_hidden % 128 == 0 && fm->d_out % 128 == 0;
+    if (!square && !layered) return HA_ERR_UNSUPPORTED;
+  }
   return HA_OK;
 }
 
 size_t hybrid_attn_value_distill_grad_workspace_bytes(const ha_problem *p, const ha_feature_map *phi_q,
                                                       const ha_feature_map *phi_k) {
   if (check_grad_maps(p, phi_q, phi_k) != HA_OK) return 0;
-  ha::Plan t, s;
-  ha::GradPlan gp;
-  size_t off;
-  return grad_layout(*p, phi_q, phi_k, t, s, off, gp);
+  GradLayout gl;
+  grad_layout(*p, phi_q, phi_k, gl);
+  return gl.total;
 }
 
 ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, const void *k, const void *v,
@@ -397,11 +418,11 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
       !ha::aligned16(y_student) || (reinterpret_cast<uintptr_t>(row_den) & 3u) || (reinterpret_cast<uintptr_t>(loss) & 7u))
     return HA_ERR_ALIGN;
   if (y_teacher == y_student) return HA_ERR_SHAPE;
-  ha::Plan pt, ps;
-  ha::GradPlan gp;
-  size_t off_partial;
-  const size_t need = grad_layout(*p, phi_q, phi_k, pt, ps, off_partial, gp);
-  if (!workspace || workspace_bytes < need) return HA_ERR_WORKSPACE;
+  GradLayout gl;
+  grad_layout(*p, phi_q, phi_k, gl);
+  const ha::Plan &ps = gl.student;
+  const size_t off_partial = gl.off_partial;
+  if (!workspace || workspace_bytes < gl.total) return HA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (!teacher_is_cached) {
@@ -416,23 +437,31 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
     if (s != HA_OK) return s;
   } else if (ps.NL > 0) {
     // the backward pass needs S, z of the current phi_k in the workspace
-    s = ha::run_key_side(ps, k, v, phi_k, workspace, st);
+    ha::Plan pf;
+    ha::WidePlan wpf;
+    bool wide;
+    ha::full_plan(*p, phi_q, phi_k, pf, wpf, wide);
+    s = ha::run_key_side(ps, k, v, phi_k, workspace, st, nullptr, wide ? &wpf : nullptr);
     if (s != HA_OK) return s;
   }
   double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + off_partial);
   if ((e = ha::launch_l1_distance(ps, y_teacher, y_student, partial, loss, st)) != hipSuccess) return ha::device_error(e);
-  const size_t H = (size_t)p->H, D = (size_t)p->d_head;
+  const size_t H = (size_t)p->H, D = (size_t)p->d_head, HD = (size_t)phi_q->d_hidden, F = (size_t)phi_q->d_out;
   if (ps.NL == 0) {
     for (const ha_feature_map_grad *gm : {grad_q, grad_k}) {
-      if ((e = ha::launch_fill_zero(gm->w1, H * D * D, st)) != hipSuccess) return ha::device_error(e);
-      if ((e = ha::launch_fill_zero(gm->w2, H * D * D, st)) != hipSuccess) return ha::device_error(e);
-      if ((e = ha::launch_fill_zero(gm->b1, H * D, st)) != hipSuccess) return ha::device_error(e);
-      if ((e = ha::launch_fill_zero(gm->b2, H * D, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->w1, H * HD * D, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->w2, H * F * HD, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->b1, H * HD, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->b2, H * F, st)) != hipSuccess) return ha::device_error(e);
     }
     return HA_OK;
   }
-  e = ha::launch_value_distill_backward(ps, gp, q, k, v, *phi_q, *phi_k, y_teacher, y_student, row_den, *grad_q, *grad_k,
-                                        workspace, st);
+  if (gl.layered)
+    e = ha::launch_wide_value_distill_backward(ps, gl.wp, gl.wgp, q, k, v, *phi_q, *phi_k, y_teacher, y_student, row_den,
+                                               *grad_q, *grad_k, workspace, st);
+  else
+    e = ha::launch_value_distill_backward(ps, gl.gp, q, k, v, *phi_q, *phi_k, y_teacher, y_student, row_den, *grad_q, *grad_k,
+                                          workspace, st);
   if (e != hipSuccess) return ha::device_error(e);
   return HA_OK;
 }

@@ -514,6 +514,25 @@ hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st) {
   return hipGetLastError();
 }
 
+hipError_t launch_vd_rows(const Plan &pl, const void *y_teacher, const void *y_student, const float *row_den, void *gsign,
+                          float *rs, float *wp, hipStream_t st) {
+  const int D = pl.D, rpb = 256 / (D / 8);
+  dim3 grid((pl.N + rpb - 1) / rpb, pl.B * pl.H);
+#define HA_ROWS(DD, F32) \
+  vd_rows_kernel<DD, F32><<<grid, 256, 0, st>>>(y_teacher, y_student, row_den, static_cast<bf16x8 *>(gsign), rs, wp, pl.H, pl.N, \
+                                                pl.sb, pl.sh, pl.sn)
+  if (D == 64) { if (pl.f32) HA_ROWS(64, true); else HA_ROWS(64, false); }
+  else { if (pl.f32) HA_ROWS(128, true); else HA_ROWS(128, false); }
+#undef HA_ROWS
+  return hipGetLastError();
+}
+
+hipError_t launch_natural_frags(const float *M, void *hi, void *lo, int rows, int cols, int n_mat, hipStream_t st) {
+  dim3 grid((rows * cols + 255) / 256, n_mat);
+  natural_frags_kernel<<<grid, 256, 0, st>>>(M, static_cast<__bf16 *>(hi), static_cast<__bf16 *>(lo), rows, cols);
+  return hipGetLastError();
+}
+
 // Everything after the student's forward: S, z are in the forward's workspace region (`pl` offsets), y_teacher,
 // y_student and row_den hold the two outputs and the student's row denominators.
 hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, const void *q, const void *k, const void *v,
@@ -536,24 +555,14 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
       grad_weight_prep_kernel<false><<<grid, 256, 0, st>>>(phi_k.w2, ws_ptr<__bf16>(ws, gp.off_w2tk), D, D);
     }
     HA_CHECK();
-    dim3 gridm((D * D + 255) / 256, BH);
-    natural_frags_kernel<<<gridm, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_S), ws_ptr<__bf16>(ws, gp.off_shi),
-                                                ws_ptr<__bf16>(ws, gp.off_slo), D, D);
-    HA_CHECK();
+    if ((e = launch_natural_frags(ws_ptr<float>(ws, pl.off_S), ws_ptr<void>(ws, gp.off_shi), ws_ptr<void>(ws, gp.off_slo), D, D,
+                                  BH, st)) != hipSuccess)
+      return e;
   }
   // per-row factors
-  {
-    const int rpb = 256 / (D / 8);
-    dim3 grid((pl.N + rpb - 1) / rpb, BH);
-#define HA_ROWS(DD, F32) \
-  vd_rows_kernel<DD, F32><<<grid, 256, 0, st>>>(y_teacher, y_student, row_den, ws_ptr<bf16x8>(ws, gp.off_gsign), \
-                                                ws_ptr<float>(ws, gp.off_rs), ws_ptr<float>(ws, gp.off_wp), pl.H, pl.N, \
-                                                pl.sb, pl.sh, pl.sn)
-    if (D == 64) { if (pl.f32) HA_ROWS(64, true); else HA_ROWS(64, false); }
-    else { if (pl.f32) HA_ROWS(128, true); else HA_ROWS(128, false); }
-#undef HA_ROWS
-    HA_CHECK();
-  }
+  if ((e = launch_vd_rows(pl, y_teacher, y_student, row_den, ws_ptr<void>(ws, gp.off_gsign), ws_ptr<float>(ws, gp.off_rs),
+                          ws_ptr<float>(ws, gp.off_wp), st)) != hipSuccess)
+    return e;
   GradArgs a;
   a.H = pl.H; a.N = pl.N; a.R = pl.R; a.P = pl.P;
   a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
@@ -583,10 +592,9 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     grad_reduce_kernel<<<rgrid_bh, 256, 0, st>>>(a.part, ws_ptr<float>(ws, gp.off_dS), ws_ptr<float>(ws, gp.off_dz), D,
                                                  gp.n_chunks_q, 1, 0, 1, 0);
     HA_CHECK();
-    dim3 gridm((D * D + 255) / 256, BH);
-    natural_frags_kernel<<<gridm, 256, 0, st>>>(ws_ptr<float>(ws, gp.off_dS), ws_ptr<__bf16>(ws, gp.off_dshi),
-                                                ws_ptr<__bf16>(ws, gp.off_dslo), D, D);
-    HA_CHECK();
+    if ((e = launch_natural_frags(ws_ptr<float>(ws, gp.off_dS), ws_ptr<void>(ws, gp.off_dshi), ws_ptr<void>(ws, gp.off_dslo), D,
+                                  D, BH, st)) != hipSuccess)
+      return e;
   }
   // key pass over the linear tokens: phi_k's gradient
   {

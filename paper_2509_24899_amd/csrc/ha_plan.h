@@ -39,6 +39,13 @@ struct WidePlan {
   size_t off_hhi, off_hlo, off_h2hi, off_h2lo, off_u, off_stat, off_phi, off_lin, off_e, total;
 };
 
+// Workspace of the value-distillation gradient of maps that take the layer-by-layer path (beyond WidePlan's).
+struct WideGradPlan {
+  int CHq, n_chunks_q, CHk, n_chunks_k;
+  size_t off_wt, off_shi, off_slo, off_dS, off_dz, off_dshi, off_dslo, off_gsign, off_rs, off_wp, off_tdt, off_pdot, off_du,
+      off_dpre, off_part, total;
+};
+
 // Fills `pl` from a validated problem.  Pure host arithmetic.
 void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, Plan &pl);
 
@@ -69,6 +76,18 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
                                          const ha_feature_map &phi_q, const ha_feature_map &phi_k, const void *y_teacher,
                                          const void *y_student, const float *row_den, const ha_feature_map_grad &gq,
                                          const ha_feature_map_grad &gk, void *ws, hipStream_t st);
+hipError_t launch_vd_rows(const Plan &pl, const void *y_teacher, const void *y_student, const float *row_den, void *gsign,
+                          float *rs, float *wp, hipStream_t st);
+hipError_t launch_natural_frags(const float *M, void *hi, void *lo, int rows, int cols, int n_mat, hipStream_t st);
+// ha_wide.hip / ha_wide_grad.hip
+hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query, void *ws,
+                           hipStream_t st);
+void make_wide_grad_plan(const Plan &pl, const WidePlan &wp, size_t base_off, WideGradPlan &gp);
+hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp, const WideGradPlan &gp, const void *q,
+                                              const void *k, const void *v, const ha_feature_map &phi_q,
+                                              const ha_feature_map &phi_k, const void *y_teacher, const void *y_student,
+                                              const float *row_den, const ha_feature_map_grad &gq, const ha_feature_map_grad &gk,
+                                              void *ws, hipStream_t st);
 hipError_t launch_mfma_probe(float *sink, int workgroups, int iters, int random_operands, hipStream_t st);
 
 }  // namespace ha

@@ -468,8 +468,8 @@ void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp) {
 
 // One feature map over one token set: weight fragments, layer 1, (middle layer,) last layer, output stage.  is_query: all N tokens of q, and
 // phi.z is formed; otherwise the linear tokens of k.
-static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query,
-                               void *ws, hipStream_t st) {
+hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query,
+                           void *ws, hipStream_t st) {
   const int BH = pl.B * pl.H;
   const int n_tok = is_query ? pl.N : pl.NL, n_tb = is_query ? wp.n_tb_q : wp.n_tb_k;
   hipError_t e;
@@ -550,7 +550,7 @@ static hipError_t run_wide_map(const Plan &pl, const WidePlan &wp, const void *x
 // Key side: phi_k over the linear tokens, then [S | z] (partials + the forward's reduction).
 hipError_t launch_wide_key_side(const Plan &pl, const WidePlan &wp, const void *k, const void *v, const ha_feature_map &phi_k,
                                 void *ws, hipStream_t st) {
-  hipError_t e = run_wide_map(pl, wp, k, phi_k, false, ws, st);
+  hipError_t e = launch_wide_map(pl, wp, k, phi_k, false, ws, st);
   if (e != hipSuccess) return e;
   dim3 grid(pl.n_chunks, pl.B * pl.H, pl.F / 128);
   if (pl.f32)
@@ -566,7 +566,7 @@ hipError_t launch_wide_key_side(const Plan &pl, const WidePlan &wp, const void *
 // Query side: phi_q over all tokens, e = phi_q . z, n = phi_q S; the query kernel picks both up in its epilogue.
 hipError_t launch_wide_query_side(const Plan &pl, const WidePlan &wp, const void *q, const ha_feature_map &phi_q, void *ws,
                                   hipStream_t st) {
-  hipError_t e = run_wide_map(pl, wp, q, phi_q, true, ws, st);
+  hipError_t e = launch_wide_map(pl, wp, q, phi_q, true, ws, st);
   if (e != hipSuccess) return e;
   dim3 grid((wp.n_tb_q + 3) / 4, pl.B * pl.H);
   wide_lin_kernel<128><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), ws_ptr<bf16x8>(ws, pl.off_sthi),

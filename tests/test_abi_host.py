@@ -188,8 +188,10 @@ def test_value_distill_grad_workspace_and_errors(lib):
     need = lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(fm), ctypes.byref(fm))
     # beyond the loss's workspace: the sign tensor (one bf16 per element of q) and the partial tiles, at least
     assert need >= loss_ws + 12 * 32760 * 128 * 2
+    # two-layer maps of the other supported widths go pass by pass and bring image buffers of their own
     wide = _map(256, 256)
-    assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(wide), ctypes.byref(wide)) == 0
+    assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(wide), ctypes.byref(wide)) > need
+    three = ha.ha_feature_map(FAKE, None, FAKE + 0x100000, None, 768, 768, 6, ha.HA_ACT_SOFTMAX, FAKE + 0x200000, None, 768, 0)
     f = lib.hybrid_attn_value_distill_grad
     A = [FAKE + i * 0x10000000 for i in range(16)]
     gq = ha.ha_feature_map_grad(A[8], A[9], A[10], A[11])
@@ -207,7 +209,9 @@ def test_value_distill_grad_workspace_and_errors(lib):
     assert f(*args(den=A[5] + 2)) == ha.HA_ERR_ALIGN
     assert f(*args(wsb=need - 1)) == ha.HA_ERR_WORKSPACE
     assert f(*args(ws=None)) == ha.HA_ERR_WORKSPACE
-    assert f(*args(fq=wide, fk=wide)) == ha.HA_ERR_UNSUPPORTED      # only d -> d -> d maps have a gradient kernel
+    assert f(*args(fq=three, fk=three)) == ha.HA_ERR_UNSUPPORTED    # two-layer maps only
+    assert f(*args(fq=wide, fk=wide)) == ha.HA_ERR_WORKSPACE        # supported, but `need` was sized for the narrow map
+    assert f(*args(fq=wide, fk=fm)) == ha.HA_ERR_SHAPE
     assert f(*args(p=_problem(d=96))) == ha.HA_ERR_UNSUPPORTED
     # rate 1: the maps are still required (they give the gradients their shapes)
     p1 = _problem(R=1)
@@ -237,5 +241,5 @@ def test_wider_and_three_layer_maps_validate(lib):
     assert ha.hybrid_attn_validate(p, bad, bad) == ha.HA_ERR_SHAPE
     odd = ha.ha_feature_map(FAKE, None, FAKE + 0x100000, None, 768, 768, 6, ha.HA_ACT_SOFTMAX, FAKE + 0x200000, None, 192, 0)
     assert ha.hybrid_attn_validate(p, odd, odd) == ha.HA_ERR_UNSUPPORTED
-    # the gradient entry point has kernels for the d -> d -> d map only
+    # the gradient entry point has kernels for two-layer maps only
     assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(three), ctypes.byref(three)) == 0
