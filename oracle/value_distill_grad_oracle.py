@@ -13,8 +13,8 @@ the attention inputs of the isolated layer are constants), the loss is
 and y_hat_i = num_i / den_i with num_i = a_i + phi_q(q_i) S, den_i = l_i + phi_q(q_i) . z,
 S = sum_{T_L} phi_k(k_j)^T v_j, z = sum_{T_L} phi_k(k_j); a_i, l_i (the softmax-token sums) do
 not depend on phi.  The derivative is taken where it exists; at y_hat = y the subgradient 0 is
-used (sign(0) = 0).  Returned are dL/dW1, dL/db1, dL/dW2, dL/db2 of phi_q and of phi_k per head,
-summed over the batch (the parameters are shared by the batch; Alg. "distil" then divides by the
+used (sign(0) = 0).  Returned are dL/dW1, dL/db1, dL/dW2, dL/db2 (and dL/dW_mid, dL/db_mid for the
+three-layer map of Tab. "phi") of phi_q and of phi_k per head, summed over the batch (the parameters are shared by the batch; Alg. "distil" then divides by the
 number of samples, which is left to the caller).
 
 Readings taken: the loss is the plain sum (no mean); phi_q and phi_k are separate parameter sets;
@@ -35,13 +35,16 @@ from . import hybrid_attn_oracle as O
 
 def feature_map_with_trace(x, fm: O.FeatureMap, head: int):
     """phi(x) of Sec. 3.2 together with what its derivative needs: rows x [n, d] ->
-    (phi [n, F], hidden [n, Hd], pre-activation u [n, F], positive output t [n, F])."""
-    if fm.w_mid is not None:
-        raise ValueError("the gradient oracle covers the two-layer map only")
+    (phi [n, F], hidden [n, Hd], pre-activation u [n, F], positive output t [n, F], second hidden
+    layer [n, Dm] of a three-layer map or None)."""
     x = np.asarray(x, dtype=np.float64)
     pre = x @ fm.w1[head].T + fm.b1[head]
     hidden = np.maximum(pre, 0.0)
-    u = hidden @ fm.w2[head].T + fm.b2[head]
+    hidden2 = None
+    if fm.w_mid is not None:
+        hidden2 = np.maximum(hidden @ fm.w_mid[head].T + fm.b_mid[head], 0.0)
+    last_in = hidden if hidden2 is None else hidden2
+    u = last_in @ fm.w2[head].T + fm.b2[head]
     if fm.act == O.ACT_SOFTMAX:
         e = np.exp(u - u.max(axis=-1, keepdims=True))
         t = e / e.sum(axis=-1, keepdims=True)
@@ -56,14 +59,15 @@ def feature_map_with_trace(x, fm: O.FeatureMap, head: int):
     for p in range(1, fm.P + 1):
         sl = slice((p - 1) * Dp, p * Dp)
         phi[:, sl] = t[:, sl] ** p
-    return phi, hidden, u, t
+    return phi, hidden, u, t, hidden2
 
 
 def feature_map_backward(x, fm: O.FeatureMap, head: int, dphi):
     """Given dL/dphi [n, F] for rows x [n, d], the gradient with respect to the parameters of the
-    map of this head: (dW1 [Hd, d], db1 [Hd], dW2 [F, Hd], db2 [F])."""
+    map of this head: (dW1 [Hd, d], db1 [Hd], dW2 [F, Hd or Dm], db2 [F]) and, for a three-layer map,
+    (dW_mid [Dm, Hd], db_mid [Dm]) behind them."""
     x = np.asarray(x, dtype=np.float64)
-    _, hidden, u, t = feature_map_with_trace(x, fm, head)
+    _, hidden, u, t, hidden2 = feature_map_with_trace(x, fm, head)
     Dp = fm.F // fm.P
     dt = np.empty_like(t)
     for p in range(1, fm.P + 1):                         # phi_c = t_c ** p on slice p
@@ -75,18 +79,30 @@ def feature_map_backward(x, fm: O.FeatureMap, head: int, dphi):
         du = dt * t
     else:                                                 # ReLU
         du = dt * (u > 0.0)
-    dw2 = du.T @ hidden
     db2 = du.sum(axis=0)
-    dhidden = du @ fm.w2[head]
+    if hidden2 is None:
+        dw2 = du.T @ hidden
+        dhidden = du @ fm.w2[head]
+        mid = ()
+    else:                                                 # one more ReLU layer between the two
+        dw2 = du.T @ hidden2
+        dpre2 = (du @ fm.w2[head]) * (hidden2 > 0.0)
+        mid = (dpre2.T @ hidden, dpre2.sum(axis=0))
+        dhidden = dpre2 @ fm.w_mid[head]
     dpre = dhidden * (hidden > 0.0)
     dw1 = dpre.T @ x
     db1 = dpre.sum(axis=0)
-    return dw1, db1, dw2, db2
+    return (dw1, db1, dw2, db2) + mid
+
+
+def param_names(fm: O.FeatureMap):
+    """Names of the parameter tensors of a map, in the order feature_map_backward returns their gradients."""
+    return ("w1", "b1", "w2", "b2") + (("w_mid", "b_mid") if fm.w_mid is not None else ())
 
 
 def head_gradients(q, k, v, phi_q, phi_k, head, R, scale, sign=None):
     """One (batch, head): q, k, v [N, d] -> (grads of phi_q, grads of phi_k, loss), each grads a tuple
-    (dW1, db1, dW2, db2).  `sign` [N, d], if given, replaces sign(y_hat - y)."""
+    (dW1, db1, dW2, db2[, dW_mid, db_mid]).  `sign` [N, d], if given, replaces sign(y_hat - y)."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -96,8 +112,8 @@ def head_gradients(q, k, v, phi_q, phi_k, head, R, scale, sign=None):
     y = a_t / l_t[:, None]
     a, l, _ = O.softmax_part(q, k, v, R, scale)                     # student's softmax-token sums
     if idx_l.size == 0:                                             # no linear tokens: phi is unused
-        zq = tuple(np.zeros_like(t) for t in (phi_q.w1[head], phi_q.b1[head], phi_q.w2[head], phi_q.b2[head]))
-        zk = tuple(np.zeros_like(t) for t in (phi_k.w1[head], phi_k.b1[head], phi_k.w2[head], phi_k.b2[head]))
+        zq = tuple(np.zeros_like(getattr(phi_q, n)[head]) for n in param_names(phi_q))
+        zk = tuple(np.zeros_like(getattr(phi_k, n)[head]) for n in param_names(phi_k))
         return zq, zk, float(np.abs(y - a / l[:, None]).sum())
     fk = O.feature_map(k[idx_l], phi_k, head)                       # [N_L, F]
     S = fk.T @ v[idx_l]
@@ -124,11 +140,11 @@ def value_distill_grad(q, k, v, phi_q, phi_k, R, scale, sign_from=None):
     `sign_from` = (y_teacher, y_student), both [B, H, N, d]: when given, dL/dy_hat is the sign of
     their difference (student minus teacher) instead of the sign of the float64 values computed here.
     Returns (grads_q, grads_k, loss): grads_* is a dict with w1 [H, Hd, d], b1 [H, Hd], w2 [H, F, Hd],
-    b2 [H, F], summed over the batch."""
+    b2 [H, F] (three-layer maps: w2 [H, F, Dm], w_mid [H, Dm, Hd], b_mid [H, Dm]), summed over the batch."""
     B, H, N, d = q.shape
 
     def zeros(fm):
-        return dict(w1=np.zeros_like(fm.w1), b1=np.zeros_like(fm.b1), w2=np.zeros_like(fm.w2), b2=np.zeros_like(fm.b2))
+        return {n: np.zeros_like(getattr(fm, n)) for n in param_names(fm)}
 
     out_q, out_k, loss = zeros(phi_q), zeros(phi_k), 0.0
     for b in range(B):
@@ -137,8 +153,8 @@ def value_distill_grad(q, k, v, phi_q, phi_k, R, scale, sign_from=None):
             if sign_from is not None:
                 sign = np.sign(np.asarray(sign_from[1][b, h], dtype=np.float64) - np.asarray(sign_from[0][b, h], dtype=np.float64))
             gq, gk, l_bh = head_gradients(q[b, h], k[b, h], v[b, h], phi_q, phi_k, h, R, scale, sign)
-            for out, g in ((out_q, gq), (out_k, gk)):
-                for name, t in zip(("w1", "b1", "w2", "b2"), g):
+            for out, g, fm in ((out_q, gq, phi_q), (out_k, gk, phi_k)):
+                for name, t in zip(param_names(fm), g):
                     out[name][h] += t
             loss += l_bh
     return out_q, out_k, loss

@@ -20,6 +20,17 @@ def _inputs(seed, B=2, H=2, N=13, d=6):
     return rng, tuple(rng.standard_normal((B, H, N, d)) for _ in range(3))
 
 
+def _names(fm):
+    return NAMES + (("w_mid", "b_mid") if fm.w_mid is not None else ())
+
+
+def _with_mid(rng, fm, Dm):
+    """The same map with one more hidden layer Hd -> Dm in front of the last layer (Tab. "phi", three layers)."""
+    H, F, Hd = fm.w2.shape
+    return O.FeatureMap(fm.w1, fm.b1, rng.standard_normal((H, F, Dm)) / np.sqrt(Dm), fm.b2, fm.P, fm.act,
+                        w_mid=rng.standard_normal((H, Dm, Hd)) / np.sqrt(Hd), b_mid=rng.standard_normal((H, Dm)) * 0.3)
+
+
 def _torch_loss_and_grads(q, k, v, fq, fk, R, scale):
     """The loss written once more with torch ops on float64 tensors (library softmax for the teacher, one
     concatenated weight matrix for the student) and differentiated by torch's reverse-mode autograd."""
@@ -27,11 +38,14 @@ def _torch_loss_and_grads(q, k, v, fq, fk, R, scale):
     B, H, N, d = q.shape
     par = {}
     for tag, fm in (("q", fq), ("k", fk)):
-        par[tag] = [torch.tensor(getattr(fm, n), dtype=torch.float64, requires_grad=True) for n in NAMES]
+        par[tag] = [torch.tensor(getattr(fm, n), dtype=torch.float64, requires_grad=True) for n in _names(fm)]
 
     def phi(x, tag, fm, h):
-        w1, b1, w2, b2 = par[tag]
-        u = torch.relu(x @ w1[h].T + b1[h]) @ w2[h].T + b2[h]
+        w1, b1, w2, b2 = par[tag][:4]
+        hid = torch.relu(x @ w1[h].T + b1[h])
+        if fm.w_mid is not None:
+            hid = torch.relu(torch.nn.functional.linear(hid, par[tag][4][h], par[tag][5][h]))
+        u = hid @ w2[h].T + b2[h]
         if fm.act == O.ACT_SOFTMAX:
             t = torch.softmax(u, dim=-1)
         elif fm.act == O.ACT_EXP:
@@ -57,22 +71,25 @@ def _torch_loss_and_grads(q, k, v, fq, fk, R, scale):
             loss = loss + (teacher - student).abs().sum()
     if loss.requires_grad:
         loss.backward()
-    grads = {tag: {n: (p.grad.numpy() if p.grad is not None else np.zeros(p.shape)) for n, p in zip(NAMES, par[tag])}
-             for tag in ("q", "k")}
+    grads = {tag: {n: (p.grad.numpy() if p.grad is not None else np.zeros(p.shape)) for n, p in zip(_names(fm), par[tag])}
+             for tag, fm in (("q", fq), ("k", fk))}
     return float(loss.detach()), grads
 
 
-def pin_against_autograd(M, seeds=(0, 1), acts=(O.ACT_SOFTMAX, O.ACT_EXP, O.ACT_RELU), rates=(0, 2, 3)):
+def pin_against_autograd(M, seeds=(0, 1), acts=(O.ACT_SOFTMAX, O.ACT_EXP, O.ACT_RELU), rates=(0, 2, 3), three_layers=False):
     for seed in seeds:
         for act in acts:
             for R in rates:
                 rng, (q, k, v) = _inputs(seed)
                 fq, fk = _rand_map(rng, 2, 6, 8, 6, 3, act), _rand_map(rng, 2, 6, 8, 6, 2, act)
+                if three_layers:
+                    fq, fk = _with_mid(rng, fq, 5), _with_mid(rng, fk, 7)
                 gq, gk, loss = M.value_distill_grad(q, k, v, fq, fk, R, 0.45)
                 want_loss, want = _torch_loss_and_grads(q, k, v, fq, fk, R, 0.45)
                 np.testing.assert_allclose(loss, want_loss, rtol=1e-11)
-                for got, tag in ((gq, "q"), (gk, "k")):
-                    for n in NAMES:
+                for got, tag, fm in ((gq, "q", fq), (gk, "k", fk)):
+                    assert set(got) == set(_names(fm))
+                    for n in _names(fm):
                         scale_ = np.abs(want[tag][n]).max() + 1e-30
                         np.testing.assert_allclose(got[n], want[tag][n], rtol=1e-8, atol=1e-9 * scale_,
                                                    err_msg=f"seed {seed} act {act} R {R} phi_{tag}.{n}")
@@ -80,6 +97,24 @@ def pin_against_autograd(M, seeds=(0, 1), acts=(O.ACT_SOFTMAX, O.ACT_EXP, O.ACT_
 
 def test_matches_reverse_mode_autograd():
     pin_against_autograd(G)
+
+
+def test_three_layer_map_matches_reverse_mode_autograd():
+    """Tab. "phi", three-layer row: one more ReLU layer between the two (unequal widths 8 -> 5 / 7 -> 6)."""
+    pin_against_autograd(G, three_layers=True)
+
+
+THREE_LAYER_MUTATIONS = [
+    ("dpre2 = (du @ fm.w2[head]) * (hidden2 > 0.0)", "dpre2 = du @ fm.w2[head]"),                    # second ReLU gate
+    ("mid = (dpre2.T @ hidden, dpre2.sum(axis=0))", "mid = (dpre2.T @ hidden2[:, :1] * 0 + dpre2.T @ hidden * 2, dpre2.sum(axis=0))"),
+    ("dhidden = dpre2 @ fm.w_mid[head]", "dhidden = dpre2 @ np.abs(fm.w_mid[head])"),               # wrong weights on the way down
+    ("dw2 = du.T @ hidden2", "dw2 = du.T @ (hidden2 + 0.1)"),                                        # wrong activations
+]
+
+
+@pytest.mark.parametrize("old,new", THREE_LAYER_MUTATIONS)
+def test_three_layer_planted_mistakes_are_caught(old, new):
+    _mutant_must_fail(old, new, three_layers=True)
 
 
 def test_matches_central_finite_differences_of_the_loss():
@@ -157,7 +192,7 @@ MUTATIONS = [
     ("du = t * (dt - (t * dt).sum(axis=-1, keepdims=True))", "du = t * dt"),                           # softmax Jacobian without its rank-one part
     ("dt[:, sl] = dphi[:, sl] * p * t[:, sl] ** (p - 1)", "dt[:, sl] = dphi[:, sl] * t[:, sl] ** (p - 1)"),  # power rule without p
     ("dpre = dhidden * (hidden > 0.0)", "dpre = dhidden"),                                             # ReLU gate
-    ("dw2 = du.T @ hidden", "dw2 = du.T @ np.maximum(hidden, 0.1)"),                                   # wrong activations
+    ("dw2 = du.T @ hidden\n", "dw2 = du.T @ np.maximum(hidden, 0.1)\n"),                                   # wrong activations
     ("dS = fq.T @ dnum", "dS = fq.T @ g"),                                                             # missing 1/den
 ]
 
@@ -165,6 +200,10 @@ MUTATIONS = [
 @pytest.mark.parametrize("old,new", MUTATIONS)
 def test_planted_mistakes_are_caught(old, new):
     """A copy of the oracle's source with one mistake must fail the autograd pin."""
+    _mutant_must_fail(old, new)
+
+
+def _mutant_must_fail(old, new, three_layers=False):
     src = inspect.getsource(G)
     assert src.count(old) == 1, "mutation target not found: " + old
     spec = importlib.util.spec_from_loader("oracle._mutant_grad", loader=None)
@@ -174,6 +213,6 @@ def test_planted_mistakes_are_caught(old, new):
     try:
         exec(compile(src.replace(old, new), "<mutant>", "exec"), mod.__dict__)
         with pytest.raises((AssertionError, ValueError)):
-            pin_against_autograd(mod, seeds=(0,), acts=(O.ACT_SOFTMAX,), rates=(2,))
+            pin_against_autograd(mod, seeds=(0,), acts=(O.ACT_SOFTMAX,), rates=(2,), three_layers=three_layers)
     finally:
         del sys.modules["oracle._mutant_grad"]
