@@ -137,7 +137,7 @@ def rate_selection_mode(args, w, ha, W, torch, q, k, v, fq, fk, out):
 def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
     """One student update of the attention-distillation loop (Sec. 3.3, Alg. 1, inner loop) on the cached teacher
     output: student forward, loss, gradient with respect to phi_q and phi_k.  Prints one JSON line."""
-    assert w.R != 1 and w.d_mid == 0, "the gradient needs linear tokens and two-layer maps"
+    assert w.R != 1, "the gradient needs linear tokens"
     prob = ha.make_problem(q, w.R, w.block_size, w.scale)
     lib_ws = torch.empty(max(ha.hybrid_attn_value_distill_grad_workspace_bytes(prob, fq, fk), 256), dtype=torch.uint8,
                          device=q.device)
@@ -169,8 +169,10 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
     _, ev_bwd = timed(backward_only)          # state pass + loss + backward (no student query kernel)
     n_l = w.n_linear
     # algorithmic flops of the backward pass per token: map recomputed (d Hd + Hd F), dphi (F d), W2^T du (F Hd),
-    # dW2 (F Hd), dW1 (Hd d); queries also dS (F d); 2 flops per multiply-add
-    per_q = 2.0 * (w.d * w.d_hidden + w.d_hidden * w.d_feat + w.d_feat * w.d + 2 * w.d_feat * w.d_hidden + w.d_hidden * w.d + w.d_feat * w.d)
+    # dW2 (F Hd), dW1 (Hd d); queries also dS (F d); a middle layer adds its forward, its transpose and its weight
+    # gradient (3 Dm Hd) and makes Dm the last layer's input width; 2 flops per multiply-add
+    kl = w.d_mid if w.d_mid else w.d_hidden
+    per_q = 2.0 * (w.d * w.d_hidden + 3 * w.d_mid * w.d_hidden + kl * w.d_feat + w.d_feat * w.d + 2 * w.d_feat * kl + w.d_hidden * w.d + w.d_feat * w.d)
     per_k = per_q - 2.0 * w.d_feat * w.d
     bwd_flops = w.B * w.H * (w.N * per_q + n_l * per_k)
     rec = {
@@ -178,7 +180,7 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_full, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype, "hybrid_rate_R": w.R,
-                   "block_size": w.block_size, "feature_map": f"{w.d}->{w.d_hidden}->{w.d_feat}, P={w.poly_degree}",
+                   "block_size": w.block_size, "feature_map": f"{w.d}->{w.d_hidden}->" + (f"{w.d_mid}->" if w.d_mid else "") + f"{w.d_feat}, P={w.poly_degree}",
                    "step": "student forward + loss + gradient of phi_q, phi_k (teacher output cached)"},
         "step_ms_events": ev_full, "backward_with_state_pass_and_loss_ms": ev_bwd,
         "roofline": {"bound": "mfma", "kernel": ("grad_kernel (query pass + key pass) with its small helpers" if w.d_hidden == w.d and w.d_feat == w.d

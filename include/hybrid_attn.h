@@ -171,9 +171,12 @@ ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, con
  * line of Alg. 1, phi <- phi - eta grad_phi L, with L of Eq. "vd_loss"; everything but phi_q, phi_k is frozen in
  * that stage, so q, k, v are constants).  Buffers of one map's gradient, all device fp32, overwritten in full,
  * summed over the batch (the parameters are shared by it): w1 [H, d_hidden, d_head], b1 [H, d_hidden],
- * w2 [H, d_out, d_hidden], b2 [H, d_out].  All four are required, also for a map given without biases. */
+ * w2 [H, d_out, d_hidden], b2 [H, d_out].  All four are required, also for a map given without biases.  For a
+ * three-layer map (w_mid given): w2 [H, d_out, d_mid], and w_mid [H, d_mid, d_hidden], b_mid [H, d_mid] are
+ * required as well; for a two-layer map they are ignored. */
 typedef struct ha_feature_map_grad {
   float *w1, *b1, *w2, *b2;
+  float *w_mid, *b_mid;
 } ha_feature_map_grad;
 
 /* Enqueues: the teacher forward (unless teacher_is_cached), the student forward, which also leaves the
@@ -183,9 +186,7 @@ typedef struct ha_feature_map_grad {
  * stored outputs (0 where they are equal), then the chain rule through Eq. "hybrid" and the feature maps
  * (Sec. 3.2) down to the eight parameter tensors.  The loss is the plain sum, so is the gradient; Alg. 1's
  * 1 / (m |T|) is the caller's.  row_den: device fp32 [B, H, N].  At hybrid_rate == 1 the gradients are zero.
- * Supported here: two-layer feature maps, d_hidden == d_out == d_head, or at d_head == 128 any d_hidden, d_out
- * that the forward takes (multiples of 128 up to 768; both maps of one shape); HA_ERR_UNSUPPORTED otherwise, also
- * for three-layer maps.  Matrix products
+ * Supported here: every feature-map shape the forward takes (both maps of one shape).  Matrix products
  * run in bf16 with fp32 accumulation; the sums over tokens are formed in a fixed order (bitwise reproducible).
  * workspace: device, 256-byte aligned, at least hybrid_attn_value_distill_grad_workspace_bytes() bytes.  Other
  * arguments and errors as for hybrid_attn_value_distill_loss. */

@@ -360,7 +360,7 @@ struct GradLayout {
 
 static void grad_layout(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, GradLayout &gl) {
   const size_t base = distill_layout(p, phi_q, phi_k, gl.teacher, gl.student, gl.off_partial);
-  gl.layered = phi_q->d_hidden != p.d_head || phi_q->d_out != p.d_head;
+  gl.layered = phi_q->d_hidden != p.d_head || phi_q->d_out != p.d_head || phi_q->w_mid;
   gl.total = base;
   if (gl.student.NL == 0) return;
   if (gl.layered) {
@@ -383,12 +383,8 @@ static ha_status check_grad_maps(const ha_problem *p, const ha_feature_map *phi_
     if (s != HA_OK) return s;
   }
   if (phi_q->d_out != phi_k->d_out || phi_q->d_hidden != phi_k->d_hidden) return HA_ERR_SHAPE;
-  for (const ha_feature_map *fm : {phi_q, phi_k}) {
-    if (fm->w_mid) return HA_ERR_UNSUPPORTED;                        // two-layer maps only
-    const bool square = fm->d_hidden == p->d_head && fm->d_out == p->d_head;
-    const bool layered = p->d_head == 128 && fm->d_hidden % 128 == 0 && fm->d_out % 128 == 0;
-    if (!square && !layered) return HA_ERR_UNSUPPORTED;
-  }
+  if ((phi_q->w_mid != nullptr) != (phi_k->w_mid != nullptr)) return HA_ERR_SHAPE;
+  if (phi_q->w_mid && phi_q->d_mid != phi_k->d_mid) return HA_ERR_SHAPE;
   return HA_OK;
 }
 
@@ -411,7 +407,8 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
   if (!q || !k || !v || !y_teacher || !y_student || !row_den || !loss || !grad_q || !grad_k) return HA_ERR_NULL;
   for (const ha_feature_map_grad *gm : {grad_q, grad_k}) {
     if (!gm->w1 || !gm->b1 || !gm->w2 || !gm->b2) return HA_ERR_NULL;
-    for (const float *t : {gm->w1, gm->b1, gm->w2, gm->b2})
+    if (phi_q->w_mid && (!gm->w_mid || !gm->b_mid)) return HA_ERR_NULL;
+    for (const float *t : {gm->w1, gm->b1, gm->w2, gm->b2, phi_q->w_mid ? gm->w_mid : nullptr, phi_q->w_mid ? gm->b_mid : nullptr})
       if (reinterpret_cast<uintptr_t>(t) & 3u) return HA_ERR_ALIGN;
   }
   if (!ha::aligned16(q) || !ha::aligned16(k) || !ha::aligned16(v) || !ha::aligned16(y_teacher) ||
@@ -447,12 +444,15 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
   double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + off_partial);
   if ((e = ha::launch_l1_distance(ps, y_teacher, y_student, partial, loss, st)) != hipSuccess) return ha::device_error(e);
   const size_t H = (size_t)p->H, D = (size_t)p->d_head, HD = (size_t)phi_q->d_hidden, F = (size_t)phi_q->d_out;
+  const size_t DM = phi_q->w_mid ? (size_t)phi_q->d_mid : 0, KL = DM ? DM : HD;
   if (ps.NL == 0) {
     for (const ha_feature_map_grad *gm : {grad_q, grad_k}) {
       if ((e = ha::launch_fill_zero(gm->w1, H * HD * D, st)) != hipSuccess) return ha::device_error(e);
-      if ((e = ha::launch_fill_zero(gm->w2, H * F * HD, st)) != hipSuccess) return ha::device_error(e);
+      if ((e = ha::launch_fill_zero(gm->w2, H * F * KL, st)) != hipSuccess) return ha::device_error(e);
       if ((e = ha::launch_fill_zero(gm->b1, H * HD, st)) != hipSuccess) return ha::device_error(e);
       if ((e = ha::launch_fill_zero(gm->b2, H * F, st)) != hipSuccess) return ha::device_error(e);
+      if (DM && (e = ha::launch_fill_zero(gm->w_mid, H * DM * HD, st)) != hipSuccess) return ha::device_error(e);
+      if (DM && (e = ha::launch_fill_zero(gm->b_mid, H * DM, st)) != hipSuccess) return ha::device_error(e);
     }
     return HA_OK;
   }
@@ -482,6 +482,6 @@ const char *hybrid_attn_status_string(ha_status s) {
 
 int hybrid_attn_last_device_error(void) { return ha::g_last_device_error; }
 
-int hybrid_attn_abi_version(void) { return 3; }
+int hybrid_attn_abi_version(void) { return 4; }
 
 }  // extern "C"

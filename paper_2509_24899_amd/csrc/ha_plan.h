@@ -42,7 +42,7 @@ struct WidePlan {
 // Workspace of the value-distillation gradient of maps that take the layer-by-layer path (beyond WidePlan's).
 struct WideGradPlan {
   int CHq, n_chunks_q, CHk, n_chunks_k;
-  size_t off_wt, off_shi, off_slo, off_dS, off_dz, off_dshi, off_dslo, off_gsign, off_rs, off_wp, off_tdt, off_pdot, off_du,
+  size_t off_wt, off_wtm, off_dpre2, off_shi, off_slo, off_dS, off_dz, off_dshi, off_dslo, off_gsign, off_rs, off_wp, off_tdt, off_pdot, off_du,
       off_dpre, off_part, total;
 };
 

@@ -433,7 +433,9 @@ void make_wide_grad_plan(const Plan &pl, const WidePlan &wp, size_t base_off, Wi
   const size_t n_tb = wp.n_tb_q, nblk = (pl.F + 255) / 256;
   size_t off = base_off;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
-  gp.off_wt = take((size_t)pl.H * pl.F * pl.HD * 2);
+  const size_t KL = pl.DM > 0 ? pl.DM : pl.HD;                         // input width of the last layer
+  gp.off_wt = take((size_t)pl.H * pl.F * KL * 2);
+  gp.off_wtm = take((size_t)pl.H * pl.DM * pl.HD * 2);
   gp.off_shi = take(BH * pl.F * pl.D * 2);
   gp.off_slo = take(BH * pl.F * pl.D * 2);
   gp.off_dS = take(BH * pl.F * pl.D * 4);
@@ -447,7 +449,9 @@ void make_wide_grad_plan(const Plan &pl, const WidePlan &wp, size_t base_off, Wi
   gp.off_pdot = take(BH * n_tb * nblk * 64 * 4);
   gp.off_du = take(BH * n_tb * 32 * (size_t)pl.F * 2);
   gp.off_dpre = take(BH * n_tb * 32 * (size_t)pl.HD * 2);
-  const size_t slabs = (size_t)(pl.F / 128) * (pl.HD / 128);          // the largest product: dW2
+  gp.off_dpre2 = take(BH * n_tb * 32 * (size_t)pl.DM * 2);
+  size_t slabs = (size_t)(pl.F / 128) * (KL / 128);                    // the largest product: the last layer's or the middle layer's
+  if ((size_t)(pl.DM / 128) * (pl.HD / 128) > slabs) slabs = (size_t)(pl.DM / 128) * (pl.HD / 128);
   const int nc = gp.n_chunks_q > gp.n_chunks_k ? gp.n_chunks_q : gp.n_chunks_k;
   gp.off_part = take(BH * nc * slabs * 20 * 1024 * 4);
   gp.total = off;
@@ -468,14 +472,14 @@ static hipError_t contract_and_reduce(const Plan &pl, ContractArgs c, int n_chun
   return hipGetLastError();
 }
 
-// Everything after the student's forward, for two-layer maps of any supported width: S, z are in the forward's
+// Everything after the student's forward, for maps of any supported width and depth: S, z are in the forward's
 // workspace region, y_teacher, y_student and row_den hold the two outputs and the student's row denominators.
 hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp, const WideGradPlan &gp, const void *q,
                                               const void *k, const void *v, const ha_feature_map &phi_q,
                                               const ha_feature_map &phi_k, const void *y_teacher, const void *y_student,
                                               const float *row_den, const ha_feature_map_grad &gq, const ha_feature_map_grad &gk,
                                               void *ws, hipStream_t st) {
-  const int BH = pl.B * pl.H, D = pl.D, F = pl.F, HD = pl.HD;
+  const int BH = pl.B * pl.H, D = pl.D, F = pl.F, HD = pl.HD, DM = pl.DM, KL = DM > 0 ? DM : HD;
   hipError_t e;
   if ((e = launch_vd_rows(pl, y_teacher, y_student, row_den, ws_ptr<void>(ws, gp.off_gsign), ws_ptr<float>(ws, gp.off_rs),
                           ws_ptr<float>(ws, gp.off_wp), st)) != hipSuccess)
@@ -492,10 +496,16 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
     // this side's forward passes: h (hi + lo), pre-activations, softmax maxima / sums, phi
     if ((e = launch_wide_map(pl, wp, is_query ? q : k, fm, is_query, ws, st)) != hipSuccess) return e;
     {
-      dim3 grid((F * HD + 255) / 256, pl.H);
-      if (pl.f32) wide_prep_t_kernel<true><<<grid, 256, 0, st>>>(fm.w2, ws_ptr<__bf16>(ws, gp.off_wt), F, HD);
-      else wide_prep_t_kernel<false><<<grid, 256, 0, st>>>(fm.w2, ws_ptr<__bf16>(ws, gp.off_wt), F, HD);
+      dim3 grid((F * KL + 255) / 256, pl.H);
+      if (pl.f32) wide_prep_t_kernel<true><<<grid, 256, 0, st>>>(fm.w2, ws_ptr<__bf16>(ws, gp.off_wt), F, KL);
+      else wide_prep_t_kernel<false><<<grid, 256, 0, st>>>(fm.w2, ws_ptr<__bf16>(ws, gp.off_wt), F, KL);
       if ((e = hipGetLastError()) != hipSuccess) return e;
+      if (DM > 0) {
+        dim3 gridm((DM * HD + 255) / 256, pl.H);
+        if (pl.f32) wide_prep_t_kernel<true><<<gridm, 256, 0, st>>>(fm.w_mid, ws_ptr<__bf16>(ws, gp.off_wtm), DM, HD);
+        else wide_prep_t_kernel<false><<<gridm, 256, 0, st>>>(fm.w_mid, ws_ptr<__bf16>(ws, gp.off_wtm), DM, HD);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+      }
     }
     WideGradArgs a;
     a.x = is_query ? q : k;
@@ -522,10 +532,19 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
       dim3 grid2((n_tb + 3) / 4, BH);
       wide_du_kernel<<<grid2, 256, 0, st>>>(a.t_img, a.tdt_img, a.pdot, ws_ptr<bf16x8>(ws, gp.off_du), F, n_tb, a.act);
       if ((e = hipGetLastError()) != hipSuccess) return e;
+      // back through the last layer (and the middle one): dpre = (W^T d) [h > 0]
+      const bf16x8 *d_in = ws_ptr<bf16x8>(ws, gp.off_du);
+      if (DM > 0) {
+        dim3 grid3((n_tb + 3) / 4, (DM + 255) / 256, BH);
+        wide_back_layer_kernel<<<grid3, 256, 0, st>>>(d_in, ws_ptr<bf16x8>(ws, gp.off_wt), ws_ptr<bf16x8>(ws, wp.off_h2hi),
+                                                      ws_ptr<bf16x8>(ws, gp.off_dpre2), pl.H, F, DM, n_tb);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        d_in = ws_ptr<bf16x8>(ws, gp.off_dpre2);
+      }
       dim3 grid3((n_tb + 3) / 4, (HD + 255) / 256, BH);
-      wide_back_layer_kernel<<<grid3, 256, 0, st>>>(ws_ptr<bf16x8>(ws, gp.off_du), ws_ptr<bf16x8>(ws, gp.off_wt),
-                                                    ws_ptr<bf16x8>(ws, wp.off_hhi), ws_ptr<bf16x8>(ws, gp.off_dpre), pl.H, F, HD,
-                                                    n_tb);
+      wide_back_layer_kernel<<<grid3, 256, 0, st>>>(d_in, ws_ptr<bf16x8>(ws, DM > 0 ? gp.off_wtm : gp.off_wt),
+                                                    ws_ptr<bf16x8>(ws, wp.off_hhi), ws_ptr<bf16x8>(ws, gp.off_dpre), pl.H,
+                                                    DM > 0 ? DM : F, HD, n_tb);
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     ContractArgs c;
@@ -533,10 +552,16 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
     c.part = ws_ptr<float>(ws, gp.off_part);
     c.H = pl.H; c.N = pl.N; c.n_tok = n_tok; c.n_tb = n_tb; c.R = is_query ? 0 : pl.R; c.CH = CH;
     c.sb = pl.sb; c.sh = pl.sh; c.sn = pl.sn;
-    // [dW2 | db2] = sum du [h | 1]^T
+    // [dW2 | db2] = sum du [h | 1]^T, h the input of the last layer
     c.a_img = ws_ptr<bf16x8>(ws, gp.off_du); c.WA = F;
-    c.b_img = ws_ptr<bf16x8>(ws, wp.off_hhi); c.WB = HD;
+    c.b_img = ws_ptr<bf16x8>(ws, DM > 0 ? wp.off_h2hi : wp.off_hhi); c.WB = KL;
     if ((e = contract_and_reduce<0>(pl, c, n_chunks, true, gm.w2, gm.b2, st)) != hipSuccess) return e;
+    if (DM > 0) {
+      // [dW_mid | db_mid] = sum dpre2 [h1 | 1]^T
+      c.a_img = ws_ptr<bf16x8>(ws, gp.off_dpre2); c.WA = DM;
+      c.b_img = ws_ptr<bf16x8>(ws, wp.off_hhi); c.WB = HD;
+      if ((e = contract_and_reduce<0>(pl, c, n_chunks, true, gm.w_mid, gm.b_mid, st)) != hipSuccess) return e;
+    }
     // [dW1 | db1] = sum dpre [x | 1]^T
     c.a_img = ws_ptr<bf16x8>(ws, gp.off_dpre); c.WA = HD;
     c.b_img = nullptr; c.b_rows = is_query ? q : k; c.WB = D;

@@ -29,7 +29,8 @@ class ha_feature_map(ctypes.Structure):
 
 
 class ha_feature_map_grad(ctypes.Structure):
-    _fields_ = [("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
+    _fields_ = [("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
+                ("w_mid", ctypes.c_void_p), ("b_mid", ctypes.c_void_p)]
 
 
 class ha_problem(ctypes.Structure):
@@ -359,7 +360,12 @@ def hybrid_attn_value_distill_grad(q, k, v, phi_q: FeatureMap, phi_k: FeatureMap
                  b1=torch.empty(fm.w1.shape[:2], dtype=torch.float32, device=q.device),
                  w2=torch.empty(fm.w2.shape, dtype=torch.float32, device=q.device),
                  b2=torch.empty(fm.w2.shape[:2], dtype=torch.float32, device=q.device))
-        return t, ha_feature_map_grad(t["w1"].data_ptr(), t["b1"].data_ptr(), t["w2"].data_ptr(), t["b2"].data_ptr())
+        if fm.w_mid is not None:
+            t["w_mid"] = torch.empty(fm.w_mid.shape, dtype=torch.float32, device=q.device)
+            t["b_mid"] = torch.empty(fm.w_mid.shape[:2], dtype=torch.float32, device=q.device)
+        return t, ha_feature_map_grad(t["w1"].data_ptr(), t["b1"].data_ptr(), t["w2"].data_ptr(), t["b2"].data_ptr(),
+                                      t["w_mid"].data_ptr() if "w_mid" in t else None,
+                                      t["b_mid"].data_ptr() if "b_mid" in t else None)
 
     gq, cq = grads_of(phi_q)
     gk, ck = grads_of(phi_k)

@@ -37,7 +37,7 @@ def test_header_symbols_are_exported(lib):
     assert len(set(names)) == 16
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert ha.hybrid_attn_abi_version() == 3
+    assert ha.hybrid_attn_abi_version() == 4
 
 
 def test_struct_layout_matches_header():
@@ -209,7 +209,9 @@ def test_value_distill_grad_workspace_and_errors(lib):
     assert f(*args(den=A[5] + 2)) == ha.HA_ERR_ALIGN
     assert f(*args(wsb=need - 1)) == ha.HA_ERR_WORKSPACE
     assert f(*args(ws=None)) == ha.HA_ERR_WORKSPACE
-    assert f(*args(fq=three, fk=three)) == ha.HA_ERR_UNSUPPORTED    # two-layer maps only
+    assert f(*args(fq=three, fk=three)) == ha.HA_ERR_NULL           # a three-layer map needs w_mid, b_mid gradient buffers
+    assert f(*args(fq=three, fk=wide)) == ha.HA_ERR_SHAPE
+    assert ctypes.sizeof(ha.ha_feature_map_grad) == 48 and ha.ha_feature_map_grad.w_mid.offset == 32
     assert f(*args(fq=wide, fk=wide)) == ha.HA_ERR_WORKSPACE        # supported, but `need` was sized for the narrow map
     assert f(*args(fq=wide, fk=fm)) == ha.HA_ERR_SHAPE
     assert f(*args(p=_problem(d=96))) == ha.HA_ERR_UNSUPPORTED
@@ -241,5 +243,6 @@ def test_wider_and_three_layer_maps_validate(lib):
     assert ha.hybrid_attn_validate(p, bad, bad) == ha.HA_ERR_SHAPE
     odd = ha.ha_feature_map(FAKE, None, FAKE + 0x100000, None, 768, 768, 6, ha.HA_ACT_SOFTMAX, FAKE + 0x200000, None, 192, 0)
     assert ha.hybrid_attn_validate(p, odd, odd) == ha.HA_ERR_UNSUPPORTED
-    # the gradient entry point has kernels for two-layer maps only
-    assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(three), ctypes.byref(three)) == 0
+    # the gradient entry point takes them too
+    assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(three), ctypes.byref(three)) > \
+        lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(p), ctypes.byref(three), ctypes.byref(three))

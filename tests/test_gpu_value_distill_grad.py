@@ -42,7 +42,8 @@ def round_io(a, dtype):
 def compare(tag, got, want):
     worst = 0.0
     for side, g, w_ in (("q", got[0], want[0]), ("k", got[1], want[1])):
-        for n in NAMES:
+        assert set(g) == set(w_)
+        for n in w_:
             a = g[n].cpu().numpy().astype(np.float64)
             assert a.shape == w_[n].shape
             assert np.isfinite(a).all()
@@ -56,8 +57,9 @@ def bf16_representable(inp):
     """The kernels feed the matrix cores bf16: fp32 inputs are rounded on load.  The ReLU gate of the hidden layer
     is a discontinuous decision of the gradient; for an fp32 workload both sides take it on the same numbers when
     q, k, v and the weights are bf16-representable to begin with (the biases stay fp32 on both sides)."""
-    for t in (inp.q, inp.k, inp.v, inp.phi_q.w1, inp.phi_q.w2, inp.phi_k.w1, inp.phi_k.w2):
-        t[...] = W.round_to_bf16(t)
+    for t in (inp.q, inp.k, inp.v, inp.phi_q.w1, inp.phi_q.w2, inp.phi_k.w1, inp.phi_k.w2, inp.phi_q.w_mid, inp.phi_k.w_mid):
+        if t is not None:
+            t[...] = W.round_to_bf16(t)
     return inp
 
 

@@ -1,4 +1,4 @@
-"""GPU tests of the value-distillation gradient for two-layer feature maps wider than d -> d -> d (Tab. "phi")."""
+"""GPU tests of the value-distillation gradient for the feature maps beyond d -> d -> d (Tab. "phi": wider and three-layer maps)."""
 import numpy as np
 import pytest
 import torch
@@ -18,6 +18,10 @@ WIDE_CASES = [
     (W.replace(SMALL, name="vdg_256_128", B=2, H=2, N=700, d_hidden=256, d_feat=128, poly_degree=1, seed=92), 3),
     (W.replace(LOGIT_STD1, name="vdg_P4_linear", B=1, H=2, N=515, d_hidden=512, d_feat=512, poly_degree=4, seed=93), 0),
     (W.replace(SMALL, name="vdg_128_384_f32", B=1, H=2, N=450, dtype="f32", d_hidden=128, d_feat=384, poly_degree=3, seed=94), 2),
+    # three layers: the P = 6 row of Tab. "phi", unequal widths, and the smallest shape
+    (W.replace(SMALL, name="vdg_P6_3layer", B=1, H=2, N=600, d_hidden=768, d_mid=768, d_feat=768, poly_degree=6, seed=95), 4),
+    (W.replace(SMALL, name="vdg_3layer_256_128_384", B=2, H=2, N=500, d_hidden=256, d_mid=128, d_feat=384, poly_degree=3, seed=96), 3),
+    (W.replace(LOGIT_STD1, name="vdg_3layer_128", B=1, H=2, N=333, d_hidden=128, d_mid=128, d_feat=128, poly_degree=2, seed=97), 0),
 ]
 
 
@@ -65,3 +69,18 @@ def test_wide_map_whole_step_and_replay():
         for n in NAMES:
             assert torch.equal(a[n], b[n])
     assert torch.equal(loss, loss2)
+
+
+def test_three_layer_whole_step():
+    """Teacher, student, loss and backward in one call for a three-layer map."""
+    wl, R = WIDE_CASES[6]
+    inp = W.make_inputs(wl)
+    fq, fk, y, yh, den = oracle_forward_pieces(inp, R)
+    want = G.value_distill_grad(inp.q, inp.k, inp.v, fq, fk, R, wl.scale)
+    q, k, v, dq, dk = ha.to_device(inp)
+    print(f"  case whole step {wl.name} R={R}", flush=True)
+    loss, gq, gk, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, dq, dk, R, wl.block_size, wl.scale)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(rd.cpu().numpy(), den, rtol=5e-3)
+    assert abs(loss.cpu().numpy()[0] - want[2]) <= 2e-2 * want[2]
+    assert compare(f"whole_step_{wl.name}_R{R}", (gq, gk), want) <= 6e-2
