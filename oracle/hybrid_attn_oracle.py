@@ -28,6 +28,10 @@ Readings of the paper taken here (each is a decision, listed again in the design
     then split into P contiguous slices and slice p (1-based) is raised elementwise to the
     power p and the slices are concatenated in channel order.
 
+Variant (not the paper's method, which Sec. 3.2 states per token): `BlockSplit(R, block)` in place of the integer
+R makes whole blocks of `block` consecutive tokens softmax tokens, every R-th block, the other reading of a
+"block rate"; everything downstream of the split is unchanged.
+
 All arithmetic is float64; nothing is rounded inside.  Inputs are whatever the caller hands in
 (already rounded to the io dtype of the GPU path and widened).
 
@@ -86,8 +90,25 @@ class FeatureMap:
         return n
 
 
-def token_split(N: int, R: int):
+class BlockSplit:
+    """Block-granular variant of the token split: token j (0-based) is a softmax token when its block
+    j // block is a multiple of R.  Accepted wherever a rate R is; block = 1 is the paper's rule."""
+
+    def __init__(self, R: int, block: int):
+        if R < 0 or block < 1:
+            raise ValueError("R must be >= 0 and block >= 1")
+        self.R, self.block = int(R), int(block)
+
+
+def token_split(N: int, R):
     """Index sets (0-based) of softmax tokens T_S and linear tokens T_L (Sec. 3.2)."""
+    if isinstance(R, BlockSplit):
+        idx = np.arange(N)
+        if R.R == 0:
+            is_s = np.zeros(N, dtype=bool)
+        else:
+            is_s = ((idx // R.block) % R.R) == 0
+        return idx[is_s], idx[~is_s]
     if R < 0:
         raise ValueError("R must be >= 0")
     idx = np.arange(N)
@@ -211,7 +232,16 @@ def hybrid_attn_dense_loops(q, k, v, phi_q, phi_k, head, R, scale):
     y_i = sum_j w_ij v_j / sum_j w_ij.
     """
     N, d = q.shape
-    is_s = [(R >= 1 and (j + 1) % R == (1 % R)) for j in range(N)]   # the rule in 1-indexed form
+    if isinstance(R, BlockSplit):                                    # variant: every R-th block of tokens, counted in loops
+        is_s, j = [], 0
+        while j < N:
+            for blk in range(max(R.R, 1)):
+                for _ in range(R.block):
+                    if j < N:
+                        is_s.append(R.R >= 1 and blk == 0)
+                        j += 1
+    else:
+        is_s = [(R >= 1 and (j + 1) % R == (1 % R)) for j in range(N)]   # the rule in 1-indexed form
     gq = feature_map(q, phi_q, head) if phi_q is not None else None
     fk = feature_map(k, phi_k, head) if phi_k is not None else None
     y = np.zeros((N, d))

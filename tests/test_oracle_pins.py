@@ -212,9 +212,42 @@ def pin_split_rule(M):
     assert len(s) == 8190
 
 
+def pin_block_granular_split(M):
+    """The block-granular variant: explicit index lists, block = 1 equals the paper's rule, the closed form for a
+    constant feature map (sensitive to which tokens are softmax tokens) and the loop form with its own counting."""
+    s, l = M.token_split(11, M.BlockSplit(3, 2))
+    assert list(s) == [0, 1, 6, 7] and list(l) == [2, 3, 4, 5, 8, 9, 10]
+    s, l = M.token_split(7, M.BlockSplit(2, 4))
+    assert list(s) == [0, 1, 2, 3] and list(l) == [4, 5, 6]
+    assert len(M.token_split(9, M.BlockSplit(0, 4))[0]) == 0 and len(M.token_split(9, M.BlockSplit(1, 4))[1]) == 0
+    for N, R in ((10, 3), (17, 4), (5, 1), (6, 0)):
+        for a, b in zip(M.token_split(N, M.BlockSplit(R, 1)), M.token_split(N, R)):
+            assert list(a) == list(b)
+    rng = np.random.default_rng(14)
+    N, d, F, P, R, blk = 23, 5, 6, 2, 3, 4
+    q = np.zeros((1, 2, N, d))
+    k = rng.standard_normal((1, 2, N, d))
+    v = rng.standard_normal((1, 2, N, d)) + np.arange(N)[None, None, :, None]
+    fm = _const_map(2, d, 4, F, P, mod=M)
+    y = M.hybrid_attn(q, k, v, fm, fm, M.BlockSplit(R, blk), 0.5)
+    kappa = (F // P) * sum(float(F) ** (-2 * p) for p in range(1, P + 1))
+    s_tok = [0, 1, 2, 3, 12, 13, 14, 15]                          # blocks 0 and 3 of four tokens
+    l_tok = [j for j in range(N) if j not in s_tok]
+    for h in range(2):
+        num = v[0, h, s_tok].sum(0) + kappa * v[0, h, l_tok].sum(0)
+        np.testing.assert_allclose(y[0, h], np.broadcast_to(num / (len(s_tok) + kappa * len(l_tok)), (N, d)), rtol=1e-12)
+    q, k, v = (rng.standard_normal((1, 2, 19, 4)) * 1.3 for _ in range(3))
+    fq, fk = _rand_map(rng, 2, 4, 5, 6, 2, mod=M), _rand_map(rng, 2, 4, 5, 6, 2, mod=M)
+    for R, blk in ((2, 3), (4, 2), (3, 8), (0, 2), (1, 5)):
+        y = M.hybrid_attn(q, k, v, fq, fk, M.BlockSplit(R, blk), 0.7)
+        for h in range(2):
+            ref = O.hybrid_attn_dense_loops(q[0, h], k[0, h], v[0, h], fq, fk, h, O.BlockSplit(R, blk), 0.7)
+            np.testing.assert_allclose(y[0, h], ref, rtol=1e-11, atol=1e-13)
+
+
 PINS = [pin_r1_is_library_softmax_attention, pin_feature_map_is_grouped_conv, pin_two_token_golden,
         pin_constant_phi_closed_form, pin_r0_is_linear_attention_nxn, pin_dense_loops, pin_invariants,
-        pin_split_rule]
+        pin_split_rule, pin_block_granular_split]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
@@ -242,9 +275,26 @@ def test_tab_phi_parameter_counts():
 # ----------------------------------------------------------------------------- planted mistakes
 
 def _mut_split_off_by_one(mp):
+    good = O.token_split
+
     def bad(N, R):
+        if isinstance(R, O.BlockSplit):
+            return good(N, R)
         idx = np.arange(N)
         is_s = (idx % R) == (1 % R) if R else np.zeros(N, bool)
+        return idx[is_s], idx[~is_s]
+    mp.setattr(O, "token_split", bad)
+
+
+def _mut_block_split_counts_tokens_not_blocks(mp):
+    """The variant's rule with the block index dropped: the first token of every R-th block only."""
+    good = O.token_split
+
+    def bad(N, R):
+        if not isinstance(R, O.BlockSplit):
+            return good(N, R)
+        idx = np.arange(N)
+        is_s = (idx % (R.R * R.block)) == 0 if R.R else np.zeros(N, bool)
         return idx[is_s], idx[~is_s]
     mp.setattr(O, "token_split", bad)
 
@@ -339,7 +389,7 @@ def _mut_phi_sees_scaled_input(mp):
     mp.setattr(O, "feature_map", lambda x, fm, head: good(np.asarray(x) * 0.5, fm, head))
 
 
-MUTATIONS = [_mut_split_off_by_one, _mut_softmax_per_slice, _mut_no_powers, _mut_powers_from_zero, _mut_no_relu,
+MUTATIONS = [_mut_split_off_by_one, _mut_block_split_counts_tokens_not_blocks, _mut_softmax_per_slice, _mut_no_powers, _mut_powers_from_zero, _mut_no_relu,
              _mut_no_scale, _mut_unstabilised, _mut_max_over_all_tokens, _mut_drop_z, _mut_state_over_all_tokens,
              _mut_phi_sees_scaled_input]
 
