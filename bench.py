@@ -28,7 +28,7 @@ def cpu_baseline(w, heads=12):
     fq = O.FeatureMap(inp.phi_q.w1, inp.phi_q.b1, inp.phi_q.w2, inp.phi_q.b2, w.poly_degree)
     fk = O.FeatureMap(inp.phi_k.w1, inp.phi_k.b1, inp.phi_k.w2, inp.phi_k.b2, w.poly_degree)
     t0 = time.perf_counter()
-    O.hybrid_attn(inp.q, inp.k, inp.v, fq, fk, w.R, w.scale)
+    O.hybrid_attn(inp.q, inp.k, inp.v, fq, fk, O.BlockSplit(w.R, w.split_granularity) if w.split_granularity > 1 else w.R, w.scale)
     t_sample = time.perf_counter() - t0
     t_full = t_sample * (w.B * w.H) / heads
     try:
@@ -138,18 +138,18 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
     """One student update of the attention-distillation loop (Sec. 3.3, Alg. 1, inner loop) on the cached teacher
     output: student forward, loss, gradient with respect to phi_q and phi_k.  Prints one JSON line."""
     assert w.R != 1, "the gradient needs linear tokens"
-    prob = ha.make_problem(q, w.R, w.block_size, w.scale)
+    prob = ha.make_problem(q, w.rate, w.block_size, w.scale)
     lib_ws = torch.empty(max(ha.hybrid_attn_value_distill_grad_workspace_bytes(prob, fq, fk), 256), dtype=torch.uint8,
                          device=q.device)
-    loss, gq, gk, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale, workspace=lib_ws)
+    loss, gq, gk, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.rate, w.block_size, w.scale, workspace=lib_ws)
     torch.cuda.synchronize()
 
     def full_step():
-        ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
+        ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.rate, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
                                           y_student=ys, row_den=rd, workspace=lib_ws)
 
     def backward_only():
-        ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.R, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
+        ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.rate, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
                                           y_student=ys, row_den=rd, student_is_cached=True, workspace=lib_ws)
 
     def timed(fn):
@@ -206,6 +206,8 @@ def main():
                          "are the two-layer rows P = 2, 3, 4 of Tab. phi at d = 128, 768 the width of its P = 6 row)")
     ap.add_argument("--phi-layers", type=int, default=2, choices=[2, 3],
                     help="MLP depth of both feature maps; 3 adds a hidden layer of the same width (Tab. phi, P = 6 row)")
+    ap.add_argument("--split-granularity", type=int, default=0, metavar="G",
+                    help="variant of the token split: groups of G consecutive tokens, every R-th group softmax tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
@@ -246,6 +248,8 @@ def main():
                       poly_degree=args.phi_width // w.d if args.phi_width % w.d == 0 else w.poly_degree)
     if args.phi_layers == 3:
         w = W.replace(w, d_mid=w.d_hidden)
+    if args.split_granularity > 1:
+        w = W.replace(w, split_granularity=args.split_granularity)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
@@ -268,13 +272,13 @@ def main():
             fm.b_mid = torch.randn(w.H, w.d_mid, generator=gen, device=dev) * 0.1
         return fm
     fq, fk = (dmap(), dmap()) if w.R != 1 else (None, None)
-    prob = ha.make_problem(q, w.R, w.block_size, w.scale)
+    prob = ha.make_problem(q, w.rate, w.block_size, w.scale)
     ws = torch.empty(ha.hybrid_attn_workspace_bytes(prob, fq, fk), dtype=torch.uint8, device=dev)
     out = torch.empty_like(q)
     stream = torch.cuda.current_stream()
 
     def step():
-        ha.hybrid_attn_forward(q, k, v, fq, fk, w.R, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
+        ha.hybrid_attn_forward(q, k, v, fq, fk, w.rate, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
 
     if args.distill_step:
         distill_step_mode(args, w, ha, torch, q, k, v, fq, fk)
@@ -359,7 +363,7 @@ def main():
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (null when this
     # workload has not been profiled)
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d:   # profiled with the d -> d -> d maps
+    if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d and w.split_granularity <= 1:   # profiled with the d -> d -> d maps
         t = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
         if t:
             roofline["traffic"] = t["read_bytes"] + t["written_bytes"]
@@ -374,6 +378,7 @@ def main():
         "data": "synthetic" if not args.zero_inputs else "all-zero q, k, v (clock experiment, not a benchmark)",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype,
                    "hybrid_rate_R": w.R, "r": (1.0 / w.R if w.R else 0.0), "block_size": w.block_size,
+                   **({"split_granularity": w.split_granularity} if w.split_granularity > 1 else {}),
                    "feature_map": (f"{w.d}->{w.d_hidden}->{w.d_mid}->{w.d_feat}" if w.d_mid else f"{w.d}->{w.d_hidden}->{w.d_feat}")
                    + f", P={w.poly_degree}"},
         "tflops": flops / (ms_per_step * 1e-3) / 1e12,

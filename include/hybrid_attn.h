@@ -91,6 +91,11 @@ typedef struct {
                              Any R <= N is accepted; it is never rounded. */
   float   softmax_scale;  /* multiplies q.k; pass 1/sqrt(d_head) for the paper's operator */
   int64_t stride_b, stride_h, stride_n;
+  int32_t split_granularity; /* 0 or 1: the split of Sec. 3.2, per token.  g >= 2 (a variant, not the paper's
+                             method): whole groups of g consecutive tokens are softmax tokens, every R-th
+                             group: token j is a softmax token when (j / g) mod R == 0.  Any g <= N
+                             with R g <= 2^30. */
+  int32_t reserved;       /* must be 0 */
 } ha_problem;
 
 /* Host-only argument check (no HIP call).  phi_q and phi_k may be NULL iff the problem has no

@@ -49,6 +49,8 @@ static ha_status validate(const ha_problem *p, const ha_feature_map *phi_q, cons
   if (!p) return HA_ERR_NULL;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d_head <= 0) return HA_ERR_SHAPE;
   if (p->hybrid_rate < 0 || p->hybrid_rate > p->N) return HA_ERR_SHAPE;
+  if (p->split_granularity < 0 || p->split_granularity > p->N || p->reserved != 0) return HA_ERR_SHAPE;
+  if ((int64_t)p->hybrid_rate * p->split_granularity > (int64_t)1 << 30) return HA_ERR_UNSUPPORTED;
   if (!(p->softmax_scale > 0.f) || !std::isfinite(p->softmax_scale)) return HA_ERR_SHAPE;
   if (p->dtype != HA_BF16 && p->dtype != HA_F32) return HA_ERR_UNSUPPORTED;
   if (p->d_head != 64 && p->d_head != 128) return HA_ERR_UNSUPPORTED;
@@ -78,7 +80,9 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.f32 = p.dtype == HA_F32;
   pl.sb = p.stride_b; pl.sh = p.stride_h; pl.sn = p.stride_n;
   pl.scale = p.softmax_scale;
-  pl.NS = pl.R == 0 ? 0 : (pl.N + pl.R - 1) / pl.R;
+  pl.G = p.split_granularity > 1 ? p.split_granularity : 1;
+  // softmax tokens: the first G of every R G tokens
+  pl.NS = pl.R == 0 ? 0 : (pl.N / (pl.R * pl.G)) * pl.G + (pl.N % (pl.R * pl.G) < pl.G ? pl.N % (pl.R * pl.G) : pl.G);
   pl.NL = pl.N - pl.NS;
   const bool has_linear = pl.NL > 0 && phi_q && phi_k;
   pl.HD = has_linear ? phi_k->d_hidden : pl.D;
@@ -482,6 +486,6 @@ const char *hybrid_attn_status_string(ha_status s) {
 
 int hybrid_attn_last_device_error(void) { return ha::g_last_device_error; }
 
-int hybrid_attn_abi_version(void) { return 4; }
+int hybrid_attn_abi_version(void) { return 5; }
 
 }  // extern "C"

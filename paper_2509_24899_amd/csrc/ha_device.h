@@ -65,15 +65,15 @@ static __device__ __forceinline__ bf16x8 load8(const void *base, int64_t elem_of
 // i.e. i + i / (R - 1) + 1.  The quotient comes from a float reciprocal plus one correction step
 // (exact for i < 2^23).
 struct LinearMap {
-  int d;        // R - 1, or a huge divisor when R == 0
-  int one;      // 1 if R != 0
+  int d;        // (R - 1) G linear tokens per group of R G tokens, or a huge divisor when R == 0
+  int g;        // G softmax tokens lead every group; 0 if R == 0
   float rcp;
-  __device__ __forceinline__ explicit LinearMap(int R) : d(R == 0 ? 0x7fffffff : R - 1), one(R != 0), rcp(1.0f / (float)d) {}
+  __device__ __forceinline__ LinearMap(int R, int G) : d(R == 0 ? 0x7fffffff : (R - 1) * G), g(R != 0 ? G : 0), rcp(1.0f / (float)d) {}
   __device__ __forceinline__ int token(int i) const {
     int q = (int)((float)i * rcp);
     int rem = i - q * d;
     q += (rem >= d) - (rem < 0);
-    return i + q + one;
+    return i + (q + 1) * g;
   }
 };
 

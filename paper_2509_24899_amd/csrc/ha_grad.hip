@@ -145,7 +145,7 @@ struct GradArgs {
   const bf16x8 *m_hi, *m_lo;        // [B*H][D*D/8]: natural-order fragments of S (queries) or dS (keys)
   const float *zvec;                // [B*H][D]: z (queries) or dz (keys)
   float *part;
-  int H, N, NT, R, CH, P, act;
+  int H, N, NT, R, G, CH, P, act;
   int64_t sb, sh, sn;
 };
 
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
   const GlobalFrags mlo = global_frags(a.m_lo + (int64_t)bh * (D * D / 8), D * D * 2);
   const float *b1 = &blds[0], *b2 = &blds[D], *zl = &blds[2 * D];
 
-  const LinearMap lmap(QUERY ? 0 : a.R);
+  const LinearMap lmap(QUERY ? 0 : a.R, a.G);
 
   f32x16 acc2[NCB], acc1[NCB];
 #pragma unroll
@@ -564,7 +564,7 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
                           ws_ptr<float>(ws, gp.off_wp), st)) != hipSuccess)
     return e;
   GradArgs a;
-  a.H = pl.H; a.N = pl.N; a.R = pl.R; a.P = pl.P;
+  a.H = pl.H; a.N = pl.N; a.R = pl.R; a.G = pl.G; a.P = pl.P;
   a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
   a.part = ws_ptr<float>(ws, gp.off_part);
   a.rs = ws_ptr<float>(ws, gp.off_rs);

@@ -54,12 +54,12 @@ __global__ __launch_bounds__(256) void weight_prep_kernel(const void *__restrict
 // compact_kernel: grid (n_kblocks, B*H); one workgroup builds one 32-key block of both fragment arrays.
 //   ks_frag[bh][kb][ks][lane]          = K[token(32kb + r)][16ks + 8g .. +7]
 //   vs_frag[bh][kb][rb][s][lane][t]    = V[token(32kb + crow(8s + t, g))][32rb + r]
-// token(key) = key * R; keys >= NS are zero padding.
+// token(key) = key * R, or with groups of G tokens (key / G) R G + key % G; keys >= NS are zero padding.
 template <int D, bool F32>
 __global__ __launch_bounds__(256) void compact_kernel(const void *__restrict__ k, const void *__restrict__ v,
                                                       bf16x8 *__restrict__ ks_frag, bf16x8 *__restrict__ vs_frag,
-                                                      int H, int NS, int R, int n_kblocks, int64_t sb, int64_t sh,
-                                                      int64_t sn) {
+                                                      int H, int NS, int R, int G, int n_kblocks, int64_t sb,
+                                                      int64_t sh, int64_t sn) {
   constexpr int CPR = D / 8;            // 16-byte chunks per row
   constexpr int FRAG = D * 4;           // bf16x8 per 32-key block (= D*32*2/16)
   __shared__ __align__(16) __bf16 vt[32][D + 8];
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const void *__restrict__ k
     const int key = kb * 32 + r;
     bf16x8 kv = {0, 0, 0, 0, 0, 0, 0, 0}, vv = kv;
     if (key < NS) {
-      const int64_t off = base + (int64_t)key * R * sn + c8 * 8;
+      const int64_t off = base + (int64_t)(G == 1 ? key * R : (key / G) * R * G + key % G) * sn + c8 * 8;
       kv = load8<F32>(k, off);
       vv = load8<F32>(v, off);
     }
@@ -110,7 +110,7 @@ template <int D, int HD, int F, bool F32, bool WEIGHTED = false>
 __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ k, const void *__restrict__ v,
                                                        const bf16x8 *w1f_all, const bf16x8 *w2f_all,
                                                        const float *__restrict__ b1_all, const float *__restrict__ b2_all,
-                                                       float *__restrict__ part, int H, int NL, int R, int CH, int P,
+                                                       float *__restrict__ part, int H, int NL, int R, int G, int CH, int P,
                                                        int act, int64_t sb, int64_t sh, int64_t sn,
                                                        const float *__restrict__ rs_all = nullptr,
                                                        const float *__restrict__ wp_all = nullptr) {
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   const float *b1 = &blds[0];
   const float *b2 = &blds[HD];
   const int Dp = F / P;
-  const LinearMap lmap(R);
+  const LinearMap lmap(R, G);
 
   // wave w < GW owns row blocks fb = w*RPW .. + RPW - 1 of [S | z] with all NCB column blocks each
   // (tile = fb * NCB + cb), so every A fragment read from LDS feeds NCB products
@@ -409,7 +409,7 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, void *ws
   dim3 grid(pl.n_kblocks, pl.B * pl.H);
   bf16x8 *ksf = ws_ptr<bf16x8>(ws, pl.off_ks), *vsf = ws_ptr<bf16x8>(ws, pl.off_vs);
 #define HA_COMPACT(DD, FF) \
-  compact_kernel<DD, FF><<<grid, 256, 0, st>>>(k, v, ksf, vsf, pl.H, pl.NS, pl.R, pl.n_kblocks, pl.sb, pl.sh, pl.sn)
+  compact_kernel<DD, FF><<<grid, 256, 0, st>>>(k, v, ksf, vsf, pl.H, pl.NS, pl.R, pl.G, pl.n_kblocks, pl.sb, pl.sh, pl.sn)
   if (pl.D == 64) { if (pl.f32) HA_COMPACT(64, true); else HA_COMPACT(64, false); }
   else { if (pl.f32) HA_COMPACT(128, true); else HA_COMPACT(128, false); }
 #undef HA_COMPACT
@@ -422,7 +422,7 @@ hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_f
   const bf16x8 *w1f = ws_ptr<bf16x8>(ws, pl.off_w1k), *w2f = ws_ptr<bf16x8>(ws, pl.off_w2k);
   float *part = ws_ptr<float>(ws, pl.off_part);
 #define HA_STATE(DD, HH, FF, F32) \
-  state_kernel<DD, HH, FF, F32><<<grid, 256, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.CH, \
+  state_kernel<DD, HH, FF, F32><<<grid, 256, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.G, pl.CH, \
                                                      pl.P, pl.act_k, pl.sb, pl.sh, pl.sn)
   if (pl.D == 64) { if (pl.f32) HA_STATE(64, 64, 64, true); else HA_STATE(64, 64, 64, false); }
   else if (pl.HD == 128) { if (pl.f32) HA_STATE(128, 128, 128, true); else HA_STATE(128, 128, 128, false); }
@@ -438,7 +438,7 @@ hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsig
   dim3 grid(n_chunks, pl.B * pl.H);
   const bf16x8 *w1f = static_cast<const bf16x8 *>(w1f_), *w2f = static_cast<const bf16x8 *>(w2f_);
 #define HA_WSTATE(DD, F32) \
-  state_kernel<DD, DD, DD, F32, true><<<grid, 256, 0, st>>>(q, gsign, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.N, 0, CH, pl.P, \
+  state_kernel<DD, DD, DD, F32, true><<<grid, 256, 0, st>>>(q, gsign, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.N, 0, 1, CH, pl.P, \
                                                             pl.act_q, pl.sb, pl.sh, pl.sn, rs, wp)
   if (pl.D == 64) { if (pl.f32) HA_WSTATE(64, true); else HA_WSTATE(64, false); }
   else { if (pl.f32) HA_WSTATE(128, true); else HA_WSTATE(128, false); }

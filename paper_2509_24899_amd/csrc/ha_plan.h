@@ -11,6 +11,7 @@ namespace ha {
 struct Plan {
   // problem
   int B, H, N, D, HD, F, R, NS, NL, P, act_q, act_k;
+  int G;                 // granularity of the token split (1: per token, Sec. 3.2)
   int DM;   // width of the second hidden layer of a three-layer feature map, 0 for two layers
   bool f32;
   int64_t sb, sh, sn;

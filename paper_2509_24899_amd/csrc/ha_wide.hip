@@ -29,7 +29,7 @@ struct WideArgs {
   bf16x8 *out_hi, *out_lo;       // hidden layers
   f32x4 *out_u;                  // last layer
   float *out_stat;               // last layer: [bh][tb][256-channel block][2][64] running maximum and sum of exponentials
-  int H, K, NOUT, n_tok, n_tb, R;
+  int H, K, NOUT, n_tok, n_tb, R, G;
   int64_t sb, sh, sn;
 };
 
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void wide_layer1_kernel(WideArgs a) {
   const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tb >= a.n_tb) return;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
-  const LinearMap lmap(a.R);
+  const LinearMap lmap(a.R, a.G);
   const int tok = lmap.token(min(32 * tb + r, a.n_tok - 1));
   bf16x8 xf[KS];
 #pragma unroll
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void wide_phi_finish_kernel(const f32x4 *__res
 // (part[bh][chunk][row block * NCB + column block][v][lane]), so state_reduce_kernel serves both.
 template <int D, bool F32>
 __global__ __launch_bounds__(256, 1) void wide_state_kernel(const bf16x8 *__restrict__ phi, const void *__restrict__ v,
-                                                            float *__restrict__ part, int H, int NL, int R, int CH,
+                                                            float *__restrict__ part, int H, int NL, int R, int G, int CH,
                                                             int F, int n_tb, int64_t sb, int64_t sh, int64_t sn) {
   constexpr int TOK = 128, PITCH = TOK + 8, NCB = D / 32 + 1;
   constexpr int CG = D / 32, VPT = (TOK / 16) * CG / 4;
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(256, 1) void wide_state_kernel(const bf16x8 *__rest
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int FB = F / 32;
-  const LinearMap lmap(R);
+  const LinearMap lmap(R, G);
   f32x16 acc[NCB];
 #pragma unroll
   for (int i = 0; i < NCB; ++i)
@@ -494,7 +494,7 @@ hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, co
   }
   WideArgs a;
   a.x = x;
-  a.H = pl.H; a.n_tok = n_tok; a.n_tb = n_tb; a.R = is_query ? 0 : pl.R;
+  a.H = pl.H; a.n_tok = n_tok; a.n_tb = n_tb; a.R = is_query ? 0 : pl.R; a.G = pl.G;
   a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
   a.in_hi = a.in_lo = nullptr;
   a.out_u = nullptr;
@@ -555,10 +555,10 @@ hipError_t launch_wide_key_side(const Plan &pl, const WidePlan &wp, const void *
   dim3 grid(pl.n_chunks, pl.B * pl.H, pl.F / 128);
   if (pl.f32)
     wide_state_kernel<128, true><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), v, ws_ptr<float>(ws, pl.off_part), pl.H,
-                                                       pl.NL, pl.R, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
+                                                       pl.NL, pl.R, pl.G, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
   else
     wide_state_kernel<128, false><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), v, ws_ptr<float>(ws, pl.off_part), pl.H,
-                                                        pl.NL, pl.R, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
+                                                        pl.NL, pl.R, pl.G, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return launch_state_reduce(pl, ws, st);
 }

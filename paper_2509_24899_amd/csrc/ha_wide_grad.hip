@@ -46,7 +46,7 @@ struct WideGradArgs {
   f32x4 *tdt_img;                 // out: t dt (softmax), dt t (exp), dt [u > 0] (relu)
   const float *stat;              // softmax maxima / sums per 256-channel block (last layer of the forward)
   float *pdot;                    // [bh][tb][blocks][64]: per-token sum of t dt over the block's channels
-  int H, N, F, n_tok, n_tb, R, P, act;
+  int H, N, F, n_tok, n_tb, R, G, P, act;
   int64_t sb, sh, sn;
 };
 
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void wide_dphi_kernel(WideGradArgs a) {
   const int FB = a.F / 32, nblk = (a.F + 255) / 256;
   const int fb0 = blockIdx.y * NT, nt = min(NT, FB - fb0);
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
-  const LinearMap lmap(QUERY ? 0 : a.R);
+  const LinearMap lmap(QUERY ? 0 : a.R, a.G);
   const bool valid = 32 * tb + r < a.n_tok;
   const int tok = lmap.token(min(32 * tb + r, a.n_tok - 1));
   bf16x8 uf[KS];
@@ -257,7 +257,7 @@ struct ContractArgs {
   const void *b_rows;        // BSRC 1 (io dtype, strided) / 2 (bf16 dense [B*H][N][D])
   const float *wcol;         // or null
   float *part;
-  int H, N, WA, WB, n_tok, n_tb, R, CH;
+  int H, N, WA, WB, n_tok, n_tb, R, G, CH;
   int64_t sb, sh, sn;
 };
 
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256, 1) void wide_contract_kernel(ContractArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int AB = a.WA / 32, BB = a.WB / 32;
-  const LinearMap lmap(BSRC == 1 ? a.R : 0);
+  const LinearMap lmap(BSRC == 1 ? a.R : 0, a.G);
   f32x16 acc[NCB];
 #pragma unroll
   for (int i = 0; i < NCB; ++i)
@@ -516,7 +516,7 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
     a.zvec = is_query ? ws_ptr<float>(ws, pl.off_z) : ws_ptr<float>(ws, gp.off_dz);
     a.t_img = ws_ptr<f32x4>(ws, wp.off_u); a.tdt_img = ws_ptr<f32x4>(ws, gp.off_tdt);
     a.stat = ws_ptr<float>(ws, wp.off_stat); a.pdot = ws_ptr<float>(ws, gp.off_pdot);
-    a.H = pl.H; a.N = pl.N; a.F = F; a.n_tok = n_tok; a.n_tb = n_tb; a.R = pl.R; a.P = pl.P;
+    a.H = pl.H; a.N = pl.N; a.F = F; a.n_tok = n_tok; a.n_tb = n_tb; a.R = pl.R; a.G = pl.G; a.P = pl.P;
     a.act = is_query ? pl.act_q : pl.act_k;
     a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
     {
@@ -550,7 +550,7 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
     ContractArgs c;
     c.a_scale = nullptr; c.b_img = nullptr; c.b_rows = nullptr; c.wcol = nullptr;
     c.part = ws_ptr<float>(ws, gp.off_part);
-    c.H = pl.H; c.N = pl.N; c.n_tok = n_tok; c.n_tb = n_tb; c.R = is_query ? 0 : pl.R; c.CH = CH;
+    c.H = pl.H; c.N = pl.N; c.n_tok = n_tok; c.n_tb = n_tb; c.R = is_query ? 0 : pl.R; c.G = pl.G; c.CH = CH;
     c.sb = pl.sb; c.sh = pl.sh; c.sn = pl.sn;
     // [dW2 | db2] = sum du [h | 1]^T, h the input of the last layer
     c.a_img = ws_ptr<bf16x8>(ws, gp.off_du); c.WA = F;

@@ -37,7 +37,8 @@ class ha_problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d_head", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32), ("hybrid_rate", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float),
-                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+                ("split_granularity", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class HybridAttnError(RuntimeError):
@@ -142,13 +143,17 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise ValueError(f"unsupported dtype {t.dtype}: q, k, v must be bfloat16 or float32")
 
 
-def make_problem(q: torch.Tensor, hybrid_rate: int, block_size: int, softmax_scale: float) -> ha_problem:
-    """ha_problem for a [B, H, N, d] tensor view (any strides with a contiguous last dim)."""
+def make_problem(q: torch.Tensor, hybrid_rate, block_size: int, softmax_scale: float) -> ha_problem:
+    """ha_problem for a [B, H, N, d] tensor view (any strides with a contiguous last dim).  hybrid_rate: R, or a pair
+    (R, g) for the block-granular variant of the split (groups of g tokens, every R-th group softmax tokens)."""
+    granularity = 0
+    if isinstance(hybrid_rate, (tuple, list)):
+        hybrid_rate, granularity = hybrid_rate
     if q.dim() != 4 or q.stride(3) != 1:
         raise ValueError("q, k, v must be [B, H, N, d] views with a contiguous last dimension")
     B, H, N, d = q.shape
     return ha_problem(B, H, N, d, _dtype_code(q), block_size, hybrid_rate, softmax_scale,
-                      q.stride(0), q.stride(1), q.stride(2))
+                      q.stride(0), q.stride(1), q.stride(2), int(granularity), 0)
 
 
 def _fm_ptr(fm):

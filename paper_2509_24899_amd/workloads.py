@@ -35,10 +35,19 @@ class Workload:
     qk_gain: float = 1.0  # stress sets multiply q and k by this
     w_gain: float = 1.0   # stress sets multiply the MLP weights by this
     d_mid: int = 0        # width of the second hidden layer of a three-layer feature map (0: two layers)
+    split_granularity: int = 0   # > 1: the block-granular variant of the split (groups of this many tokens)
+
+    @property
+    def rate(self):
+        """What the binding takes as hybrid_rate: R, or (R, group size) for the block-granular variant."""
+        return (self.R, self.split_granularity) if self.split_granularity > 1 else self.R
 
     @property
     def n_softmax(self):
-        return 0 if self.R == 0 else -(-self.N // self.R)
+        if self.R == 0:
+            return 0
+        g = max(self.split_granularity, 1)
+        return (self.N // (self.R * g)) * g + min(self.N % (self.R * g), g)
 
     @property
     def n_linear(self):

@@ -21,9 +21,9 @@ def lib():
     return ha._lib()
 
 
-def _problem(B=1, H=12, N=32760, d=128, dtype=ha.HA_BF16, bs=128, R=4, scale=None, strides=None):
+def _problem(B=1, H=12, N=32760, d=128, dtype=ha.HA_BF16, bs=128, R=4, scale=None, strides=None, g=0, reserved=0):
     sb, sh, sn = strides if strides else (H * N * d, N * d, d)
-    return ha.ha_problem(B, H, N, d, dtype, bs, R, scale if scale is not None else d ** -0.5, sb, sh, sn)
+    return ha.ha_problem(B, H, N, d, dtype, bs, R, scale if scale is not None else d ** -0.5, sb, sh, sn, g, reserved)
 
 
 def _map(Hd=128, F=128, P=2, act=ha.HA_ACT_SOFTMAX, w1=FAKE, w2=FAKE + 0x100000, b1=None, b2=None):
@@ -37,12 +37,12 @@ def test_header_symbols_are_exported(lib):
     assert len(set(names)) == 16
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert ha.hybrid_attn_abi_version() == 4
+    assert ha.hybrid_attn_abi_version() == 5
 
 
 def test_struct_layout_matches_header():
     # 7 int32 + float, then three int64 at offset 32; four pointers, four int32, two pointers, two int32
-    assert ha.ha_problem.stride_b.offset == 32 and ctypes.sizeof(ha.ha_problem) == 56
+    assert ha.ha_problem.stride_b.offset == 32 and ctypes.sizeof(ha.ha_problem) == 64 and ha.ha_problem.split_granularity.offset == 56
     assert ha.ha_feature_map.d_hidden.offset == 32 and ha.ha_feature_map.w_mid.offset == 48 and ctypes.sizeof(ha.ha_feature_map) == 72
 
 
@@ -52,6 +52,14 @@ def test_valid_problems(lib):
     assert ha.hybrid_attn_validate(_problem(R=1), None, None) == ha.HA_OK           # full softmax needs no phi
     assert ha.hybrid_attn_validate(_problem(R=0), fm, fm) == ha.HA_OK
     assert ha.hybrid_attn_validate(_problem(R=3), fm, fm) == ha.HA_OK               # Fig. "method" uses rate 3
+    # block-granular variant of the split: any group size up to N; fewer softmax keys to stage when groups are cut short
+    assert ha.hybrid_attn_validate(_problem(g=128), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(g=32760), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(g=-1), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(g=32761), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(reserved=1), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(N=75600, R=75600, g=75600), fm, fm) == ha.HA_ERR_UNSUPPORTED    # R g beyond 2^30
+    assert ha.hybrid_attn_workspace_bytes(_problem(g=1), fm, fm) == ha.hybrid_attn_workspace_bytes(_problem(), fm, fm)
     fm64 = _map(64, 64)
     assert ha.hybrid_attn_validate(_problem(H=2, N=1024, d=64, dtype=ha.HA_F32, bs=64), fm64, fm64) == ha.HA_OK
     wide = _map(256, 256)
