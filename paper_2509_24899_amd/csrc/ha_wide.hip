@@ -466,10 +466,11 @@ void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp) {
   wp.total = off;
 }
 
-// One feature map over one token set: weight fragments, layer 1, (middle layer,) last layer, output stage.  is_query: all N tokens of q, and
-// phi.z is formed; otherwise the linear tokens of k.
+// One feature map over one token set: weight fragments, layer 1, (middle layer,) last layer, output stage (unless
+// finish is false: the backward pass forms phi itself).  is_query: all N tokens of q, and phi.z is formed; otherwise
+// the linear tokens of k.
 hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query,
-                           void *ws, hipStream_t st) {
+                           void *ws, hipStream_t st, bool finish) {
   const int BH = pl.B * pl.H;
   const int n_tok = is_query ? pl.N : pl.NL, n_tb = is_query ? wp.n_tb_q : wp.n_tb_k;
   hipError_t e;
@@ -531,7 +532,7 @@ hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, co
     wide_layer_kernel<true><<<grid, 256, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  {
+  if (finish) {
     dim3 grid((n_tb + 3) / 4, BH);
     if (is_query)
       wide_phi_finish_kernel<true><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat),

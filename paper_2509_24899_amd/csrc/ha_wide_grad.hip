@@ -4,9 +4,11 @@
 // images in HBM (layout: ha_wide.hip), per side (queries, then linear keys) right after that side's forward passes
 // have been re-run so that its hidden activations h, pre-activations u and phi are in the workspace:
 //
-//   wide_dphi_kernel        dphi = rs (M u) + wz zvec per 256-channel block; t = activation(u) replaces u in place,
-//                           t (dphi p t^(p-1)) goes to a second fp32 image, its per-token sum over the block aside
-//   wide_du_kernel          du = t dt - t (sum over all channels)   (softmax; the other activations have no sum) -> bf16
+//   wide_dphi_kernel        dphi = rs (M u) + wz zvec per 256-channel block, t = activation(u), phi_q = t^p for the dS
+//                           product, and du = t dt - t (sum over all channels of t dt) as a bf16 image; only a softmax
+//                           over more than 256 channels needs the sum from other workgroups: then t replaces u in place,
+//                           t dt goes to a second fp32 image, its per-token sum over the block aside, and
+//   wide_du_kernel          finishes du = t dt - t (sum over all blocks) -> bf16
 //   wide_back_layer_kernel  dpre = (W2^T du) [h > 0] -> bf16        (W2^T fragments staged through LDS)
 //   wide_contract_kernel    sum over tokens of  A^T [B | 1]  for  (du, h) -> dW2, db2;  (dpre, x) -> dW1, db1;
 //                           queries also (rs phi_q, [g | wp]) -> dS, dz.  A from an image, B from an image or from
@@ -46,13 +48,19 @@ struct WideGradArgs {
   f32x4 *tdt_img;                 // out: t dt (softmax), dt t (exp), dt [u > 0] (relu)
   const float *stat;              // softmax maxima / sums per 256-channel block (last layer of the forward)
   float *pdot;                    // [bh][tb][blocks][64]: per-token sum of t dt over the block's channels
+  bf16x8 *du_img;                 // FUSED: du, bf16 image
+  bf16x8 *phi_img;                // QUERY: phi_q, bf16 image (zero for tokens past the end)
   int H, N, F, n_tok, n_tb, R, G, P, act;
   int64_t sb, sh, sn;
 };
 
 // ------------------------------------------------------------------------------------------------
 // wide_dphi_kernel: grid (ceil(n_tb / 4), ceil(F / 256), B*H), one 32-token block per wave.
-template <int D, bool F32, bool QUERY>
+// FUSED (every case but a softmax over more than one 256-channel block): the sum of the softmax Jacobian is complete
+// inside the workgroup's block, so du is formed here (t dt of the eight tiles waits in registers for the sum, t is
+// recomputed from the pre-activations, which the wave has just read) and written as the bf16 image; the fp32 side
+// images and wide_du_kernel are not needed.  QUERY: phi_q = t^p is written as a bf16 image for the dS product.
+template <int D, bool F32, bool QUERY, bool FUSED>
 __global__ __launch_bounds__(256) void wide_dphi_kernel(WideGradArgs a) {
   constexpr int KS = D / 16, NT = 8;
   const int bh = blockIdx.z, h = bh % a.H;
@@ -89,8 +97,16 @@ __global__ __launch_bounds__(256) void wide_dphi_kernel(WideGradArgs a) {
   const GlobalFrags mhi = global_frags(a.m_hi + (int64_t)bh * ((int64_t)a.F * D / 8), a.F * D * 2);
   const GlobalFrags mlo = global_frags(a.m_lo + (int64_t)bh * ((int64_t)a.F * D / 8), a.F * D * 2);
   const float inv_groups = 8.0f * (float)a.P / (float)a.F;
+  auto activation = [&](float u) {
+    if (a.act == 0) return fast_exp2(__builtin_fmaf(u, kLog2e, off)) * inv;
+    if (a.act == 1) return fast_exp2(u * kLog2e);
+    return fmaxf(u, 0.f);
+  };
   float pdot = 0.f;
-  for (int j = 0; j < nt; ++j) {
+  f32x16 keep[FUSED ? NT : 1];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    if (j >= nt) break;
     const int fb = fb0 + j;
     f32x16 acc;
 #pragma unroll
@@ -107,6 +123,7 @@ __global__ __launch_bounds__(256) void wide_dphi_kernel(WideGradArgs a) {
       acc = mfma32(fh[ks], uf[ks], acc);
     }
     const int64_t img = (((int64_t)bh * a.n_tb + tb) * FB + fb) * 4;
+    f32x16 phi;
 #pragma unroll
     for (int x4 = 0; x4 < 4; ++x4) {
       const f32x4 uq = a.t_img[(img + x4) * 64 + lane];
@@ -116,10 +133,7 @@ __global__ __launch_bounds__(256) void wide_dphi_kernel(WideGradArgs a) {
       for (int i = 0; i < 4; ++i) {
         const int c = 32 * fb + crow(4 * x4 + i, g);
         const float dphi = rs_ * acc[4 * x4 + i] + wz_ * a.zvec[(int64_t)bh * a.F + c];
-        float t;
-        if (a.act == 0) t = fast_exp2(__builtin_fmaf(uq[i], kLog2e, off)) * inv;
-        else if (a.act == 1) t = fast_exp2(uq[i] * kLog2e);
-        else t = fmaxf(uq[i], 0.f);
+        const float t = activation(uq[i]);
         const float t2 = t * t;
         float pw = (extra & 1) ? t : 1.f;                                        // t^extra
         pw = (extra & 2) ? pw * t2 : pw;
@@ -131,14 +145,53 @@ __global__ __launch_bounds__(256) void wide_dphi_kernel(WideGradArgs a) {
         v = valid ? v : 0.f;
         tq[i] = t;
         dq[i] = v;
+        phi[4 * x4 + i] = valid ? pw * t : 0.f;
         pdot += v;
       }
-      a.t_img[(img + x4) * 64 + lane] = tq;
-      a.tdt_img[(img + x4) * 64 + lane] = dq;
+      if constexpr (FUSED) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) keep[j][4 * x4 + i] = dq[i];
+      } else {
+        a.t_img[(img + x4) * 64 + lane] = tq;
+        a.tdt_img[(img + x4) * 64 + lane] = dq;
+      }
+    }
+    if constexpr (QUERY) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        f32x8 o;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = phi[8 * s + i];
+        a.phi_img[(img / 4 * 2 + s) * 64 + lane] = __builtin_convertvector(o, bf16x8);
+      }
     }
   }
   pdot = xhalf_sum(pdot);
-  a.pdot[(((int64_t)bh * a.n_tb + tb) * nblk + blockIdx.y) * 64 + lane] = pdot;
+  if constexpr (!FUSED) {
+    a.pdot[(((int64_t)bh * a.n_tb + tb) * nblk + blockIdx.y) * 64 + lane] = pdot;
+  } else {
+    const float dot = a.act == 0 ? pdot : 0.f;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      if (j >= nt) break;
+      const int64_t img = (((int64_t)bh * a.n_tb + tb) * FB + fb0 + j) * 4;
+      if (a.act == 0) {
+#pragma unroll
+        for (int x4 = 0; x4 < 4; ++x4) {
+          const f32x4 uq = a.t_img[(img + x4) * 64 + lane];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) keep[j][4 * x4 + i] -= activation(uq[i]) * dot;
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        f32x8 o;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = keep[j][8 * s + i];
+        a.du_img[(img / 4 * 2 + s) * 64 + lane] = __builtin_convertvector(o, bf16x8);
+      }
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -493,8 +546,8 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
     const ha_feature_map_grad &gm = is_query ? gq : gk;
     const int n_tok = is_query ? pl.N : pl.NL, n_tb = is_query ? wp.n_tb_q : wp.n_tb_k;
     const int n_chunks = is_query ? gp.n_chunks_q : gp.n_chunks_k, CH = is_query ? gp.CHq : gp.CHk;
-    // this side's forward passes: h (hi + lo), pre-activations, softmax maxima / sums, phi
-    if ((e = launch_wide_map(pl, wp, is_query ? q : k, fm, is_query, ws, st)) != hipSuccess) return e;
+    // this side's forward passes: h (hi + lo), pre-activations, softmax maxima / sums (phi_q is formed below)
+    if ((e = launch_wide_map(pl, wp, is_query ? q : k, fm, is_query, ws, st, false)) != hipSuccess) return e;
     {
       dim3 grid((F * KL + 255) / 256, pl.H);
       if (pl.f32) wide_prep_t_kernel<true><<<grid, 256, 0, st>>>(fm.w2, ws_ptr<__bf16>(ws, gp.off_wt), F, KL);
@@ -516,22 +569,27 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
     a.zvec = is_query ? ws_ptr<float>(ws, pl.off_z) : ws_ptr<float>(ws, gp.off_dz);
     a.t_img = ws_ptr<f32x4>(ws, wp.off_u); a.tdt_img = ws_ptr<f32x4>(ws, gp.off_tdt);
     a.stat = ws_ptr<float>(ws, wp.off_stat); a.pdot = ws_ptr<float>(ws, gp.off_pdot);
+    a.du_img = ws_ptr<bf16x8>(ws, gp.off_du); a.phi_img = ws_ptr<bf16x8>(ws, wp.off_phi);
     a.H = pl.H; a.N = pl.N; a.F = F; a.n_tok = n_tok; a.n_tb = n_tb; a.R = pl.R; a.G = pl.G; a.P = pl.P;
     a.act = is_query ? pl.act_q : pl.act_k;
+    const bool fused = a.act != 0 || F <= 256;       // the softmax Jacobian's sum stays inside one workgroup
     a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
     {
       dim3 grid((n_tb + 3) / 4, (F + 255) / 256, BH);
-      if (is_query) {
-        if (pl.f32) wide_dphi_kernel<128, true, true><<<grid, 256, 0, st>>>(a);
-        else wide_dphi_kernel<128, false, true><<<grid, 256, 0, st>>>(a);
-      } else {
-        if (pl.f32) wide_dphi_kernel<128, true, false><<<grid, 256, 0, st>>>(a);
-        else wide_dphi_kernel<128, false, false><<<grid, 256, 0, st>>>(a);
+#define HA_DPHI(F32, QUERY)                                                      \
+  do {                                                                          \
+    if (fused) wide_dphi_kernel<128, F32, QUERY, true><<<grid, 256, 0, st>>>(a); \
+    else wide_dphi_kernel<128, F32, QUERY, false><<<grid, 256, 0, st>>>(a);      \
+  } while (0)
+      if (is_query) { if (pl.f32) HA_DPHI(true, true); else HA_DPHI(false, true); }
+      else { if (pl.f32) HA_DPHI(true, false); else HA_DPHI(false, false); }
+#undef HA_DPHI
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      if (!fused) {
+        dim3 grid2((n_tb + 3) / 4, BH);
+        wide_du_kernel<<<grid2, 256, 0, st>>>(a.t_img, a.tdt_img, a.pdot, ws_ptr<bf16x8>(ws, gp.off_du), F, n_tb, a.act);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
       }
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-      dim3 grid2((n_tb + 3) / 4, BH);
-      wide_du_kernel<<<grid2, 256, 0, st>>>(a.t_img, a.tdt_img, a.pdot, ws_ptr<bf16x8>(ws, gp.off_du), F, n_tb, a.act);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
       // back through the last layer (and the middle one): dpre = (W^T d) [h > 0]
       const bf16x8 *d_in = ws_ptr<bf16x8>(ws, gp.off_du);
       if (DM > 0) {
