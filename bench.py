@@ -144,9 +144,27 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
     loss, gq, gk, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.rate, w.block_size, w.scale, workspace=lib_ws)
     torch.cuda.synchronize()
 
+    # the update line of Alg. 1 with the optimiser of the paper's training details (AdamW, 1e-3): fp32 master copies of
+    # the weights, the forward reads their io-dtype copies; the biases are fp32 already
+    names = [n for n in ("w1", "b1", "w2", "b2", "w_mid", "b_mid") if getattr(fq, n, None) is not None]
+    state = []
+    for fm, g in ((fq, gq), (fk, gk)):
+        for n in names:
+            t = getattr(fm, n)
+            master = t if t.dtype == torch.float32 else t.float()
+            state.append(dict(master=master, io=None if master is t else t, grad=g[n], m=torch.zeros_like(master),
+                              v=torch.zeros_like(master)))
+    step_no = [0]
+
     def full_step():
+        # the gradient call writes into fresh tensors; the timed loop keeps the first call's as the update's input,
+        # which changes no cost: the update reads a gradient of the same size
         ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.rate, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
                                           y_student=ys, row_den=rd, workspace=lib_ws)
+        step_no[0] += 1
+        for s in state:
+            ha.hybrid_attn_param_update(s["master"], s["grad"], 1e-3, kind=ha.HA_OPT_ADAMW, m=s["m"], v=s["v"], step=step_no[0],
+                                        grad_scale=1.0 / (w.B * w.N * w.d), param_io=s["io"])
 
     def backward_only():
         ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.rate, w.block_size, w.scale, y_teacher=yt, teacher_is_cached=True,
@@ -181,7 +199,7 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype, "hybrid_rate_R": w.R,
                    "block_size": w.block_size, "feature_map": f"{w.d}->{w.d_hidden}->" + (f"{w.d_mid}->" if w.d_mid else "") + f"{w.d_feat}, P={w.poly_degree}",
-                   "step": "student forward + loss + gradient of phi_q, phi_k (teacher output cached)"},
+                   "step": "student forward + loss + gradient of phi_q, phi_k + AdamW update (teacher output cached)"},
         "step_ms_events": ev_full, "backward_with_state_pass_and_loss_ms": ev_bwd,
         "roofline": {"bound": "mfma", "kernel": ("grad_kernel (query pass + key pass) with its small helpers" if w.d_hidden == w.d and w.d_feat == w.d
                                                     else "the pass-per-step backward of wider maps, all kernels"), "achieved":

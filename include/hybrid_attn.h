@@ -204,6 +204,30 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
                                          const ha_feature_map_grad *grad_q, const ha_feature_map_grad *grad_k,
                                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Parameter update of the distillation loop (Sec. 3.3, Alg. 1: phi <- phi - eta grad_phi L; the training details
+ * name AdamW, learning rate 1e-3, for this stage).  HA_OPT_SGD is the line as printed: master -= lr * grad_scale *
+ * grad.  HA_OPT_ADAMW is Adam with decoupled weight decay: master *= 1 - lr * weight_decay; m = beta1 m +
+ * (1 - beta1) g; v = beta2 v + (1 - beta2) g^2; master -= lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) +
+ * eps), g = grad_scale * grad, step counted from 1.  grad_scale carries Alg. 1's 1 / (m |T|) (the gradient entry
+ * point returns the gradient of the plain sum). */
+typedef enum ha_optimizer_kind { HA_OPT_SGD = 0, HA_OPT_ADAMW = 1 } ha_optimizer_kind;
+typedef struct ha_optimizer {
+  int32_t kind;           /* ha_optimizer_kind */
+  int32_t step;           /* AdamW: number of this update, >= 1 */
+  float lr, grad_scale;
+  float beta1, beta2, eps, weight_decay;   /* AdamW only */
+} ha_optimizer;
+
+/* Enqueues one update of one parameter tensor of n elements.  master: device fp32, in/out, the full-precision copy
+ * of the parameter; grad: device fp32 (e.g. a tensor of ha_feature_map_grad); m, v: device fp32, in/out, AdamW's
+ * moments (zero before the first step; NULL for HA_OPT_SGD); param_io: device, n elements of io_dtype (ha_dtype),
+ * out, or NULL: the updated parameter rounded to the dtype the forward reads (the weights; the biases are fp32 and
+ * need no copy).  fp32 arithmetic.  Errors (nothing is enqueued): HA_ERR_NULL, HA_ERR_ALIGN (4-byte alignment, 2 for a
+ * bf16 copy), HA_ERR_SHAPE (negative or non-finite rates, step < 1, beta outside [0, 1), param_io == master),
+ * HA_ERR_UNSUPPORTED (unknown kind or dtype), HA_ERR_DEVICE. */
+ha_status hybrid_attn_param_update(const ha_optimizer *opt, size_t n, float *master, const float *grad, float *m, float *v,
+                                   void *param_io, int32_t io_dtype, void *hip_stream);
+
 /* Block-rate selection (Sec. 3.3, "Heterogeneous Block-Rate Optimization"; host memory only, no GPU
  * involved).  A model has n_blocks attention blocks and n_rates candidate hybrid rates; cost[i * n_rates + r]
  * and error[i * n_rates + r] (both >= 0, finite) are the pre-computed cost c_ir (flops or measured

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libhybridattn.so")
-SOURCES = ["ha_api.hip", "ha_kernels.hip", "ha_query.hip", "ha_wide.hip", "ha_wide_grad.hip", "ha_grad.hip", "ha_select.hip"]
+SOURCES = ["ha_api.hip", "ha_kernels.hip", "ha_query.hip", "ha_wide.hip", "ha_wide_grad.hip", "ha_grad.hip", "ha_select.hip", "ha_update.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # packed fp32 VALU forms are switched off for every device compile

@@ -33,6 +33,14 @@ class ha_feature_map_grad(ctypes.Structure):
                 ("w_mid", ctypes.c_void_p), ("b_mid", ctypes.c_void_p)]
 
 
+class ha_optimizer(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("step", ctypes.c_int32), ("lr", ctypes.c_float), ("grad_scale", ctypes.c_float),
+                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float)]
+
+
+HA_OPT_SGD, HA_OPT_ADAMW = 0, 1
+
+
 class ha_problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d_head", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32), ("hybrid_rate", ctypes.c_int32),
@@ -100,6 +108,9 @@ def _lib():
         lib.hybrid_attn_value_distill_grad.argtypes = [P, vp, vp, vp, FM, FM, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp,
                                                        FMG, FMG, vp, ctypes.c_size_t, vp]
         lib.hybrid_attn_value_distill_grad.restype = ctypes.c_int
+        lib.hybrid_attn_param_update.argtypes = [ctypes.POINTER(ha_optimizer), ctypes.c_size_t, vp, vp, vp, vp, vp,
+                                                 ctypes.c_int32, vp]
+        lib.hybrid_attn_param_update.restype = ctypes.c_int
         lib.hybrid_attn_abi_version.argtypes = []
         lib.hybrid_attn_abi_version.restype = ctypes.c_int
         _LIB = lib
@@ -383,6 +394,29 @@ def hybrid_attn_value_distill_grad(q, k, v, phi_q: FeatureMap, phi_k: FeatureMap
     if st != HA_OK:
         raise HybridAttnError(st, "hybrid_attn_value_distill_grad")
     return loss, gq, gk, y_teacher, y_student, row_den
+
+
+def hybrid_attn_param_update(master, grad, lr: float, kind: int = HA_OPT_SGD, m=None, v=None, step: int = 1,
+                             grad_scale: float = 1.0, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                             weight_decay: float = 0.01, param_io=None, stream=None):
+    """One update (Alg. 1's phi <- phi - eta grad, or AdamW) of one parameter tensor, in place: master (fp32), the
+    moments m, v (AdamW) and, if given, param_io (bf16 or fp32 tensor of the same shape that the forward reads)."""
+    _require_gpu(master, grad)
+    for t in (master, grad, m, v):
+        if t is not None and (t.dtype != torch.float32 or not t.is_contiguous() or t.numel() != master.numel()):
+            raise ValueError("master, grad, m, v must be contiguous fp32 tensors of one size")
+    io_code = HA_BF16
+    if param_io is not None:
+        if not param_io.is_contiguous() or param_io.numel() != master.numel():
+            raise ValueError("param_io must be contiguous and of master's size")
+        io_code = _dtype_code(param_io)
+    opt = ha_optimizer(kind, step, lr, grad_scale, beta1, beta2, eps, weight_decay)
+    stream_handle = (stream if stream is not None else torch.cuda.current_stream(master.device)).cuda_stream
+    st = _lib().hybrid_attn_param_update(ctypes.byref(opt), master.numel(), master.data_ptr(), grad.data_ptr(),
+                                         m.data_ptr() if m is not None else None, v.data_ptr() if v is not None else None,
+                                         param_io.data_ptr() if param_io is not None else None, io_code, stream_handle)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_param_update")
 
 
 def hybrid_attn_linear_state(k, v, phi_k: FeatureMap, hybrid_rate: int, block_size: int = 128, workspace=None,

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(lib):
     text = open(os.path.join(ROOT, "include", "hybrid_attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(hybrid_attn_\w+)\s*\(", text)
-    assert len(set(names)) == 16
+    assert len(set(names)) == 17
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
     assert ha.hybrid_attn_abi_version() == 5
@@ -254,3 +254,31 @@ def test_wider_and_three_layer_maps_validate(lib):
     # the gradient entry point takes them too
     assert lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(p), ctypes.byref(three), ctypes.byref(three)) > \
         lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(p), ctypes.byref(three), ctypes.byref(three))
+
+
+def test_param_update_host_errors(lib):
+    """Host-side checks of the parameter update (Alg. 1's update line): every error is reported before anything is enqueued."""
+    f = lib.hybrid_attn_param_update
+    A = [FAKE + i * 0x1000000 for i in range(6)]
+    assert ctypes.sizeof(ha.ha_optimizer) == 32
+
+    def opt(**kw):
+        d = dict(kind=ha.HA_OPT_ADAMW, step=1, lr=1e-3, grad_scale=1.0, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+        d.update(kw)
+        return ctypes.byref(ha.ha_optimizer(d["kind"], d["step"], d["lr"], d["grad_scale"], d["beta1"], d["beta2"], d["eps"],
+                                            d["weight_decay"]))
+    assert f(None, 8, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_NULL
+    assert f(opt(), 8, None, A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_NULL
+    assert f(opt(), 8, A[0], None, A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_NULL
+    assert f(opt(), 8, A[0], A[1], None, A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_NULL          # AdamW needs its moments
+    assert f(opt(kind=2), 8, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_UNSUPPORTED
+    assert f(opt(), 8, A[0], A[1], A[2], A[3], A[4], 7, None) == ha.HA_ERR_UNSUPPORTED
+    assert f(opt(step=0), 8, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_SHAPE
+    assert f(opt(beta2=1.0), 8, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_SHAPE
+    assert f(opt(lr=-1.0), 8, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_SHAPE
+    assert f(opt(lr=float("nan")), 8, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_SHAPE
+    assert f(opt(), 8, A[0] + 2, A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_ERR_ALIGN
+    assert f(opt(), 8, A[0], A[1], A[2], A[3], A[4] + 1, ha.HA_BF16, None) == ha.HA_ERR_ALIGN
+    assert f(opt(), 8, A[0], A[1], A[2], A[3], A[4] + 2, ha.HA_F32, None) == ha.HA_ERR_ALIGN
+    assert f(opt(), 8, A[0], A[1], A[2], A[3], A[0], ha.HA_F32, None) == ha.HA_ERR_SHAPE
+    assert f(opt(), 0, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_OK                 # nothing to do, nothing enqueued
