@@ -32,6 +32,11 @@ Variant (not the paper's method, which Sec. 3.2 states per token): `BlockSplit(R
 R makes whole blocks of `block` consecutive tokens softmax tokens, every R-th block, the other reading of a
 "block rate"; everything downstream of the split is unchanged.
 
+Second variant (the paper names causal attention as future work and defines none): `hybrid_attn_chunk_causal`
+cuts the sequence into chunks of `chunk` consecutive tokens; a query sees the keys of its own and of all earlier
+chunks, softmax tokens and linear tokens alike, so S and z become prefix sums over chunks.  It is written as the
+pinned non-causal function applied to every prefix of the sequence.
+
 All arithmetic is float64; nothing is rounded inside.  Inputs are whatever the caller hands in
 (already rounded to the io dtype of the GPU path and widened).
 
@@ -206,6 +211,28 @@ def hybrid_attn(q, k, v, phi_q, phi_k, R, scale, rows=None):
     for b in range(B):
         for h in range(H):
             y[b, h] = hybrid_attn_head(q[b, h], k[b, h], v[b, h], phi_q, phi_k, h, R, scale, rows)
+    return y
+
+
+def hybrid_attn_chunk_causal(q, k, v, phi_q, phi_k, R, scale, chunk: int, rows=None):
+    """Chunk-causal variant of Eq. "hybrid" for q, k, v [B, H, N, d]: query i attends to the tokens j with
+    j // chunk <= i // chunk; among those the split into softmax and linear tokens is the usual one (position in the
+    whole sequence decides).  For the queries of chunk c this is Eq. "hybrid" on the first (c + 1) chunk tokens, and
+    that is how it is computed.  `rows` (optional, sorted 1-D indices) restricts the output to those queries."""
+    if chunk < 1:
+        raise ValueError("chunk must be >= 1")
+    B, H, N, d = q.shape
+    sel = np.arange(N) if rows is None else np.asarray(rows)
+    y = np.empty((B, H, sel.size, d))
+    for c in range(-(-N // chunk)):
+        end = min((c + 1) * chunk, N)
+        pos = np.nonzero((sel >= c * chunk) & (sel < end))[0]
+        if pos.size == 0:
+            continue
+        for b in range(B):
+            for h in range(H):
+                y[b, h, pos] = hybrid_attn_head(q[b, h, :end], k[b, h, :end], v[b, h, :end], phi_q, phi_k, h, R, scale,
+                                                rows=sel[pos])
     return y
 
 

@@ -245,9 +245,45 @@ def pin_block_granular_split(M):
             np.testing.assert_allclose(y[0, h], ref, rtol=1e-11, atol=1e-13)
 
 
+def pin_chunk_causal(M):
+    """The chunk-causal variant against an N x N weight matrix built entry by entry with the visibility rule written
+    as a mask (own loops, own split rule), against library causal softmax attention at R = 1 with chunks of one
+    token, and its reductions: one chunk covering everything is Eq. "hybrid"; the last chunk's rows equal Eq. "hybrid"
+    on the whole sequence; the first chunk's rows equal Eq. "hybrid" on the first chunk alone."""
+    rng = np.random.default_rng(15)
+    H, N, d, F = 2, 23, 4, 6
+    q, k, v = (rng.standard_normal((1, H, N, d)) * 1.2 for _ in range(3))
+    fq, fk = _rand_map(rng, H, d, 5, F, 2, mod=M), _rand_map(rng, H, d, 5, F, 2, mod=M)
+    for R, C in ((3, 5), (2, 8), (4, 4), (0, 6), (1, 7)):
+        y = M.hybrid_attn_chunk_causal(q, k, v, fq, fk, R, 0.6, C)
+        for h in range(H):
+            gq, gk = M.feature_map(q[0, h], fq, h), M.feature_map(k[0, h], fk, h)
+            for i in range(N):
+                vis = [j for j in range(N) if j // C <= i // C]
+                soft = [j for j in vis if R >= 1 and j % R == 0]
+                c = max((0.6 * float(q[0, h, i] @ k[0, h, j]) for j in soft), default=0.0)
+                num, den = np.zeros(d), 0.0
+                for j in vis:
+                    w = np.exp(0.6 * float(q[0, h, i] @ k[0, h, j]) - c) if j in soft else float(gq[i] @ gk[j])
+                    num += w * v[0, h, j]
+                    den += w
+                np.testing.assert_allclose(y[0, h, i], num / den, rtol=1e-10, atol=1e-13)
+    y1 = M.hybrid_attn_chunk_causal(q, k, v, None, None, 1, 0.6, 1)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q), torch.from_numpy(k), torch.from_numpy(v),
+                                                           is_causal=True, scale=0.6).numpy()
+    np.testing.assert_allclose(y1, ref, rtol=1e-10, atol=1e-13)
+    full = M.hybrid_attn(q, k, v, fq, fk, 3, 0.6)
+    np.testing.assert_allclose(M.hybrid_attn_chunk_causal(q, k, v, fq, fk, 3, 0.6, N), full, rtol=1e-13)
+    yc = M.hybrid_attn_chunk_causal(q, k, v, fq, fk, 3, 0.6, 6)
+    np.testing.assert_allclose(yc[:, :, 18:], full[:, :, 18:], rtol=1e-13)
+    np.testing.assert_allclose(yc[:, :, :6], M.hybrid_attn(q[:, :, :6], k[:, :, :6], v[:, :, :6], fq, fk, 3, 0.6), rtol=1e-13)
+    rows = np.array([0, 5, 6, 17, 22])
+    np.testing.assert_allclose(M.hybrid_attn_chunk_causal(q, k, v, fq, fk, 3, 0.6, 6, rows=rows), yc[:, :, rows], rtol=1e-13)
+
+
 PINS = [pin_r1_is_library_softmax_attention, pin_feature_map_is_grouped_conv, pin_two_token_golden,
         pin_constant_phi_closed_form, pin_r0_is_linear_attention_nxn, pin_dense_loops, pin_invariants,
-        pin_split_rule, pin_block_granular_split]
+        pin_split_rule, pin_block_granular_split, pin_chunk_causal]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
@@ -297,6 +333,21 @@ def _mut_block_split_counts_tokens_not_blocks(mp):
         is_s = (idx % (R.R * R.block)) == 0 if R.R else np.zeros(N, bool)
         return idx[is_s], idx[~is_s]
     mp.setattr(O, "token_split", bad)
+
+
+def _mut_causal_per_token(mp):
+    """Token-causal instead of chunk-causal: a query sees only the tokens up to itself inside its own chunk."""
+    def bad(q, k, v, phi_q, phi_k, R, scale, chunk, rows=None):
+        B, H, N, d = q.shape
+        sel = np.arange(N) if rows is None else np.asarray(rows)
+        y = np.empty((B, H, sel.size, d))
+        for n, i in enumerate(sel):
+            for b in range(B):
+                for h in range(H):
+                    y[b, h, n] = O.hybrid_attn_head(q[b, h, :i + 1], k[b, h, :i + 1], v[b, h, :i + 1], phi_q, phi_k, h, R, scale,
+                                                    rows=[i])[0]
+        return y
+    mp.setattr(O, "hybrid_attn_chunk_causal", bad)
 
 
 def _mut_softmax_per_slice(mp):
@@ -389,7 +440,7 @@ def _mut_phi_sees_scaled_input(mp):
     mp.setattr(O, "feature_map", lambda x, fm, head: good(np.asarray(x) * 0.5, fm, head))
 
 
-MUTATIONS = [_mut_split_off_by_one, _mut_block_split_counts_tokens_not_blocks, _mut_softmax_per_slice, _mut_no_powers, _mut_powers_from_zero, _mut_no_relu,
+MUTATIONS = [_mut_split_off_by_one, _mut_block_split_counts_tokens_not_blocks, _mut_causal_per_token, _mut_softmax_per_slice, _mut_no_powers, _mut_powers_from_zero, _mut_no_relu,
              _mut_no_scale, _mut_unstabilised, _mut_max_over_all_tokens, _mut_drop_z, _mut_state_over_all_tokens,
              _mut_phi_sees_scaled_input]
 
