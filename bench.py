@@ -28,7 +28,11 @@ def cpu_baseline(w, heads=12):
     fq = O.FeatureMap(inp.phi_q.w1, inp.phi_q.b1, inp.phi_q.w2, inp.phi_q.b2, w.poly_degree)
     fk = O.FeatureMap(inp.phi_k.w1, inp.phi_k.b1, inp.phi_k.w2, inp.phi_k.b2, w.poly_degree)
     t0 = time.perf_counter()
-    O.hybrid_attn(inp.q, inp.k, inp.v, fq, fk, O.BlockSplit(w.R, w.split_granularity) if w.split_granularity > 1 else w.R, w.scale)
+    split = O.BlockSplit(w.R, w.split_granularity) if w.split_granularity > 1 else w.R
+    if 0 < w.causal_chunk < w.N:
+        O.hybrid_attn_chunk_causal(inp.q, inp.k, inp.v, fq, fk, split, w.scale, w.causal_chunk)
+    else:
+        O.hybrid_attn(inp.q, inp.k, inp.v, fq, fk, split, w.scale)
     t_sample = time.perf_counter() - t0
     t_full = t_sample * (w.B * w.H) / heads
     try:
@@ -226,6 +230,8 @@ def main():
                     help="MLP depth of both feature maps; 3 adds a hidden layer of the same width (Tab. phi, P = 6 row)")
     ap.add_argument("--split-granularity", type=int, default=0, metavar="G",
                     help="variant of the token split: groups of G consecutive tokens, every R-th group softmax tokens")
+    ap.add_argument("--causal-chunk", type=int, default=0, metavar="C",
+                    help="chunk-causal variant: a query sees its own and all earlier chunks of C tokens (multiple of 2 * block size)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
@@ -268,6 +274,8 @@ def main():
         w = W.replace(w, d_mid=w.d_hidden)
     if args.split_granularity > 1:
         w = W.replace(w, split_granularity=args.split_granularity)
+    if args.causal_chunk > 0:
+        w = W.replace(w, causal_chunk=args.causal_chunk)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
@@ -367,7 +375,11 @@ def main():
         # key-side feature map and state (4 N N_S d + phi_q MLP + g.S, g.z)
         layered = n_l > 0 and (w.d_mid or not ((w.d_hidden == w.d and w.d_feat == w.d) or (w.d_hidden == 256 and w.d_feat == 256)))
         # (maps that go layer by layer through HBM leave only the softmax loop and the merge to the query kernel)
-        k_flops = w.B * w.H * (4.0 * w.N * n_s * w.d + (2.0 * w.N * (w.d * w.d_hidden + w.d_hidden * w.d_feat)
+        softmax_flops = 4.0 * w.N * n_s * w.d
+        if 0 < w.causal_chunk < w.N:       # chunk-causal variant: the softmax keys up to the end of the query's chunk
+            C = w.causal_chunk
+            softmax_flops = 4.0 * w.d * sum((min(lo + C, w.N) - lo) * w.softmax_before(min(lo + C, w.N)) for lo in range(0, w.N, C))
+        k_flops = w.B * w.H * (softmax_flops + (2.0 * w.N * (w.d * w.d_hidden + w.d_hidden * w.d_feat)
                                                          + 2.0 * w.N * w.d_feat * w.d + 2.0 * w.N * w.d_feat
                                                          if n_l > 0 and not layered else 0.0))
         achieved = k_flops / (mean[3] * 1e-3) / 1e12
@@ -381,7 +393,7 @@ def main():
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (null when this
     # workload has not been profiled)
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d and w.split_granularity <= 1:   # profiled with the d -> d -> d maps
+    if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d and w.split_granularity <= 1 and not w.causal_chunk:   # profiled with the d -> d -> d maps
         t = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
         if t:
             roofline["traffic"] = t["read_bytes"] + t["written_bytes"]
@@ -397,6 +409,7 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype,
                    "hybrid_rate_R": w.R, "r": (1.0 / w.R if w.R else 0.0), "block_size": w.block_size,
                    **({"split_granularity": w.split_granularity} if w.split_granularity > 1 else {}),
+                   **({"causal_chunk": w.causal_chunk} if w.causal_chunk else {}),
                    "feature_map": (f"{w.d}->{w.d_hidden}->{w.d_mid}->{w.d_feat}" if w.d_mid else f"{w.d}->{w.d_hidden}->{w.d_feat}")
                    + f", P={w.poly_degree}"},
         "tflops": flops / (ms_per_step * 1e-3) / 1e12,

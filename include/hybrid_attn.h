@@ -95,7 +95,12 @@ typedef struct {
                              method): whole groups of g consecutive tokens are softmax tokens, every R-th
                              group: token j is a softmax token when (j / g) mod R == 0.  Any g <= N
                              with R g <= 2^30. */
-  int32_t reserved;       /* must be 0 */
+  int32_t causal_chunk;   /* 0: every query sees every token (the paper's operator).  C > 0 (a variant; the paper
+                             leaves causal attention to future work and defines none): chunks of C consecutive
+                             tokens, a query sees its own and all earlier chunks, so S and z are prefix sums over
+                             chunks.  C must be a multiple of 2 * block_size.  hybrid_attn_forward only, with maps
+                             the fused kernels take (d_hidden, d_out = d_head, or 256 at d_head = 128);
+                             HA_ERR_UNSUPPORTED elsewhere. */
 } ha_problem;
 
 /* Host-only argument check (no HIP call).  phi_q and phi_k may be NULL iff the problem has no

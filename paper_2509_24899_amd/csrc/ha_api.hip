@@ -49,7 +49,7 @@ static ha_status validate(const ha_problem *p, const ha_feature_map *phi_q, cons
   if (!p) return HA_ERR_NULL;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0 || p->d_head <= 0) return HA_ERR_SHAPE;
   if (p->hybrid_rate < 0 || p->hybrid_rate > p->N) return HA_ERR_SHAPE;
-  if (p->split_granularity < 0 || p->split_granularity > p->N || p->reserved != 0) return HA_ERR_SHAPE;
+  if (p->split_granularity < 0 || p->split_granularity > p->N || p->causal_chunk < 0) return HA_ERR_SHAPE;
   if ((int64_t)p->hybrid_rate * p->split_granularity > (int64_t)1 << 30) return HA_ERR_UNSUPPORTED;
   if (!(p->softmax_scale > 0.f) || !std::isfinite(p->softmax_scale)) return HA_ERR_SHAPE;
   if (p->dtype != HA_BF16 && p->dtype != HA_F32) return HA_ERR_UNSUPPORTED;
@@ -71,6 +71,14 @@ static ha_status validate(const ha_problem *p, const ha_feature_map *phi_q, cons
     if ((phi_q->w_mid != nullptr) != (phi_k->w_mid != nullptr)) return HA_ERR_SHAPE;
     if (phi_q->w_mid && phi_q->d_mid != phi_k->d_mid) return HA_ERR_SHAPE;
   }
+  if (p->causal_chunk > 0) {
+    if (p->causal_chunk % (2 * p->block_size)) return HA_ERR_UNSUPPORTED;      // whole query tiles per chunk
+    if (has_linear) {
+      const bool square = phi_q->d_hidden == p->d_head && phi_q->d_out == p->d_head;
+      const bool paper_width = p->d_head == 128 && phi_q->d_hidden == 256 && phi_q->d_out == 256;
+      if ((!square && !paper_width) || phi_q->w_mid) return HA_ERR_UNSUPPORTED;   // the layer-by-layer path has no prefix states
+    }
+  }
   return HA_OK;
 }
 
@@ -83,6 +91,9 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.G = p.split_granularity > 1 ? p.split_granularity : 1;
   // softmax tokens: the first G of every R G tokens
   pl.NS = pl.R == 0 ? 0 : (pl.N / (pl.R * pl.G)) * pl.G + (pl.N % (pl.R * pl.G) < pl.G ? pl.N % (pl.R * pl.G) : pl.G);
+  pl.CC = p.causal_chunk < p.N ? p.causal_chunk : 0;      // one chunk that covers everything is the plain operator
+  pl.n_cc = pl.CC > 0 ? (pl.N + pl.CC - 1) / pl.CC : 1;
+  pl.nsub = 1;
   pl.NL = pl.N - pl.NS;
   const bool has_linear = pl.NL > 0 && phi_q && phi_k;
   pl.HD = has_linear ? phi_k->d_hidden : pl.D;
@@ -105,6 +116,21 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
     pl.CH = ((tiles + want - 1) / want) * 128;
     if (pl.CH < 128) pl.CH = 128;
     pl.n_chunks = has_linear ? (pl.NL + pl.CH - 1) / pl.CH : 0;
+    if (pl.CC > 0 && has_linear) {
+      // chunk-causal: every causal chunk is a group of nsub state-pass workgroups of its own; CH from the most linear
+      // tokens a chunk can hold
+      int most = 0;
+      for (int c = 0; c < pl.n_cc; ++c) {
+        const int lo = c * pl.CC, hi = (c + 1) * pl.CC < pl.N ? (c + 1) * pl.CC : pl.N;
+        const int cnt = (hi - lo) - (softmax_before(hi, pl.R, pl.G) - softmax_before(lo, pl.R, pl.G));
+        most = cnt > most ? cnt : most;
+      }
+      const int tiles_c = (most + 127) / 128 > 0 ? (most + 127) / 128 : 1;
+      const int room = 256 / (pl.B * pl.H * pl.n_cc);
+      pl.nsub = room < 1 ? 1 : (room > tiles_c ? tiles_c : room);
+      pl.CH = ((tiles_c + pl.nsub - 1) / pl.nsub) * 128;
+      pl.n_chunks = pl.n_cc * pl.nsub;
+    }
   }
   pl.n_state_tiles = (pl.F / 32) * (pl.D / 32 + 1);
   const size_t BH = (size_t)pl.B * pl.H;
@@ -118,9 +144,9 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.off_vs = take(BH * pl.n_kblocks * 32 * pl.D * 2);
   pl.off_part = take(BH * pl.n_chunks * pl.n_state_tiles * 1024 * 4);
   pl.off_S = take(BH * pl.F * pl.D * 4);
-  pl.off_z = take(BH * pl.F * 4);
-  pl.off_sthi = take(BH * pl.F * pl.D * 2);
-  pl.off_stlo = take(BH * pl.F * pl.D * 2);
+  pl.off_z = take(BH * pl.n_cc * pl.F * 4);
+  pl.off_sthi = take(BH * pl.n_cc * pl.F * pl.D * 2);
+  pl.off_stlo = take(BH * pl.n_cc * pl.F * pl.D * 2);
   pl.total = off;
 }
 
@@ -264,6 +290,7 @@ ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const voi
   if (s != HA_OK) return s;
   if (!k || !v || !state_S || !state_z || !phi_k) return HA_ERR_NULL;
   if (p->hybrid_rate == 1) return HA_ERR_SHAPE;   // no linear tokens, no state
+  if (p->causal_chunk > 0) return HA_ERR_UNSUPPORTED;
   if (!ha::aligned16(k) || !ha::aligned16(v)) return HA_ERR_ALIGN;
   ha::Plan pl;
   ha::WidePlan wp;
@@ -330,6 +357,7 @@ ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, con
                                          void *workspace, size_t workspace_bytes, void *hip_stream) {
   ha_status s = ha::validate(p, phi_q, phi_k);
   if (s != HA_OK) return s;
+  if (p->causal_chunk > 0) return HA_ERR_UNSUPPORTED;      // the teacher of Eq. "vd_loss" is not causal
   if (!q || !k || !v || !y_teacher || !y_student || !loss) return HA_ERR_NULL;
   if (!ha::aligned16(y_teacher) || !ha::aligned16(y_student) || (reinterpret_cast<uintptr_t>(loss) & 7u)) return HA_ERR_ALIGN;
   if (y_teacher == y_student) return HA_ERR_SHAPE;
@@ -408,6 +436,7 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
                                          void *workspace, size_t workspace_bytes, void *hip_stream) {
   ha_status s = check_grad_maps(p, phi_q, phi_k);
   if (s != HA_OK) return s;
+  if (p->causal_chunk > 0) return HA_ERR_UNSUPPORTED;
   if (!q || !k || !v || !y_teacher || !y_student || !row_den || !loss || !grad_q || !grad_k) return HA_ERR_NULL;
   for (const ha_feature_map_grad *gm : {grad_q, grad_k}) {
     if (!gm->w1 || !gm->b1 || !gm->w2 || !gm->b2) return HA_ERR_NULL;

@@ -113,7 +113,8 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
                                                        float *__restrict__ part, int H, int NL, int R, int G, int CH, int P,
                                                        int act, int64_t sb, int64_t sh, int64_t sn,
                                                        const float *__restrict__ rs_all = nullptr,
-                                                       const float *__restrict__ wp_all = nullptr) {
+                                                       const float *__restrict__ wp_all = nullptr, int N = 0, int CC = 0,
+                                                       int nsub = 1) {
   constexpr int TOK = 128, PITCH = TOK + 8;
   constexpr int KS = D / 16, FB = F / 32, NCB = D / 32 + 1, NT = FB * NCB;
   constexpr int RPW = FB >= 4 ? FB / 4 : 1;   // row blocks of [S | z] per wave
@@ -193,8 +194,15 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
   __bf16 *ftp = WIDE ? reinterpret_cast<__bf16 *>(&raw[0]) : &ft_s[0][0];
   __bf16 *vtp = WIDE ? reinterpret_cast<__bf16 *>(&raw[0]) + F * PITCH : &vt_s[0][0];
 
-  const int lt_begin = chunk * CH;
-  const int lt_end = min(lt_begin + CH, NL);
+  // this workgroup's range of linear tokens: chunk number `chunk` of CH tokens, or (chunk-causal variant) piece
+  // chunk % nsub of the linear tokens of causal chunk chunk / nsub
+  int lt_begin = chunk * CH;
+  int lt_end = min(lt_begin + CH, NL);
+  if (CC > 0) {
+    const int cc = chunk / nsub, lo = cc * CC, hi = min(lo + CC, N);
+    lt_begin = lo - softmax_before(lo, R, G) + (chunk % nsub) * CH;
+    lt_end = min(lt_begin + CH, hi - softmax_before(hi, R, G));
+  }
   // rows past the end of T_L are clamped to the last linear token (valid memory) and masked later
   auto load_k = [&](int t0, bf16x8 (&dst)[KS]) {
     const int tok = lmap.token(min(t0 + tf, NL - 1));
@@ -270,8 +278,8 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
         load_v();
         __syncthreads();                                    // the weights have been read by every wave: the area becomes phi^T | V^T
       }
-      if (t0 + TOK > NL) {                                 // ragged end of T_L: padded tokens add nothing
-        const bool valid = t0 + tf < NL;
+      if (t0 + TOK > lt_end) {                             // ragged end of the range: padded tokens add nothing
+        const bool valid = t0 + tf < lt_end;
         const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb)
@@ -390,6 +398,39 @@ __global__ __launch_bounds__(256) void state_reduce_kernel(const float *__restri
 }
 
 // ------------------------------------------------------------------------------------------------
+// state_prefix_kernel (chunk-causal variant): grid as state_reduce_kernel.  Running sum of the chunk partials in
+// chunk order; after every nsub of them (one causal chunk) the sum so far is written as that chunk's z and S^T
+// fragments: st[bh][cc][...], z[bh][cc][F].  S (fp32) receives the total.
+__global__ __launch_bounds__(256) void state_prefix_kernel(const float *__restrict__ part, float *__restrict__ S,
+                                                           float *__restrict__ z, __bf16 *__restrict__ st_hi,
+                                                           __bf16 *__restrict__ st_lo, int D, int F, int n_cc, int nsub) {
+  const int NCB = D / 32 + 1, FB = F / 32, NT = FB * NCB;
+  const int bh = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= NT * 1024) return;
+  const int ti = e >> 10, x = (e >> 6) & 15, lane = e & 63, r = lane & 31, g = lane >> 5;
+  const int fb = ti / NCB, cb = ti % NCB;
+  const int ch = 32 * fb + crow(x, g);
+  const float *src = part + (int64_t)bh * n_cc * nsub * NT * 1024 + e;
+  float sum = 0.f;
+  for (int cc = 0; cc < n_cc; ++cc) {
+    for (int s = 0; s < nsub; ++s) sum += src[(int64_t)(cc * nsub + s) * NT * 1024];
+    const int64_t sbh = (int64_t)bh * n_cc + cc;
+    if (cb < D / 32) {
+      const __bf16 hi = static_cast<__bf16>(sum);
+      const __bf16 lo = static_cast<__bf16>(sum - static_cast<float>(hi));
+      const int c5 = ch & 31, s = c5 >> 4, w16 = c5 & 15, g2 = (w16 >> 2) & 1, t = 4 * (w16 >> 3) + (w16 & 3);
+      const int64_t idx = (((sbh * (D / 32) + cb) * FB + fb) * 2 + s) * 512 + (g2 * 32 + r) * 8 + t;
+      st_hi[idx] = hi;
+      st_lo[idx] = lo;
+    } else if (r == 0) {
+      z[sbh * F + ch] = sum;
+    }
+  }
+  if (cb < D / 32) S[((int64_t)bh * F + ch) * D + 32 * cb + r] = sum;
+}
+
+// ------------------------------------------------------------------------------------------------
 // host launchers
 
 template <typename T>
@@ -423,7 +464,7 @@ hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_f
   float *part = ws_ptr<float>(ws, pl.off_part);
 #define HA_STATE(DD, HH, FF, F32) \
   state_kernel<DD, HH, FF, F32><<<grid, 256, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.G, pl.CH, \
-                                                     pl.P, pl.act_k, pl.sb, pl.sh, pl.sn)
+                                                     pl.P, pl.act_k, pl.sb, pl.sh, pl.sn, nullptr, nullptr, pl.N, pl.CC, pl.nsub)
   if (pl.D == 64) { if (pl.f32) HA_STATE(64, 64, 64, true); else HA_STATE(64, 64, 64, false); }
   else if (pl.HD == 128) { if (pl.f32) HA_STATE(128, 128, 128, true); else HA_STATE(128, 128, 128, false); }
   else { if (pl.f32) HA_STATE(128, 256, 256, true); else HA_STATE(128, 256, 256, false); }
@@ -448,6 +489,12 @@ hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsig
 
 hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st) {
   dim3 grid(pl.n_state_tiles * 1024 / 256, pl.B * pl.H);
+  if (pl.CC > 0) {
+    state_prefix_kernel<<<grid, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_part), ws_ptr<float>(ws, pl.off_S),
+                                              ws_ptr<float>(ws, pl.off_z), ws_ptr<__bf16>(ws, pl.off_sthi),
+                                              ws_ptr<__bf16>(ws, pl.off_stlo), pl.D, pl.F, pl.n_cc, pl.nsub);
+    return hipGetLastError();
+  }
   state_reduce_kernel<<<grid, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_part), ws_ptr<float>(ws, pl.off_S),
                                             ws_ptr<float>(ws, pl.off_z), ws_ptr<__bf16>(ws, pl.off_sthi),
                                             ws_ptr<__bf16>(ws, pl.off_stlo), pl.D, pl.F, pl.n_chunks);

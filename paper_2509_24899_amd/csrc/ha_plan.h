@@ -12,6 +12,8 @@ struct Plan {
   // problem
   int B, H, N, D, HD, F, R, NS, NL, P, act_q, act_k;
   int G;                 // granularity of the token split (1: per token, Sec. 3.2)
+  int CC, n_cc, nsub;    // chunk-causal variant: chunk length in tokens (0: off), number of chunks, state-pass
+                         // workgroups per chunk
   int DM;   // width of the second hidden layer of a three-layer feature map, 0 for two layers
   bool f32;
   int64_t sb, sh, sn;
@@ -39,6 +41,13 @@ struct WidePlan {
   size_t off_w1, off_wm, off_w2;   // weight fragments of the map being evaluated (key side, then query side)
   size_t off_hhi, off_hlo, off_h2hi, off_h2lo, off_u, off_stat, off_phi, off_lin, off_e, total;
 };
+
+// Number of softmax tokens among the first t tokens: the first G of every R G tokens (Sec. 3.2 with G = 1).
+static __host__ __device__ inline int softmax_before(int t, int R, int G) {
+  if (R == 0) return 0;
+  const int grp = R * G, rem = t % grp;
+  return (t / grp) * G + (rem < G ? rem : G);
+}
 
 // Workspace of the value-distillation gradient of maps that take the layer-by-layer path (beyond WidePlan's).
 struct WideGradPlan {

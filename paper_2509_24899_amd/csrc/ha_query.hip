@@ -26,6 +26,7 @@ struct QueryArgs {
   const float *lin_e;                   // [B*H][N]
   int n_tb;
   int H, N, NS, n_qtiles, n_ktiles, n_kblocks, total_wg;
+  int CC, n_cc, R, G;                   // chunk-causal variant (CC > 0): chunk length, chunk count, the token split
   int has_linear, P, act;
   int64_t sb, sh, sn;
   float scale_log2e;
@@ -185,7 +186,8 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
 // is first read (as K(j+2)) at least one barrier after it was requested.
 // LIN: the linear part arrives precomputed (maps too wide for the epilogue below); a variant of its own so that
 // the usual kernel carries none of it.
-template <int D, int HD, int F, int NW, int NB, int G, bool F32, bool LIN = false>
+// CAUSAL: the chunk-causal variant, likewise a variant of its own.
+template <int D, int HD, int F, int NW, int NB, int G, bool F32, bool LIN = false, bool CAUSAL = false>
 __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   static_assert(G <= 2 && NB >= 2 * G + 2 && (NB & (NB - 1)) == 0, "ring too short for the barrier period");
   constexpr int KS = D / 16, RB = D / 32;
@@ -210,14 +212,32 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
                           NW1 % 64 == 0 && (NW2 / 2) % 64 == 0 && NST % 64 == 0 && (F / 32) % 2 == 0;
 
   const int per_xcd = (a.total_wg + 7) >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if constexpr (CAUSAL) logical = blockIdx.x;
   if (logical >= a.total_wg) return;
-  const int bh = logical / a.n_qtiles, qtile = logical % a.n_qtiles;
+  int bh = logical / a.n_qtiles, qtile = logical % a.n_qtiles;
+  if constexpr (CAUSAL) {
+    // the work of a tile grows with its position: the longest tiles of every (batch, head) are started first, and
+    // consecutive workgroups (which land on different XCDs) take tiles of the same length
+    const int n_bh = a.total_wg / a.n_qtiles;
+    bh = logical % n_bh;
+    qtile = a.n_qtiles - 1 - logical / n_bh;
+  }
   const int h = bh % a.H;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, kept scalar
   const int q0 = qtile * QT + w * 32;
+  if constexpr (CAUSAL) {
+    // chunk-causal variant: this tile lies inside causal chunk cc (chunks are whole query tiles); it sees the softmax
+    // keys of the first cc + 1 chunks, which lead the compacted arrays, and the prefix state of chunk cc
+    const int cc = (qtile * QT) / a.CC;
+    const int64_t shift = (int64_t)bh * (a.n_cc - 1) + cc;
+    a.NS = softmax_before(min((cc + 1) * a.CC, a.N), a.R, a.G);
+    a.z += shift * F;
+    a.st_hi += shift * (D * F / 8);
+    a.st_lo += shift * (D * F / 8);
+  }
   // n_chunks 1 KiB wave-chunks global -> LDS, dealt round-robin to the waves (direct-to-LDS loads, see below)
   auto stage_in = [&](const bf16x8 *gsrc, bf16x8 *ldst, int n_chunks) {
     const unsigned lane_off16 = lane * 16;
@@ -537,6 +557,7 @@ hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi
   a.st_lo = ws_ptr<bf16x8>(ws, pl.off_stlo);
   a.z = ws_ptr<float>(ws, pl.off_z);
   a.H = pl.H; a.N = pl.N; a.NS = pl.NS;
+  a.CC = pl.CC; a.n_cc = pl.n_cc; a.R = pl.R; a.G = pl.G;
   a.n_ktiles = pl.n_ktiles; a.n_kblocks = pl.n_kblocks;
   a.has_linear = pl.NL > 0; a.P = pl.P; a.act = pl.act_q;
   a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
@@ -549,8 +570,13 @@ hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi
   dim3 grid(((a.total_wg + 7) / 8) * 8);
 #define HA_QUERY(DD, HH, FF, F32) \
   do { \
-    if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32><<<grid, 512, 0, st>>>(a); \
-    else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \
+    if (pl.CC > 0) { \
+      if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32, false, true><<<grid, 512, 0, st>>>(a); \
+      else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32, false, true><<<grid, 256, 0, st>>>(a); \
+    } else { \
+      if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32><<<grid, 512, 0, st>>>(a); \
+      else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \
+    } \
   } while (0)
   if (wide) {
     if (big) {

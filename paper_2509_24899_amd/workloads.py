@@ -36,11 +36,21 @@ class Workload:
     w_gain: float = 1.0   # stress sets multiply the MLP weights by this
     d_mid: int = 0        # width of the second hidden layer of a three-layer feature map (0: two layers)
     split_granularity: int = 0   # > 1: the block-granular variant of the split (groups of this many tokens)
+    causal_chunk: int = 0        # > 0: the chunk-causal variant (chunks of this many tokens)
 
     @property
     def rate(self):
-        """What the binding takes as hybrid_rate: R, or (R, group size) for the block-granular variant."""
+        """What the binding takes as hybrid_rate: R, or (R, group size[, causal chunk]) for the variants."""
+        if self.causal_chunk > 0:
+            return (self.R, self.split_granularity, self.causal_chunk)
         return (self.R, self.split_granularity) if self.split_granularity > 1 else self.R
+
+    def softmax_before(self, t):
+        """Number of softmax tokens among the first t tokens."""
+        if self.R == 0:
+            return 0
+        g = max(self.split_granularity, 1)
+        return (t // (self.R * g)) * g + min(t % (self.R * g), g)
 
     @property
     def n_softmax(self):
@@ -152,6 +162,9 @@ def algorithmic_flops(w: Workload) -> float:
     exp, max, powers and the division are not counted; with no linear keys phi is skipped."""
     n_s, n_l, N, d, Hd, F = w.n_softmax, w.n_linear, w.N, w.d, w.d_hidden, w.d_feat
     per_head = 4.0 * N * n_s * d
+    if 0 < w.causal_chunk < N:       # chunk-causal variant: a query sees the softmax keys up to the end of its chunk
+        C = w.causal_chunk
+        per_head = 4.0 * d * sum((min(lo + C, N) - lo) * w.softmax_before(min(lo + C, N)) for lo in range(0, N, C))
     if n_l > 0:
         mlp = d * Hd + (Hd * w.d_mid + w.d_mid * F if w.d_mid else Hd * F)       # multiply-adds per token
         per_head += 2.0 * (N + n_l) * mlp

@@ -21,9 +21,9 @@ def lib():
     return ha._lib()
 
 
-def _problem(B=1, H=12, N=32760, d=128, dtype=ha.HA_BF16, bs=128, R=4, scale=None, strides=None, g=0, reserved=0):
+def _problem(B=1, H=12, N=32760, d=128, dtype=ha.HA_BF16, bs=128, R=4, scale=None, strides=None, g=0, causal=0):
     sb, sh, sn = strides if strides else (H * N * d, N * d, d)
-    return ha.ha_problem(B, H, N, d, dtype, bs, R, scale if scale is not None else d ** -0.5, sb, sh, sn, g, reserved)
+    return ha.ha_problem(B, H, N, d, dtype, bs, R, scale if scale is not None else d ** -0.5, sb, sh, sn, g, causal)
 
 
 def _map(Hd=128, F=128, P=2, act=ha.HA_ACT_SOFTMAX, w1=FAKE, w2=FAKE + 0x100000, b1=None, b2=None):
@@ -57,7 +57,18 @@ def test_valid_problems(lib):
     assert ha.hybrid_attn_validate(_problem(g=32760), fm, fm) == ha.HA_OK
     assert ha.hybrid_attn_validate(_problem(g=-1), fm, fm) == ha.HA_ERR_SHAPE
     assert ha.hybrid_attn_validate(_problem(g=32761), fm, fm) == ha.HA_ERR_SHAPE
-    assert ha.hybrid_attn_validate(_problem(reserved=1), fm, fm) == ha.HA_ERR_SHAPE
+    # chunk-causal variant: whole query tiles per chunk, fused feature-map kernels only, forward only
+    assert ha.hybrid_attn_validate(_problem(causal=1536), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(causal=128, bs=64), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(causal=128), fm, fm) == ha.HA_ERR_UNSUPPORTED
+    assert ha.hybrid_attn_validate(_problem(causal=1560), fm, fm) == ha.HA_ERR_UNSUPPORTED
+    assert ha.hybrid_attn_validate(_problem(causal=-256), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(causal=1536), _map(256, 256), _map(256, 256)) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(causal=1536), _map(384, 384, 3), _map(384, 384, 3)) == ha.HA_ERR_UNSUPPORTED
+    assert ha.hybrid_attn_validate(_problem(causal=1536, R=1), None, None) == ha.HA_OK
+    # one prefix state per chunk
+    assert ha.hybrid_attn_workspace_bytes(_problem(causal=4096), fm, fm) > ha.hybrid_attn_workspace_bytes(_problem(), fm, fm)
+    assert lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(_problem(causal=4096)), ctypes.byref(fm), ctypes.byref(fm)) > 0
     assert ha.hybrid_attn_validate(_problem(N=75600, R=75600, g=75600), fm, fm) == ha.HA_ERR_UNSUPPORTED    # R g beyond 2^30
     assert ha.hybrid_attn_workspace_bytes(_problem(g=1), fm, fm) == ha.hybrid_attn_workspace_bytes(_problem(), fm, fm)
     fm64 = _map(64, 64)

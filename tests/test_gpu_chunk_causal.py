@@ -1,0 +1,80 @@
+"""GPU tests of the chunk-causal variant (the paper leaves causal attention to future work and defines none; here: a query
+sees the tokens of its own and of all earlier chunks, the state S, z becomes a prefix sum over chunks)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hybrid_attn_oracle as O
+from paper_2509_24899_amd import hybrid_attn as ha
+from paper_2509_24899_amd import workloads as W
+from tests.test_gpu_parity import MAX_ABS, REL_L2, SMALL, SMALL64, metrics, oracle_map, record
+
+pytestmark = pytest.mark.gpu
+
+
+def causal_case(name, inp, R, C, g=0, block_size=128, rows=None, layout="bhnd"):
+    w = inp.workload
+    q, k, v, fq, fk = ha.to_device(inp)
+    if layout == "bnhd":
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    print(f"  case {name} R={R} g={g} C={C} bs={block_size}", flush=True)
+    y = ha.hybrid_attn_forward(q, k, v, fq if R != 1 else None, fk if R != 1 else None, (R, g, C), block_size, w.scale)
+    torch.cuda.synchronize()
+    y = y.float().cpu().numpy()
+    split = O.BlockSplit(R, g) if g > 1 else R
+    ref = O.hybrid_attn_chunk_causal(inp.q, inp.k, inp.v, oracle_map(inp.phi_q), oracle_map(inp.phi_k), split, w.scale, C, rows=rows)
+    if rows is not None:
+        y = y[:, :, rows]
+    assert np.isfinite(y).all()
+    ma, rl = metrics(y, ref)
+    record(name, ma, rl, R=R, g=g, C=C, N=w.N)
+    assert ma <= MAX_ABS and rl <= REL_L2, (name, ma, rl)
+    return y
+
+
+@pytest.mark.parametrize("R", (4, 3, 2, 0, 1, 16))
+@pytest.mark.parametrize("C,bs", [(256, 128), (128, 64), (512, 128), (1280, 128), (384, 64)])
+def test_forward_chunk_causal(R, C, bs):
+    """Chunks of one and of several query tiles, a last chunk cut short (1337 tokens), every kind of rate."""
+    causal_case(f"causal_R{R}_C{C}", W.make_inputs(SMALL), R, C, block_size=bs)
+
+
+def test_one_chunk_is_the_plain_operator():
+    inp = W.make_inputs(SMALL)
+    q, k, v, fq, fk = ha.to_device(inp)
+    a = ha.hybrid_attn_forward(q, k, v, fq, fk, 4, 128, SMALL.scale)
+    b = ha.hybrid_attn_forward(q, k, v, fq, fk, (4, 0, 1536), 128, SMALL.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_other_paths_chunk_causal():
+    """d_head = 64, fp32 io, the 256-wide fused map, the block-granular split underneath, [B, N, H, d] memory."""
+    causal_case("causal_d64", W.make_inputs(SMALL64), 3, 256, block_size=64)
+    causal_case("causal_tiny_f32", W.make_inputs(W.TINY), 4, 256, block_size=128)
+    w = W.replace(SMALL, B=1, H=2, d_hidden=256, d_feat=256, seed=50)
+    causal_case("causal_phi256", W.make_inputs(w), 4, 512)
+    causal_case("causal_phi256_R0", W.make_inputs(w), 0, 256)
+    causal_case("causal_blocksplit", W.make_inputs(SMALL), 4, 512, g=48)
+    causal_case("causal_bnhd", W.make_inputs(SMALL), 2, 256, layout="bnhd")
+
+
+def test_chunk_causal_rejected_where_it_has_no_kernels():
+    inp = W.make_inputs(SMALL)
+    q, k, v, fq, fk = ha.to_device(inp)
+    with pytest.raises(ha.HybridAttnError):
+        ha.hybrid_attn_forward(q, k, v, fq, fk, (4, 0, 200), 128, SMALL.scale)           # not whole query tiles
+    with pytest.raises(ha.HybridAttnError):
+        ha.hybrid_attn_value_distill_loss(q, k, v, fq, fk, (4, 0, 256), 128, SMALL.scale)
+    with pytest.raises(ha.HybridAttnError):
+        ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, (4, 0, 256), 128, SMALL.scale)
+    with pytest.raises(ha.HybridAttnError):
+        ha.hybrid_attn_linear_state(k, v, fk, (4, 0, 256))
+
+
+def test_headline_shape_chunk_causal_sampled_rows():
+    """480p / 81 frames, R = 4, chunks of 4096 tokens (eight chunks, the last one short): sampled rows of every chunk."""
+    wl = W.replace(W.WAN_480P_81F, H=2, seed=78)
+    inp = W.make_inputs(wl)
+    rows = np.unique(np.concatenate([np.array([0, 255, 4095, 4096, 8191, 8192, 28671, 28672, 32759]), W.sample_rows(wl, n_random=40)]))
+    causal_case("causal_headline_R4_C4096", inp, 4, 4096, rows=rows)
