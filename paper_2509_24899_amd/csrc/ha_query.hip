@@ -263,6 +263,18 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   // expressed against; it follows m_true only when the gap would let exponentials exceed 2^kLazy.
   constexpr float kLazy = 8.0f;
   float m = -INFINITY, m_true = -INFINITY, lsum = 0.f;
+  // Row sums of P on the matrix cores (the issue port, not the matrix core, is what the loop's vector work crowds): a 16x16x32 product of a constant 0/1 matrix with the very B operand of P V.
+  // Its lane layout (column = lane % 16, contraction group = lane / 16) sees the 32-query operand as two interleaved
+  // 16-query ones: groups 0, 2 hold query lane % 16, groups 1, 3 hold query 16 + lane % 16.  Row 0 of the constant
+  // matrix selects groups 0, 2 and row 4 groups 1, 3, so register 0 of lane r < 32 receives the whole sum of query r
+  // (both halves of its keys) and the upper 32 lanes receive zero, which is what the final cross-half sum expects.
+  f32x4 lacc = {0.f, 0.f, 0.f, 0.f};
+  bf16x8 sel;
+  {
+    const int row = lane & 15, kq = lane >> 4;
+    const __bf16 one = static_cast<__bf16>(((row == 0 && (kq & 1) == 0) || (row == 4 && (kq & 1) == 1)) ? 1.0f : 0.0f);
+    sel = bf16x8{one, one, one, one, one, one, one, one};
+  }
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -342,7 +354,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
       m_true = fmaxf(m_true, xhalf_max(t));
       if (__any((m_true - m) * c > kLazy)) {
         const float alpha = fast_exp2((m - m_true) * c);
-        lsum *= alpha;
+        lacc[0] *= alpha;                                 // registers 1 - 3 hold rows of zeros
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -372,7 +384,6 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
       const bf16x8 *vsrc_lds = ring_v[j & (NB - 1)], *ksrc_lds = ring_k[(j + 2) & (NB - 1)];
       // phase 1: S(j+1)^T on the matrix cores, exponentials of S(j)^T on the VALU
       const float mc = m * c;
-      float ps = 0.f;
       bf16x8 pb[2];
 #pragma unroll
       for (int x = 0; x < 16; ++x) s_nxt[x] = 0.f;
@@ -402,24 +413,17 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
           s_cur[x] = fast_exp2(__builtin_fmaf(s_cur[x], c, -mc));
         }
         // once a half of the block is exponentiated it is rounded to bf16 (the B operand of P V) and its
-        // row-sum contribution is taken from the rounded values, two per v_dot2, so that numerator and
-        // denominator see the same weights
+        // row-sum contribution is taken from the rounded values, so that numerator and denominator see the
+        // same weights
         if (ks == KS / 2 - 1 || ks == KS - 1) {
           const int sp = ks == KS - 1;
           f32x8 p8;
 #pragma unroll
           for (int i = 0; i < 8; ++i) p8[i] = s_cur[8 * sp + i];
           pb[sp] = __builtin_convertvector(p8, bf16x8);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-            const bf16x2 pr = {pb[sp][2 * i], pb[sp][2 * i + 1]};
-            const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-            ps = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, ps, false);
-          }
+          lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, pb[sp], lacc, 0, 0, 0);
         }
       }
-      lsum += ps;
       // phase 2: O^T += V(j)^T P(j)^T on the matrix cores; the column maxima of S(j+1)^T on the VALU
 #pragma unroll
       for (int sp = 0; sp < 2; ++sp)
@@ -449,7 +453,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     ring_barrier(Fa{});   // everything landed and read: the ring is free for the epilogue
     // express the accumulators against the exact c_i (Eq. "hybrid": the largest softmax weight is 1)
     const float alpha = fast_exp2((m - m_true) * c);
-    lsum *= alpha;
+    lsum = lacc[0] * alpha;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
