@@ -37,6 +37,10 @@ cuts the sequence into chunks of `chunk` consecutive tokens; a query sees the ke
 chunks, softmax tokens and linear tokens alike, so S and z become prefix sums over chunks.  It is written as the
 pinned non-causal function applied to every prefix of the sequence.
 
+Third variant: `hybrid_attn_local_window`, the design Sec. 3.2 sets its uniform stride against: the softmax tokens of
+a query are a local window around it, every other token is a linear token.  Blocked form: the sequence is cut into
+tiles of `tile` tokens and the window of a query is its own tile and `w_tiles` tiles on either side.
+
 All arithmetic is float64; nothing is rounded inside.  Inputs are whatever the caller hands in
 (already rounded to the io dtype of the GPU path and widened).
 
@@ -233,6 +237,40 @@ def hybrid_attn_chunk_causal(q, k, v, phi_q, phi_k, R, scale, chunk: int, rows=N
             for h in range(H):
                 y[b, h, pos] = hybrid_attn_head(q[b, h, :end], k[b, h, :end], v[b, h, :end], phi_q, phi_k, h, R, scale,
                                                 rows=sel[pos])
+    return y
+
+
+def hybrid_attn_local_window(q, k, v, phi_q, phi_k, scale, tile: int, w_tiles: int, rows=None):
+    """Local-window variant of Eq. "hybrid" for q, k, v [B, H, N, d]: for a query in tile t (tiles of `tile`
+    consecutive tokens) T_S is the set of tokens in tiles t - w_tiles .. t + w_tiles and T_L is every other token;
+    with those sets the equation is evaluated as printed (c_i over the window only).  `rows` (optional, sorted
+    1-D indices) restricts the output to those queries."""
+    if tile < 1 or w_tiles < 0:
+        raise ValueError("tile must be >= 1 and w_tiles >= 0")
+    B, H, N, d = q.shape
+    sel = np.arange(N) if rows is None else np.asarray(rows)
+    y = np.empty((B, H, sel.size, d))
+    tok = np.arange(N)
+    for t in range(-(-N // tile)):
+        pos = np.nonzero((sel >= t * tile) & (sel < (t + 1) * tile))[0]
+        if pos.size == 0:
+            continue
+        in_win = (tok // tile >= t - w_tiles) & (tok // tile <= t + w_tiles)
+        win, rest = tok[in_win], tok[~in_win]
+        for b in range(B):
+            for h in range(H):
+                qs = np.asarray(q[b, h], dtype=np.float64)[sel[pos]]
+                kk = np.asarray(k[b, h], dtype=np.float64)
+                vv = np.asarray(v[b, h], dtype=np.float64)
+                s = (qs @ kk[win].T) * scale
+                p = np.exp(s - s.max(axis=1, keepdims=True))
+                num, den = p @ vv[win], p.sum(axis=1)
+                if rest.size:
+                    fk = feature_map(kk[rest], phi_k, h)
+                    g = feature_map(qs, phi_q, h)
+                    num = num + g @ (fk.T @ vv[rest])
+                    den = den + g @ fk.sum(axis=0)
+                y[b, h, pos] = num / den[:, None]
     return y
 
 

@@ -281,9 +281,47 @@ def pin_chunk_causal(M):
     np.testing.assert_allclose(M.hybrid_attn_chunk_causal(q, k, v, fq, fk, 3, 0.6, 6, rows=rows), yc[:, :, rows], rtol=1e-13)
 
 
+def pin_local_window(M):
+    """The local-window variant against an N x N weight matrix built entry by entry (own loops), and its reductions: a
+    window that covers every tile is plain softmax attention; with constant feature maps and q = 0 the closed form
+    (sum over the window + kappa sum over the rest) / (window size + kappa rest size)."""
+    rng = np.random.default_rng(16)
+    H, N, d, F = 2, 22, 4, 6
+    q, k, v = (rng.standard_normal((1, H, N, d)) * 1.2 for _ in range(3))
+    fq, fk = _rand_map(rng, H, d, 5, F, 2, mod=M), _rand_map(rng, H, d, 5, F, 2, mod=M)
+    for T, W in ((4, 1), (5, 0), (3, 2), (8, 1)):
+        y = M.hybrid_attn_local_window(q, k, v, fq, fk, 0.6, T, W)
+        for h in range(H):
+            gq, gk = M.feature_map(q[0, h], fq, h), M.feature_map(k[0, h], fk, h)
+            for i in range(N):
+                soft = [j for j in range(N) if abs(j // T - i // T) <= W]
+                c = max(0.6 * float(q[0, h, i] @ k[0, h, j]) for j in soft)
+                num, den = np.zeros(d), 0.0
+                for j in range(N):
+                    w = np.exp(0.6 * float(q[0, h, i] @ k[0, h, j]) - c) if j in soft else float(gq[i] @ gk[j])
+                    num += w * v[0, h, j]
+                    den += w
+                np.testing.assert_allclose(y[0, h, i], num / den, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(M.hybrid_attn_local_window(q, k, v, fq, fk, 0.6, 4, 6), M.hybrid_attn(q, k, v, None, None, 1, 0.6),
+                               rtol=1e-12)
+    rows = np.array([0, 3, 4, 11, 21])
+    np.testing.assert_allclose(M.hybrid_attn_local_window(q, k, v, fq, fk, 0.6, 4, 1, rows=rows),
+                               M.hybrid_attn_local_window(q, k, v, fq, fk, 0.6, 4, 1)[:, :, rows], rtol=1e-13)
+    fm = _const_map(2, d, 4, F, 2, mod=M)
+    vv = rng.standard_normal((1, 2, N, d)) + np.arange(N)[None, None, :, None]
+    y = M.hybrid_attn_local_window(np.zeros((1, 2, N, d)), k, vv, fm, fm, 0.5, 4, 1)
+    kappa = (F // 2) * sum(float(F) ** (-2 * p) for p in (1, 2))
+    for i in (0, 5, 13, 21):
+        win = [j for j in range(N) if abs(j // 4 - i // 4) <= 1]
+        rest = [j for j in range(N) if j not in win]
+        for h in range(2):
+            ref = (vv[0, h, win].sum(0) + kappa * vv[0, h, rest].sum(0)) / (len(win) + kappa * len(rest))
+            np.testing.assert_allclose(y[0, h, i], ref, rtol=1e-12)
+
+
 PINS = [pin_r1_is_library_softmax_attention, pin_feature_map_is_grouped_conv, pin_two_token_golden,
         pin_constant_phi_closed_form, pin_r0_is_linear_attention_nxn, pin_dense_loops, pin_invariants,
-        pin_split_rule, pin_block_granular_split, pin_chunk_causal]
+        pin_split_rule, pin_block_granular_split, pin_chunk_causal, pin_local_window]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
@@ -348,6 +386,29 @@ def _mut_causal_per_token(mp):
                                                     rows=[i])[0]
         return y
     mp.setattr(O, "hybrid_attn_chunk_causal", bad)
+
+
+def _mut_window_one_sided(mp):
+    """The window reaching back only (tiles t - w .. t), as a causal language model would have it."""
+    def bad(q, k, v, phi_q, phi_k, scale, tile, w_tiles, rows=None):
+        B, H, N, d = q.shape
+        sel = np.arange(N) if rows is None else np.asarray(rows)
+        y = np.empty((B, H, sel.size, d))
+        tok = np.arange(N)
+        for n, i in enumerate(sel):
+            in_win = (tok // tile >= i // tile - w_tiles) & (tok // tile <= i // tile)
+            for b_ in range(B):
+                for h in range(H):
+                    s_ = (q[b_, h, i] @ k[b_, h, in_win].T) * scale
+                    p_ = np.exp(s_ - s_.max())
+                    num, den = p_ @ v[b_, h, in_win], p_.sum()
+                    if (~in_win).any():
+                        fk = O.feature_map(k[b_, h, ~in_win], phi_k, h)
+                        g = O.feature_map(q[b_, h, i:i + 1], phi_q, h)[0]
+                        num, den = num + g @ (fk.T @ v[b_, h, ~in_win]), den + g @ fk.sum(axis=0)
+                    y[b_, h, n] = num / den
+        return y
+    mp.setattr(O, "hybrid_attn_local_window", bad)
 
 
 def _mut_softmax_per_slice(mp):
@@ -440,7 +501,8 @@ def _mut_phi_sees_scaled_input(mp):
     mp.setattr(O, "feature_map", lambda x, fm, head: good(np.asarray(x) * 0.5, fm, head))
 
 
-MUTATIONS = [_mut_split_off_by_one, _mut_block_split_counts_tokens_not_blocks, _mut_causal_per_token, _mut_softmax_per_slice, _mut_no_powers, _mut_powers_from_zero, _mut_no_relu,
+MUTATIONS = [_mut_split_off_by_one, _mut_block_split_counts_tokens_not_blocks, _mut_causal_per_token, _mut_window_one_sided,
+             _mut_softmax_per_slice, _mut_no_powers, _mut_powers_from_zero, _mut_no_relu,
              _mut_no_scale, _mut_unstabilised, _mut_max_over_all_tokens, _mut_drop_z, _mut_state_over_all_tokens,
              _mut_phi_sees_scaled_input]
 
