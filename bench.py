@@ -29,7 +29,9 @@ def cpu_baseline(w, heads=12):
     fk = O.FeatureMap(inp.phi_k.w1, inp.phi_k.b1, inp.phi_k.w2, inp.phi_k.b2, w.poly_degree)
     t0 = time.perf_counter()
     split = O.BlockSplit(w.R, w.split_granularity) if w.split_granularity > 1 else w.R
-    if 0 < w.causal_chunk < w.N:
+    if w.local_window > 0:
+        O.hybrid_attn_local_window(inp.q, inp.k, inp.v, fq, fk, w.scale, 2 * w.block_size, w.local_window // (2 * w.block_size))
+    elif 0 < w.causal_chunk < w.N:
         O.hybrid_attn_chunk_causal(inp.q, inp.k, inp.v, fq, fk, split, w.scale, w.causal_chunk)
     else:
         O.hybrid_attn(inp.q, inp.k, inp.v, fq, fk, split, w.scale)
@@ -232,6 +234,9 @@ def main():
                     help="variant of the token split: groups of G consecutive tokens, every R-th group softmax tokens")
     ap.add_argument("--causal-chunk", type=int, default=0, metavar="C",
                     help="chunk-causal variant: a query sees its own and all earlier chunks of C tokens (multiple of 2 * block size)")
+    ap.add_argument("--local-window", type=int, default=0, metavar="W",
+                    help="local-window variant: softmax over the query's tile and W tokens on either side (multiple of 2 * block "
+                         "size), linear attention over every other token; sets the rate to 0")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
@@ -276,6 +281,8 @@ def main():
         w = W.replace(w, split_granularity=args.split_granularity)
     if args.causal_chunk > 0:
         w = W.replace(w, causal_chunk=args.causal_chunk)
+    if args.local_window > 0:
+        w = W.replace(w, R=0, local_window=args.local_window)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
@@ -370,15 +377,14 @@ def main():
     flops = W.algorithmic_flops(w)
     mean = [sum(r[i] for r in stage_ms) / len(stage_ms) for i in range(5)]
     n_s, n_l = w.n_softmax, w.n_linear
+    if w.local_window > 0:
+        n_s = n_l = w.N
     if n_s > 0:
         # dominant kernel: the fused query kernel; its algorithmic flops are everything except the
         # key-side feature map and state (4 N N_S d + phi_q MLP + g.S, g.z)
         layered = n_l > 0 and (w.d_mid or not ((w.d_hidden == w.d and w.d_feat == w.d) or (w.d_hidden == 256 and w.d_feat == 256)))
         # (maps that go layer by layer through HBM leave only the softmax loop and the merge to the query kernel)
-        softmax_flops = 4.0 * w.N * n_s * w.d
-        if 0 < w.causal_chunk < w.N:       # chunk-causal variant: the softmax keys up to the end of the query's chunk
-            C = w.causal_chunk
-            softmax_flops = 4.0 * w.d * sum((min(lo + C, w.N) - lo) * w.softmax_before(min(lo + C, w.N)) for lo in range(0, w.N, C))
+        softmax_flops = 4.0 * w.d * W.softmax_pairs(w)       # fewer pairs than N N_S for the causal / local-window variants
         k_flops = w.B * w.H * (softmax_flops + (2.0 * w.N * (w.d * w.d_hidden + w.d_hidden * w.d_feat)
                                                          + 2.0 * w.N * w.d_feat * w.d + 2.0 * w.N * w.d_feat
                                                          if n_l > 0 and not layered else 0.0))
@@ -393,7 +399,7 @@ def main():
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (null when this
     # workload has not been profiled)
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d and w.split_granularity <= 1 and not w.causal_chunk:   # profiled with the d -> d -> d maps
+    if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d and w.split_granularity <= 1 and not w.causal_chunk and not w.local_window:   # profiled with the d -> d -> d maps
         t = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
         if t:
             roofline["traffic"] = t["read_bytes"] + t["written_bytes"]
@@ -410,6 +416,7 @@ def main():
                    "hybrid_rate_R": w.R, "r": (1.0 / w.R if w.R else 0.0), "block_size": w.block_size,
                    **({"split_granularity": w.split_granularity} if w.split_granularity > 1 else {}),
                    **({"causal_chunk": w.causal_chunk} if w.causal_chunk else {}),
+                   **({"local_window": w.local_window} if w.local_window else {}),
                    "feature_map": (f"{w.d}->{w.d_hidden}->{w.d_mid}->{w.d_feat}" if w.d_mid else f"{w.d}->{w.d_hidden}->{w.d_feat}")
                    + f", P={w.poly_degree}"},
         "tflops": flops / (ms_per_step * 1e-3) / 1e12,

@@ -101,6 +101,14 @@ typedef struct {
                              chunks.  C must be a multiple of 2 * block_size.  hybrid_attn_forward only, with maps
                              the fused kernels take (d_hidden, d_out = d_head, or 256 at d_head = 128);
                              HA_ERR_UNSUPPORTED elsewhere. */
+  int32_t local_window;   /* 0: off.  W > 0 (a variant: the local-window design that Sec. 3.2 sets the uniform
+                             stride against, in a blocked form): with tiles of T = 2 * block_size tokens, the
+                             softmax tokens of a query in tile t are the tokens of tiles t - W/T .. t + W/T, every
+                             other token is a linear token; Eq. "hybrid" is evaluated with these per-tile sets.
+                             W must be a multiple of T, hybrid_rate must be 0 (no strided softmax tokens),
+                             split_granularity <= 1 and causal_chunk == 0.  hybrid_attn_forward only, fused maps
+                             only, as for causal_chunk. */
+  int32_t reserved;       /* must be 0 */
 } ha_problem;
 
 /* Host-only argument check (no HIP call).  phi_q and phi_k may be NULL iff the problem has no

@@ -71,7 +71,12 @@ static ha_status validate(const ha_problem *p, const ha_feature_map *phi_q, cons
     if ((phi_q->w_mid != nullptr) != (phi_k->w_mid != nullptr)) return HA_ERR_SHAPE;
     if (phi_q->w_mid && phi_q->d_mid != phi_k->d_mid) return HA_ERR_SHAPE;
   }
-  if (p->causal_chunk > 0) {
+  if (p->local_window < 0 || p->reserved != 0) return HA_ERR_SHAPE;
+  if (p->local_window > 0) {
+    if (p->hybrid_rate != 0 || p->split_granularity > 1 || p->causal_chunk != 0) return HA_ERR_SHAPE;
+    if (p->local_window % (2 * p->block_size)) return HA_ERR_UNSUPPORTED;      // whole query tiles
+  }
+  if (p->causal_chunk > 0 || p->local_window > 0) {
     if (p->causal_chunk % (2 * p->block_size)) return HA_ERR_UNSUPPORTED;      // whole query tiles per chunk
     if (has_linear) {
       const bool square = phi_q->d_hidden == p->d_head && phi_q->d_out == p->d_head;
@@ -94,7 +99,14 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
   pl.CC = p.causal_chunk < p.N ? p.causal_chunk : 0;      // one chunk that covers everything is the plain operator
   pl.n_cc = pl.CC > 0 ? (pl.N + pl.CC - 1) / pl.CC : 1;
   pl.nsub = 1;
-  pl.NL = pl.N - pl.NS;
+  pl.LW = p.local_window;
+  if (pl.LW > 0) {
+    // every token is a candidate softmax key (compacted at rate 1) and a linear key of the tiles that do not see it
+    pl.NS = pl.N;
+    pl.CC = 2 * p.block_size;                             // one state-pass chunk and one state per query tile
+    pl.n_cc = (pl.N + pl.CC - 1) / pl.CC;
+  }
+  pl.NL = pl.LW > 0 ? pl.N : pl.N - pl.NS;
   const bool has_linear = pl.NL > 0 && phi_q && phi_k;
   pl.HD = has_linear ? phi_k->d_hidden : pl.D;
   pl.F = has_linear ? phi_k->d_out : pl.D;
@@ -116,7 +128,10 @@ void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_featur
     pl.CH = ((tiles + want - 1) / want) * 128;
     if (pl.CH < 128) pl.CH = 128;
     pl.n_chunks = has_linear ? (pl.NL + pl.CH - 1) / pl.CH : 0;
-    if (pl.CC > 0 && has_linear) {
+    if (pl.LW > 0) {
+      pl.CH = pl.CC;
+      pl.n_chunks = pl.n_cc;
+    } else if (pl.CC > 0 && has_linear) {
       // chunk-causal: every causal chunk is a group of nsub state-pass workgroups of its own; CH from the most linear
       // tokens a chunk can hold
       int most = 0;
@@ -290,7 +305,7 @@ ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const voi
   if (s != HA_OK) return s;
   if (!k || !v || !state_S || !state_z || !phi_k) return HA_ERR_NULL;
   if (p->hybrid_rate == 1) return HA_ERR_SHAPE;   // no linear tokens, no state
-  if (p->causal_chunk > 0) return HA_ERR_UNSUPPORTED;
+  if (p->causal_chunk > 0 || p->local_window > 0) return HA_ERR_UNSUPPORTED;
   if (!ha::aligned16(k) || !ha::aligned16(v)) return HA_ERR_ALIGN;
   ha::Plan pl;
   ha::WidePlan wp;
@@ -357,7 +372,7 @@ ha_status hybrid_attn_value_distill_loss(const ha_problem *p, const void *q, con
                                          void *workspace, size_t workspace_bytes, void *hip_stream) {
   ha_status s = ha::validate(p, phi_q, phi_k);
   if (s != HA_OK) return s;
-  if (p->causal_chunk > 0) return HA_ERR_UNSUPPORTED;      // the teacher of Eq. "vd_loss" is not causal
+  if (p->causal_chunk > 0 || p->local_window > 0) return HA_ERR_UNSUPPORTED;      // the teacher of Eq. "vd_loss" is not causal
   if (!q || !k || !v || !y_teacher || !y_student || !loss) return HA_ERR_NULL;
   if (!ha::aligned16(y_teacher) || !ha::aligned16(y_student) || (reinterpret_cast<uintptr_t>(loss) & 7u)) return HA_ERR_ALIGN;
   if (y_teacher == y_student) return HA_ERR_SHAPE;
@@ -436,7 +451,7 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
                                          void *workspace, size_t workspace_bytes, void *hip_stream) {
   ha_status s = check_grad_maps(p, phi_q, phi_k);
   if (s != HA_OK) return s;
-  if (p->causal_chunk > 0) return HA_ERR_UNSUPPORTED;
+  if (p->causal_chunk > 0 || p->local_window > 0) return HA_ERR_UNSUPPORTED;
   if (!q || !k || !v || !y_teacher || !y_student || !row_den || !loss || !grad_q || !grad_k) return HA_ERR_NULL;
   for (const ha_feature_map_grad *gm : {grad_q, grad_k}) {
     if (!gm->w1 || !gm->b1 || !gm->w2 || !gm->b2) return HA_ERR_NULL;
@@ -515,6 +530,6 @@ const char *hybrid_attn_status_string(ha_status s) {
 
 int hybrid_attn_last_device_error(void) { return ha::g_last_device_error; }
 
-int hybrid_attn_abi_version(void) { return 5; }
+int hybrid_attn_abi_version(void) { return 6; }
 
 }  // extern "C"

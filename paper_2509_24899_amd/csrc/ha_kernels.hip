@@ -431,6 +431,44 @@ __global__ __launch_bounds__(256) void state_prefix_kernel(const float *__restri
 }
 
 // ------------------------------------------------------------------------------------------------
+// state_window_kernel (local-window variant): grid as state_reduce_kernel; one chunk partial per query tile.  For
+// tile t the state of the tokens OUTSIDE its window, i.e. the chunks before t - w and after t + w: a prefix that
+// grows and a suffix that shrinks as t advances (no subtraction of nearly equal totals).  Output as in
+// state_prefix_kernel: st[bh][t][...], z[bh][t][F].
+__global__ __launch_bounds__(256) void state_window_kernel(const float *__restrict__ part, float *__restrict__ z,
+                                                           __bf16 *__restrict__ st_hi, __bf16 *__restrict__ st_lo, int D,
+                                                           int F, int n_t, int w) {
+  const int NCB = D / 32 + 1, FB = F / 32, NT = FB * NCB;
+  const int bh = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= NT * 1024) return;
+  const int ti = e >> 10, x = (e >> 6) & 15, lane = e & 63, r = lane & 31, g = lane >> 5;
+  const int fb = ti / NCB, cb = ti % NCB;
+  const int ch = 32 * fb + crow(x, g);
+  const float *src = part + (int64_t)bh * n_t * NT * 1024 + e;
+  const int64_t cs = (int64_t)NT * 1024;
+  float pre = 0.f, suf = 0.f;
+  for (int c = n_t - 1; c > w; --c) suf += src[c * cs];            // chunks after the window of tile 0
+  for (int t = 0; t < n_t; ++t) {
+    const float sum = pre + suf;
+    const int64_t sbh = (int64_t)bh * n_t + t;
+    if (cb < D / 32) {
+      const __bf16 hi = static_cast<__bf16>(sum);
+      const __bf16 lo = static_cast<__bf16>(sum - static_cast<float>(hi));
+      const int c5 = ch & 31, s = c5 >> 4, w16 = c5 & 15, g2 = (w16 >> 2) & 1, tt = 4 * (w16 >> 3) + (w16 & 3);
+      const int64_t idx = (((sbh * (D / 32) + cb) * FB + fb) * 2 + s) * 512 + (g2 * 32 + r) * 8 + tt;
+      st_hi[idx] = hi;
+      st_lo[idx] = lo;
+    } else if (r == 0) {
+      z[sbh * F + ch] = sum;
+    }
+    // tile t + 1: chunk t - w leaves the window on the left, chunk t + 1 + w enters it on the right
+    if (t - w >= 0) pre += src[(t - w) * cs];
+    if (t + 1 + w < n_t) suf -= src[(t + 1 + w) * cs];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // host launchers
 
 template <typename T>
@@ -450,7 +488,8 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, void *ws
   dim3 grid(pl.n_kblocks, pl.B * pl.H);
   bf16x8 *ksf = ws_ptr<bf16x8>(ws, pl.off_ks), *vsf = ws_ptr<bf16x8>(ws, pl.off_vs);
 #define HA_COMPACT(DD, FF) \
-  compact_kernel<DD, FF><<<grid, 256, 0, st>>>(k, v, ksf, vsf, pl.H, pl.NS, pl.R, pl.G, pl.n_kblocks, pl.sb, pl.sh, pl.sn)
+  compact_kernel<DD, FF><<<grid, 256, 0, st>>>(k, v, ksf, vsf, pl.H, pl.NS, pl.LW > 0 ? 1 : pl.R, pl.G, pl.n_kblocks, pl.sb, \
+                                               pl.sh, pl.sn)
   if (pl.D == 64) { if (pl.f32) HA_COMPACT(64, true); else HA_COMPACT(64, false); }
   else { if (pl.f32) HA_COMPACT(128, true); else HA_COMPACT(128, false); }
 #undef HA_COMPACT
@@ -489,6 +528,12 @@ hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsig
 
 hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st) {
   dim3 grid(pl.n_state_tiles * 1024 / 256, pl.B * pl.H);
+  if (pl.LW > 0) {
+    state_window_kernel<<<grid, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_part), ws_ptr<float>(ws, pl.off_z),
+                                              ws_ptr<__bf16>(ws, pl.off_sthi), ws_ptr<__bf16>(ws, pl.off_stlo), pl.D, pl.F,
+                                              pl.n_cc, pl.LW / pl.CC);
+    return hipGetLastError();
+  }
   if (pl.CC > 0) {
     state_prefix_kernel<<<grid, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_part), ws_ptr<float>(ws, pl.off_S),
                                               ws_ptr<float>(ws, pl.off_z), ws_ptr<__bf16>(ws, pl.off_sthi),

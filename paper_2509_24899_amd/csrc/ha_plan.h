@@ -13,7 +13,8 @@ struct Plan {
   int B, H, N, D, HD, F, R, NS, NL, P, act_q, act_k;
   int G;                 // granularity of the token split (1: per token, Sec. 3.2)
   int CC, n_cc, nsub;    // chunk-causal variant: chunk length in tokens (0: off), number of chunks, state-pass
-                         // workgroups per chunk
+                         // workgroups per chunk.  Local-window variant: CC = the query tile, one state per tile
+  int LW;                // local-window variant: window in tokens on either side of the query's tile (0: off)
   int DM;   // width of the second hidden layer of a three-layer feature map, 0 for two layers
   bool f32;
   int64_t sb, sh, sn;

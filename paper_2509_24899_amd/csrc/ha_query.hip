@@ -27,6 +27,7 @@ struct QueryArgs {
   int n_tb;
   int H, N, NS, n_qtiles, n_ktiles, n_kblocks, total_wg;
   int CC, n_cc, R, G;                   // chunk-causal variant (CC > 0): chunk length, chunk count, the token split
+  int LW;                               // local-window variant: window in tokens on either side of the query tile
   int has_linear, P, act;
   int64_t sb, sh, sn;
   float scale_log2e;
@@ -186,8 +187,8 @@ static __device__ __forceinline__ void query_epilogue(const QueryArgs &a, int bh
 // is first read (as K(j+2)) at least one barrier after it was requested.
 // LIN: the linear part arrives precomputed (maps too wide for the epilogue below); a variant of its own so that
 // the usual kernel carries none of it.
-// CAUSAL: the chunk-causal variant, likewise a variant of its own.
-template <int D, int HD, int F, int NW, int NB, int G, bool F32, bool LIN = false, bool CAUSAL = false>
+// MODE 1: the chunk-causal variant, 2: the local-window variant; likewise variants of their own.
+template <int D, int HD, int F, int NW, int NB, int G, bool F32, bool LIN = false, int MODE = 0>
 __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
   static_assert(G <= 2 && NB >= 2 * G + 2 && (NB & (NB - 1)) == 0, "ring too short for the barrier period");
   constexpr int KS = D / 16, RB = D / 32;
@@ -213,6 +214,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
 
   const int per_xcd = (a.total_wg + 7) >> 3;
   int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  constexpr bool CAUSAL = MODE == 1;
   if constexpr (CAUSAL) logical = blockIdx.x;
   if (logical >= a.total_wg) return;
   int bh = logical / a.n_qtiles, qtile = logical % a.n_qtiles;
@@ -234,6 +236,18 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     const int cc = (qtile * QT) / a.CC;
     const int64_t shift = (int64_t)bh * (a.n_cc - 1) + cc;
     a.NS = softmax_before(min((cc + 1) * a.CC, a.N), a.R, a.G);
+    a.z += shift * F;
+    a.st_hi += shift * (D * F / 8);
+    a.st_lo += shift * (D * F / 8);
+  }
+  int kb_lo = 0;                            // first key block this tile reads (local-window variant)
+  if constexpr (MODE == 2) {
+    // local-window variant: the softmax keys are the tokens of the tiles qtile - w .. qtile + w (every token sits in
+    // the compacted arrays, in order), the state is the one of the tokens outside that window
+    const int w_t = a.LW / QT, lo_tile = max(qtile - w_t, 0);
+    const int64_t shift = (int64_t)bh * (a.n_cc - 1) + qtile;
+    kb_lo = lo_tile * (QT / 32);
+    a.NS = min((qtile + w_t + 1) * QT, a.N) - lo_tile * QT;
     a.z += shift * F;
     a.st_hi += shift * (D * F / 8);
     a.st_lo += shift * (D * F / 8);
@@ -282,8 +296,9 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
 
   const int nblk = (a.NS + 31) >> 5;     // key blocks that hold at least one real key
   if (nblk > 0) {
-    const bf16x8 *ksrc = a.ks_frag + (int64_t)bh * a.n_kblocks * FRAG;
-    const bf16x8 *vsrc = a.vs_frag + (int64_t)bh * a.n_kblocks * FRAG;
+    const bf16x8 *ksrc = a.ks_frag + ((int64_t)bh * a.n_kblocks + kb_lo) * FRAG;
+    const bf16x8 *vsrc = a.vs_frag + ((int64_t)bh * a.n_kblocks + kb_lo) * FRAG;
+    const int kb_last = a.n_kblocks - 1 - kb_lo;
     const unsigned lane_off = lane * 16;
     // block b: global -> ring slot b % NB with direct-to-LDS loads; one instruction moves 64 lanes x 16 B
     // = one 1 KiB wave-chunk (LDS address = M0 + 16 * lane, global address = scalar base + 16 * lane), and
@@ -326,7 +341,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     // Every step of the loop below runs the same code, also past the last block (its logits are masked
     // and its weights are zero), so every ring slot must hold finite data before it is read: requests past
     // the end re-fetch the last block of the (zero padded) fragment arrays.
-    for (int b = 0; b < LEAD; ++b) request(min(b, a.n_kblocks - 1));
+    for (int b = 0; b < LEAD; ++b) request(min(b, kb_last));
     ring_barrier(std::false_type{});
 
     const float c = a.scale_log2e;
@@ -380,7 +395,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     // MASK: block j + 1 may hold padding keys (or lie past the end).
     auto step = [&](int j, f32x16 &s_cur, f32x16 &s_nxt, bf16x8 (&k_cur)[KS], bf16x8 (&k_nxt)[KS], auto mask_c) {
       constexpr bool MASK = decltype(mask_c)::value;
-      request(min(j + LEAD, a.n_kblocks - 1));
+      request(min(j + LEAD, kb_last));
       const bf16x8 *vsrc_lds = ring_v[j & (NB - 1)], *ksrc_lds = ring_k[(j + 2) & (NB - 1)];
       // phase 1: S(j+1)^T on the matrix cores, exponentials of S(j)^T on the VALU
       const float mc = m * c;
@@ -561,7 +576,7 @@ hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi
   a.st_lo = ws_ptr<bf16x8>(ws, pl.off_stlo);
   a.z = ws_ptr<float>(ws, pl.off_z);
   a.H = pl.H; a.N = pl.N; a.NS = pl.NS;
-  a.CC = pl.CC; a.n_cc = pl.n_cc; a.R = pl.R; a.G = pl.G;
+  a.CC = pl.CC; a.n_cc = pl.n_cc; a.R = pl.R; a.G = pl.G; a.LW = pl.LW;
   a.n_ktiles = pl.n_ktiles; a.n_kblocks = pl.n_kblocks;
   a.has_linear = pl.NL > 0; a.P = pl.P; a.act = pl.act_q;
   a.sb = pl.sb; a.sh = pl.sh; a.sn = pl.sn;
@@ -574,9 +589,12 @@ hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi
   dim3 grid(((a.total_wg + 7) / 8) * 8);
 #define HA_QUERY(DD, HH, FF, F32) \
   do { \
-    if (pl.CC > 0) { \
-      if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32, false, true><<<grid, 512, 0, st>>>(a); \
-      else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32, false, true><<<grid, 256, 0, st>>>(a); \
+    if (pl.LW > 0) { \
+      if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32, false, 2><<<grid, 512, 0, st>>>(a); \
+      else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32, false, 2><<<grid, 256, 0, st>>>(a); \
+    } else if (pl.CC > 0) { \
+      if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32, false, 1><<<grid, 512, 0, st>>>(a); \
+      else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32, false, 1><<<grid, 256, 0, st>>>(a); \
     } else { \
       if (big) query_kernel_ring<DD, HH, FF, 8, 8, 2, F32><<<grid, 512, 0, st>>>(a); \
       else query_kernel_ring<DD, HH, FF, 4, 4, 1, F32><<<grid, 256, 0, st>>>(a); \

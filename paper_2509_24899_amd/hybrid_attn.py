@@ -46,7 +46,8 @@ class ha_problem(ctypes.Structure):
                 ("dtype", ctypes.c_int32), ("block_size", ctypes.c_int32), ("hybrid_rate", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
-                ("split_granularity", ctypes.c_int32), ("causal_chunk", ctypes.c_int32)]
+                ("split_granularity", ctypes.c_int32), ("causal_chunk", ctypes.c_int32),
+                ("local_window", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class HybridAttnError(RuntimeError):
@@ -157,10 +158,13 @@ def _dtype_code(t: torch.Tensor) -> int:
 def make_problem(q: torch.Tensor, hybrid_rate, block_size: int, softmax_scale: float) -> ha_problem:
     """ha_problem for a [B, H, N, d] tensor view (any strides with a contiguous last dim).  hybrid_rate: R, or a pair
     (R, g) for the block-granular variant of the split (groups of g tokens, every R-th group softmax tokens), or a
-    triple (R, g, C) for the chunk-causal variant on top (chunks of C tokens; g = 0 for the per-token split)."""
-    granularity, causal = 0, 0
+    triple (R, g, C) for the chunk-causal variant on top (chunks of C tokens; g = 0 for the per-token split), or
+    (0, 0, 0, W) for the local-window variant (W tokens on either side of the query's tile)."""
+    granularity, causal, window = 0, 0, 0
     if isinstance(hybrid_rate, (tuple, list)):
-        if len(hybrid_rate) == 3:
+        if len(hybrid_rate) == 4:
+            hybrid_rate, granularity, causal, window = hybrid_rate
+        elif len(hybrid_rate) == 3:
             hybrid_rate, granularity, causal = hybrid_rate
         else:
             hybrid_rate, granularity = hybrid_rate
@@ -168,7 +172,7 @@ def make_problem(q: torch.Tensor, hybrid_rate, block_size: int, softmax_scale: f
         raise ValueError("q, k, v must be [B, H, N, d] views with a contiguous last dimension")
     B, H, N, d = q.shape
     return ha_problem(B, H, N, d, _dtype_code(q), block_size, hybrid_rate, softmax_scale,
-                      q.stride(0), q.stride(1), q.stride(2), int(granularity), int(causal))
+                      q.stride(0), q.stride(1), q.stride(2), int(granularity), int(causal), int(window), 0)
 
 
 def _fm_ptr(fm):

@@ -37,10 +37,13 @@ class Workload:
     d_mid: int = 0        # width of the second hidden layer of a three-layer feature map (0: two layers)
     split_granularity: int = 0   # > 1: the block-granular variant of the split (groups of this many tokens)
     causal_chunk: int = 0        # > 0: the chunk-causal variant (chunks of this many tokens)
+    local_window: int = 0        # > 0: the local-window variant (tokens on either side of the query's tile; R = 0)
 
     @property
     def rate(self):
         """What the binding takes as hybrid_rate: R, or (R, group size[, causal chunk]) for the variants."""
+        if self.local_window > 0:
+            return (0, 0, 0, self.local_window)
         if self.causal_chunk > 0:
             return (self.R, self.split_granularity, self.causal_chunk)
         return (self.R, self.split_granularity) if self.split_granularity > 1 else self.R
@@ -156,15 +159,28 @@ def sample_rows(w: Workload, n_random: int = 256, seed: int = 12345) -> np.ndarr
     return np.array(sorted(rows), dtype=np.int64)
 
 
+def softmax_pairs(w: Workload) -> float:
+    """Number of (query, softmax key) pairs per (batch, head): N N_S for the paper's operator, fewer for the variants."""
+    N = w.N
+    if w.local_window > 0:
+        T = 2 * w.block_size
+        wt = w.local_window // T
+        return float(sum((min(lo + T, N) - lo) * (min((lo // T + wt + 1) * T, N) - max(lo // T - wt, 0) * T) for lo in range(0, N, T)))
+    if 0 < w.causal_chunk < N:
+        C = w.causal_chunk
+        return float(sum((min(lo + C, N) - lo) * w.softmax_before(min(lo + C, N)) for lo in range(0, N, C)))
+    return float(N) * w.n_softmax
+
+
 def algorithmic_flops(w: Workload) -> float:
     """FLOPs the method itself needs for one forward: the two GEMMs of the softmax part, both
     feature-map MLPs (phi_k on linear keys only), the state, and its contraction with phi_q(q).
     exp, max, powers and the division are not counted; with no linear keys phi is skipped."""
     n_s, n_l, N, d, Hd, F = w.n_softmax, w.n_linear, w.N, w.d, w.d_hidden, w.d_feat
     per_head = 4.0 * N * n_s * d
-    if 0 < w.causal_chunk < N:       # chunk-causal variant: a query sees the softmax keys up to the end of its chunk
-        C = w.causal_chunk
-        per_head = 4.0 * d * sum((min(lo + C, N) - lo) * w.softmax_before(min(lo + C, N)) for lo in range(0, N, C))
+    per_head = 4.0 * d * softmax_pairs(w)
+    if w.local_window > 0:           # local-window variant: every token is a linear key of the tiles that do not see it
+        n_l = N
     if n_l > 0:
         mlp = d * Hd + (Hd * w.d_mid + w.d_mid * F if w.d_mid else Hd * F)       # multiply-adds per token
         per_head += 2.0 * (N + n_l) * mlp

@@ -21,9 +21,10 @@ def lib():
     return ha._lib()
 
 
-def _problem(B=1, H=12, N=32760, d=128, dtype=ha.HA_BF16, bs=128, R=4, scale=None, strides=None, g=0, causal=0):
+def _problem(B=1, H=12, N=32760, d=128, dtype=ha.HA_BF16, bs=128, R=4, scale=None, strides=None, g=0, causal=0, window=0,
+             reserved=0):
     sb, sh, sn = strides if strides else (H * N * d, N * d, d)
-    return ha.ha_problem(B, H, N, d, dtype, bs, R, scale if scale is not None else d ** -0.5, sb, sh, sn, g, causal)
+    return ha.ha_problem(B, H, N, d, dtype, bs, R, scale if scale is not None else d ** -0.5, sb, sh, sn, g, causal, window, reserved)
 
 
 def _map(Hd=128, F=128, P=2, act=ha.HA_ACT_SOFTMAX, w1=FAKE, w2=FAKE + 0x100000, b1=None, b2=None):
@@ -37,12 +38,12 @@ def test_header_symbols_are_exported(lib):
     assert len(set(names)) == 17
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert ha.hybrid_attn_abi_version() == 5
+    assert ha.hybrid_attn_abi_version() == 6
 
 
 def test_struct_layout_matches_header():
     # 7 int32 + float, then three int64 at offset 32; four pointers, four int32, two pointers, two int32
-    assert ha.ha_problem.stride_b.offset == 32 and ctypes.sizeof(ha.ha_problem) == 64 and ha.ha_problem.split_granularity.offset == 56
+    assert ha.ha_problem.stride_b.offset == 32 and ctypes.sizeof(ha.ha_problem) == 72 and ha.ha_problem.split_granularity.offset == 56 and ha.ha_problem.local_window.offset == 64
     assert ha.ha_feature_map.d_hidden.offset == 32 and ha.ha_feature_map.w_mid.offset == 48 and ctypes.sizeof(ha.ha_feature_map) == 72
 
 
@@ -66,6 +67,16 @@ def test_valid_problems(lib):
     assert ha.hybrid_attn_validate(_problem(causal=1536), _map(256, 256), _map(256, 256)) == ha.HA_OK
     assert ha.hybrid_attn_validate(_problem(causal=1536), _map(384, 384, 3), _map(384, 384, 3)) == ha.HA_ERR_UNSUPPORTED
     assert ha.hybrid_attn_validate(_problem(causal=1536, R=1), None, None) == ha.HA_OK
+    # local-window variant: rate 0 plus a window of whole query tiles; the other variants stay off
+    assert ha.hybrid_attn_validate(_problem(R=0, window=1024), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(R=0, window=128, bs=64), fm, fm) == ha.HA_OK
+    assert ha.hybrid_attn_validate(_problem(R=4, window=1024), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(R=0, window=1024, causal=1024), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(R=0, window=1024, g=8), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(R=0, window=1000), fm, fm) == ha.HA_ERR_UNSUPPORTED
+    assert ha.hybrid_attn_validate(_problem(R=0, window=-1), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(reserved=1), fm, fm) == ha.HA_ERR_SHAPE
+    assert ha.hybrid_attn_validate(_problem(R=0, window=1024), _map(384, 384, 3), _map(384, 384, 3)) == ha.HA_ERR_UNSUPPORTED
     # one prefix state per chunk
     assert ha.hybrid_attn_workspace_bytes(_problem(causal=4096), fm, fm) > ha.hybrid_attn_workspace_bytes(_problem(), fm, fm)
     assert lib.hybrid_attn_value_distill_workspace_bytes(ctypes.byref(_problem(causal=4096)), ctypes.byref(fm), ctypes.byref(fm)) > 0
