@@ -39,6 +39,14 @@ def test_forward_chunk_causal(R, C, bs):
     causal_case(f"causal_R{R}_C{C}", W.make_inputs(SMALL), R, C, block_size=bs)
 
 
+@pytest.mark.parametrize("N,R", [(19, 2), (128, 4), (129, 0), (257, 3), (600, 1), (600, 600)])
+def test_short_sequences_chunk_causal(N, R):
+    """Fewer tokens than one chunk (the plain operator), exactly one chunk, one token more, a few chunks."""
+    w = W.replace(SMALL, N=N, B=1, H=2, seed=400 + N)
+    causal_case(f"causal_N{N}_R{R}", W.make_inputs(w), R, 128, block_size=64)
+    causal_case(f"causal_N{N}_R{R}_bs128", W.make_inputs(w), R, 256, block_size=128)
+
+
 def test_one_chunk_is_the_plain_operator():
     inp = W.make_inputs(SMALL)
     q, k, v, fq, fk = ha.to_device(inp)

@@ -59,6 +59,14 @@ def test_other_paths_local_window():
     window_case("window_logit_std1", W.make_inputs(W.replace(SMALL, seed=21, qk_gain=float(128 ** 0.5))), 256)
 
 
+@pytest.mark.parametrize("N", (19, 128, 129, 257, 600))
+def test_short_sequences_local_window(N):
+    """Fewer tokens than one tile, exactly one tile, one token more, and a few tiles; window of one tile on either side."""
+    w = W.replace(SMALL, N=N, B=1, H=2, seed=300 + N)
+    window_case(f"window_N{N}", W.make_inputs(w), 128, block_size=64)
+    window_case(f"window_N{N}_bs128", W.make_inputs(w), 256, block_size=128)
+
+
 def test_local_window_rejected_where_it_has_no_kernels():
     inp = W.make_inputs(SMALL)
     q, k, v, fq, fk = ha.to_device(inp)
