@@ -448,23 +448,43 @@ __global__ __launch_bounds__(256) void state_window_kernel(const float *__restri
   const float *src = part + (int64_t)bh * n_t * NT * 1024 + e;
   const int64_t cs = (int64_t)NT * 1024;
   float pre = 0.f, suf = 0.f;
-  for (int c = n_t - 1; c > w; --c) suf += src[c * cs];            // chunks after the window of tile 0
-  for (int t = 0; t < n_t; ++t) {
-    const float sum = pre + suf;
-    const int64_t sbh = (int64_t)bh * n_t + t;
-    if (cb < D / 32) {
-      const __bf16 hi = static_cast<__bf16>(sum);
-      const __bf16 lo = static_cast<__bf16>(sum - static_cast<float>(hi));
-      const int c5 = ch & 31, s = c5 >> 4, w16 = c5 & 15, g2 = (w16 >> 2) & 1, tt = 4 * (w16 >> 3) + (w16 & 3);
-      const int64_t idx = (((sbh * (D / 32) + cb) * FB + fb) * 2 + s) * 512 + (g2 * 32 + r) * 8 + tt;
-      st_hi[idx] = hi;
-      st_lo[idx] = lo;
-    } else if (r == 0) {
-      z[sbh * F + ch] = sum;
+  // chunks after the window of tile 0, four loads in flight at a time, added in a fixed order
+  for (int c = n_t - 1; c > w; c -= 4) {
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = c - i > w ? src[(c - i) * cs] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) suf += v[i];
+  }
+  const int c5 = ch & 31, s = c5 >> 4, w16 = c5 & 15, g2 = (w16 >> 2) & 1, tt = 4 * (w16 >> 3) + (w16 & 3);
+  for (int t0 = 0; t0 < n_t; t0 += 4) {
+    // tile t -> t + 1: chunk t - w leaves the window on the left, chunk t + 1 + w enters it on the right
+    float leave[4], enter[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int t = t0 + i;
+      leave[i] = (t - w >= 0 && t < n_t) ? src[(t - w) * cs] : 0.f;
+      enter[i] = (t + 1 + w < n_t) ? src[(t + 1 + w) * cs] : 0.f;
     }
-    // tile t + 1: chunk t - w leaves the window on the left, chunk t + 1 + w enters it on the right
-    if (t - w >= 0) pre += src[(t - w) * cs];
-    if (t + 1 + w < n_t) suf -= src[(t + 1 + w) * cs];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int t = t0 + i;
+      if (t < n_t) {
+        const float sum = pre + suf;
+        const int64_t sbh = (int64_t)bh * n_t + t;
+        if (cb < D / 32) {
+          const __bf16 hi = static_cast<__bf16>(sum);
+          const __bf16 lo = static_cast<__bf16>(sum - static_cast<float>(hi));
+          const int64_t idx = (((sbh * (D / 32) + cb) * FB + fb) * 2 + s) * 512 + (g2 * 32 + r) * 8 + tt;
+          st_hi[idx] = hi;
+          st_lo[idx] = lo;
+        } else if (r == 0) {
+          z[sbh * F + ch] = sum;
+        }
+        pre += leave[i];
+        suf -= enter[i];
+      }
+    }
   }
 }
 
