@@ -92,7 +92,7 @@ hipError_t launch_vd_rows(const Plan &pl, const void *y_teacher, const void *y_s
 hipError_t launch_natural_frags(const float *M, void *hi, void *lo, int rows, int cols, int n_mat, hipStream_t st);
 // ha_wide.hip / ha_wide_grad.hip
 hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query, void *ws,
-                           hipStream_t st, bool finish = true);
+                           hipStream_t st);
 void make_wide_grad_plan(const Plan &pl, const WidePlan &wp, size_t base_off, WideGradPlan &gp);
 hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp, const WideGradPlan &gp, const void *q,
                                               const void *k, const void *v, const ha_feature_map &phi_q,

@@ -6,10 +6,10 @@
 //   wide_prep_kernel       one weight matrix -> A-operand fragments (natural order for layer 1, chained after it)
 //   wide_layer1_kernel     h^T = relu(W1 x^T + b1)                     x from q / k, h as hi + lo bf16
 //   wide_layer_kernel      h'^T = relu(W h^T + b)  or  u^T = W h^T + b  (last layer: fp32 pre-activations)
-//   wide_phi_finish_kernel softmax / exp / relu over all channels of a token, slice powers, bf16; for the queries
-//                          also e_i = phi_q(q_i).z
+//   (output stage)         softmax / exp / relu over all channels of a token, slice powers, bf16: applied by the two
+//                          consumers below while they read the pre-activations, so phi never visits HBM
 //   wide_state_kernel      [S | z] += phi_k^T [V | 1], one 128-channel slab of S per workgroup
-//   wide_lin_kernel        n_i = phi_q(q_i) S   (fp32, in the layout of the query kernel's accumulators)
+//   wide_lin_kernel        n_i = phi_q(q_i) S   (fp32, in the layout of the query kernel's accumulators), e_i = phi_q(q_i).z
 // The query kernel then adds n_i and e_i in its epilogue instead of evaluating phi_q itself.
 //
 // Register images ("C image" of a 32-token block tb of (batch, head) bh; lane = 32 g + r owns token 32 tb + r):
@@ -222,96 +222,87 @@ __global__ __launch_bounds__(256, 2) void wide_layer_kernel(WideArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// wide_phi_finish_kernel: grid (ceil(n_tb / 4), B*H), one 32-token block per wave.  One sweep over the fp32
-// pre-activations of the block, one 32-channel tile in registers at a time: normalisation (softmax: against the
-// maximum and sum combined from the last layer's per-block values), slice powers and rounding.  Output: phi as bf16 C image
-// (zero for tokens past the end); QUERY: e[bh][token] = phi . z with the rounded phi, as the numerator uses it.
+// Output stage of a feature map, applied by the consumers of phi while they read the fp32 pre-activations (so phi
+// itself never visits HBM): normalisation (softmax: against the maximum and sum combined from the per-256-channel-block
+// values the last layer left behind), slice powers, rounding.
 constexpr int WIDE_FMAX = 768;
 
-template <bool QUERY>
-__global__ __launch_bounds__(256) void wide_phi_finish_kernel(const f32x4 *__restrict__ u_in, const float *__restrict__ stat,
-                                                              bf16x8 *__restrict__ phi_out, const float *__restrict__ z,
-                                                              float *__restrict__ e_out, int F, int n_tok, int n_tb, int act,
-                                                              int P) {
-  __shared__ float zl[QUERY ? WIDE_FMAX : 1];
-  const int bh = blockIdx.y;
-  if constexpr (QUERY) {
-    for (int i = threadIdx.x; i < F; i += 256) zl[i] = z[(int64_t)bh * F + i];
-    __syncthreads();
-  }
-  const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
-  const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (tb >= n_tb) return;
-  const int FB = F / 32;
-  const float inv_groups = 8.0f * (float)P / (float)F;        // 1 / (8-channel groups per slice)
-  const bool valid = 32 * tb + r < n_tok;
-  const f32x4 *src = u_in + ((int64_t)bh * n_tb + tb) * FB * 256 + lane;
-  auto load_tile = [&](int fb, f32x16 &u) {
-#pragma unroll
-    for (int x4 = 0; x4 < 4; ++x4) {
-      const f32x4 t = src[(fb * 4 + x4) * 64];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) u[4 * x4 + j] = t[j];
-    }
-  };
-  float off = 0.f, inv = 1.f;
+struct WideOutStage {
+  float off, inv, inv_groups;     // softmax: exp2(u log2 e + off) * inv;  1 / (8-channel groups per slice)
+  int act;
+};
+
+// One lane's view (token 32 tb + lane % 32) of the softmax statistics of its token.
+static __device__ __forceinline__ WideOutStage wide_out_stage(const float *__restrict__ stat, int64_t bh_tb, int F, int act,
+                                                              int P, int lane) {
+  WideOutStage o;
+  o.off = 0.f; o.inv = 1.f; o.act = act;
+  o.inv_groups = 8.0f * (float)P / (float)F;
   if (act == 0) {
-    // softmax over all channels from the per-block maxima and sums the last layer left behind
     const int nblk = (F + 255) / 256;
-    const float *st = stat + (((int64_t)bh * n_tb + tb) * nblk * 2) * 64 + lane;
+    const float *st = stat + (bh_tb * nblk * 2) * 64 + lane;
     float m = -INFINITY;
     for (int b = 0; b < nblk; ++b) m = fmaxf(m, st[b * 128]);
     float sum = 0.f;
     for (int b = 0; b < nblk; ++b) sum += st[b * 128 + 64] * fast_exp2((st[b * 128] - m) * kLog2e);
-    off = -m * kLog2e;
-    inv = 1.0f / sum;
+    o.off = -m * kLog2e;
+    o.inv = 1.0f / sum;
   }
-  float dot = 0.f;
-  for (int fb = 0; fb < FB; ++fb) {
-    f32x16 u;
-    load_tile(fb, u);
+  return o;
+}
+
+// phi of the 32-channel tile fb of one token block from its fp32 C image piece: the two bf16 pieces (chained order)
+// the next product takes as its B operand; zero for tokens past the end.
+static __device__ __forceinline__ void wide_phi_tile(const f32x4 (&raw)[4], int fb, const WideOutStage &o, bool valid,
+                                                     bf16x8 (&out)[2]) {
+  f32x16 u;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (act == 0) u[v] = fast_exp2(__builtin_fmaf(u[v], kLog2e, off)) * inv;
-      else if (act == 1) u[v] = fast_exp2(u[v] * kLog2e);
-      else u[v] = fmaxf(u[v], 0.f);
+  for (int x4 = 0; x4 < 4; ++x4)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) u[4 * x4 + j] = raw[x4][j];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    if (o.act == 0) u[v] = fast_exp2(__builtin_fmaf(u[v], kLog2e, o.off)) * o.inv;
+    else if (o.act == 1) u[v] = fast_exp2(u[v] * kLog2e);
+    else u[v] = fmaxf(u[v], 0.f);
+  }
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    f32x8 t8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      // slice power - 1 = (8-channel group index) / (groups per slice), wave-uniform; exact in fp32 for these sizes
+      const int extra = (int)(((float)(4 * fb + 2 * s + i / 4) + 0.5f) * o.inv_groups);
+      const float t0 = u[8 * s + i], t2 = t0 * t0;
+      float t = (extra & 1) ? t2 : t0;                           // t0^(extra + 1), extra in 0..7
+      t = (extra & 2) ? t * t2 : t;
+      t = (extra & 4) ? t * (t2 * t2) : t;
+      t8[i] = valid ? t : 0.f;
     }
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      f32x8 t8;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        // slice power - 1 = (8-channel group index) / (groups per slice), wave-uniform; exact in fp32 for these sizes
-        const int extra = (int)(((float)(4 * fb + 2 * s + i / 4) + 0.5f) * inv_groups);
-        const float t0 = u[8 * s + i], t2 = t0 * t0;
-        float t = (extra & 1) ? t2 : t0;                           // t0^(extra + 1), extra in 0..7
-        t = (extra & 2) ? t * t2 : t;
-        t = (extra & 4) ? t * (t2 * t2) : t;
-        t8[i] = valid ? t : 0.f;
-      }
-      const bf16x8 p8 = __builtin_convertvector(t8, bf16x8);
-      phi_out[((((int64_t)bh * n_tb + tb) * FB + fb) * 2 + s) * 64 + lane] = p8;
-      if constexpr (QUERY) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) dot += static_cast<float>(p8[i]) * zl[32 * fb + crow(8 * s + i, g)];
-      }
-    }
+    out[s] = __builtin_convertvector(t8, bf16x8);
   }
-  if constexpr (QUERY) {
-    dot = xhalf_sum(dot);
-    if (g == 0 && valid) e_out[(int64_t)bh * n_tok + 32 * tb + r] = dot;
-  }
+}
+static __device__ __forceinline__ void wide_load_tile(const f32x4 *__restrict__ src, int fb, f32x4 (&raw)[4]) {
+#pragma unroll
+  for (int x4 = 0; x4 < 4; ++x4) raw[x4] = src[(fb * 4 + x4) * 64];
+}
+static __device__ __forceinline__ void wide_phi_tile(const f32x4 *__restrict__ src, int fb, const WideOutStage &o, bool valid,
+                                                     bf16x8 (&out)[2]) {
+  f32x4 raw[4];
+  wide_load_tile(src, fb, raw);
+  wide_phi_tile(raw, fb, o, valid, out);
 }
 
 // ------------------------------------------------------------------------------------------------
 // wide_state_kernel: grid (n_chunks, B*H, F / 128), 4 waves.  As the contraction half of state_kernel, with
-// phi_k read back from its C image instead of being computed in place; workgroup z owns feature rows
+// phi_k formed from the fp32 pre-activations of the last layer as they are read; workgroup z owns feature rows
 // 128 z .. 128 z + 127 of [S | z], wave w row block w of those.  Partial tiles go where state_kernel puts them
 // (part[bh][chunk][row block * NCB + column block][v][lane]), so state_reduce_kernel serves both.
 template <int D, bool F32>
-__global__ __launch_bounds__(256, 1) void wide_state_kernel(const bf16x8 *__restrict__ phi, const void *__restrict__ v,
-                                                            float *__restrict__ part, int H, int NL, int R, int G, int CH,
-                                                            int F, int n_tb, int64_t sb, int64_t sh, int64_t sn) {
+__global__ __launch_bounds__(256, 1) void wide_state_kernel(const f32x4 *__restrict__ u_img, const float *__restrict__ stat,
+                                                            const void *__restrict__ v, float *__restrict__ part, int H,
+                                                            int NL, int R, int G, int CH, int F, int n_tb, int act, int P,
+                                                            int64_t sb, int64_t sh, int64_t sn) {
   constexpr int TOK = 128, PITCH = TOK + 8, NCB = D / 32 + 1;
   constexpr int CG = D / 32, VPT = (TOK / 16) * CG / 4;
   __shared__ __align__(16) __bf16 ft[128][PITCH];
@@ -347,15 +338,13 @@ __global__ __launch_bounds__(256, 1) void wide_state_kernel(const bf16x8 *__rest
       const int tok = lmap.token(min(t0 + trow, NL - 1));
       vreg[p] = load8<F32>(v, base + (int64_t)tok * sn + c8 * 8);
     }
-    const int tb = t0 / 32 + w;
+    const int tb = min(t0 / 32 + w, n_tb - 1);            // blocks past the end: clamped, their tokens are not valid
+    const bool valid = t0 + tf < NL;
+    const WideOutStage os = wide_out_stage(stat, (int64_t)bh * n_tb + tb, F, act, P, lane);
+    const f32x4 *usrc = u_img + ((int64_t)bh * n_tb + tb) * FB * 256 + lane;
     bf16x8 ph[4][2];
 #pragma unroll
-    for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-        ph[fb][s] = tb < n_tb ? phi[((((int64_t)bh * n_tb + tb) * FB + 4 * zb + fb) * 2 + s) * 64 + lane] : zero;
-      }
+    for (int fb = 0; fb < 4; ++fb) wide_phi_tile(usrc, 4 * zb + fb, os, valid, ph[fb]);
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
@@ -388,46 +377,59 @@ __global__ __launch_bounds__(256, 1) void wide_state_kernel(const bf16x8 *__rest
 }
 
 // ------------------------------------------------------------------------------------------------
-// wide_lin_kernel: grid (ceil(n_tb / 4), B*H).  n^T = S^T phi_q^T per 32-query block: A operand = S^T as hi + lo
-// fragments in chained order (state_reduce_kernel's layout), B operand = the C image of phi_q.  Output: fp32 C
-// image of width D, i.e. the layout of the query kernel's accumulators.
+// wide_lin_kernel: grid (ceil(n_tb / 4), B*H).  Output stage of phi_q and the linear part of Eq. "hybrid" per 32-query
+// block: n^T = S^T phi_q^T (A operand = S^T as hi + lo fragments in chained order, state_reduce_kernel's layout; B
+// operand = phi_q, formed tile by tile from the fp32 pre-activations) and e = phi_q . z with the rounded phi_q, as the
+// numerator uses it.  Output: n as an fp32 C image of width D, i.e. the layout of the query kernel's accumulators;
+// e[bh][token].
 template <int D>
-__global__ __launch_bounds__(256) void wide_lin_kernel(const bf16x8 *__restrict__ phi, const bf16x8 *__restrict__ st_hi,
-                                                       const bf16x8 *__restrict__ st_lo, f32x4 *__restrict__ lin, int F,
-                                                       int n_tb) {
+__global__ __launch_bounds__(256) void wide_lin_kernel(const f32x4 *__restrict__ u_img, const float *__restrict__ stat,
+                                                       const bf16x8 *__restrict__ st_hi, const bf16x8 *__restrict__ st_lo,
+                                                       const float *__restrict__ z, f32x4 *__restrict__ lin,
+                                                       float *__restrict__ e_out, int F, int n_tok, int n_tb, int act, int P) {
   constexpr int RB = D / 32;
+  __shared__ float zl[WIDE_FMAX];
   const int bh = blockIdx.y;
-  const int lane = threadIdx.x & 63;
+  for (int i = threadIdx.x; i < F; i += 256) zl[i] = z[(int64_t)bh * F + i];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
   const int tb = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tb >= n_tb) return;
   const int FB = F / 32;
+  const bool valid = 32 * tb + r < n_tok;
+  const WideOutStage os = wide_out_stage(stat, (int64_t)bh * n_tb + tb, F, act, P, lane);
+  const f32x4 *usrc = u_img + ((int64_t)bh * n_tb + tb) * FB * 256 + lane;
   const GlobalFrags shi = global_frags(st_hi + (int64_t)bh * (D * F / 8), D * F * 2);
   const GlobalFrags slo = global_frags(st_lo + (int64_t)bh * (D * F / 8), D * F * 2);
-  const bf16x8 *pb = phi + ((int64_t)bh * n_tb + tb) * FB * 128 + lane;
   f32x16 acc[RB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
+  float dot = 0.f;
   for (int fb = 0; fb < FB; ++fb) {
     bf16x8 b[2], ahi[RB][2], alo[RB][2];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      b[s] = pb[(fb * 2 + s) * 64];
+    for (int s = 0; s < 2; ++s)
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         ahi[rb][s] = frag_at(shi, (rb * FB + fb) * 2 + s, lane);
         alo[rb][s] = frag_at(slo, (rb * FB + fb) * 2 + s, lane);
       }
-    }
+    wide_phi_tile(usrc, fb, os, valid, b);
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dot += static_cast<float>(b[s][i]) * zl[32 * fb + crow(8 * s + i, g)];
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         acc[rb] = mfma32(alo[rb][s], b[s], acc[rb]);
         acc[rb] = mfma32(ahi[rb][s], b[s], acc[rb]);
       }
+    }
   }
+  dot = xhalf_sum(dot);
+  if (g == 0 && valid) e_out[(int64_t)bh * n_tok + 32 * tb + r] = dot;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -466,11 +468,11 @@ void make_wide_plan(const Plan &pl, size_t base_off, WidePlan &wp) {
   wp.total = off;
 }
 
-// One feature map over one token set: weight fragments, layer 1, (middle layer,) last layer, output stage (unless
-// finish is false: the backward pass forms phi itself).  is_query: all N tokens of q, and phi.z is formed; otherwise
-// the linear tokens of k.
+// One feature map over one token set: weight fragments, layer 1, (middle layer,) last layer, which leaves the fp32
+// pre-activations and the softmax statistics; the output stage belongs to whoever reads them next.  is_query: all N
+// tokens of q; otherwise the linear tokens of k.
 hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query,
-                           void *ws, hipStream_t st, bool finish) {
+                           void *ws, hipStream_t st) {
   const int BH = pl.B * pl.H;
   const int n_tok = is_query ? pl.N : pl.NL, n_tb = is_query ? wp.n_tb_q : wp.n_tb_k;
   hipError_t e;
@@ -532,19 +534,6 @@ hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, co
     wide_layer_kernel<true><<<grid, 256, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  if (finish) {
-    dim3 grid((n_tb + 3) / 4, BH);
-    if (is_query)
-      wide_phi_finish_kernel<true><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat),
-                                                         ws_ptr<bf16x8>(ws, wp.off_phi),
-                                                         ws_ptr<float>(ws, pl.off_z), ws_ptr<float>(ws, wp.off_e), pl.F, n_tok,
-                                                         n_tb, pl.act_q, pl.P);
-    else
-      wide_phi_finish_kernel<false><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat),
-                                                          ws_ptr<bf16x8>(ws, wp.off_phi), nullptr,
-                                                          nullptr, pl.F, n_tok, n_tb, pl.act_k, pl.P);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
   return hipSuccess;
 }
 
@@ -555,11 +544,13 @@ hipError_t launch_wide_key_side(const Plan &pl, const WidePlan &wp, const void *
   if (e != hipSuccess) return e;
   dim3 grid(pl.n_chunks, pl.B * pl.H, pl.F / 128);
   if (pl.f32)
-    wide_state_kernel<128, true><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), v, ws_ptr<float>(ws, pl.off_part), pl.H,
-                                                       pl.NL, pl.R, pl.G, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
+    wide_state_kernel<128, true><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat), v,
+                                                       ws_ptr<float>(ws, pl.off_part), pl.H, pl.NL, pl.R, pl.G, pl.CH, pl.F,
+                                                       wp.n_tb_k, pl.act_k, pl.P, pl.sb, pl.sh, pl.sn);
   else
-    wide_state_kernel<128, false><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), v, ws_ptr<float>(ws, pl.off_part), pl.H,
-                                                        pl.NL, pl.R, pl.G, pl.CH, pl.F, wp.n_tb_k, pl.sb, pl.sh, pl.sn);
+    wide_state_kernel<128, false><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat), v,
+                                                        ws_ptr<float>(ws, pl.off_part), pl.H, pl.NL, pl.R, pl.G, pl.CH, pl.F,
+                                                        wp.n_tb_k, pl.act_k, pl.P, pl.sb, pl.sh, pl.sn);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return launch_state_reduce(pl, ws, st);
 }
@@ -570,8 +561,10 @@ hipError_t launch_wide_query_side(const Plan &pl, const WidePlan &wp, const void
   hipError_t e = launch_wide_map(pl, wp, q, phi_q, true, ws, st);
   if (e != hipSuccess) return e;
   dim3 grid((wp.n_tb_q + 3) / 4, pl.B * pl.H);
-  wide_lin_kernel<128><<<grid, 256, 0, st>>>(ws_ptr<bf16x8>(ws, wp.off_phi), ws_ptr<bf16x8>(ws, pl.off_sthi),
-                                             ws_ptr<bf16x8>(ws, pl.off_stlo), ws_ptr<f32x4>(ws, wp.off_lin), pl.F, wp.n_tb_q);
+  wide_lin_kernel<128><<<grid, 256, 0, st>>>(ws_ptr<f32x4>(ws, wp.off_u), ws_ptr<float>(ws, wp.off_stat),
+                                             ws_ptr<bf16x8>(ws, pl.off_sthi), ws_ptr<bf16x8>(ws, pl.off_stlo),
+                                             ws_ptr<float>(ws, pl.off_z), ws_ptr<f32x4>(ws, wp.off_lin),
+                                             ws_ptr<float>(ws, wp.off_e), pl.F, pl.N, wp.n_tb_q, pl.act_q, pl.P);
   return hipGetLastError();
 }
 

@@ -547,7 +547,7 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
     const int n_tok = is_query ? pl.N : pl.NL, n_tb = is_query ? wp.n_tb_q : wp.n_tb_k;
     const int n_chunks = is_query ? gp.n_chunks_q : gp.n_chunks_k, CH = is_query ? gp.CHq : gp.CHk;
     // this side's forward passes: h (hi + lo), pre-activations, softmax maxima / sums (phi_q is formed below)
-    if ((e = launch_wide_map(pl, wp, is_query ? q : k, fm, is_query, ws, st, false)) != hipSuccess) return e;
+    if ((e = launch_wide_map(pl, wp, is_query ? q : k, fm, is_query, ws, st)) != hipSuccess) return e;
     {
       dim3 grid((F * KL + 255) / 256, pl.H);
       if (pl.f32) wide_prep_t_kernel<true><<<grid, 256, 0, st>>>(fm.w2, ws_ptr<__bf16>(ws, gp.off_wt), F, KL);
