@@ -113,7 +113,9 @@ __global__ __launch_bounds__(256) void wide_layer1_kernel(WideArgs a) {
 // workgroup, so an activation fragment is read once per 256 output channels; the weight fragments are the same
 // for the four waves and pass through LDS, two 32-channel input blocks per stage, the next stage in flight
 // (direct-to-LDS) while the 64 matrix instructions of the current one run.
-template <bool LAST>
+// FULL: NOUT is a multiple of 256, every workgroup has all eight output tiles: the inner loops carry no tile-count
+// tests, so the weight fragments of a half step are requested together ahead of their matrix instructions.
+template <bool LAST, bool FULL>
 __global__ __launch_bounds__(256, 2) void wide_layer_kernel(WideArgs a) {
   constexpr int NT = 8, KCH = 2, STG = NT * KCH * 2 * 64;       // bf16x8 per stage buffer (32 KiB)
   __shared__ bf16x8 wl[2][STG];
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void wide_layer_kernel(WideArgs a) {
   const int tb = live ? blockIdx.x * 4 + w : a.n_tb - 1;
   const int KB = a.K / 32, OB = a.NOUT / 32;
   const int ob0 = blockIdx.y * NT;
-  const int nt = min(NT, OB - ob0);
+  const int nt = FULL ? NT : min(NT, OB - ob0);
   const bf16x8 *wg = a.wf + (int64_t)h * ((int64_t)a.NOUT * a.K / 8);
   const bf16x8 *bhi = a.in_hi + ((int64_t)bh * a.n_tb + tb) * KB * 128 + lane;
   const bf16x8 *blo = a.in_lo + ((int64_t)bh * a.n_tb + tb) * KB * 128 + lane;
@@ -157,15 +159,31 @@ __global__ __launch_bounds__(256, 2) void wide_layer_kernel(WideArgs a) {
     for (int kbl = 0; kbl < KCH; ++kbl) {
       const int kb = c * KCH + kbl;
       if (kb + 1 < KB) request_b(kb + 1, nb_hi, nb_lo);
+      if constexpr (FULL) {
 #pragma unroll
-      for (int s = 0; s < 2; ++s)
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-          if (j < nt) {
-            const bf16x8 af = wbuf[(j * KCH * 2 + kbl * 2 + s) * 64];
-            acc[j] = mfma32(af, cb_lo[s], acc[j]);
-            acc[j] = mfma32(af, cb_hi[s], acc[j]);
+          for (int j0 = 0; j0 < NT; j0 += 4) {
+            bf16x8 af[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) af[j] = wbuf[((j0 + j) * KCH * 2 + kbl * 2 + s) * 64];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              acc[j0 + j] = mfma32(af[j], cb_lo[s], acc[j0 + j]);
+              acc[j0 + j] = mfma32(af[j], cb_hi[s], acc[j0 + j]);
+            }
           }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            if (j < nt) {
+              const bf16x8 af = wbuf[(j * KCH * 2 + kbl * 2 + s) * 64];
+              acc[j] = mfma32(af, cb_lo[s], acc[j]);
+              acc[j] = mfma32(af, cb_hi[s], acc[j]);
+            }
+      }
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
         cb_hi[s] = nb_hi[s];
@@ -519,7 +537,8 @@ hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, co
     a.bias = fm.b_mid; a.K = pl.HD; a.NOUT = pl.DM;
     a.out_hi = ws_ptr<bf16x8>(ws, wp.off_h2hi); a.out_lo = ws_ptr<bf16x8>(ws, wp.off_h2lo);
     dim3 grid((n_tb + 3) / 4, (pl.DM + 255) / 256, BH);
-    wide_layer_kernel<false><<<grid, 256, 0, st>>>(a);
+    if (pl.DM % 256 == 0) wide_layer_kernel<false, true><<<grid, 256, 0, st>>>(a);
+    else wide_layer_kernel<false, false><<<grid, 256, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     a.in_hi = ws_ptr<bf16x8>(ws, wp.off_h2hi); a.in_lo = ws_ptr<bf16x8>(ws, wp.off_h2lo);
   }
@@ -531,7 +550,8 @@ hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, co
   a.out_stat = ws_ptr<float>(ws, wp.off_stat);
   {
     dim3 grid((n_tb + 3) / 4, (pl.F + 255) / 256, BH);
-    wide_layer_kernel<true><<<grid, 256, 0, st>>>(a);
+    if (pl.F % 256 == 0) wide_layer_kernel<true, true><<<grid, 256, 0, st>>>(a);
+    else wide_layer_kernel<true, false><<<grid, 256, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   return hipSuccess;
