@@ -100,3 +100,68 @@ def test_inner_loop_of_the_distillation_reduces_the_loss(kind):
     print("  ref loss", [round(x, 2) for x in ref_loss], flush=True)
     assert gpu_loss[-1] < 0.97 * gpu_loss[0] and ref_loss[-1] < 0.97 * ref_loss[0]
     np.testing.assert_allclose(gpu_loss, ref_loss, rtol=1e-2)
+
+
+def test_student_update_under_hip_graph_capture():
+    """One whole student update (student forward, loss, gradient, plain-step update of the eight parameter tensors) is a
+    fixed sequence of launches on the caller's stream with no host synchronisation and no memset, so it can be captured
+    into a HIP graph once and replayed per update.  Three replays, with eager work and synchronisations in between,
+    must reproduce three eager updates bit for bit: the loss of every step and the final parameters."""
+    wl, R, lr = W.replace(LOGIT_STD1, B=1, H=2, N=300, seed=32), 4, 50.0
+    inp = W.make_inputs(wl)
+    q, k, v, dq, dk = ha.to_device(inp)
+    names = ("w1", "b1", "w2", "b2")
+    scale_g = 1.0 / (wl.N * wl.d)
+    prob = ha.make_problem(q, R, wl.block_size, wl.scale)
+    ws = torch.empty(ha.hybrid_attn_value_distill_grad_workspace_bytes(prob, dq, dk), dtype=torch.uint8, device="cuda")
+    start = {(tag, n): getattr(fm, n).clone() for tag, fm in (("q", dq), ("k", dk)) for n in names}
+    masters = {key: (t.float().clone() if t.dtype != torch.float32 else None) for key, t in start.items()}
+    _, _, _, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, dq, dk, R, wl.block_size, wl.scale, workspace=ws)
+    torch.cuda.synchronize()
+
+    def reset():
+        for (tag, n), t in start.items():
+            getattr(dq if tag == "q" else dk, n).copy_(t)
+            if masters[tag, n] is not None:
+                masters[tag, n].copy_(t.float())
+
+    def one_update():
+        loss, gq, gk, _, _, _ = ha.hybrid_attn_value_distill_grad(q, k, v, dq, dk, R, wl.block_size, wl.scale, y_teacher=yt,
+                                                                  teacher_is_cached=True, y_student=ys, row_den=rd, workspace=ws,
+                                                                  stream=torch.cuda.current_stream())
+        for tag, fm, g in (("q", dq, gq), ("k", dk, gk)):
+            for n in names:
+                t = getattr(fm, n)
+                m = masters[tag, n]
+                ha.hybrid_attn_param_update(m if m is not None else t, g[n], lr, grad_scale=scale_g,
+                                            param_io=t if m is not None else None, stream=torch.cuda.current_stream())
+        return loss
+
+    reset()
+    eager_losses = []
+    for _ in range(3):
+        eager_losses.append(one_update().clone())
+    torch.cuda.synchronize()
+    eager_final = {(tag, n): getattr(dq if tag == "q" else dk, n).clone() for (tag, n) in start}
+    assert eager_losses[2][0] < eager_losses[0][0]
+
+    reset()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_update()                                    # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    reset()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        loss_g = one_update()
+    reset()                                             # capture runs nothing; start the replays from the initial weights
+    for rep in range(3):
+        ws.random_(0, 255)                              # eager work between replays: the workspace holds garbage
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(loss_g, eager_losses[rep]), f"replay {rep}: loss differs from the eager update"
+    for (tag, n), t in eager_final.items():
+        assert torch.equal(getattr(dq if tag == "q" else dk, n), t), (tag, n)
