@@ -273,8 +273,10 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     for (int ks = 0; ks < KS; ++ks) qf[ks] = load8<F32>(a.q, base + (int64_t)qi * a.sn + 16 * ks + 8 * g);
   }
   f32x16 o[RB];
-  // m_true: exact running maximum c_i.  m: the (possibly older) maximum the accumulators are currently
-  // expressed against; it follows m_true only when the gap would let exponentials exceed 2^kLazy.
+  // m_true: exact running maximum c_i over the keys this lane has seen, i.e. over its half of every key block (the
+  // two halves of a query column meet only when it matters: in the rare rescale and once after the loop).
+  // m: the (possibly older) maximum the accumulators are currently expressed against, the same in both halves; it
+  // follows m_true only when the gap would let exponentials exceed 2^kLazy.
   constexpr float kLazy = 8.0f;
   float m = -INFINITY, m_true = -INFINITY, lsum = 0.f;
   // Row sums of P on the matrix cores (the issue port, not the matrix core, is what the loop's vector work crowds): a 16x16x32 product of a constant 0/1 matrix with the very B operand of P V.
@@ -345,6 +347,8 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     ring_barrier(std::false_type{});
 
     const float c = a.scale_log2e;
+    const float lazy_gap = kLazy / c;                   // the threshold in units of the raw logits
+    float mc = 0.f;                                     // m c, kept beside m (it changes only in the rare rescale)
     bf16x8 k_a[KS], k_b[KS], vf[RB][2];
     f32x16 s_a, s_b;
     auto load_k = [&](int b, bf16x8 (&dst)[KS]) {
@@ -363,11 +367,12 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     // they are expressed against, which keeps every exponential below 2^kLazy; the exact c_i is restored
     // once after the loop.
     auto fold_max = [&](const f32x16 &s) {
-      float t = s[0];
+      float t = m_true;                                 // the running maximum rides along as a seventeenth value
 #pragma unroll
-      for (int x = 1; x < 16; ++x) t = fmaxf(t, s[x]);
-      m_true = fmaxf(m_true, xhalf_max(t));
-      if (__any((m_true - m) * c > kLazy)) {
+      for (int x = 0; x < 16; ++x) t = fmaxf(t, s[x]);
+      m_true = t;
+      if (__any(m_true - m > lazy_gap)) {
+        m_true = xhalf_max(m_true);
         const float alpha = fast_exp2((m - m_true) * c);
         lacc[0] *= alpha;                                 // registers 1 - 3 hold rows of zeros
 #pragma unroll
@@ -375,6 +380,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
 #pragma unroll
           for (int x = 0; x < 16; ++x) o[rb][x] *= alpha;
         m = m_true;
+        mc = m * c;
       }
     };
 
@@ -398,7 +404,6 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
       request(min(j + LEAD, kb_last));
       const bf16x8 *vsrc_lds = ring_v[j & (NB - 1)], *ksrc_lds = ring_k[(j + 2) & (NB - 1)];
       // phase 1: S(j+1)^T on the matrix cores, exponentials of S(j)^T on the VALU
-      const float mc = m * c;
       bf16x8 pb[2];
 #pragma unroll
       for (int x = 0; x < 16; ++x) s_nxt[x] = 0.f;
@@ -467,6 +472,7 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
     }
     ring_barrier(Fa{});   // everything landed and read: the ring is free for the epilogue
     // express the accumulators against the exact c_i (Eq. "hybrid": the largest softmax weight is 1)
+    m_true = xhalf_max(m_true);
     const float alpha = fast_exp2((m - m_true) * c);
     lsum = lacc[0] * alpha;
 #pragma unroll
