@@ -137,6 +137,23 @@ ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k,
                               const ha_feature_map *phi_q, const ha_feature_map *phi_k,
                               void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture with a foreign allocator, tight
+ * serving loops, harnesses that forbid hipMalloc): hybrid_attn_forward with the scratch taken from a static device
+ * array inside the library instead of a caller workspace.  The array is HA_STATIC_SCRATCH_MIB MiB; every GPU the
+ * library runs on holds its own copy until the process ends, and its address on a GPU is looked up at the first
+ * call on that GPU.  The call allocates nothing, frees nothing and does not synchronise; apart from the workspace
+ * it takes the arguments of hybrid_attn_forward and returns the same result bit for bit.  A problem whose
+ * hybrid_attn_workspace_bytes() exceeds hybrid_attn_static_scratch_bytes() is refused with HA_ERR_WORKSPACE before
+ * any HIP call (at the 480p / 81-frame shape with 12 heads the workspace is about 75 MB, so that shape does not fit;
+ * 12 heads of 16 K tokens at rate 4 do).  All calls on one GPU share the one array, whose contents are undefined
+ * between calls (nothing in it has to start at zero): calls on one GPU must be ordered on one stream, or
+ * otherwise not overlap; calls that overlap on one GPU race. */
+#define HA_STATIC_SCRATCH_MIB 64
+size_t hybrid_attn_static_scratch_bytes(void);
+ha_status hybrid_attn_forward_static(const ha_problem *p, const void *q, const void *k, const void *v,
+                                     const ha_feature_map *phi_q, const ha_feature_map *phi_k,
+                                     void *out, void *hip_stream);
+
 /* Debug / test taps into the same pipeline: run only the key-side passes (weight re-ordering,
  * softmax-key compaction, state pass) and copy the reduced state out in plain layout.
  * state_S: device fp32 [B, H, F, d_head]; state_z: device fp32 [B, H, F]. */

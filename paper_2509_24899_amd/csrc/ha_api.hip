@@ -2,6 +2,7 @@
 // sequence.  Nothing here touches the device except through the launchers and hipMemcpyAsync.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "ha_plan.h"
 
@@ -258,6 +259,55 @@ ha_status hybrid_attn_forward(const ha_problem *p, const void *q, const void *k,
                               const ha_feature_map *phi_q, const ha_feature_map *phi_k, void *out, void *workspace,
                               size_t workspace_bytes, void *hip_stream) {
   return forward_impl(p, q, k, v, phi_q, phi_k, out, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Forward without a caller workspace and without any allocation: the scratch is a file-scope device array.
+// In host code the array's name only stands for the symbol; its device address (one per GPU, each GPU holds its
+// own copy) is looked up once per device and kept.
+namespace ha {
+constexpr size_t kStaticScratchBytes = (size_t)HA_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up at the first call on that device).
+static hipError_t static_scratch(void **ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace ha
+
+size_t hybrid_attn_static_scratch_bytes(void) { return ha::kStaticScratchBytes; }
+
+ha_status hybrid_attn_forward_static(const ha_problem *p, const void *q, const void *k, const void *v,
+                                     const ha_feature_map *phi_q, const ha_feature_map *phi_k, void *out,
+                                     void *hip_stream) {
+  ha_status s = ha::validate(p, phi_q, phi_k);
+  if (s != HA_OK) return s;
+  ha::Plan pl;
+  ha::WidePlan wp;
+  bool wide;
+  // the size check is host arithmetic: a problem beyond the static array is refused before any HIP call
+  if (ha::full_plan(*p, phi_q, phi_k, pl, wp, wide) > ha::kStaticScratchBytes) return HA_ERR_WORKSPACE;
+  if (!q || !k || !v || !out) return HA_ERR_NULL;
+  void *ws = nullptr;
+  hipError_t e = ha::static_scratch(&ws);
+  if (e != hipSuccess) return ha::device_error(e);
+  return forward_impl(p, q, k, v, phi_q, phi_k, out, nullptr, ws, ha::kStaticScratchBytes, hip_stream);
 }
 
 ha_status hybrid_attn_profile_enable(int n_records) {
@@ -530,6 +580,6 @@ const char *hybrid_attn_status_string(ha_status s) {
 
 int hybrid_attn_last_device_error(void) { return ha::g_last_device_error; }
 
-int hybrid_attn_abi_version(void) { return 6; }
+int hybrid_attn_abi_version(void) { return 7; }
 
 }  // extern "C"

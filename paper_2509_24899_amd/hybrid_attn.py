@@ -79,6 +79,10 @@ def _lib():
         lib.hybrid_attn_workspace_bytes.restype = ctypes.c_size_t
         lib.hybrid_attn_forward.argtypes = [P, vp, vp, vp, FM, FM, vp, vp, ctypes.c_size_t, vp]
         lib.hybrid_attn_forward.restype = ctypes.c_int
+        lib.hybrid_attn_forward_static.argtypes = [P, vp, vp, vp, FM, FM, vp, vp]
+        lib.hybrid_attn_forward_static.restype = ctypes.c_int
+        lib.hybrid_attn_static_scratch_bytes.argtypes = []
+        lib.hybrid_attn_static_scratch_bytes.restype = ctypes.c_size_t
         lib.hybrid_attn_linear_state.argtypes = [P, vp, vp, FM, vp, vp, vp, ctypes.c_size_t, vp]
         lib.hybrid_attn_linear_state.restype = ctypes.c_int
         lib.hybrid_attn_status_string.argtypes = [ctypes.c_int]
@@ -307,6 +311,29 @@ def hybrid_attn_forward(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[Fe
         raise HybridAttnError(st, "hybrid_attn_forward")
     return out
 
+
+
+def hybrid_attn_static_scratch_bytes() -> int:
+    return _lib().hybrid_attn_static_scratch_bytes()
+
+
+def hybrid_attn_forward_static(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[FeatureMap], hybrid_rate: int,
+                               out, block_size: int = 128, softmax_scale: Optional[float] = None, stream=None):
+    """hybrid_attn_forward for callers that cannot allocate: the library's static device array is the workspace and
+    `out` is the caller's.  Nothing is allocated here or in the library.  Does not synchronise."""
+    _require_gpu(q, k, v, out)
+    if softmax_scale is None:
+        softmax_scale = float(q.shape[-1]) ** -0.5
+    _same_layout(q, k, v, out)
+    prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
+    sq, pq = _fm_ptr(phi_q)
+    sk, pk = _fm_ptr(phi_k)
+    stream_handle = (stream if stream is not None else torch.cuda.current_stream(q.device)).cuda_stream
+    st = _lib().hybrid_attn_forward_static(ctypes.byref(prob), q.data_ptr(), k.data_ptr(), v.data_ptr(), pq, pk,
+                                           out.data_ptr(), stream_handle)
+    if st != HA_OK:
+        raise HybridAttnError(st, "hybrid_attn_forward_static")
+    return out
 
 
 def hybrid_attn_value_distill_loss(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[FeatureMap], hybrid_rate: int,

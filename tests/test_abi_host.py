@@ -35,10 +35,10 @@ def test_header_symbols_are_exported(lib):
     text = open(os.path.join(ROOT, "include", "hybrid_attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(hybrid_attn_\w+)\s*\(", text)
-    assert len(set(names)) == 17
+    assert len(set(names)) == 19
     for n in set(names):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert ha.hybrid_attn_abi_version() == 6
+    assert ha.hybrid_attn_abi_version() == 7
 
 
 def test_struct_layout_matches_header():
