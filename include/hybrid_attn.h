@@ -10,7 +10,7 @@
  *
  *    S = sum_{j in T_L} phi_k(k_j)^T v_j  (F x d),   z = sum_{j in T_L} phi_k(k_j)  (F),
  *
- * T_S = every R-th token starting with the first (Sec. 3.2: 1-indexed "i mod R = 1"),
+ * T_S = every R-th token starting with the first (the stride rule of Sec. 3.2, stated there on 1-indexed tokens),
  * T_L = the other tokens, c_i = max_{j in T_S} scale q_i.k_j (it stabilises the softmax terms
  * only, exactly as the equation is printed), and phi the polynomial feature map of Sec. 3.2
  * ("Characterization of phi"): per-head 2-layer MLP with ReLU, a positive output activation,
@@ -50,8 +50,8 @@ typedef enum { HA_BF16 = 0, HA_F32 = 1 } ha_dtype;
  * all F output channels of one token and head, before the slice / power step. */
 typedef enum { HA_ACT_SOFTMAX = 0, HA_ACT_EXP = 1, HA_ACT_RELU = 2 } ha_act;
 
-/* One feature map (phi_q or phi_k).  Weights are per head and shared over the batch
- * (Sec. 3.2: "per-head embedding network ... grouped 1x1 convolutions").
+/* One feature map (phi_q or phi_k): the per-head map of Sec. 3.2 ("Characterization of phi"), one set of weights
+ * per head, shared over the batch.
  *   hidden = relu(W1 x + b1),  u = W2 hidden + b2,  t = act(u),
  *   phi(x)[c] = t[c] ^ (1 + c / (F / P))          (integer division: slice p gets power p).
  * Three-layer map (Tab. "phi", the P = 6 row): with w_mid != NULL, hidden2 = relu(W_mid hidden + b_mid) sits

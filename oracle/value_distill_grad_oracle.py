@@ -134,6 +134,49 @@ def head_gradients(q, k, v, phi_q, phi_k, head, R, scale, sign=None):
     return gq, gk, float(np.abs(y - y_hat).sum())
 
 
+def head_gradients_by_row_chunks(q, k, v, phi_q, phi_k, head, R, scale, sign=None, rows_per_chunk=2048):
+    """head_gradients for sequences too long to hold the N x N_S weights at once.  Every sum over the query tokens i
+    (the state gradients dS, dz and the parameter gradients of phi_q) is a plain sum of per-row terms, so the rows are
+    taken `rows_per_chunk` at a time and their contributions added up; S, z and the key-side chain are as in
+    head_gradients.  Same return value; with `sign` given the teacher is not evaluated and the loss is None.
+    Pinned against head_gradients on small inputs with chunk lengths that do and do not divide N."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    N, d = q.shape
+    _, idx_l = O.token_split(N, R)
+    if idx_l.size == 0:
+        return head_gradients(q, k, v, phi_q, phi_k, head, R, scale, sign)
+    fk = O.feature_map(k[idx_l], phi_k, head)
+    S = fk.T @ v[idx_l]
+    z = fk.sum(axis=0)
+    dS = np.zeros_like(S)
+    dz = np.zeros_like(z)
+    gq = None
+    loss = 0.0 if sign is None else None
+    for lo in range(0, N, rows_per_chunk):
+        rows = slice(lo, min(lo + rows_per_chunk, N))
+        a, l, _ = O.softmax_part(q[rows], k, v, R, scale)
+        fq = O.feature_map(q[rows], phi_q, head)
+        den = l + fq @ z
+        y_hat = (a + fq @ S) / den[:, None]
+        if sign is None:
+            a_t, l_t, _ = O.softmax_part(q[rows], k, v, 1, scale)
+            y = a_t / l_t[:, None]
+            g = np.sign(y_hat - y)
+            loss += float(np.abs(y - y_hat).sum())
+        else:
+            g = np.asarray(sign[rows], dtype=np.float64)
+        dnum = g / den[:, None]
+        dden = -(g * y_hat).sum(axis=1) / den
+        dS += fq.T @ dnum
+        dz += fq.T @ dden
+        part = feature_map_backward(q[rows], phi_q, head, dnum @ S.T + dden[:, None] * z[None, :])
+        gq = part if gq is None else tuple(x + y_ for x, y_ in zip(gq, part))
+    gk = feature_map_backward(k[idx_l], phi_k, head, v[idx_l] @ dS.T + dz[None, :])
+    return gq, gk, loss
+
+
 def value_distill_grad(q, k, v, phi_q, phi_k, R, scale, sign_from=None):
     """Gradient of the value-distillation loss for q, k, v [B, H, N, d].
 

@@ -48,5 +48,42 @@ def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PAT
     return out_path
 
 
+# Host-side sanitizer build (AddressSanitizer + UndefinedBehaviorSanitizer on the CPU code only; the device code is
+# compiled as always).  The sources whose host code does real work (argument validation, workspace planning, the
+# block-rate dynamic programme) are instrumented; the others are linked from the regular objects.
+SANITIZED = ("ha_api.hip", "ha_select.hip")
+SANITIZER_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+                   "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+SANITIZED_LIB_PATH = os.path.join(LIB_DIR, "libhybridattn_san.so")
+
+
+def asan_runtime() -> str:
+    """Path of the shared AddressSanitizer runtime of the compiler that hipcc drives (to be preloaded into an
+    uninstrumented host program such as python)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = subprocess.run([hipcc, "-print-file-name=libclang_rt.asan-x86_64.so"], check=True, capture_output=True, text=True)
+    return out.stdout.strip()
+
+
+def build_sanitized_host_library() -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(LIB_DIR, exist_ok=True)
+    plain = [os.path.join(LIB_DIR, s.replace(".hip", ".o")) for s in SOURCES if s not in SANITIZED]
+    if not all(os.path.exists(o) for o in plain):
+        build_library()
+    objs, procs = list(plain), []
+    for src in SANITIZED:
+        obj = os.path.join(LIB_DIR, src.replace(".hip", "_san.o"))
+        cmd = [hipcc, *HIPCC_FLAGS, *FILE_FLAGS.get(src, []), *SANITIZER_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    for src, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized) failed on {src}:\n{out}")
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", SANITIZED_LIB_PATH], check=True)
+    return SANITIZED_LIB_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose="-v" in sys.argv))

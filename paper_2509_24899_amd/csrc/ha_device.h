@@ -61,16 +61,17 @@ static __device__ __forceinline__ bf16x8 load8(const void *base, int64_t elem_of
   }
 }
 
-// Linear-token index -> token index: the tokens with j % R != 0 in increasing order (R = 0: all),
-// i.e. i + i / (R - 1) + 1.  The quotient comes from a float reciprocal plus one correction step
-// (exact for i < 2^23).
+// Linear-token index -> token index: the tokens outside the softmax set in increasing order (R = 0: all).  With
+// groups of G tokens, every R-th group being softmax tokens, linear token i lies in group-of-R-groups i / ((R - 1) G)
+// and i + (that quotient + 1) G is its token index.  The quotient is exact for every int32 i: a double-precision
+// reciprocal puts the estimate within one of the true floor, and one correction step settles it.
 struct LinearMap {
   int d;        // (R - 1) G linear tokens per group of R G tokens, or a huge divisor when R == 0
   int g;        // G softmax tokens lead every group; 0 if R == 0
-  float rcp;
-  __device__ __forceinline__ LinearMap(int R, int G) : d(R == 0 ? 0x7fffffff : (R - 1) * G), g(R != 0 ? G : 0), rcp(1.0f / (float)d) {}
+  double rcp;
+  __device__ __forceinline__ LinearMap(int R, int G) : d(R == 0 ? 0x7fffffff : (R - 1) * G), g(R != 0 ? G : 0), rcp(1.0 / (double)d) {}
   __device__ __forceinline__ int token(int i) const {
-    int q = (int)((float)i * rcp);
+    int q = (int)((double)i * rcp);
     int rem = i - q * d;
     q += (rem >= d) - (rem < 0);
     return i + (q + 1) * g;

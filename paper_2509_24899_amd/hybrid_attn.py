@@ -6,7 +6,10 @@ library is not built, or no GPU is present, calls raise.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
+import functools
+import inspect
 import os
 from dataclasses import dataclass
 from typing import Optional
@@ -136,6 +139,32 @@ class FeatureMap:
     w_mid: Optional[torch.Tensor] = None
     b_mid: Optional[torch.Tensor] = None
 
+    def check(self, H: int, d_head: int, dtype, device) -> None:
+        """The C ABI reads these tensors through raw pointers with the shapes and dtype it derives from the problem;
+        a mismatch would be garbage or an out-of-bounds device read, so every dimension, dtype and device is checked
+        here against the problem's (H heads of width d_head, io dtype, device of q)."""
+        def need(cond, what):
+            if not cond:
+                raise ValueError(f"feature map does not match the problem: {what}")
+        Hd = self.w1.shape[1] if self.w1.dim() == 3 else -1
+        need(self.w1.dim() == 3 and tuple(self.w1.shape) == (H, Hd, d_head), f"w1 must be [H={H}, d_hidden, d_head={d_head}], got {tuple(self.w1.shape)}")
+        kl = Hd
+        if self.w_mid is not None:
+            need(self.w_mid.dim() == 3 and tuple(self.w_mid.shape[::2]) == (H, Hd), f"w_mid must be [H={H}, d_mid, d_hidden={Hd}], got {tuple(self.w_mid.shape)}")
+            kl = self.w_mid.shape[1]
+        need(self.w2.dim() == 3 and self.w2.shape[0] == H and self.w2.shape[2] == kl, f"w2 must be [H={H}, d_out, {kl}], got {tuple(self.w2.shape)}")
+        F = self.w2.shape[1]
+        for name, b, width in (("b1", self.b1, Hd), ("b2", self.b2, F), ("b_mid", self.b_mid, kl)):
+            if b is not None:
+                need(name != "b_mid" or self.w_mid is not None, "b_mid given without w_mid")
+                need(tuple(b.shape) == (H, width), f"{name} must be [H={H}, {width}], got {tuple(b.shape)}")
+                need(b.device == device, f"{name} is on {b.device}, q on {device}")
+        for name, t in (("w1", self.w1), ("w2", self.w2), ("w_mid", self.w_mid)):
+            if t is not None:
+                need(t.dtype == dtype, f"{name} is {t.dtype}, q is {dtype}")
+                need(t.device == device, f"{name} is on {t.device}, q on {device}")
+        need(self.poly_degree >= 1 and F % self.poly_degree == 0, f"poly_degree {self.poly_degree} must divide d_out {F}")
+
     def c_struct(self) -> ha_feature_map:
         for t in (self.w1, self.w2, self.w_mid):
             if t is not None and not t.is_contiguous():
@@ -179,11 +208,33 @@ def make_problem(q: torch.Tensor, hybrid_rate, block_size: int, softmax_scale: f
                       q.stride(0), q.stride(1), q.stride(2), int(granularity), int(causal), int(window), 0)
 
 
-def _fm_ptr(fm):
+def _fm_ptr(fm, like=None):
+    """(struct, pointer) of a feature map for the C ABI; with `like` (the q or k tensor of the call) a FeatureMap is
+    first checked against its heads, head width, dtype and device."""
     if fm is None:
         return None, None
+    if isinstance(fm, FeatureMap) and like is not None:
+        fm.check(like.shape[1], like.shape[3], like.dtype, like.device)
     s = fm.c_struct() if isinstance(fm, FeatureMap) else fm
     return s, ctypes.byref(s)
+
+
+def _allocations_follow_stream(fn):
+    """Runs `fn` with its `stream` argument (if given) as torch's current stream, see _alloc_on."""
+    sig = inspect.signature(fn)
+
+    @functools.wraps(fn)
+    def wrapper(*args, **kwargs):
+        with _alloc_on(sig.bind(*args, **kwargs).arguments.get("stream")):
+            return fn(*args, **kwargs)
+    return wrapper
+
+
+def _alloc_on(stream):
+    """Context for the binding's own allocations: with an explicit stream they are made under it, so that torch's
+    caching allocator ties the block to the stream the kernels run on (a block allocated under another stream could be
+    handed out again while they still run)."""
+    return torch.cuda.stream(stream) if stream is not None else contextlib.nullcontext()
 
 
 def hybrid_attn_validate(problem: ha_problem, phi_q=None, phi_k=None) -> int:
@@ -291,18 +342,20 @@ def hybrid_attn_forward(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[Fe
     if softmax_scale is None:
         softmax_scale = float(q.shape[-1]) ** -0.5
     if out is None:
-        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        with _alloc_on(stream):
+            out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     _same_layout(q, k, v, out)
     prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
-    sq, pq = _fm_ptr(phi_q)
-    sk, pk = _fm_ptr(phi_k)
+    sq, pq = _fm_ptr(phi_q, q)
+    sk, pk = _fm_ptr(phi_k, q)
     lib = _lib()
     st = lib.hybrid_attn_validate(ctypes.byref(prob), pq, pk)
     if st != HA_OK:
         raise HybridAttnError(st, "hybrid_attn_validate")
     need = lib.hybrid_attn_workspace_bytes(ctypes.byref(prob), pq, pk)
     if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        with _alloc_on(stream):
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     stream_handle = (stream if stream is not None else torch.cuda.current_stream(q.device)).cuda_stream
     st = lib.hybrid_attn_forward(ctypes.byref(prob), q.data_ptr(), k.data_ptr(), v.data_ptr(), pq, pk,
                                  out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
@@ -326,8 +379,8 @@ def hybrid_attn_forward_static(q, k, v, phi_q: Optional[FeatureMap], phi_k: Opti
         softmax_scale = float(q.shape[-1]) ** -0.5
     _same_layout(q, k, v, out)
     prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
-    sq, pq = _fm_ptr(phi_q)
-    sk, pk = _fm_ptr(phi_k)
+    sq, pq = _fm_ptr(phi_q, q)
+    sk, pk = _fm_ptr(phi_k, q)
     stream_handle = (stream if stream is not None else torch.cuda.current_stream(q.device)).cuda_stream
     st = _lib().hybrid_attn_forward_static(ctypes.byref(prob), q.data_ptr(), k.data_ptr(), v.data_ptr(), pq, pk,
                                            out.data_ptr(), stream_handle)
@@ -336,6 +389,7 @@ def hybrid_attn_forward_static(q, k, v, phi_q: Optional[FeatureMap], phi_k: Opti
     return out
 
 
+@_allocations_follow_stream
 def hybrid_attn_value_distill_loss(q, k, v, phi_q: Optional[FeatureMap], phi_k: Optional[FeatureMap], hybrid_rate: int,
                                    block_size: int = 128, softmax_scale: Optional[float] = None, y_teacher=None,
                                    teacher_is_cached: bool = False, y_student=None, workspace=None, stream=None):
@@ -353,8 +407,8 @@ def hybrid_attn_value_distill_loss(q, k, v, phi_q: Optional[FeatureMap], phi_k: 
         y_student = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     _same_layout(q, k, v, y_teacher, y_student)
     prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
-    sq, pq = _fm_ptr(phi_q)
-    sk, pk = _fm_ptr(phi_k)
+    sq, pq = _fm_ptr(phi_q, q)
+    sk, pk = _fm_ptr(phi_k, q)
     lib = _lib()
     st = lib.hybrid_attn_validate(ctypes.byref(prob), pq, pk)
     if st != HA_OK:
@@ -373,6 +427,7 @@ def hybrid_attn_value_distill_loss(q, k, v, phi_q: Optional[FeatureMap], phi_k: 
     return loss, y_teacher, y_student
 
 
+@_allocations_follow_stream
 def hybrid_attn_value_distill_grad(q, k, v, phi_q: FeatureMap, phi_k: FeatureMap, hybrid_rate: int, block_size: int = 128,
                                    softmax_scale: Optional[float] = None, y_teacher=None, teacher_is_cached: bool = False,
                                    y_student=None, row_den=None, student_is_cached: bool = False, workspace=None,
@@ -397,8 +452,8 @@ def hybrid_attn_value_distill_grad(q, k, v, phi_q: FeatureMap, phi_k: FeatureMap
         raise ValueError("row_den must be a contiguous fp32 tensor [B, H, N]")
     _same_layout(q, k, v, y_teacher, y_student)
     prob = make_problem(q, hybrid_rate, block_size, softmax_scale)
-    sq, pq = _fm_ptr(phi_q)
-    sk, pk = _fm_ptr(phi_k)
+    sq, pq = _fm_ptr(phi_q, q)
+    sk, pk = _fm_ptr(phi_k, q)
     lib = _lib()
     need = lib.hybrid_attn_value_distill_grad_workspace_bytes(ctypes.byref(prob), pq, pk)
     if workspace is None:
@@ -454,13 +509,14 @@ def hybrid_attn_param_update(master, grad, lr: float, kind: int = HA_OPT_SGD, m=
         raise HybridAttnError(st, "hybrid_attn_param_update")
 
 
+@_allocations_follow_stream
 def hybrid_attn_linear_state(k, v, phi_k: FeatureMap, hybrid_rate: int, block_size: int = 128, workspace=None,
                              stream=None):
     """Key-side passes only: returns (S [B, H, F, d], z [B, H, F]) in fp32 (test tap)."""
     _require_gpu(k, v)
     _same_layout(k, v)
     prob = make_problem(k, hybrid_rate, block_size, 1.0)
-    sk, pk = _fm_ptr(phi_k)
+    sk, pk = _fm_ptr(phi_k, k)
     lib = _lib()
     need = lib.hybrid_attn_workspace_bytes(ctypes.byref(prob), pk, pk)
     if need == 0:
@@ -492,3 +548,13 @@ def to_device(inputs, device="cuda"):
                           p.poly_degree, w_mid=dev(mid, dt) if mid is not None else None,
                           b_mid=dev(p.b_mid, torch.float32) if mid is not None else None)
     return dev(inputs.q, dt), dev(inputs.k, dt), dev(inputs.v, dt), fm(inputs.phi_q), fm(inputs.phi_k)
+
+
+def device_inputs(w, device="cuda"):
+    """workloads.make_inputs_on_device as (q, k, v, FeatureMap phi_q, FeatureMap phi_k)."""
+    from . import workloads as W
+    q, k, v, mq, mk = W.make_inputs_on_device(w, device)
+
+    def fm(m):
+        return FeatureMap(m["w1"], m["b1"], m["w2"], m["b2"], w.poly_degree, w_mid=m.get("w_mid"), b_mid=m.get("b_mid"))
+    return q, k, v, fm(mq), fm(mk)

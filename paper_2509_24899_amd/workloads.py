@@ -146,6 +146,31 @@ def make_inputs(w: Workload, heads: Optional[int] = None) -> Inputs:
     return Inputs(q, k, v, phi_q, phi_k, replace(w, H=H))
 
 
+def make_inputs_on_device(w: Workload, device="cuda"):
+    """The same distributions drawn on the device with a seeded torch.Generator (seed = w.seed), for workloads too
+    large to draw on the host (the 720p stack: 1.9 GB per layer): q, k, v in the io dtype, then the tensors of phi_q
+    and of phi_k as dicts (w1, b1, w2, b2[, w_mid, b_mid]), in that order from one generator.  Benchmarks and parity
+    tests both call this, so both see the same tensors."""
+    import torch
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    gen = torch.Generator(device=device).manual_seed(w.seed)
+    s = w.qk_gain * w.d ** -0.5
+    q, k = ((torch.randn(w.B, w.H, w.N, w.d, generator=gen, device=device, dtype=torch.float32) * s).to(dt) for _ in range(2))
+    v = (torch.randn(w.B, w.H, w.N, w.d, generator=gen, device=device, dtype=torch.float32) * w.d ** -0.5).to(dt)
+
+    def draw_map():
+        kl = w.d_mid if w.d_mid else w.d_hidden
+        m = dict(w1=(torch.randn(w.H, w.d_hidden, w.d, generator=gen, device=device) * (w.w_gain * w.d ** -0.5)).to(dt),
+                 b1=torch.randn(w.H, w.d_hidden, generator=gen, device=device) * 0.1,
+                 w2=(torch.randn(w.H, w.d_feat, kl, generator=gen, device=device) * (w.w_gain * kl ** -0.5)).to(dt),
+                 b2=torch.randn(w.H, w.d_feat, generator=gen, device=device) * 0.1)
+        if w.d_mid:
+            m["w_mid"] = (torch.randn(w.H, w.d_mid, w.d_hidden, generator=gen, device=device) * (w.w_gain * w.d_hidden ** -0.5)).to(dt)
+            m["b_mid"] = torch.randn(w.H, w.d_mid, generator=gen, device=device) * 0.1
+        return m
+    return q, k, v, draw_map(), draw_map()
+
+
 def sample_rows(w: Workload, n_random: int = 256, seed: int = 12345) -> np.ndarray:
     """Query rows for sampled parity at sizes the oracle cannot cover in full: the first tile,
     the ragged tail tile, both sides of every 16th tile boundary, and n_random random rows."""

@@ -304,3 +304,45 @@ def test_param_update_host_errors(lib):
     assert f(opt(), 8, A[0], A[1], A[2], A[3], A[4] + 2, ha.HA_F32, None) == ha.HA_ERR_ALIGN
     assert f(opt(), 8, A[0], A[1], A[2], A[3], A[0], ha.HA_F32, None) == ha.HA_ERR_SHAPE
     assert f(opt(), 0, A[0], A[1], A[2], A[3], A[4], ha.HA_BF16, None) == ha.HA_OK                 # nothing to do, nothing enqueued
+
+
+# ---------------------------------------------------------------- binding-side checks of the feature-map tensors
+
+def _cpu_map(H=3, d=128, Hd=128, F=128, dtype=None, mid=0):
+    import torch
+    dtype = dtype or torch.bfloat16
+    kl = mid or Hd
+    return ha.FeatureMap(torch.zeros(H, Hd, d, dtype=dtype), torch.zeros(H, Hd), torch.zeros(H, F, kl, dtype=dtype), torch.zeros(H, F), 2,
+                         w_mid=torch.zeros(H, mid, Hd, dtype=dtype) if mid else None, b_mid=torch.zeros(H, mid) if mid else None)
+
+
+def test_binding_checks_feature_map_tensors_against_the_problem():
+    """The C ABI reads the weights through raw pointers: the binding must refuse tensors whose dtype, heads, widths or
+    device differ from what the library will assume (host-only: CPU tensors, nothing is launched)."""
+    import torch
+    cpu = torch.device("cpu")
+    _cpu_map().check(3, 128, torch.bfloat16, cpu)
+    _cpu_map(Hd=256, F=256).check(3, 128, torch.bfloat16, cpu)
+    _cpu_map(Hd=768, F=768, mid=768).check(3, 128, torch.bfloat16, cpu)
+    bad = [
+        (_cpu_map(dtype=torch.float32), "fp32 weights with bf16 q"),
+        (_cpu_map(H=2), "maps for fewer heads"),
+        (_cpu_map(d=64), "w1 inner width != d_head"),
+    ]
+    m = _cpu_map(); m.w2 = torch.zeros(3, 128, 64, dtype=torch.bfloat16); bad.append((m, "w2 inner width != d_hidden"))
+    m = _cpu_map(); m.b1 = torch.zeros(3, 64); bad.append((m, "b1 too short"))
+    m = _cpu_map(); m.b2 = torch.zeros(2, 128); bad.append((m, "b2 for fewer heads"))
+    m = _cpu_map(mid=256); m.w2 = torch.zeros(3, 128, 128, dtype=torch.bfloat16); bad.append((m, "w2 inner width != d_mid"))
+    m = _cpu_map(); m.b_mid = torch.zeros(3, 128); bad.append((m, "b_mid without w_mid"))
+    m = _cpu_map(); m.poly_degree = 3; bad.append((m, "P does not divide F"))
+    m = _cpu_map(); m.w1 = torch.zeros(3, 128 * 128, dtype=torch.bfloat16); bad.append((m, "w1 not 3-d"))
+    for fm, why in bad:
+        with pytest.raises(ValueError):
+            fm.check(3, 128, torch.bfloat16, cpu)
+            pytest.fail(why)
+    with pytest.raises(ValueError):
+        _cpu_map().check(3, 128, torch.bfloat16, torch.device("meta"))
+    # the entry points run the check before anything else that touches the library's compute calls
+    q = torch.zeros(1, 3, 16, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        ha._fm_ptr(_cpu_map(H=2), q)

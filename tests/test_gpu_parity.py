@@ -1,8 +1,13 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
 
-Bar (both must hold): max |y_gpu - y_ref| <= 2e-2 and ||y_gpu - y_ref||_2 / ||y_ref||_2 <= 5e-3
-for bf16 inputs with fp32 accumulation.  With the benchmark distributions the outputs are O(1e-3),
-so the relative L2 bound is the binding one; the stress sets make the max / rescale paths matter.
+Bar (all must hold): max |y_gpu - y_ref| <= 2e-2 and ||y_gpu - y_ref||_2 / ||y_ref||_2 <= 5e-3
+for bf16 inputs with fp32 accumulation, and, row by row, ||y_gpu[i] - y_ref[i]||_2 / ||y_ref[i]||_2 <= 2e-2.
+With the benchmark distributions the outputs are O(1e-3), so the global max-abs never binds and one wrong row among
+thousands moves the global relative L2 by ~1e-3 only: the per-row bound is what catches a tail or mask mistake
+that spoils a single row.  Its value: a row's error is dominated by the bf16 rounding of the output (<= 2^-9 per
+element), of the softmax weights and of phi (2^-9 each, averaged over many terms), about 2e-3 r.m.s. and 4e-3 at
+the worst row of a sample; rows whose value nearly cancels (norm far below the values that were averaged) lose
+relative accuracy in proportion, hence the factor of five of margin.
 """
 import json
 import os
@@ -18,6 +23,7 @@ from paper_2509_24899_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 MAX_ABS, REL_L2 = 2e-2, 5e-3
+ROW_REL_L2 = 2e-2
 LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "parity_metrics.jsonl")
 
 
@@ -28,6 +34,16 @@ def oracle_map(p, act=O.ACT_SOFTMAX):
 def metrics(y_gpu, y_ref):
     diff = y_gpu.astype(np.float64) - y_ref
     return float(np.abs(diff).max()), float(np.linalg.norm(diff) / max(np.linalg.norm(y_ref), 1e-300))
+
+
+def worst_row(y_gpu, y_ref):
+    """Largest per-row relative L2 error over [..., rows, d] arrays, and where."""
+    diff = y_gpu.astype(np.float64) - y_ref
+    num = np.linalg.norm(diff, axis=-1)
+    den = np.maximum(np.linalg.norm(y_ref, axis=-1), 1e-300)
+    rel = num / den
+    i = int(np.argmax(rel))
+    return float(rel.reshape(-1)[i]), tuple(int(x) for x in np.unravel_index(i, rel.shape))
 
 
 def record(name, max_abs, rel_l2, **extra):
@@ -53,7 +69,8 @@ def gpu_forward(inp, R=None, block_size=None, act=ha.HA_ACT_SOFTMAX, layout="bhn
     return out.float().cpu().numpy()
 
 
-def check(name, inp, R=None, block_size=None, rows=None, act=ha.HA_ACT_SOFTMAX, layout="bhnd", tol=(MAX_ABS, REL_L2)):
+def check(name, inp, R=None, block_size=None, rows=None, act=ha.HA_ACT_SOFTMAX, layout="bhnd", tol=(MAX_ABS, REL_L2),
+          row_tol=ROW_REL_L2):
     w = inp.workload
     R = w.R if R is None else R
     y = gpu_forward(inp, R, block_size, act, layout)
@@ -62,8 +79,10 @@ def check(name, inp, R=None, block_size=None, rows=None, act=ha.HA_ACT_SOFTMAX, 
         y = y[:, :, rows]
     assert np.isfinite(y).all(), f"{name}: non-finite output"
     ma, rl = metrics(y, ref)
-    record(name, ma, rl, R=R, block_size=block_size or w.block_size, N=w.N)
+    wr, where = worst_row(y, ref)
+    record(name, ma, rl, row_rel_l2=wr, R=R, block_size=block_size or w.block_size, N=w.N)
     assert ma <= tol[0] and rl <= tol[1], f"{name}: max_abs {ma:.3e} rel_l2 {rl:.3e}"
+    assert wr <= row_tol, f"{name}: row {where} (index into the compared rows) is off by {wr:.3e} relative L2"
     return y, ref
 
 
@@ -80,8 +99,7 @@ def test_rate_sweep_tiny(R):
     inp = W.make_inputs(W.TINY)
     y64, _ = check(f"cfg3_R{R}_bs64", inp, R=R, block_size=64)
     y128, _ = check(f"cfg3_R{R}_bs128", inp, R=R, block_size=128)
-    ma, rl = metrics(y64, y128.astype(np.float64))          # block size is a tiling knob only
-    assert rl <= 1e-4, (ma, rl)
+    assert np.array_equal(y64, y128)          # block size is a tiling knob only: same keys in the same order per query
 
 
 @pytest.mark.parametrize("R", (0, 1, 2, 3, 4, 5, 8, 16))
@@ -285,23 +303,13 @@ def test_config4_wan_480p_161f_sampled():
     _sampled("cfg4_N63960_R8", W.WAN_480P_161F, n_random=128)
 
 
-@pytest.mark.parametrize("layer", (0, 1, 2))
+@pytest.mark.parametrize("layer", (0, 1, 2, 27, 28, 29))
 def test_config5_stack_layer_sampled(layer):
-    """One layer of the 30-layer 720p stack (B = 2 for classifier-free guidance): rate cycles
-    16, 8, 4; inputs drawn on the device; oracle on two (batch, head) pairs and sampled rows."""
+    """Layers of the 30-layer 720p stack (B = 2 for classifier-free guidance): the first and the last rate triple
+    (rates cycle 16, 8, 4); inputs drawn on the device with the layer's seed 1000 + l, exactly as bench.py --stack draws
+    them; oracle on six (batch, head) pairs (both batch entries, first / middle / last heads) and sampled rows."""
     w = W.replace(W.WAN_720P_81F_CFG, R=W.STACK_RATES[layer % 3], seed=1000 + layer)
-    gen = torch.Generator(device="cuda").manual_seed(w.seed)
-    s = w.d ** -0.5
-    q, k, v = ((torch.randn(w.B, w.H, w.N, w.d, generator=gen, device="cuda", dtype=torch.float32) * s).to(torch.bfloat16)
-               for _ in range(3))
-
-    def dmap():
-        w1 = (torch.randn(w.H, w.d_hidden, w.d, generator=gen, device="cuda") * w.d ** -0.5).to(torch.bfloat16)
-        b1 = torch.randn(w.H, w.d_hidden, generator=gen, device="cuda") * 0.1
-        w2 = (torch.randn(w.H, w.d_feat, w.d_hidden, generator=gen, device="cuda") * w.d_hidden ** -0.5).to(torch.bfloat16)
-        b2 = torch.randn(w.H, w.d_feat, generator=gen, device="cuda") * 0.1
-        return ha.FeatureMap(w1, b1, w2, b2, w.poly_degree)
-    fq, fk = dmap(), dmap()
+    q, k, v, fq, fk = ha.device_inputs(w)
     out = ha.hybrid_attn_forward(q, k, v, fq, fk, w.R, w.block_size, w.scale)
     torch.cuda.synchronize()
     rows = W.sample_rows(w, 64)
@@ -310,13 +318,47 @@ def test_config5_stack_layer_sampled(layer):
         return O.FeatureMap(m.w1.float().cpu().numpy(), m.b1.cpu().numpy(), m.w2.float().cpu().numpy(),
                             m.b2.cpu().numpy(), m.poly_degree)
     oq, ok = host(fq), host(fk)
-    for (b, h) in ((0, 0), (1, w.H - 1)):
+    for (b, h) in ((0, 0), (0, 5), (0, w.H - 1), (1, 0), (1, 6), (1, w.H - 1)):
         ref = O.hybrid_attn_head(q[b, h].float().cpu().numpy(), k[b, h].float().cpu().numpy(),
                                  v[b, h].float().cpu().numpy(), oq, ok, h, w.R, w.scale, rows=rows)
         y = out[b, h].float().cpu().numpy()[rows]
         ma, rl = metrics(y, ref)
-        record(f"cfg5_layer{layer}_R{w.R}_b{b}h{h}", ma, rl)
-        assert ma <= MAX_ABS and rl <= REL_L2
+        wr, where = worst_row(y, ref)
+        record(f"cfg5_layer{layer}_R{w.R}_b{b}h{h}", ma, rl, row_rel_l2=wr)
+        assert ma <= MAX_ABS and rl <= REL_L2 and wr <= ROW_REL_L2, (b, h, ma, rl, wr, where)
+
+
+def test_linear_token_map_beyond_2_pow_23():
+    """Index arithmetic of the linear-token map far past 2^23 linear tokens in one head (the size up to which a
+    single-precision quotient is exact): 48 M tokens at rate 4, i.e. 36 M linear tokens.  A property that holds at any
+    size stands in for the oracle: every key row is the same vector, so phi_k(k_j) is one vector f for all j, and
+    channel 0 of v is 1 on the linear tokens and 0 on the softmax tokens.  Then column 0 of S accumulates exactly the
+    terms that z accumulates, in the same order: S[:, 0] == z bit for bit if and only if every row the state pass
+    read was a linear token; column 1 of v holds 1 on the softmax tokens instead, so S[:, 1] must be exactly 0."""
+    N, R, d = 48_000_003, 4, 64
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    row = (torch.randn(d, generator=gen, device="cuda") * d ** -0.5).to(torch.bfloat16)
+    k = row.expand(1, 1, N, d).contiguous()
+    v = torch.zeros(1, 1, N, d, dtype=torch.bfloat16, device="cuda")
+    is_softmax = (torch.arange(N, device="cuda") % R) == 0
+    v[0, 0, :, 0] = (~is_softmax).to(torch.bfloat16)
+    v[0, 0, :, 1] = is_softmax.to(torch.bfloat16)
+    fk = ha.FeatureMap((torch.randn(1, d, d, generator=gen, device="cuda") * d ** -0.5).to(torch.bfloat16),
+                       torch.randn(1, d, generator=gen, device="cuda") * 0.1,
+                       (torch.randn(1, d, d, generator=gen, device="cuda") * d ** -0.5).to(torch.bfloat16),
+                       torch.randn(1, d, generator=gen, device="cuda") * 0.1, 2)
+    S, z = ha.hybrid_attn_linear_state(k, v, fk, R)
+    torch.cuda.synchronize()
+    S, z = S[0, 0].cpu().numpy(), z[0, 0].cpu().numpy()
+    assert (z > 0).all()
+    assert np.array_equal(S[:, 0], z)
+    assert (S[:, 1] == 0).all() and (S[:, 2:] == 0).all()
+    # the sum itself: N_L copies of the bf16-rounded f, so z / N_L is f up to the fp32 accumulation
+    n_l = N - (N + R - 1) // R
+    f = O.feature_map(row.float().cpu().numpy()[None, :].astype(np.float64),
+                      O.FeatureMap(fk.w1.float().cpu().numpy(), fk.b1.cpu().numpy(), fk.w2.float().cpu().numpy(),
+                                   fk.b2.cpu().numpy(), 2), 0)[0]
+    assert np.abs(z / n_l - f).max() <= 5e-3 * f.max()
 
 
 def test_mfma_probe_runs_and_reports_its_flops():

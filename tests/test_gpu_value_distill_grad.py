@@ -172,6 +172,55 @@ def test_other_activations_and_no_biases():
         assert compare(f"act{act}_bias{int(with_bias)}", (gq, gk), want) <= GRAD_REL_L2
 
 
+def test_headline_shape_one_head_against_the_oracle():
+    """480p / 81 frames, R = 4, all 12 heads in the launch configuration bench.py times; the gradient of one head
+    against the oracle, tensor by tensor, at the bar of the small cases.  The oracle takes that head's query rows a
+    chunk at a time (the sums over query tokens are additive).  As in the small cases both sides take the one
+    discontinuous decision, sign(y_hat - y), from the same stored tensors: the oracle's teacher and student outputs
+    of that head rounded to bf16, and the oracle's row denominators, are written over the GPU's own before the
+    backward pass runs with both outputs cached."""
+    w = W.WAN_480P_81F
+    h = 5
+    inp = W.make_inputs(W.replace(w, seed=11))
+    q, k, v, dq, dk = ha.to_device(inp)
+    print("  case headline gradient against the oracle: GPU forward of all heads", flush=True)
+    _, _, _, yt, ys, rd = ha.hybrid_attn_value_distill_grad(q, k, v, dq, dk, w.R, w.block_size, w.scale)
+    torch.cuda.synchronize()
+    fq, fk = oracle_map(inp.phi_q), oracle_map(inp.phi_k)
+    print("  case headline gradient against the oracle: oracle forward of one head", flush=True)
+    qh, kh, vh = inp.q[0, h], inp.k[0, h], inp.v[0, h]
+    y = O.hybrid_attn_head(qh, kh, vh, None, None, h, 1, w.scale)
+    yh = O.hybrid_attn_head(qh, kh, vh, fq, fk, h, w.R, w.scale)
+    _, z = O.linear_state(kh, vh, fk, h, w.R)
+    den = np.empty(w.N)
+    for lo in range(0, w.N, 4096):
+        _, l, _ = O.softmax_part(qh[lo:lo + 4096], kh, vh, w.R, w.scale)
+        den[lo:lo + 4096] = l + O.feature_map(qh[lo:lo + 4096], fq, h) @ z
+    y_r, yh_r = round_io(y, w.dtype), round_io(yh, w.dtype)
+    # the GPU's own forward of that head is within the forward's bar of the oracle's (checked elsewhere on sampled rows)
+    assert float(np.linalg.norm(ys[0, h].float().cpu().numpy() - yh) / np.linalg.norm(yh)) <= 5e-3
+    yt[0, h] = torch.from_numpy(y_r).to(device="cuda", dtype=yt.dtype)
+    ys[0, h] = torch.from_numpy(yh_r).to(device="cuda", dtype=ys.dtype)
+    rd[0, h] = torch.from_numpy(den).to(device="cuda", dtype=torch.float32)
+    print("  case headline gradient against the oracle: GPU backward, both outputs cached", flush=True)
+    _, gq, gk, _, _, _ = ha.hybrid_attn_value_distill_grad(q, k, v, dq, dk, w.R, w.block_size, w.scale, y_teacher=yt,
+                                                          teacher_is_cached=True, y_student=ys, row_den=rd,
+                                                          student_is_cached=True)
+    torch.cuda.synchronize()
+    print("  case headline gradient against the oracle: oracle gradient of one head", flush=True)
+    want_q, want_k, _ = G.head_gradients_by_row_chunks(qh, kh, vh, fq, fk, h, w.R, w.scale, sign=np.sign(yh_r - y_r),
+                                                        rows_per_chunk=2048)
+    worst = 0.0
+    for side, g, want in (("q", gq, want_q), ("k", gk, want_k)):
+        for n, ref in zip(NAMES, want):
+            a = g[n][h].cpu().numpy().astype(np.float64)
+            assert a.shape == ref.shape and np.isfinite(a).all()
+            rel = float(np.linalg.norm(a - ref) / np.linalg.norm(ref))
+            record(f"vd_grad_headline_oracle_head{h}_phi_{side}.{n}", float(np.abs(a - ref).max()), rel, norm=float(np.linalg.norm(ref)))
+            worst = max(worst, rel)
+    assert worst <= GRAD_REL_L2
+
+
 def test_headline_shape_properties():
     """480p / 81 frames, R = 4, the launch configuration bench.py times.  The oracle cannot run a whole head at this
     length, so the gradient is held to what must hold at any size: (a) the second-layer bias gradient of a softmax

@@ -68,6 +68,33 @@ def pin_feature_map_is_grouped_conv(M):
             assert (got > 0).all()                        # phi must be non-negative (Sec. 3.1)
 
 
+@pytest.mark.parametrize("act", ("exp", "relu"))
+def test_alternate_output_activations_against_library_ops(act):
+    """The two optional output activations of the feature map (exp, ReLU) elementwise against torch: grouped 1x1
+    convolutions, torch.exp / torch.relu on the pre-activations, chunk / pow / cat for the P slices.  ReLU outputs may
+    be exactly zero, exp outputs are strictly positive; a swapped or missing branch fails the comparison."""
+    rng = np.random.default_rng(31)
+    H, d, Hd, n = 3, 6, 10, 17
+    code = {"exp": O.ACT_EXP, "relu": O.ACT_RELU}[act]
+    for P, F in ((1, 8), (2, 8), (3, 9)):
+        fm = O.FeatureMap(rng.standard_normal((H, Hd, d)) / np.sqrt(d), rng.standard_normal((H, Hd)) * 0.3,
+                          rng.standard_normal((H, F, Hd)) / np.sqrt(Hd), rng.standard_normal((H, F)) * 0.3, P, code)
+        x = rng.standard_normal((H, n, d))
+        xt = torch.from_numpy(x).permute(0, 2, 1).reshape(1, H * d, n)
+        conv = torch.nn.functional.conv1d
+        h1 = torch.relu(conv(xt, torch.from_numpy(fm.w1).reshape(H * Hd, d, 1), torch.from_numpy(fm.b1).reshape(-1), groups=H))
+        u = conv(h1, torch.from_numpy(fm.w2).reshape(H * F, Hd, 1), torch.from_numpy(fm.b2).reshape(-1), groups=H).reshape(H, F, n)
+        t = torch.exp(u) if act == "exp" else torch.relu(u)
+        ref = torch.cat([torch.pow(part, p + 1) for p, part in enumerate(torch.chunk(t, P, dim=1))], dim=1)
+        for h in range(H):
+            got = O.feature_map(x[h], fm, h)
+            np.testing.assert_allclose(got, ref[h].T.numpy(), rtol=1e-11, atol=1e-300)
+            assert (got > 0).all() if act == "exp" else ((got >= 0).all() and (got == 0).any())
+            # the three activations differ from one another on the same pre-activations
+            other = O.FeatureMap(fm.w1, fm.b1, fm.w2, fm.b2, P, O.ACT_SOFTMAX if act == "exp" else O.ACT_EXP)
+            assert not np.allclose(O.feature_map(x[h], other, h), got)
+
+
 def test_three_layer_feature_map_is_grouped_conv():
     """The three-layer map of Tab. "phi" (its P = 6 row): three grouped 1x1 convolutions with a ReLU after the
     first two, same output stage; and its parameter count through n_params() (15.4 M at d = 128, 12 heads)."""

@@ -141,6 +141,30 @@ def test_matches_central_finite_differences_of_the_loss():
                 assert abs(fd - grads[n][idx]) <= 2e-5 * max(1.0, abs(fd)), (n, idx, fd, grads[n][idx])
 
 
+@pytest.mark.parametrize("rows_per_chunk", (1, 4, 5, 13, 64))
+def test_row_chunked_driver_equals_the_whole_head(rows_per_chunk):
+    """head_gradients_by_row_chunks (rows taken a chunk at a time, for sequences whose N x N_S weights do not fit)
+    against head_gradients on the same head: every tensor and the loss to rounding, for chunk lengths that divide N,
+    that do not, of one row, and longer than N; with the sign pattern computed and handed in; R = 0, 1, 3."""
+    rng, (q, k, v) = _inputs(5, B=1, H=2, N=13, d=6)
+    fq, fk = _rand_map(rng, 2, 6, 7, 8, 2), _rand_map(rng, 2, 6, 7, 8, 2)
+    for R in (0, 1, 3):
+        for h in (0, 1):
+            want_q, want_k, want_loss = G.head_gradients(q[0, h], k[0, h], v[0, h], fq, fk, h, R, 0.4)
+            got_q, got_k, got_loss = G.head_gradients_by_row_chunks(q[0, h], k[0, h], v[0, h], fq, fk, h, R, 0.4,
+                                                                    rows_per_chunk=rows_per_chunk)
+            assert got_loss == pytest.approx(want_loss, rel=1e-12)
+            for a, b in zip(got_q + got_k, want_q + want_k):
+                np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-13)
+            sign = rng.choice([-1.0, 0.0, 1.0], size=q[0, h].shape)
+            want_q, want_k, _ = G.head_gradients(q[0, h], k[0, h], v[0, h], fq, fk, h, R, 0.4, sign)
+            got_q, got_k, none = G.head_gradients_by_row_chunks(q[0, h], k[0, h], v[0, h], fq, fk, h, R, 0.4, sign,
+                                                                rows_per_chunk=rows_per_chunk)
+            assert none is None or R == 1
+            for a, b in zip(got_q + got_k, want_q + want_k):
+                np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-13)
+
+
 def test_no_linear_tokens_no_gradient():
     """R = 1: T_L is empty, the student never evaluates phi, every gradient is exactly zero."""
     rng, (q, k, v) = _inputs(2)
