@@ -167,11 +167,11 @@ def head_gradients_by_row_chunks(q, k, v, phi_q, phi_k, head, R, scale, sign=Non
             loss += float(np.abs(y - y_hat).sum())
         else:
             g = np.asarray(sign[rows], dtype=np.float64)
-        dnum = g / den[:, None]
-        dden = -(g * y_hat).sum(axis=1) / den
-        dS += fq.T @ dnum
-        dz += fq.T @ dden
-        part = feature_map_backward(q[rows], phi_q, head, dnum @ S.T + dden[:, None] * z[None, :])
+        dnum_rows = g / den[:, None]
+        dden_rows = -(g * y_hat).sum(axis=1) / den
+        dS += fq.T @ dnum_rows
+        dz += fq.T @ dden_rows
+        part = feature_map_backward(q[rows], phi_q, head, dnum_rows @ S.T + dden_rows[:, None] * z[None, :])
         gq = part if gq is None else tuple(x + y_ for x, y_ in zip(gq, part))
     gk = feature_map_backward(k[idx_l], phi_k, head, v[idx_l] @ dS.T + dz[None, :])
     return gq, gk, loss
