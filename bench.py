@@ -37,12 +37,7 @@ def cpu_baseline(w, heads=12):
         O.hybrid_attn(inp.q, inp.k, inp.v, fq, fk, split, w.scale)
     t_sample = time.perf_counter() - t0
     t_full = t_sample * (w.B * w.H) / heads
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    return {"value": w.B * w.N / t_full, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+    return {"value": w.B * w.N / t_full, "unit": "tokens/s", "cores": host_threads(), "cpu_model": cpu_model(), "kind": "oracle",
             "sample": f"full fp64 oracle forward (all {w.N} rows, all keys) of {heads} of the {w.B * w.H} (batch, head) "
                       f"pairs: {t_sample:.1f} s, scaled to all pairs: {t_full:.1f} s per forward"}
 
@@ -217,6 +212,248 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
     print(json.dumps(rec), flush=True)
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def host_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        return max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        return os.cpu_count() or 1
+
+
+def load_inputs(w, ha, W, zero=False):
+    """Inputs resident in HBM.  One-batch workloads are drawn on the host from the numpy stream the parity tests use
+    (workloads.make_inputs, seed = w.seed), so bench and parity test see the same tensors; the B = 2 720p layers
+    (1.9 GB each) are drawn on the device by the generator their parity test uses (workloads.make_inputs_on_device)."""
+    if w.B == 1:
+        q, k, v, fq, fk = ha.to_device(W.make_inputs(w), "cuda:0")
+    else:
+        q, k, v, fq, fk = ha.device_inputs(w, "cuda:0")
+    if zero:
+        q.zero_(), k.zero_(), v.zero_()
+    if w.R == 1 and not w.local_window:
+        fq = fk = None
+    return q, k, v, fq, fk
+
+
+def query_kernel_flops(w, W):
+    """Algorithmic flops of the fused query kernel: 4 d per (query, softmax key) pair, the phi_q MLP and the contraction
+    with the state (the latter two only when the kernel evaluates phi_q itself)."""
+    n_l = w.N if w.local_window > 0 else w.n_linear
+    layered = n_l > 0 and (w.d_mid or not ((w.d_hidden == w.d and w.d_feat == w.d) or (w.d_hidden == 256 and w.d_feat == 256)))
+    fl = 4.0 * w.d * W.softmax_pairs(w)
+    if n_l > 0 and not layered:
+        fl += 2.0 * w.N * (w.d * w.d_hidden + w.d_hidden * w.d_feat) + 2.0 * w.N * w.d_feat * w.d + 2.0 * w.N * w.d_feat
+    return w.B * w.H * fl
+
+
+def mfma_probe_rates(ha, torch, dev):
+    """Sustained matrix-core rate of this device next to the published peak: a kernel of nothing but MFMA instructions,
+    run for a few hundred ms so that power management settles; operand values matter (zero operands keep the clock at
+    its ceiling, random ones do not).  Recorded beside every figure so that runs on different boxes can be compared."""
+    sink = torch.empty(torch.cuda.get_device_properties(0).multi_processor_count * 512, device=dev)
+    out = {}
+    for name, rnd in (("zero_operands", False), ("random_operands", True)):
+        ha.hybrid_attn_mfma_probe(rnd, 20000, 20, sink)          # settle
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fl = ha.hybrid_attn_mfma_probe(rnd, 20000, 60, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_tflops"] = fl * 60 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    # the zero-operand probe runs at the clock ceiling: its rate over the per-clock width gives that clock
+    out["clock_ghz_zero_operands"] = out["zero_operands_tflops"] * 1e12 / (256 * 4096) / 1e9
+    out["clock_ghz_random_operands"] = out["random_operands_tflops"] * 1e12 / (256 * 4096) / 1e9
+    return out
+
+
+def time_forward(ha, torch, step, steps, warmup):
+    """`warmup` untimed steps, then exactly `steps` timed ones between two synchronisations.  During the timed steps the
+    library records one pair of HIP events around the dominant kernel on the stream it is launched on (the light tap);
+    returns (wall ms per step, mean kernel ms, sorted per-step kernel ms)."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ha.hybrid_attn_profile_enable(-steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms = [ha.hybrid_attn_profile_read(i)[3] for i in range(steps)]
+    ha.hybrid_attn_profile_enable(0)
+    return elapsed * 1e3 / steps, sum(kernel_ms) / len(kernel_ms), sorted(kernel_ms)
+
+
+def stage_breakdown(ha, torch, step, steps):
+    """A second, untimed-for-the-headline pass with the full tap (five event records per forward): mean stage ms."""
+    ha.hybrid_attn_profile_enable(steps)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    rows = [ha.hybrid_attn_profile_read(i) for i in range(steps)]
+    ha.hybrid_attn_profile_enable(0)
+    mean = [sum(r[i] for r in rows) / len(rows) for i in range(5)]
+    fwd = sorted(r[4] for r in rows)
+    return mean, fwd
+
+
+def stack_mode(args, ha, W, torch):
+    """The 720p / 81-frame stack: 30 layers with B = 2 (classifier-free guidance), rates cycling 16, 8, 4, every layer
+    with its own seeded q, k, v and feature maps (seed 1000 + l), all resident in HBM (56 GB); one step = one pass over
+    the 30 layers; tokens/s = B N 30 / t."""
+    base = W.WAN_720P_81F_CFG
+    dev = "cuda:0"
+    layers = []
+    for l in range(W.STACK_LAYERS):
+        w = W.replace(base, R=W.STACK_RATES[l % len(W.STACK_RATES)], seed=1000 + l)
+        q, k, v, fq, fk = ha.device_inputs(w, dev)
+        layers.append((w, q, k, v, fq, fk, torch.empty_like(q)))
+    ws_bytes = max(ha.hybrid_attn_workspace_bytes(ha.make_problem(L[1], L[0].R, L[0].block_size, L[0].scale), L[4], L[5]) for L in layers)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def run_stack():
+        for (w, q, k, v, fq, fk, out) in layers:
+            ha.hybrid_attn_forward(q, k, v, fq, fk, w.R, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        run_stack()
+    torch.cuda.synchronize()
+    n_l = len(layers)
+    ha.hybrid_attn_profile_enable(-n_l * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_stack()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    k_ms = [ha.hybrid_attn_profile_read(i)[3] for i in range(n_l * args.steps)]
+    ha.hybrid_attn_profile_enable(0)
+    for L in layers:
+        assert torch.isfinite(L[6][:, :, ::997].float()).all().item(), "non-finite output"
+    ms_per_step = elapsed * 1e3 / args.steps
+    flops = sum(W.algorithmic_flops(L[0]) for L in layers)
+    kflops = sum(query_kernel_flops(L[0], W) for L in layers)
+    kernel_ms_per_stack = sum(k_ms) / args.steps
+    per_rate = {}
+    for i, ms in enumerate(k_ms):
+        per_rate.setdefault(str(layers[i % n_l][0].R), []).append(ms)
+    achieved = kflops / (kernel_ms_per_stack * 1e-3) / 1e12
+    probe = None if args.no_mfma_probe else mfma_probe_rates(ha, torch, dev)
+    rec = {
+        "metric": "hybrid-attention fwd tokens/s", "value": base.B * base.N * n_l / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "wan1.3b_720p_81f_cfg2 x 30 layers", "B": base.B, "H": base.H, "N": base.N, "d_head": base.d,
+                   "io_dtype": base.dtype, "layers": n_l, "hybrid_rates_R": list(W.STACK_RATES), "block_size": base.block_size,
+                   "feature_map": f"{base.d}->{base.d_hidden}->{base.d_feat}, P={base.poly_degree}", "layer_seeds": "1000 + l",
+                   "step": "one pass over the 30 layers"},
+        "tflops": flops / (ms_per_step * 1e-3) / 1e12,
+        "pct_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "query_kernel_ms_by_rate": {r: sum(v) / len(v) for r, v in per_rate.items()},
+        "roofline": {"bound": "mfma", "kernel": "query_kernel (all 30 layers)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "kernel_ms": kernel_ms_per_stack, "traffic": None,
+                     "traffic_source": "not profiled for this workload",
+                     "kernel_ms_source": "HIP events the library records around the kernel's launch on its stream, the timed steps of this run, summed over the 30 layers"},
+    }
+    if probe:
+        rec["mfma_probe"] = probe
+        rec["roofline"]["frac_of_sustained_mfma_rate"] = achieved / probe["random_operands_tflops"]
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline_extrapolated(layers[:3], W, torch)
+    print(json.dumps(rec), flush=True)
+
+
+def cpu_baseline_extrapolated(layers, W, torch):
+    """The stack is 317 TFLOP of fp64 for the oracle: far beyond a bounded sample.  For one layer of each rate
+    (16, 8, 4) and one (batch, head) pair the oracle's state pass is run in full and its per-query part on a sample of
+    rows; t_layer = B H (t_state + t_row N), the stack is ten times the three layers.  EXTRAPOLATED, and labelled so."""
+    from oracle import hybrid_attn_oracle as O
+    t_stack, notes = 0.0, []
+    for (w, q, k, v, fq, fk, _) in layers:
+        qh, kh, vh = (t[0, 0].float().cpu().numpy() for t in (q, k, v))
+        oq, ok = (O.FeatureMap(m.w1.float().cpu().numpy(), m.b1.cpu().numpy(), m.w2.float().cpu().numpy(), m.b2.cpu().numpy(),
+                               m.poly_degree) for m in (fq, fk))
+        t0 = time.perf_counter()
+        O.linear_state(kh, vh, ok, 0, w.R)
+        t_state = time.perf_counter() - t0
+        rows = W.sample_rows(w, 256)
+        t0 = time.perf_counter()
+        O.hybrid_attn_head(qh, kh, vh, oq, ok, 0, w.R, w.scale, rows=rows)
+        t_rows = time.perf_counter() - t0 - t_state          # hybrid_attn_head recomputes the state
+        t_layer = w.B * w.H * (t_state + max(t_rows, 0.0) / len(rows) * w.N)
+        notes.append(f"R={w.R}: state {t_state:.2f} s, {len(rows)} rows {t_rows:.2f} s -> {t_layer:.0f} s per layer")
+        t_stack += t_layer * (W.STACK_LAYERS // len(W.STACK_RATES))
+    w = layers[0][0]
+    return {"value": w.B * w.N * W.STACK_LAYERS / t_stack, "unit": "tokens/s", "cores": host_threads(), "cpu_model": cpu_model(),
+            "kind": "oracle", "extrapolated": True,
+            "sample": "EXTRAPOLATED: per rate one (batch, head) pair, full fp64 state pass + per-query part on sampled rows, scaled "
+                      "to B H pairs, N rows and 10 layers per rate; " + "; ".join(notes) + f"; stack {t_stack:.0f} s"}
+
+
+def rate_sweep_mode(args, ha, W, torch):
+    """Cost against the softmax fraction r = 1/R (Sec. 3.3: the per-block rates the knapsack chooses from; Fig. "teaser":
+    cost against length): the 480p / 81-frame shape at R in {0, 16, 8, 4, 2, 1} and the 1024-token fp32 case at
+    R in {0, 8, 4, 2, 1}; least-squares fit t(r) = t0 + t1 r over the r > 0 points.  Writes one JSON document."""
+    dev = "cuda:0"
+    probe = mfma_probe_rates(ha, torch, dev)
+    doc = {"command": "python bench.py --rate-sweep --steps %d --warmup %d" % (args.steps, args.warmup),
+           "mfma_probe": probe, "sweeps": {}}
+    for name, base, rates in (("wan1.3b_480p_81f", W.WAN_480P_81F, (0, 16, 8, 4, 2, 1)), ("tiny", W.TINY, W.RATE_SWEEP)):
+        inp = ha.to_device(W.make_inputs(base), dev)
+        rows = []
+        for R in rates:
+            w = W.with_rate(base, R)
+            q, k, v = inp[:3]
+            fq, fk = (None, None) if R == 1 else inp[3:]
+            ws = torch.empty(ha.hybrid_attn_workspace_bytes(ha.make_problem(q, R, w.block_size, w.scale), fq, fk), dtype=torch.uint8, device=dev)
+            out = torch.empty_like(q)
+            stream = torch.cuda.current_stream()
+
+            def step():
+                ha.hybrid_attn_forward(q, k, v, fq, fk, R, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
+            ms, kernel_ms, _ = time_forward(ha, torch, step, args.steps, args.warmup)
+            fl = W.algorithmic_flops(w)
+            row = {"R": R, "r": (1.0 / R if R else 0.0), "forward_ms": ms, "query_kernel_ms": kernel_ms, "algorithmic_gflop": fl / 1e9,
+                   "tflops": fl / (ms * 1e-3) / 1e12, "pct_bf16_mfma_peak": 100.0 * fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                   "tokens_per_s": w.B * w.N / (ms * 1e-3)}
+            if R == 0:
+                row["hbm_gbs_on_algorithmic_bytes"] = W.algorithmic_bytes(w) / (ms * 1e-3) / 1e9
+            rows.append(row)
+            print(f"  {name} R={R}: {ms:.4f} ms", file=sys.stderr, flush=True)
+        pos = [r for r in rows if r["R"] > 0]
+        n = len(pos)
+        sx, sy = sum(r["r"] for r in pos), sum(r["forward_ms"] for r in pos)
+        sxx, sxy = sum(r["r"] ** 2 for r in pos), sum(r["r"] * r["forward_ms"] for r in pos)
+        t1 = (n * sxy - sx * sy) / (n * sxx - sx * sx)
+        t0 = (sy - t1 * sx) / n
+        full = next(r["forward_ms"] for r in rows if r["R"] == 1)
+        for r in rows:
+            r["speedup_over_r1"] = full / r["forward_ms"]
+        doc["sweeps"][name] = {"shape": {"B": base.B, "H": base.H, "N": base.N, "d_head": base.d, "io_dtype": base.dtype,
+                                         "block_size": base.block_size}, "points": rows,
+                               "fit_ms": {"t0": t0, "t1": t1, "model": "t(r) = t0 + t1 r, least squares over r > 0",
+                                          "max_rel_residual": max(abs(t0 + t1 * r["r"] - r["forward_ms"]) / r["forward_ms"] for r in pos)},
+                               "linear_floor_ms_r0": next(r["forward_ms"] for r in rows if r["R"] == 0)}
+    doc["mfma_probe_after"] = mfma_probe_rates(ha, torch, dev)
+    text = json.dumps(doc, indent=1)
+    if args.out:
+        os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
+        open(args.out, "w").write(text + "\n")
+    print(json.dumps(doc), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,6 +475,13 @@ def main():
                     help="local-window variant: softmax over the query's tile and W tokens on either side (multiple of 2 * block "
                          "size), linear attention over every other token; sets the rate to 0")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stack", action="store_true",
+                    help="the 720p / 81-frame stack: 30 layers, B = 2, rates cycling 16, 8, 4, per-layer seeds 1000 + l; one step = "
+                         "one pass over the stack; prints one JSON line about it instead of the headline line")
+    ap.add_argument("--rate-sweep", action="store_true",
+                    help="forward time against the softmax fraction r = 1/R at the 480p / 81-frame shape and at the 1024-token "
+                         "case, with the fit t0 + t1 r; prints (and with --out writes) one JSON document")
+    ap.add_argument("--out", default=None, help="with --rate-sweep: file to write the JSON document to")
     ap.add_argument("--select-rates", type=float, default=None, metavar="BETA",
                     help="block-rate selection mode (Sec. 3.3): measure the cost of one layer at R in {1, 2, 4, 8}, draw "
                          "synthetic per-layer errors, solve the knapsack for a budget of BETA x the all-softmax stack, "
@@ -265,6 +509,16 @@ def main():
     from paper_2509_24899_amd import hybrid_attn as ha
     from paper_2509_24899_amd import workloads as W
 
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    if args.stack:
+        stack_mode(args, ha, W, torch)
+        return
+    if args.rate_sweep:
+        rate_sweep_mode(args, ha, W, torch)
+        return
+
     w = {"tiny": W.TINY, "wan_480p_81f": W.WAN_480P_81F, "wan_480p_161f": W.WAN_480P_161F,
          "wan_720p_81f_cfg": W.WAN_720P_81F_CFG}[args.workload]
     if args.rate is not None:
@@ -283,28 +537,16 @@ def main():
         w = W.replace(w, causal_chunk=args.causal_chunk)
     if args.local_window > 0:
         w = W.replace(w, R=0, local_window=args.local_window)
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    dev = "cuda:0"
-    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
 
-    # synthetic inputs drawn on the device (seeded), resident in HBM before the timed region
-    gen = torch.Generator(device=dev).manual_seed(w.seed)
-    s = w.d ** -0.5
-    q, k, v = ((torch.randn(w.B, w.H, w.N, w.d, generator=gen, device=dev) * s).to(dt) for _ in range(3))
-    if args.zero_inputs:
-        q.zero_(), k.zero_(), v.zero_()
-
-    def dmap():
-        fm = ha.FeatureMap((torch.randn(w.H, w.d_hidden, w.d, generator=gen, device=dev) * w.d ** -0.5).to(dt),
-                           torch.randn(w.H, w.d_hidden, generator=gen, device=dev) * 0.1,
-                           (torch.randn(w.H, w.d_feat, w.d_hidden, generator=gen, device=dev) * w.d_hidden ** -0.5).to(dt),
-                           torch.randn(w.H, w.d_feat, generator=gen, device=dev) * 0.1, w.poly_degree)
-        if w.d_mid:
-            fm.w_mid = (torch.randn(w.H, w.d_mid, w.d_hidden, generator=gen, device=dev) * w.d_hidden ** -0.5).to(dt)
-            fm.b_mid = torch.randn(w.H, w.d_mid, generator=gen, device=dev) * 0.1
-        return fm
-    fq, fk = (dmap(), dmap()) if w.R != 1 else (None, None)
+    # synthetic inputs, seeded, resident in HBM before the timed region
+    if args.distill_step or args.select_rates is not None:
+        q, k, v, fq, fk = load_inputs(W.with_rate(w, w.R if w.R != 1 else 4), ha, W)     # these modes need feature maps at every rate
+        if args.distill_step:
+            distill_step_mode(args, w, ha, torch, q, k, v, fq, fk)
+        else:
+            rate_selection_mode(args, w, ha, W, torch, q, k, v, fq, fk, torch.empty_like(q))
+        return
+    q, k, v, fq, fk = load_inputs(w, ha, W, zero=args.zero_inputs)
     prob = ha.make_problem(q, w.rate, w.block_size, w.scale)
     ws = torch.empty(ha.hybrid_attn_workspace_bytes(prob, fq, fk), dtype=torch.uint8, device=dev)
     out = torch.empty_like(q)
@@ -313,31 +555,15 @@ def main():
     def step():
         ha.hybrid_attn_forward(q, k, v, fq, fk, w.rate, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
 
-    if args.distill_step:
-        distill_step_mode(args, w, ha, torch, q, k, v, fq, fk)
-        return
-    if args.select_rates is not None:
-        rate_selection_mode(args, w, ha, W, torch, q, k, v, fq if fq else dmap(), fk if fk else dmap(), out)
-        return
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         dst.copy_(src)                     # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ha.hybrid_attn_profile_enable(args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    stage_ms = [ha.hybrid_attn_profile_read(i) for i in range(args.steps)]
-    ha.hybrid_attn_profile_enable(0)
+    ms_per_step, kernel_ms, kernel_sorted = time_forward(ha, torch, step, args.steps, args.warmup)
     assert torch.isfinite(out.float()).all().item(), "non-finite output"
+    mean, fwd_sorted = stage_breakdown(ha, torch, step, args.steps)
 
     # cold-cache forwards: a 512 MiB fill between forwards evicts L2 and the 256 MiB Infinity Cache, so inputs,
     # weights and workspace come from HBM (matters for the HBM-bound r = 0 point; the timing is the forward's
@@ -355,55 +581,35 @@ def main():
         ha.hybrid_attn_profile_enable(0)
         del flush
 
-    # sustained matrix-core rate of this device next to the published peak: a kernel of nothing but MFMA
-    # instructions, run for a few hundred ms so that power management settles; operand values matter
-    # (zero operands keep the clock at its ceiling, random ones do not)
-    mfma_probe = None
-    if not args.no_mfma_probe and w.n_softmax > 0:
-        sink = torch.empty(torch.cuda.get_device_properties(0).multi_processor_count * 512, device=dev)
-        mfma_probe = {}
-        for name, rnd in (("zero_operands", False), ("random_operands", True)):
-            ha.hybrid_attn_mfma_probe(rnd, 20000, 20, sink)          # settle
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            fl = ha.hybrid_attn_mfma_probe(rnd, 20000, 60, sink)
-            e1.record()
-            torch.cuda.synchronize()
-            mfma_probe[name + "_tflops"] = fl * 60 / (e0.elapsed_time(e1) * 1e-3) / 1e12
-        del sink
+    mfma_probe = None if args.no_mfma_probe else mfma_probe_rates(ha, torch, dev)
 
-    ms_per_step = elapsed * 1e3 / args.steps
-    fwd_sorted = sorted(r[4] for r in stage_ms)
     flops = W.algorithmic_flops(w)
-    mean = [sum(r[i] for r in stage_ms) / len(stage_ms) for i in range(5)]
-    n_s, n_l = w.n_softmax, w.n_linear
-    if w.local_window > 0:
-        n_s = n_l = w.N
+    n_s = w.N if w.local_window > 0 else w.n_softmax
+    events_note = "HIP events the library records around the kernel's launch on its stream, mean over the timed steps of this run"
     if n_s > 0:
-        # dominant kernel: the fused query kernel; its algorithmic flops are everything except the
-        # key-side feature map and state (4 N N_S d + phi_q MLP + g.S, g.z)
-        layered = n_l > 0 and (w.d_mid or not ((w.d_hidden == w.d and w.d_feat == w.d) or (w.d_hidden == 256 and w.d_feat == 256)))
-        # (maps that go layer by layer through HBM leave only the softmax loop and the merge to the query kernel)
-        softmax_flops = 4.0 * w.d * W.softmax_pairs(w)       # fewer pairs than N N_S for the causal / local-window variants
-        k_flops = w.B * w.H * (softmax_flops + (2.0 * w.N * (w.d * w.d_hidden + w.d_hidden * w.d_feat)
-                                                         + 2.0 * w.N * w.d_feat * w.d + 2.0 * w.N * w.d_feat
-                                                         if n_l > 0 and not layered else 0.0))
-        achieved = k_flops / (mean[3] * 1e-3) / 1e12
+        # dominant kernel: the fused query kernel
+        achieved = query_kernel_flops(w, W) / (kernel_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "query_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_TFLOPS, "kernel_ms": mean[3], "traffic": None}
+                    "frac": achieved / PEAK_BF16_TFLOPS, "kernel_ms": kernel_ms, "kernel_ms_source": events_note, "traffic": None,
+                    "traffic_source": "this workload has not been profiled"}
     else:
+        # r = 0: no softmax keys, the whole forward is bound by HBM; the clock is the wall clock over the timed steps
         by = W.algorithmic_bytes(w)
-        achieved = by / (mean[4] * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "whole forward (r = 0)", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": achieved / PEAK_HBM_GBS, "kernel_ms": mean[4], "traffic": None}
-    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (null when this
-    # workload has not been profiled)
+        achieved = by / (ms_per_step * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "whole forward (r = 0): state pass + state reduction + query-side kernel", "achieved": achieved,
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "kernel_ms": ms_per_step,
+                    "kernel_ms_source": "wall clock over the timed steps of this run (the forward is three launches)",
+                    "query_side_kernel_ms": kernel_ms, "traffic": None, "traffic_source": "this workload has not been profiled"}
+    # HBM bytes per launch of the dominant kernel: NOT measured in this run; read from the committed summary of the
+    # rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command (null when this workload has not been profiled)
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file) and w.d_hidden == w.d and w.d_feat == w.d and w.split_granularity <= 1 and not w.causal_chunk and not w.local_window:   # profiled with the d -> d -> d maps
         t = json.load(open(traffic_file)).get(f"{w.name}_R{w.R}_bs{w.block_size}")
         if t:
             roofline["traffic"] = t["read_bytes"] + t["written_bytes"]
             roofline["traffic_detail"] = t
+            roofline["traffic_source"] = ("profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this command, scaled by a "
+                                          "1 GiB copy in the same process; committed with the profile summaries, not measured in this run")
 
     if mfma_probe and roofline["bound"] == "mfma":
         roofline["frac_of_sustained_mfma_rate"] = roofline["achieved"] / mfma_probe["random_operands_tflops"]
@@ -418,12 +624,17 @@ def main():
                    **({"causal_chunk": w.causal_chunk} if w.causal_chunk else {}),
                    **({"local_window": w.local_window} if w.local_window else {}),
                    "feature_map": (f"{w.d}->{w.d_hidden}->{w.d_mid}->{w.d_feat}" if w.d_mid else f"{w.d}->{w.d_hidden}->{w.d_feat}")
-                   + f", P={w.poly_degree}"},
+                   + f", P={w.poly_degree}",
+                   "inputs": "workloads.make_inputs (numpy stream, seed %d): the tensors of the parity test at this shape" % w.seed if w.B == 1
+                             else "workloads.make_inputs_on_device (torch generator, seed %d)" % w.seed},
         "tflops": flops / (ms_per_step * 1e-3) / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "forward_ms_median": fwd_sorted[len(fwd_sorted) // 2], "forward_ms_min": fwd_sorted[0],
+        "query_kernel_ms_median": kernel_sorted[len(kernel_sorted) // 2], "query_kernel_ms_min": kernel_sorted[0],
         "forward_ms_cold_cache_median": cold_sorted[len(cold_sorted) // 2] if cold_sorted else None,
-        "stage_ms": {"compact": mean[0], "state": mean[1], "wprep_q": mean[2], "query": mean[3], "forward": mean[4]},
+        "stage_ms": {"compact": mean[0], "state": mean[1], "wprep_q": mean[2], "query": mean[3], "forward": mean[4],
+                     "forward_median": fwd_sorted[len(fwd_sorted) // 2], "forward_min": fwd_sorted[0],
+                     "source": "a second pass of the same steps, outside the timed region, with an event record between all stages "
+                               "(the records themselves cost the stream about 15 us per forward)"},
         "roofline": roofline,
     }
     if mfma_probe:

@@ -168,7 +168,10 @@ ha_status hybrid_attn_linear_state(const ha_problem *p, const void *k, const voi
  * stage durations in milliseconds: ms[0] softmax-key compaction, ms[1] key-side feature map + state
  * pass + state reduction, ms[2] query-side weight re-ordering, ms[3] the fused query kernel (softmax
  * tile loop, phi_q, contraction with the state and merge), ms[4] the whole forward.  Stages that did
- * not run report 0.  HA_ERR_SHAPE for an index that was never recorded.  Host memory only. */
+ * not run report 0.  HA_ERR_SHAPE for an index that was never recorded.  Host memory only.
+ * A negative count, hybrid_attn_profile_enable(-n), creates n sets as well but records only the pair of events around
+ * the fused query kernel (two event records per forward instead of five, each of which costs the stream a few
+ * microseconds): ms[3] is measured, the other entries read 0. */
 ha_status hybrid_attn_profile_enable(int n_records);
 ha_status hybrid_attn_profile_read(int index, float ms[5]);
 int hybrid_attn_profile_count(void);   /* forwards recorded since the last enable */

@@ -14,6 +14,7 @@ static thread_local int g_last_device_error = 0;
 struct Profile {
   hipEvent_t *ev = nullptr;
   int n = 0, count = 0;
+  bool dominant_only = false;   // record only the pair around the dominant kernel (two events per forward)
 };
 static thread_local Profile g_prof;
 static inline hipEvent_t *prof_events() {
@@ -237,7 +238,8 @@ static ha_status forward_impl(const ha_problem *p, const void *q, const void *k,
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return HA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipEvent_t *ev = ha::prof_events();
-  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, ev, wide ? &wp : nullptr);
+  const bool light = ev && ha::g_prof.dominant_only;
+  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, light ? nullptr : ev, wide ? &wp : nullptr);
   if (s != HA_OK) return s;
   hipError_t e;
   if (wide) {
@@ -311,7 +313,9 @@ ha_status hybrid_attn_forward_static(const ha_problem *p, const void *q, const v
 }
 
 ha_status hybrid_attn_profile_enable(int n_records) {
-  if (n_records < 0 || n_records > 4096) return HA_ERR_SHAPE;
+  const bool dominant_only = n_records < 0;
+  if (dominant_only) n_records = -n_records;
+  if (n_records > 4096) return HA_ERR_SHAPE;
   ha::Profile &pf = ha::g_prof;
   for (int i = 0; i < pf.n * 6; ++i) (void)hipEventDestroy(pf.ev[i]);
   delete[] pf.ev;
@@ -329,6 +333,7 @@ ha_status hybrid_attn_profile_enable(int n_records) {
     }
   }
   pf.n = n_records;
+  pf.dominant_only = dominant_only;
   return HA_OK;
 }
 
@@ -343,6 +348,10 @@ ha_status hybrid_attn_profile_read(int index, float ms[5]) {
   if (e != hipSuccess) return ha::device_error(e);
   const int a[5] = {0, 1, 2, 3, 0}, b[5] = {1, 2, 3, 4, 4};
   for (int i = 0; i < 5; ++i) {
+    if (pf.dominant_only && i != 3) {
+      ms[i] = 0.f;
+      continue;
+    }
     if ((e = hipEventElapsedTime(&ms[i], ev[a[i]], ev[b[i]])) != hipSuccess) return ha::device_error(e);
   }
   return HA_OK;

@@ -118,7 +118,9 @@ static __device__ __forceinline__ void store_tile(const QueryArgs &a, int64_t ba
         else *reinterpret_cast<bf16x4 *>(stage + r * PITCH + dloc * 2) = __builtin_convertvector(y, bf16x4);
       }
     }
-    __syncthreads();
+    // the staging area is this wave's own and a wave's LDS instructions execute in order: no workgroup barrier, the
+    // compiler only has to keep the reads behind the writes
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
     for (int i = lane; i < 32 * CPR; i += 64) {
       const int row = i / CPR, ch = i % CPR;
@@ -128,7 +130,7 @@ static __device__ __forceinline__ void store_tile(const QueryArgs &a, int64_t ba
         *reinterpret_cast<f32x4 *>(dst) = piece;
       }
     }
-    if (PASSES > 1) __syncthreads();
+    if (PASSES > 1) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   }
 }
 
@@ -262,6 +264,9 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(l), "v"(lane_off16), "s"(gp) : "memory");
     }
   };
+  const int nblk = (a.NS + 31) >> 5;     // key blocks that hold at least one real key
+  // layer-1 weights of phi_q: not needed before the epilogue, so with a softmax loop ahead they are requested only
+  // once the loop's first key blocks have landed (nothing at the start of the workgroup waits for them)
   if constexpr (ELDS) {
     if (a.has_linear) stage_in(a.w1f + (int64_t)h * NW1, w1_lds, NW1 / 64);
   }
@@ -296,7 +301,6 @@ __global__ __launch_bounds__(64 * NW, 2) void query_kernel_ring(QueryArgs a) {
 #pragma unroll
     for (int x = 0; x < 16; ++x) o[rb][x] = 0.f;
 
-  const int nblk = (a.NS + 31) >> 5;     // key blocks that hold at least one real key
   if (nblk > 0) {
     const bf16x8 *ksrc = a.ks_frag + ((int64_t)bh * a.n_kblocks + kb_lo) * FRAG;
     const bf16x8 *vsrc = a.vs_frag + ((int64_t)bh * a.n_kblocks + kb_lo) * FRAG;
