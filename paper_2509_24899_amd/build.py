@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libhybridattn.so")
-SOURCES = ["ha_api.hip", "ha_kernels.hip", "ha_query.hip", "ha_wide.hip", "ha_wide_grad.hip", "ha_grad.hip", "ha_select.hip", "ha_update.hip"]
+SOURCES = ["ha_api.hip", "ha_kernels.hip", "ha_state.hip", "ha_query.hip", "ha_wide.hip", "ha_wide_grad.hip", "ha_grad.hip", "ha_select.hip", "ha_update.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # packed fp32 VALU forms are switched off for every device compile
@@ -21,7 +21,8 @@ HIPCC_FLAGS = [
 # instructions in their vector-register form keeps the transient products of the feature-map recomputation out
 # of the accumulator file, which the persistent partial sums fill (otherwise those are spilled to scratch and
 # reloaded in every tile).
-FILE_FLAGS = {"ha_grad.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"], "ha_kernels.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+FILE_FLAGS = {"ha_grad.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"], "ha_kernels.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+              "ha_state.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PATH, tag: str = "") -> str:

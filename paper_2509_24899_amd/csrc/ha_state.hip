@@ -1,0 +1,460 @@
+// State pass of the hybrid-attention forward for the feature maps whose widths equal the head width (d -> d -> d):
+// phi_k on the linear tokens T_L and the two cached sums of Sec. 3.1,
+//     S = sum_{j in T_L} phi_k(k_j)^T v_j   (F x d),      z = sum_{j in T_L} phi_k(k_j)   (F),
+// as per-chunk partial tiles that state_reduce_kernel adds up in a fixed order.  gfx950 only.
+//
+// One workgroup = 4 waves = one wave per SIMD with the whole register file, so nothing but the wave's own
+// instruction stream hides latency: the kernel is written as a software pipeline.
+//   * Layer 1 runs two row blocks at a time (two independent accumulator chains, their matrix instructions
+//     alternate), all weight fragments of the layer requested up front.
+//   * Layer 2 runs two output tiles at a time in steps of one hidden block; the fragments of the next step are
+//     requested before the current step's matrix instructions, and the softmax of the finished pair of tiles
+//     (online form: exponentials against the running maximum, one factor per pair at the end) is spread over the
+//     steps of the next pair, so the vector work sits under matrix work.
+//   * V goes global -> LDS with direct-to-LDS loads (no registers), row-major, one tile ahead: requested when the
+//     previous tile's contraction has ended, awaited before this tile's.  phi is written row-major as well (8-byte
+//     pieces).  Both operands of the contraction over the tokens, [S | z] += phi^T [V | 1], then come out of LDS
+//     through the transposing 64-bit reads of gfx950 (ds_read_b64_tr_b16): four consecutive tokens of one column
+//     per lane, two reads per 8-slot fragment; no 2-byte scatter anywhere.
+//   * The contraction requests the fragments of the next two 16-token slices while the matrix instructions of the
+//     current two run.
+#include "ha_device.h"
+#include "ha_plan.h"
+
+namespace ha {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+
+// Row-major [token][column] bf16 tile in LDS with rows of 2 D bytes.  The 16-byte pieces of a row are XOR-swizzled by
+// the row so that the transposing reads (4 rows x 32 bytes per 16 lanes) and the row-wise writes spread over the
+// banks.  The swizzle only has to be the same function everywhere the tile is addressed.
+template <int D>
+struct RowTile {
+  static constexpr int ROWB = 2 * D;        // bytes per row
+  static constexpr int PPR = ROWB / 16;     // 16-byte pieces per row
+  static __device__ __forceinline__ int sw(int row) { return D >= 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
+  // byte offset of 16-byte piece p of `row`
+  static __device__ __forceinline__ int piece(int row, int p) { return row * ROWB + ((p ^ sw(row)) << 4); }
+};
+
+// Transposing read: every 16 lanes form a group; lane j of a group receives, as its slot i, element j % 4 of what
+// lane 4 i + j / 4 of the group addressed (4 consecutive 16-bit values).  With lane 4 i + a of a group pointing at
+// columns c0 + 4 a .. + 3 of row T0 + i, lane j holds column c0 + j of rows T0 .. T0 + 3: four consecutive tokens of
+// one column, i.e. half of a matrix-core operand fragment.
+static __device__ __forceinline__ s16x4 ds_read_tr(const char *tile, int byte_off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + byte_off));
+}
+static __device__ __forceinline__ bf16x8 join(s16x4 a, s16x4 b) {
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+static __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+  const f32x2 t = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
+}
+// Nothing moves across: the instruction order between two fences is the compiler's, the order of the fenced groups
+// is the source's.  The kernel below places its matrix instructions, LDS reads and vector work by hand with it.
+#define HA_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// ACT0: the output activation is the softmax over the channels (the default of the paper's maps), scheduled by hand;
+// the other activations (exp, ReLU: no reduction over channels) take a plain epilogue of layer 2.
+template <bool F32, bool ACT0>
+__global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__restrict__ k, const void *__restrict__ v,
+                                                                 const bf16x8 *w1f_all, const bf16x8 *w2f_all,
+                                                                 const float *__restrict__ b1_all,
+                                                                 const float *__restrict__ b2_all, float *__restrict__ part,
+                                                                 int H, int NL, int R, int G, int CH, int P, int act,
+                                                                 int64_t sb, int64_t sh, int64_t sn, int N, int CC, int nsub) {
+  constexpr int D = 128, HD = D, F = D, TOK = 128;
+  constexpr int KS = D / 16, HB = HD / 32, FB = F / 32, NCB = D / 32 + 1, NT = FB * NCB;
+  static_assert(HB == 4 && FB == 4 && KS == 8, "the hand-placed schedule below is written for 128 -> 128 -> 128");
+  typedef RowTile<D> RT;
+  constexpr int ROWB = RT::ROWB, PPR = RT::PPR;
+  __shared__ bf16x8 wlds[(HD * D + F * HD) / 8];
+  __shared__ __align__(16) float blds[HD + F];
+  __shared__ __align__(16) char phi_t[TOK * ROWB];
+  __shared__ __align__(16) char v_t[TOK * ROWB];
+
+  const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H;
+  const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // weight fragments of this head: 64 KiB global -> LDS with direct-to-LDS loads, all in flight at once
+  dma_to_lds(w1f_all + (int64_t)h * (HD * D / 8), &wlds[0], HD * D / 8 / 64, w, 4, lane);
+  dma_to_lds(w2f_all + (int64_t)h * (F * HD / 8), &wlds[HD * D / 8], F * HD / 8 / 64, w, 4, lane);
+  for (int i = tid; i < HD; i += 256) blds[i] = b1_all ? b1_all[(int64_t)h * HD + i] : 0.f;
+  for (int i = tid; i < F; i += 256) blds[HD + i] = b2_all ? b2_all[(int64_t)h * F + i] : 0.f;
+  // a chain's accumulator starts as the bias of its 32 channels: four 16-byte LDS reads (registers 4 v .. 4 v + 3 are
+  // four consecutive channels), no vector instruction
+  auto bias_tile = [&](const float *b, int blk) {
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(b + 32 * blk + 4 * g);
+    const f32x8 lo = __builtin_shufflevector(src[0], src[2], 0, 1, 2, 3, 4, 5, 6, 7);
+    const f32x8 hi = __builtin_shufflevector(src[4], src[6], 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+  };
+  const float *b1 = &blds[0], *b2 = &blds[HD];
+  const lds_frag_ptr w1f = (lds_frag_ptr)&wlds[0], w2f = (lds_frag_ptr)&wlds[HD * D / 8];
+  const LinearMap lmap(R, G);
+
+  // this workgroup's range of linear tokens (see the chunking of the plan)
+  int lt_begin = chunk * CH;
+  int lt_end = min(lt_begin + CH, NL);
+  if (CC > 0) {
+    const int cc = chunk / nsub, lo = cc * CC, hi = min(lo + CC, N);
+    lt_begin = lo - softmax_before(lo, R, G) + (chunk % nsub) * CH;
+    lt_end = min(lt_begin + CH, hi - softmax_before(hi, R, G));
+  }
+
+  f32x16 acc[NCB];                                   // wave w owns row block w of [S | z]
+#pragma unroll
+  for (int i = 0; i < NCB; ++i)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) acc[i][x] = 0.f;
+
+  // ---- addressing of the two row-major tiles
+  // phi writes: this lane owns token row tf and, per (fb, q), the 8-byte run of channels 32 fb + 8 q + 4 g .. + 3
+  const int tf = w * 32 + r;
+  // The phi tile is swizzled over sixteen rows: piece p of row t sits at p ^ psw(t), psw(t) = 4 (t % 4) + (t / 4) % 4,
+  // so that the 32 rows one write instruction touches fall on 16 different 16-byte pieces (two rows per piece pair
+  // with the 8-byte halves of g: conflict-free in two passes) while a transposing read still finds its four rows in
+  // four different 64-byte groups.
+  auto psw = [](int t) { return 4 * (t & 3) + ((t >> 2) & 3); };
+  int phi_base[FB][4];
+#pragma unroll
+  for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) phi_base[fb][q] = tf * ROWB + 8 * g + (((4 * fb + q) ^ psw(tf)) << 4);
+  // transposing reads: lane = (group m, i, a); see ds_read_tr.  Rows T0 + i with T0 a multiple of 4, so the swizzle
+  // of the row is a per-lane constant; per column block one base offset, k-steps and half-fragments are immediates
+  const int tm = lane >> 4, ti = (lane >> 2) & 3, ta = lane & 3, tg = tm >> 1;
+  auto tr_off = [&](int blk) {
+    return (8 * tg + ti) * ROWB + (((4 * blk + 2 * (tm & 1) + (ta >> 1)) ^ RT::sw(ti)) << 4) + 8 * (ta & 1);
+  };
+  int tr_base[D / 32];                               // V columns 32 cb ..
+#pragma unroll
+  for (int blk = 0; blk < D / 32; ++blk) tr_base[blk] = tr_off(blk);
+  // this wave's channel rows 32 w .. of the phi tile: rows T0 + i with T0 = 16 ks + 8 g + 4 jj, so (T0 / 4) % 4 =
+  // (2 g + jj) % 4 and the two half-fragments have bases of their own
+  int a_base[2];
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj)
+    a_base[jj] = (8 * tg + ti) * ROWB + (((4 * w + 2 * (tm & 1) + (ta >> 1)) ^ (4 * ti + ((2 * tg + jj) & 3))) << 4) + 8 * (ta & 1);
+  // V: 1 KiB (64 pieces) per direct-to-LDS instruction; lane -> (row, physical piece) -> logical piece of that row
+  constexpr int RPI = 1024 / ROWB;                   // rows per instruction
+  constexpr int NVI = TOK / RPI;                     // instructions per tile, dealt round-robin to the 4 waves
+  const int v_row = lane / PPR, v_pp = lane % PPR;
+
+  auto load_k = [&](int t0, bf16x8 (&dst)[KS]) {
+    const int tok = lmap.token(min(t0 + tf, NL - 1));   // rows past the end repeat the last linear token; masked later
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) dst[ks] = load8<F32>(k, base + (int64_t)tok * sn + 16 * ks + 8 * g);
+  };
+  // V rows of the tile that starts at linear token t0 into v_t (bf16: direct-to-LDS; fp32: through registers).
+  // This lane's rows are 4 RPI apart: one exact division gives the first one's group, the others follow by adding
+  // the quotient and remainder of the row distance (a tile that reaches past the last linear token clamps every row
+  // on its own instead).
+  const int step_q = (4 * RPI) / lmap.d, step_r = (4 * RPI) % lmap.d;
+  auto request_v = [&](int t0) {
+    const bool whole = t0 + TOK <= NL;                 // wave-uniform
+    const int i0 = t0 + w * RPI + v_row;
+    int grp = 0, rem = 0;
+    if (whole && lmap.g != 0) {
+      grp = lmap.token(i0) - i0;                       // (i0 / d + 1) g
+      rem = i0 - (grp / lmap.g - 1) * lmap.d;
+    }
+#pragma unroll
+    for (int c = 0; c < NVI / 4; ++c) {
+      const int row = (4 * c + w) * RPI + v_row;
+      int tok;
+      if (whole) {
+        tok = t0 + row + grp;
+        rem += step_r;
+        const bool carry = rem >= lmap.d;
+        rem -= carry ? lmap.d : 0;
+        grp += (step_q + (carry ? 1 : 0)) * lmap.g;
+      } else {
+        tok = lmap.token(min(t0 + row, NL - 1));
+      }
+      const int p = v_pp ^ RT::sw(row);
+      if constexpr (F32) {
+        *reinterpret_cast<bf16x8 *>(v_t + row * ROWB + (v_pp << 4)) = load8<true>(v, base + (int64_t)tok * sn + p * 8);
+      } else {
+        const unsigned l = __builtin_amdgcn_readfirstlane(
+            (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(v_t + (4 * c + w) * 1024));
+        const __bf16 *gp = static_cast<const __bf16 *>(v) + base + (int64_t)tok * sn + p * 8;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gp) : "memory");
+      }
+    }
+  };
+
+  bf16x8 xf[KS];
+  load_k(lt_begin, xf);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(F32 ? 0 : KS) : "memory");     // the weight fragments are older than the K loads
+  __syncthreads();                                   // weights and biases are in LDS
+  if (lt_begin < lt_end) request_v(lt_begin);
+
+  for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
+    u32x4 h_hi[HB][2], h_lo[HB][2];                  // relu(W1 x + b1) as hi + lo bf16 pairs, chained order
+    f32x16 u[FB];
+    // registers x, x + 1 of a finished layer-1 tile -> ReLU -> hi + lo (8 vector instructions)
+    auto conv2 = [&](const f32x16 &hh, int hb, int x) {
+      const float a = fmaxf(hh[x], 0.f), b = fmaxf(hh[x + 1], 0.f);
+      const unsigned hi = pack_bf16(a, b);
+      h_hi[hb][x >> 3][(x & 7) >> 1] = hi;
+      h_lo[hb][x >> 3][(x & 7) >> 1] = pack_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+    };
+    auto hop = [&](const u32x4 &t) { return __builtin_bit_cast(bf16x8, t); };
+    {
+      // ---------------- layer 1: two row blocks at a time (two independent chains, alternating)
+      f32x16 ha0, ha1, ha2, ha3;
+      bf16x8 wA[2][KS], wB[2][KS];
+#pragma unroll
+      for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) wA[e][ks] = frag_at(w1f, e * KS + ks, lane);
+      ha0 = bias_tile(b1, 0);
+      ha1 = bias_tile(b1, 1);
+      ha2 = bias_tile(b1, 2);
+      ha3 = bias_tile(b1, 3);
+      HA_FENCE();
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {              // blocks 0, 1; the fragments of blocks 2, 3 are requested on the way
+        ha0 = mfma32(wA[0][ks], xf[ks], ha0);
+        wB[0][ks] = frag_at(w1f, 2 * KS + ks, lane);
+        HA_FENCE();
+        ha1 = mfma32(wA[1][ks], xf[ks], ha1);
+        wB[1][ks] = frag_at(w1f, 3 * KS + ks, lane);
+        HA_FENCE();
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {              // blocks 2, 3 under the conversion of blocks 0, 1
+        ha2 = mfma32(wB[0][ks], xf[ks], ha2);
+        conv2(ha0, 0, 2 * ks);
+        ha3 = mfma32(wB[1][ks], xf[ks], ha3);
+        conv2(ha1, 1, 2 * ks);
+      }
+      // one matrix instruction, then one conversion's worth of vector instructions, sixteen times; the accumulators
+      // are tied to the end of this stretch so that the matrix instructions cannot drift out of it
+#pragma unroll
+      for (int i = 0; i < 2 * KS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      }
+      asm volatile("" : "+v"(ha2), "+v"(ha3));
+      HA_FENCE();
+      load_k(t0 + TOK, xf);                          // the K rows of the next tile travel during the rest of this one
+      HA_FENCE();
+
+      // ---------------- layer 2: u = W2 h + b2, two 32-channel tiles at a time, one hidden block (8 matrix
+      // instructions, 4 fragments) per step; the fragments of the next step are requested behind the step's first
+      // matrix instruction.  Under the steps: first the conversion of layer-1 blocks 2, 3, later the softmax
+      // exponentials of the finished pair of tiles.
+      bf16x8 wa[2][2], wb[2][2];
+      auto w2_frags = [&](int fp, int hb, bf16x8 (&dst)[2][2]) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+          for (int s = 0; s < 2; ++s) dst[e][s] = frag_at(w2f, ((fp + e) * HB + hb) * 2 + s, lane);
+      };
+      w2_frags(0, 0, wa);
+#pragma unroll
+      for (int fb = 0; fb < FB; ++fb) u[fb] = bias_tile(b2, fb);
+      float m0 = 0.f, off0 = 0.f, sum0 = 0.f;
+      HA_FENCE();
+#pragma unroll
+      for (int fp = 0; fp < FB; fp += 2) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+          bf16x8 (&cur)[2][2] = (hb & 1) ? wb : wa;
+          bf16x8 (&nxt)[2][2] = (hb & 1) ? wa : wb;
+#pragma unroll
+          for (int slot = 0; slot < 8; ++slot) {
+            const int e = slot & 1, hi = (slot >> 1) & 1, s = slot >> 2;
+            u[fp + e] = mfma32(cur[e][s], hop(hi ? h_hi[hb][s] : h_lo[hb][s]), u[fp + e]);
+            if (slot == 0) {
+              if (hb + 1 < HB) w2_frags(fp, hb + 1, nxt);
+              else if (fp + 2 < FB) w2_frags(fp + 2, 0, nxt);
+            }
+            const int n = hb * 8 + slot;             // 0 .. 31 within the pair
+            if (fp == 0) {
+              if (n < 8) conv2(ha2, 2, 2 * n);       // needed from step 2 on
+              else if (n < 16) conv2(ha3, 3, 2 * (n - 8));
+            } else if constexpr (ACT0) {
+              // softmax of tiles 0, 1: their maximum in the first two slots, then one exponential per slot
+              if (n == 0) {
+                float t = fmaxf(u[0][0], u[0][1]);
+#pragma unroll
+                for (int x = 2; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[0][x]), u[0][x + 1]);
+                m0 = t;
+              } else if (n == 1) {
+                float t = m0;
+#pragma unroll
+                for (int x = 0; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[1][x]), u[1][x + 1]);
+                m0 = xhalf_max(t);
+                off0 = -m0 * kLog2e;
+              } else {
+                auto ex = [&](int i) {
+                  u[i >> 4][i & 15] = fast_exp2(__builtin_fmaf(u[i >> 4][i & 15], kLog2e, off0));
+                  sum0 += u[i >> 4][i & 15];
+                };
+                ex(n - 2);
+                if (n >= 30) ex(n);                  // 30 slots for 32 values: the last two slots take two each
+              }
+            }
+            HA_FENCE();
+          }
+        }
+      }
+      if constexpr (ACT0) {
+        // tiles 2, 3 against the overall maximum, which is known now
+        float t = fmaxf(u[2][0], u[2][1]);
+#pragma unroll
+        for (int x = 2; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[2][x]), u[2][x + 1]);
+#pragma unroll
+        for (int x = 0; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[3][x]), u[3][x + 1]);
+        const float m = fmaxf(m0, xhalf_max(t));
+        const float off = -m * kLog2e;
+        float sum1 = 0.f;
+#pragma unroll
+        for (int fb = 2; fb < 4; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) {
+            u[fb][x] = fast_exp2(__builtin_fmaf(u[fb][x], kLog2e, off));
+            sum1 += u[fb][x];
+          }
+        const float carry = fast_exp2((m0 - m) * kLog2e);        // tiles 0, 1 were exponentiated against m0
+        const float inv = 1.0f / xhalf_sum(sum0 * carry + sum1);
+        const float f0 = carry * inv;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          u[0][x] *= f0;
+          u[1][x] *= f0;
+          u[2][x] *= inv;
+          u[3][x] *= inv;
+        }
+      } else if (act == 1) {
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) u[fb][x] = fast_exp2(u[fb][x] * kLog2e);
+      } else {
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) u[fb][x] = fmaxf(u[fb][x], 0.f);
+      }
+    }
+    if (P == 2) {
+      // the paper's default degree: the upper half of the channels is squared
+#pragma unroll
+      for (int fb = FB / 2; fb < FB; ++fb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) u[fb][x] *= u[fb][x];
+    } else if (P > 1) {
+      // slice p = channel / Dp (0-based) gets p extra multiplications by the activation value; Dp is a multiple
+      // of 8, so the power depends only on the group of four registers
+#pragma unroll
+      for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int extra = ((32 * fb + 8 * q) * P) / F;
+          if (extra > 0) {
+            const float t0_ = u[fb][4 * q], t1_ = u[fb][4 * q + 1], t2_ = u[fb][4 * q + 2], t3_ = u[fb][4 * q + 3];
+            for (int i = 0; i < extra; ++i) {
+              u[fb][4 * q] *= t0_;
+              u[fb][4 * q + 1] *= t1_;
+              u[fb][4 * q + 2] *= t2_;
+              u[fb][4 * q + 3] *= t3_;
+            }
+          }
+        }
+    }
+    // ---------------- phi -> LDS, row-major: registers 4 q .. 4 q + 3 of tile fb are channels 32 fb + 8 q + 4 g .. + 3
+    {
+      if (t0 + TOK > lt_end) {                        // ragged end of the range: padded tokens add nothing
+        const float keep = t0 + tf < lt_end ? 1.f : 0.f;
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) u[fb][x] *= keep;
+      }
+      typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+      for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const u32x2 four = {pack_bf16(u[fb][4 * q], u[fb][4 * q + 1]), pack_bf16(u[fb][4 * q + 2], u[fb][4 * q + 3])};
+          *reinterpret_cast<u32x2 *>(phi_t + phi_base[fb][q]) = four;
+        }
+    }
+    // this wave's V requests of this tile are older than the K loads of the next one just issued
+    if constexpr (F32) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KS) : "memory");
+    __syncthreads();
+
+    // ---------------- [S | z] += phi^T [V | 1] over the 128 tokens: two 16-token slices (10 matrix instructions)
+    // per batch, the 20 transposing reads of the next batch placed two behind each matrix instruction
+    {
+      const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);     // the "1" column that yields z
+      const bf16x8 ones = bf16x8{one, one, one, one, one, one, one, one};
+      constexpr int KB = 2, NBATCH = TOK / 16 / KB;
+      constexpr int NOP = KB * (1 + D / 32);           // operand fragments per batch
+      bf16x8 fr[2][NOP];                             // [buffer][(kk, operand)]: operand 0 = phi^T, 1 + cb = V
+      auto rd = [&](int batch, int buf, int i) {     // both halves of one fragment: two transposing reads
+        const int kk = i / (1 + D / 32), op = i % (1 + D / 32);
+        const int off = (batch * KB + kk) * 16 * ROWB;
+        fr[buf][i] = op == 0 ? join(ds_read_tr(phi_t, a_base[0] + off), ds_read_tr(phi_t, a_base[1] + off + 4 * ROWB))
+                             : join(ds_read_tr(v_t, tr_base[op - 1] + off), ds_read_tr(v_t, tr_base[op - 1] + off + 4 * ROWB));
+      };
+      auto opnd = [&](int buf, int kk, int op) { return fr[buf][kk * (1 + D / 32) + op]; };
+#pragma unroll
+      for (int i = 0; i < NOP; ++i) rd(0, 0, i);
+      HA_FENCE();
+#pragma unroll
+      for (int batch = 0; batch < NBATCH; ++batch) {
+        const int buf = batch & 1;
+#pragma unroll
+        for (int kk = 0; kk < KB; ++kk) {
+          const bf16x8 a8 = opnd(buf, kk, 0);
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) {
+            acc[cb] = mfma32(a8, cb < D / 32 ? opnd(buf, kk, 1 + cb) : ones, acc[cb]);
+            if (batch + 1 < NBATCH) rd(batch + 1, buf ^ 1, kk * NCB + cb);
+            HA_FENCE();
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (t0 + TOK < lt_end) request_v(t0 + TOK);
+  }
+  {
+    float *dst = part + ((int64_t)bh * gridDim.x + chunk) * NT * 1024 + (int64_t)w * NCB * 1024;
+#pragma unroll
+    for (int i = 0; i < NCB; ++i)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) dst[i * 1024 + x * 64 + lane] = acc[i][x];
+  }
+}
+
+hipError_t launch_state_pipelined(const Plan &pl, const void *k, const void *v, const ha_feature_map &fm, void *ws,
+                                  hipStream_t st) {
+  dim3 grid(pl.n_chunks, pl.B * pl.H);
+  char *wsb = static_cast<char *>(ws);
+  const bf16x8 *w1f = reinterpret_cast<const bf16x8 *>(wsb + pl.off_w1k), *w2f = reinterpret_cast<const bf16x8 *>(wsb + pl.off_w2k);
+  float *part = reinterpret_cast<float *>(wsb + pl.off_part);
+#define HA_STATE(F32, ACT0) \
+  state_pipelined_kernel<F32, ACT0><<<grid, 256, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.G, pl.CH, pl.P, \
+                                                         pl.act_k, pl.sb, pl.sh, pl.sn, pl.N, pl.CC, pl.nsub)
+  if (pl.act_k == HA_ACT_SOFTMAX) { if (pl.f32) HA_STATE(true, true); else HA_STATE(false, true); }
+  else { if (pl.f32) HA_STATE(true, false); else HA_STATE(false, false); }
+#undef HA_STATE
+  return hipGetLastError();
+}
+
+}  // namespace ha
