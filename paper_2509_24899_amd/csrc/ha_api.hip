@@ -194,12 +194,15 @@ static ha_status run_key_side(const Plan &pl, const void *k, const void *v, cons
                               hipStream_t st, hipEvent_t *ev = nullptr, const WidePlan *wide = nullptr) {
   hipError_t e;
   if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return device_error(e);
-  if (pl.NS > 0 && (e = launch_compact(pl, k, v, ws, st)) != hipSuccess) return device_error(e);
+  // (for the 128-wide bf16 maps the state pass compacts the softmax keys on its way: one pass over K and V)
+  const bool fused_compaction = !wide && phi_k && state_compacts_softmax_keys(pl);
+  if (pl.NS > 0 && !fused_compaction && (e = launch_compact(pl, k, v, ws, st)) != hipSuccess) return device_error(e);
   if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return device_error(e);
   if (pl.NL > 0 && wide) {
     if ((e = launch_wide_key_side(pl, *wide, k, v, *phi_k, ws, st)) != hipSuccess) return device_error(e);
   } else if (pl.NL > 0) {
-    if ((e = launch_weight_prep(pl, *phi_k, false, ws, st)) != hipSuccess) return device_error(e);
+    // (the pipelined state pass of the 128-wide bf16 maps gathers the weights from the caller's tensors itself)
+    if (!state_reads_raw_weights(pl) && (e = launch_weight_prep(pl, *phi_k, false, ws, st)) != hipSuccess) return device_error(e);
     if ((e = launch_state(pl, k, v, *phi_k, ws, st)) != hipSuccess) return device_error(e);
     if ((e = launch_state_reduce(pl, ws, st)) != hipSuccess) return device_error(e);
   }

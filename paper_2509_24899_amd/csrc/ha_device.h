@@ -33,6 +33,12 @@ static __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // Row of C register v for lane group g (also the chained slot order, see above).
 static __device__ __forceinline__ constexpr int crow(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
 
+// Kernels that gather bf16 weights straight from the caller's row-major tensors keep the hidden units of every 32-block
+// in a permuted order: row rho of a layer-1 A fragment is weight row pi(rho), pi = swap of bits 2 and 3.  The C registers
+// 8 s .. 8 s + 7 of layer 1, which feed layer 2 as its B operand, then hold hidden units 16 s + 8 g .. + 7 in order, so
+// the matching A fragment piece of W2 is 16 contiguous bytes of a W2 row (no prepared, re-ordered copy of W2).
+static __device__ __forceinline__ constexpr int perm_hidden(int rho) { return (rho & ~12) | ((rho & 4) << 1) | ((rho & 8) >> 1); }
+
 // Combine a value with the lane that holds the other half of the same C column (lane ^ 32).
 // v_permlane32_swap exchanges the upper half of one register with the lower half of another: called
 // with the same value twice it hands every lane {its own value, the partner's} in some order.

@@ -518,7 +518,7 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, void *ws
 
 hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_feature_map &fm, void *ws,
                         hipStream_t st) {
-  if (pl.D == 128 && pl.HD == 128 && pl.F == 128) return launch_state_pipelined(pl, k, v, fm, ws, st);   // ha_state.hip
+  if (state_uses_pipelined_kernel(pl)) return launch_state_pipelined(pl, k, v, fm, ws, st);   // ha_state.hip
   dim3 grid(pl.n_chunks, pl.B * pl.H);
   const bf16x8 *w1f = ws_ptr<bf16x8>(ws, pl.off_w1k), *w2f = ws_ptr<bf16x8>(ws, pl.off_w2k);
   float *part = ws_ptr<float>(ws, pl.off_part);

@@ -57,6 +57,14 @@ struct WideGradPlan {
       off_dpre, off_part, total;
 };
 
+// Which kernels read bf16 feature-map weights straight from the caller's tensors (no weight_prep_kernel launch needed).
+static inline bool state_uses_pipelined_kernel(const Plan &pl) { return pl.D == 128 && pl.HD == 128 && pl.F == 128; }
+static inline bool state_reads_raw_weights(const Plan &pl) { return state_uses_pipelined_kernel(pl) && !pl.f32; }
+// ... and compacts the softmax keys on the way (no compact_kernel launch): bf16, the plain operator with both kinds of tokens
+static inline bool state_compacts_softmax_keys(const Plan &pl) {
+  return state_uses_pipelined_kernel(pl) && !pl.f32 && pl.CC == 0 && pl.LW == 0 && pl.NS > 0 && pl.NL > 0 && pl.n_chunks > 0;
+}
+
 // Fills `pl` from a validated problem.  Pure host arithmetic.
 void make_plan(const ha_problem &p, const ha_feature_map *phi_q, const ha_feature_map *phi_k, Plan &pl);
 

@@ -63,14 +63,29 @@ static __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 
 // ACT0: the output activation is the softmax over the channels (the default of the paper's maps), scheduled by hand;
 // the other activations (exp, ReLU: no reduction over channels) take a plain epilogue of layer 2.
-template <bool F32, bool ACT0>
+// Softmax-key compaction inside the state pass (COMPACT; bf16, the plain operator).  The softmax tokens T_S (Sec. 3.2)
+// still have to reach the query kernel as matrix-core fragments (ks_frag / vs_frag, see compact_kernel): the 32-key
+// blocks of a head are dealt to the head's workgroups, block chunk + j * (workgroups per head), and ride along with
+// the tiles, two blocks per tile: requested when a tile's contraction has ended, written out one tile later behind
+// the next barrier.  K pieces pass through registers (a fragment piece is 16 contiguous bytes of a key row), V rows
+// go into a small row-major LDS area of the wave's own (direct-to-LDS) and come out through transposing reads in the
+// slot order the query kernel's second product needs.  Every K, V row of the sequence is then read by exactly one
+// pass.  Key indices past the last softmax key repeat it (their logits are masked by the query kernel).
+struct CompactArgs {
+  bf16x8 *ks_frag, *vs_frag;   // [B*H][n_kblocks][512]
+  int NS, n_kblocks;
+};
+
+template <bool F32, bool ACT0, bool COMPACT>
 __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__restrict__ k, const void *__restrict__ v,
-                                                                 const bf16x8 *w1f_all, const bf16x8 *w2f_all,
+                                                                 const void *w1_src, const void *w2_src,
                                                                  const float *__restrict__ b1_all,
                                                                  const float *__restrict__ b2_all, float *__restrict__ part,
                                                                  int H, int NL, int R, int G, int CH, int P, int act,
-                                                                 int64_t sb, int64_t sh, int64_t sn, int N, int CC, int nsub) {
+                                                                 int64_t sb, int64_t sh, int64_t sn, int N, int CC, int nsub,
+                                                                 CompactArgs ca) {
   constexpr int D = 128, HD = D, F = D, TOK = 128;
+  static_assert(!(COMPACT && F32), "the compaction rides on direct-to-LDS loads of bf16 rows");
   constexpr int KS = D / 16, HB = HD / 32, FB = F / 32, NCB = D / 32 + 1, NT = FB * NCB;
   static_assert(HB == 4 && FB == 4 && KS == 8, "the hand-placed schedule below is written for 128 -> 128 -> 128");
   typedef RowTile<D> RT;
@@ -79,15 +94,42 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
   __shared__ __align__(16) float blds[HD + F];
   __shared__ __align__(16) char phi_t[TOK * ROWB];
   __shared__ __align__(16) char v_t[TOK * ROWB];
+  constexpr int CB = 2;                              // softmax-key blocks in flight per tile
+  __shared__ __align__(16) char cstage[COMPACT ? CB * 4 * 2048 : 16];   // per block and wave: 16 key rows x 128 bytes of V
 
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H;
   const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // weight fragments of this head: 64 KiB global -> LDS with direct-to-LDS loads, all in flight at once
-  dma_to_lds(w1f_all + (int64_t)h * (HD * D / 8), &wlds[0], HD * D / 8 / 64, w, 4, lane);
-  dma_to_lds(w2f_all + (int64_t)h * (F * HD / 8), &wlds[HD * D / 8], F * HD / 8 / 64, w, 4, lane);
-  for (int i = tid; i < HD; i += 256) blds[i] = b1_all ? b1_all[(int64_t)h * HD + i] : 0.f;
+  // Weight fragments of this head: 64 KiB global -> LDS with direct-to-LDS loads, all in flight at once.
+  // bf16 weights are gathered straight from the caller's row-major tensors (no preparation pass): a fragment piece is 16
+  // contiguous bytes of a weight row.  For layer 2 that holds because the hidden units of every 32-block are kept in
+  // a permuted order: row rho of a layer-1 fragment is weight row pi(rho), pi = swap of bits 2 and 3, so that the C
+  // registers 8 s .. 8 s + 7 that feed layer 2 as its B operand hold the hidden units 16 s + 8 g .. + 7 in order
+  // and the matching A fragment of W2 is a plain run of a W2 row.  fp32 weights come as prepared bf16 fragments
+  // (weight_prep_kernel; W2 then in the order of the C registers, no permutation).
+  constexpr bool RAWW = !F32;
+  auto pi = [](int rho) { return perm_hidden(rho); };
+  if constexpr (RAWW) {
+    const __bf16 *w1r = static_cast<const __bf16 *>(w1_src) + (int64_t)h * HD * D;
+    const __bf16 *w2r = static_cast<const __bf16 *>(w2_src) + (int64_t)h * F * HD;
+    auto dma = [&](const __bf16 *gp, bf16x8 *chunk) {
+      const unsigned l = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)chunk);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gp) : "memory");
+    };
+    for (int c = w; c < HB * KS; c += 4) {          // fragment (hb, ks) of W1: rows 32 hb + pi(r), columns 16 ks + 8 g ..
+      const int hb = c / KS, ks = c % KS;
+      dma(w1r + (int64_t)(32 * hb + pi(r)) * D + 16 * ks + 8 * g, &wlds[c * 64]);
+    }
+    for (int c = w; c < FB * HB * 2; c += 4) {      // fragment (fb, hb, s) of W2: rows 32 fb + r, columns 32 hb + 16 s + 8 g ..
+      const int s2 = c & 1, hb = (c >> 1) % HB, fb = (c >> 1) / HB;
+      dma(w2r + (int64_t)(32 * fb + r) * HD + 32 * hb + 16 * s2 + 8 * g, &wlds[HD * D / 8 + c * 64]);
+    }
+  } else {
+    dma_to_lds(static_cast<const bf16x8 *>(w1_src) + (int64_t)h * (HD * D / 8), &wlds[0], HD * D / 8 / 64, w, 4, lane);
+    dma_to_lds(static_cast<const bf16x8 *>(w2_src) + (int64_t)h * (F * HD / 8), &wlds[HD * D / 8], F * HD / 8 / 64, w, 4, lane);
+  }
+  for (int i = tid; i < HD; i += 256) blds[i] = b1_all ? b1_all[(int64_t)h * HD + (RAWW ? (i & ~31) + pi(i & 31) : i)] : 0.f;
   for (int i = tid; i < F; i += 256) blds[HD + i] = b2_all ? b2_all[(int64_t)h * F + i] : 0.f;
   // a chain's accumulator starts as the bias of its 32 channels: four 16-byte LDS reads (registers 4 v .. 4 v + 3 are
   // four consecutive channels), no vector instruction
@@ -197,6 +239,60 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(F32 ? 0 : KS) : "memory");     // the weight fragments are older than the K loads
   __syncthreads();                                   // weights and biases are in LDS
   if (lt_begin < lt_end) request_v(lt_begin);
+
+  // ---- softmax-key compaction riding along (see CompactArgs)
+  const int n_wg = gridDim.x;
+  const int nb = COMPACT && chunk < ca.n_kblocks ? (ca.n_kblocks - chunk + n_wg - 1) / n_wg : 0;   // blocks of this workgroup
+  bf16x8 kreg[CB][2];
+  auto key_token = [&](int key) {                    // softmax key -> token (the first G of every R G tokens)
+    key = min(key, ca.NS - 1);
+    return G == 1 ? key * R : (key / G) * R * G + key % G;
+  };
+  typedef RowTile<64> CT;                            // the staged V slice has rows of 128 bytes
+  auto compact_request = [&](int j, int c) {
+    const int kb = chunk + j * n_wg;
+    const int tok_k = key_token(32 * kb + r);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)                      // K fragment chunks ks = w, w + 4: key row r, columns 16 ks + 8 g ..
+      kreg[c][i] = load8<false>(k, base + (int64_t)tok_k * sn + 16 * (w + 4 * i) + 8 * g);
+    // V: this wave stages keys 16 (w % 2) .. + 15 of the block, columns 64 (w / 2) .. + 63
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = 8 * i + (lane >> 3), p = (lane & 7) ^ CT::sw(row);
+      const int tok_v = key_token(32 * kb + 16 * (w & 1) + row);
+      const unsigned l = __builtin_amdgcn_readfirstlane(
+          (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(cstage + (c * 4 + w) * 2048 + i * 1024));
+      const __bf16 *gp = static_cast<const __bf16 *>(v) + base + (int64_t)tok_v * sn + 64 * (w >> 1) + 8 * p;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gp) : "memory");
+    }
+  };
+  // what compact_request(j, c) fetched has landed (the caller has waited for this wave's loads): write the fragments
+  auto compact_store = [&](int j, int c) {
+    const int kb = chunk + j * n_wg;
+    bf16x8 *kdst = ca.ks_frag + ((int64_t)bh * ca.n_kblocks + kb) * 512;
+    bf16x8 *vdst = ca.vs_frag + ((int64_t)bh * ca.n_kblocks + kb) * 512;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) kdst[(w + 4 * i) * 64 + lane] = kreg[c][i];
+    // V^T fragment (rb, s) in the chained slot order: slots 4 jj .. 4 jj + 3 of lane (g, r) are keys 16 s + 8 jj + 4 g + i
+    // of column 32 rb + r; rows 8 jj + 4 g + i of this wave's slice, column block rb % 2 of its 64 columns
+    const char *st = cstage + (c * 4 + w) * 2048;
+#pragma unroll
+    for (int rbl = 0; rbl < 2; ++rbl) {
+      s16x4 half[2];
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const int row = 8 * jj + 4 * tg + ti;
+        half[jj] = ds_read_tr(st, row * 128 + (((4 * rbl + 2 * (tm & 1) + (ta >> 1)) ^ CT::sw(row)) << 4) + 8 * (ta & 1));
+      }
+      vdst[((2 * (w >> 1) + rbl) * 2 + (w & 1)) * 64 + lane] = join(half[0], half[1]);
+    }
+  };
+  if constexpr (COMPACT) {
+#pragma unroll
+    for (int c = 0; c < CB; ++c)
+      if (c < nb) compact_request(c, c);
+  }
+  int cj = 0;                                        // first of the (up to CB) blocks in flight
 
   for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
     u32x4 h_hi[HB][2], h_lo[HB][2];                  // relu(W1 x + b1) as hi + lo bf16 pairs, chained order
@@ -393,9 +489,14 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
         }
     }
     // this wave's V requests of this tile are older than the K loads of the next one just issued
-    if constexpr (F32) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (F32 || COMPACT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (loads and stores are mixed: no counting)
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KS) : "memory");
     __syncthreads();
+    if constexpr (COMPACT) {
+#pragma unroll
+      for (int c = 0; c < CB; ++c)
+        if (cj + c < nb) compact_store(cj + c, c);
+    }
 
     // ---------------- [S | z] += phi^T [V | 1] over the 128 tokens: two 16-token slices (10 matrix instructions)
     // per batch, the 20 transposing reads of the next batch placed two behind each matrix instruction
@@ -432,6 +533,27 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
     }
     __syncthreads();
     if (t0 + TOK < lt_end) request_v(t0 + TOK);
+    if constexpr (COMPACT) {
+      cj += CB;
+      if (t0 + TOK < lt_end) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+          if (cj + c < nb) compact_request(cj + c, c);
+      }
+    }
+  }
+  if constexpr (COMPACT) {
+    // blocks the tiles did not cover (few linear tokens per softmax key, or a short last chunk): two at a time
+    for (; cj < nb; cj += CB) {
+#pragma unroll
+      for (int c = 0; c < CB; ++c)
+        if (cj + c < nb) compact_request(cj + c, c);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int c = 0; c < CB; ++c)
+        if (cj + c < nb) compact_store(cj + c, c);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the staging area is requested again right away
+    }
   }
   {
     float *dst = part + ((int64_t)bh * gridDim.x + chunk) * NT * 1024 + (int64_t)w * NCB * 1024;
@@ -446,13 +568,28 @@ hipError_t launch_state_pipelined(const Plan &pl, const void *k, const void *v, 
                                   hipStream_t st) {
   dim3 grid(pl.n_chunks, pl.B * pl.H);
   char *wsb = static_cast<char *>(ws);
-  const bf16x8 *w1f = reinterpret_cast<const bf16x8 *>(wsb + pl.off_w1k), *w2f = reinterpret_cast<const bf16x8 *>(wsb + pl.off_w2k);
+  // bf16 weights are read in place; fp32 ones as the bf16 fragments weight_prep_kernel left in the workspace
+  const void *w1f = pl.f32 ? static_cast<const void *>(wsb + pl.off_w1k) : fm.w1;
+  const void *w2f = pl.f32 ? static_cast<const void *>(wsb + pl.off_w2k) : fm.w2;
   float *part = reinterpret_cast<float *>(wsb + pl.off_part);
-#define HA_STATE(F32, ACT0) \
-  state_pipelined_kernel<F32, ACT0><<<grid, 256, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.G, pl.CH, pl.P, \
-                                                         pl.act_k, pl.sb, pl.sh, pl.sn, pl.N, pl.CC, pl.nsub)
-  if (pl.act_k == HA_ACT_SOFTMAX) { if (pl.f32) HA_STATE(true, true); else HA_STATE(false, true); }
-  else { if (pl.f32) HA_STATE(true, false); else HA_STATE(false, false); }
+  CompactArgs ca;
+  ca.ks_frag = reinterpret_cast<bf16x8 *>(wsb + pl.off_ks);
+  ca.vs_frag = reinterpret_cast<bf16x8 *>(wsb + pl.off_vs);
+  ca.NS = pl.NS;
+  ca.n_kblocks = pl.n_kblocks;
+  const bool cmp = state_compacts_softmax_keys(pl);
+#define HA_STATE(F32, ACT0, CMP) \
+  state_pipelined_kernel<F32, ACT0, CMP><<<grid, 256, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.G, pl.CH, \
+                                                              pl.P, pl.act_k, pl.sb, pl.sh, pl.sn, pl.N, pl.CC, pl.nsub, ca)
+  if (pl.act_k == HA_ACT_SOFTMAX) {
+    if (pl.f32) HA_STATE(true, true, false);
+    else if (cmp) HA_STATE(false, true, true);
+    else HA_STATE(false, true, false);
+  } else {
+    if (pl.f32) HA_STATE(true, false, false);
+    else if (cmp) HA_STATE(false, false, true);
+    else HA_STATE(false, false, false);
+  }
 #undef HA_STATE
   return hipGetLastError();
 }
