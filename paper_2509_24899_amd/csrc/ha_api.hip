@@ -190,8 +190,11 @@ static ha_status device_error(hipError_t e) {
 }
 
 // ev (optional): ev[0] before compaction, ev[1] after it, ev[2] after the state is reduced.
+// prep_q (optional): the query-side map; where the plain reduction runs, its weights are re-ordered in the same launch
+// and *prep_q_done is set.
 static ha_status run_key_side(const Plan &pl, const void *k, const void *v, const ha_feature_map *phi_k, void *ws,
-                              hipStream_t st, hipEvent_t *ev = nullptr, const WidePlan *wide = nullptr) {
+                              hipStream_t st, hipEvent_t *ev = nullptr, const WidePlan *wide = nullptr,
+                              const ha_feature_map *prep_q = nullptr, bool *prep_q_done = nullptr) {
   hipError_t e;
   if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return device_error(e);
   // (for the 128-wide bf16 maps the state pass compacts the softmax keys on its way: one pass over K and V)
@@ -204,7 +207,12 @@ static ha_status run_key_side(const Plan &pl, const void *k, const void *v, cons
     // (the pipelined state pass of the 128-wide bf16 maps gathers the weights from the caller's tensors itself)
     if (!state_reads_raw_weights(pl) && (e = launch_weight_prep(pl, *phi_k, false, ws, st)) != hipSuccess) return device_error(e);
     if ((e = launch_state(pl, k, v, *phi_k, ws, st)) != hipSuccess) return device_error(e);
-    if ((e = launch_state_reduce(pl, ws, st)) != hipSuccess) return device_error(e);
+    if (prep_q && prep_q_done && pl.CC == 0 && pl.LW == 0) {
+      if ((e = launch_state_reduce_with_prep(pl, *prep_q, ws, st)) != hipSuccess) return device_error(e);
+      *prep_q_done = true;
+    } else if ((e = launch_state_reduce(pl, ws, st)) != hipSuccess) {
+      return device_error(e);
+    }
   }
   if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return device_error(e);
   return HA_OK;
@@ -242,12 +250,14 @@ static ha_status forward_impl(const ha_problem *p, const void *q, const void *k,
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipEvent_t *ev = ha::prof_events();
   const bool light = ev && ha::g_prof.dominant_only;
-  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, light ? nullptr : ev, wide ? &wp : nullptr);
+  bool prep_q_done = false;
+  s = ha::run_key_side(pl, k, v, phi_k, workspace, st, light ? nullptr : ev, wide ? &wp : nullptr, wide ? nullptr : phi_q,
+                       &prep_q_done);
   if (s != HA_OK) return s;
   hipError_t e;
   if (wide) {
     if ((e = ha::launch_wide_query_side(pl, wp, q, *phi_q, workspace, st)) != hipSuccess) return ha::device_error(e);
-  } else if (pl.NL > 0 && (e = ha::launch_weight_prep(pl, *phi_q, true, workspace, st)) != hipSuccess) {
+  } else if (pl.NL > 0 && !prep_q_done && (e = ha::launch_weight_prep(pl, *phi_q, true, workspace, st)) != hipSuccess) {
     return ha::device_error(e);
   }
   if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return ha::device_error(e);

@@ -26,11 +26,9 @@ namespace ha {
 //   w1f[h][hb][ks][lane][t] = W1[h][32hb + r][16ks + 8g + t]                       (natural order)
 //   w2f[h][fb][hb][s][lane][t] = W2[h][32fb + r][32hb + crow(8s + t, g)]           (chained order)
 template <bool F32>
-__global__ __launch_bounds__(256) void weight_prep_kernel(const void *__restrict__ w1, const void *__restrict__ w2,
-                                                          __bf16 *__restrict__ w1f, __bf16 *__restrict__ w2f,
-                                                          int D, int HD, int F) {
-  const int h = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
+static __device__ __forceinline__ void weight_prep_body(const void *__restrict__ w1, const void *__restrict__ w2,
+                                                        __bf16 *__restrict__ w1f, __bf16 *__restrict__ w2f,
+                                                        int D, int HD, int F, int h, int e) {
   const int t = e & 7, lane = (e >> 3) & 63, rest = e >> 9;
   const int r = lane & 31, g = lane >> 5;
   auto ld = [](const void *p, int64_t i) -> float {
@@ -48,6 +46,13 @@ __global__ __launch_bounds__(256) void weight_prep_kernel(const void *__restrict
     w2f[(int64_t)h * F * HD + e] =
         static_cast<__bf16>(ld(w2, ((int64_t)h * F + 32 * fb + r) * HD + 32 * hb + crow(8 * s + t, g)));
   }
+}
+
+template <bool F32>
+__global__ __launch_bounds__(256) void weight_prep_kernel(const void *__restrict__ w1, const void *__restrict__ w2,
+                                                          __bf16 *__restrict__ w1f, __bf16 *__restrict__ w2f,
+                                                          int D, int HD, int F) {
+  weight_prep_body<F32>(w1, w2, w1f, w2f, D, HD, F, blockIdx.y, blockIdx.x * 256 + threadIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -360,12 +365,10 @@ __global__ __launch_bounds__(256, 1) void state_kernel(const void *__restrict__ 
 // state_reduce_kernel: grid (NT*1024/256, B*H).  Sums the chunk partials in chunk order (bitwise
 // reproducible), writes S [F][D] and z [F] in fp32, and S^T split into hi + lo bf16 in the
 // A-operand order of the query kernel:  st[bh][rb][fb][s][lane][t] = S[32fb + crow(8s + t, g)][32rb + r].
-__global__ __launch_bounds__(256) void state_reduce_kernel(const float *__restrict__ part, float *__restrict__ S,
-                                                           float *__restrict__ z, __bf16 *__restrict__ st_hi,
-                                                           __bf16 *__restrict__ st_lo, int D, int F, int n_chunks) {
+static __device__ __forceinline__ void state_reduce_body(const float *__restrict__ part, float *__restrict__ S,
+                                                         float *__restrict__ z, __bf16 *__restrict__ st_hi,
+                                                         __bf16 *__restrict__ st_lo, int D, int F, int n_chunks, int bh, int e) {
   const int NCB = D / 32 + 1, FB = F / 32, NT = FB * NCB;
-  const int bh = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= NT * 1024) return;
   const int ti = e >> 10, x = (e >> 6) & 15, lane = e & 63, r = lane & 31, g = lane >> 5;
   // four chunks per step so that their loads are in flight together; fixed order of additions
@@ -395,6 +398,26 @@ __global__ __launch_bounds__(256) void state_reduce_kernel(const float *__restri
   } else if (r == 0) {
     z[(int64_t)bh * F + ch] = sum;
   }
+}
+
+__global__ __launch_bounds__(256) void state_reduce_kernel(const float *__restrict__ part, float *__restrict__ S,
+                                                           float *__restrict__ z, __bf16 *__restrict__ st_hi,
+                                                           __bf16 *__restrict__ st_lo, int D, int F, int n_chunks) {
+  state_reduce_body(part, S, z, st_hi, st_lo, D, F, n_chunks, blockIdx.y, blockIdx.x * 256 + threadIdx.x);
+}
+
+// The state reduction and the re-ordering of the query-side weights in one launch (two small, independent jobs that
+// would otherwise each wait for the previous kernel to drain): rows y < BH of the grid reduce, rows BH + h prepare
+// the weights of head h.
+template <bool F32>
+__global__ __launch_bounds__(256) void state_reduce_prep_kernel(const float *__restrict__ part, float *__restrict__ S,
+                                                                float *__restrict__ z, __bf16 *__restrict__ st_hi,
+                                                                __bf16 *__restrict__ st_lo, int D, int F, int n_chunks, int BH,
+                                                                const void *__restrict__ w1, const void *__restrict__ w2,
+                                                                __bf16 *__restrict__ w1f, __bf16 *__restrict__ w2f, int HD) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if ((int)blockIdx.y < BH) state_reduce_body(part, S, z, st_hi, st_lo, D, F, n_chunks, blockIdx.y, e);
+  else weight_prep_body<F32>(w1, w2, w1f, w2f, D, HD, F, blockIdx.y - BH, e);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -544,6 +567,19 @@ hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsig
   if (pl.D == 64) { if (pl.f32) HA_WSTATE(64, true); else HA_WSTATE(64, false); }
   else { if (pl.f32) HA_WSTATE(128, true); else HA_WSTATE(128, false); }
 #undef HA_WSTATE
+  return hipGetLastError();
+}
+
+hipError_t launch_state_reduce_with_prep(const Plan &pl, const ha_feature_map &phi_q, void *ws, hipStream_t st) {
+  const int n_prep = ((pl.HD * pl.D > pl.F * pl.HD ? pl.HD * pl.D : pl.F * pl.HD) + 255) / 256;
+  const int n_red = pl.n_state_tiles * 1024 / 256;
+  dim3 grid(n_red > n_prep ? n_red : n_prep, pl.B * pl.H + pl.H);
+#define HA_RP(F32) \
+  state_reduce_prep_kernel<F32><<<grid, 256, 0, st>>>(ws_ptr<float>(ws, pl.off_part), ws_ptr<float>(ws, pl.off_S), \
+      ws_ptr<float>(ws, pl.off_z), ws_ptr<__bf16>(ws, pl.off_sthi), ws_ptr<__bf16>(ws, pl.off_stlo), pl.D, pl.F, pl.n_chunks, \
+      pl.B * pl.H, phi_q.w1, phi_q.w2, ws_ptr<__bf16>(ws, pl.off_w1q), ws_ptr<__bf16>(ws, pl.off_w2q), pl.HD)
+  if (pl.f32) HA_RP(true); else HA_RP(false);
+#undef HA_RP
   return hipGetLastError();
 }
 

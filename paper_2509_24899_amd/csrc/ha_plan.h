@@ -79,6 +79,8 @@ hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsig
                                  const ha_feature_map &fm, const void *w1f, const void *w2f, float *part, int CH,
                                  int n_chunks, hipStream_t st);
 hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st);
+// the plain reduction (no prefix / window states) together with the re-ordering of phi_q's weights, one launch
+hipError_t launch_state_reduce_with_prep(const Plan &pl, const ha_feature_map &phi_q, void *ws, hipStream_t st);
 hipError_t launch_query(const Plan &pl, const void *q, const ha_feature_map *phi_q, void *out, float *row_den, void *ws,
                         hipStream_t st, const WidePlan *wide = nullptr);
 // ha_wide.hip
