@@ -3,21 +3,23 @@
 //     S = sum_{j in T_L} phi_k(k_j)^T v_j   (F x d),      z = sum_{j in T_L} phi_k(k_j)   (F),
 // as per-chunk partial tiles that state_reduce_kernel adds up in a fixed order.  gfx950 only.
 //
-// One workgroup = 4 waves = one wave per SIMD with the whole register file, so nothing but the wave's own
-// instruction stream hides latency: the kernel is written as a software pipeline.
-//   * Layer 1 runs two row blocks at a time (two independent accumulator chains, their matrix instructions
-//     alternate), all weight fragments of the layer requested up front.
-//   * Layer 2 runs two output tiles at a time in steps of one hidden block; the fragments of the next step are
-//     requested before the current step's matrix instructions, and the softmax of the finished pair of tiles
-//     (online form: exponentials against the running maximum, one factor per pair at the end) is spread over the
-//     steps of the next pair, so the vector work sits under matrix work.
-//   * V goes global -> LDS with direct-to-LDS loads (no registers), row-major, one tile ahead: requested when the
-//     previous tile's contraction has ended, awaited before this tile's.  phi is written row-major as well (8-byte
-//     pieces).  Both operands of the contraction over the tokens, [S | z] += phi^T [V | 1], then come out of LDS
-//     through the transposing 64-bit reads of gfx950 (ds_read_b64_tr_b16): four consecutive tokens of one column
-//     per lane, two reads per 8-slot fragment; no 2-byte scatter anywhere.
-//   * The contraction requests the fragments of the next two 16-token slices while the matrix instructions of the
-//     current two run.
+// One workgroup = 8 waves, two per SIMD, in two roles that meet at two barriers per 128-token tile:
+//   * waves 0 - 3 evaluate phi_k, 32 token rows each, as a software pipeline: layer 1 runs two row blocks at a time
+//     (two independent accumulator chains, their matrix instructions alternate); layer 2 runs two output tiles at a
+//     time in steps of one hidden block, the fragments of the next step requested before the current step's matrix
+//     instructions, and the softmax of the finished pair of tiles (online form: exponentials against the running
+//     maximum, one factor per pair at the end) is spread over the steps of the next pair, so vector work sits under
+//     matrix work.  The K rows of the next tile are requested in the middle of the current one.  phi leaves as
+//     row-major bf16 (8-byte pieces) into LDS between the two barriers.
+//   * waves 4 - 7 own one 32-row block of [S | z] each.  They fetch the V rows one tile ahead (global -> registers),
+//     write them row-major into LDS between the two barriers, and contract [S | z] += phi^T [V | 1] over the tile
+//     while the other four waves are already in the next tile's layers.  Both operands of that contraction come out
+//     of LDS through the transposing 64-bit reads of gfx950 (ds_read_b64_tr_b16): four consecutive tokens of one
+//     column per lane, two reads per 8-slot fragment, no 2-byte scatter anywhere; the fragments of the next two
+//     16-token slices are requested while the matrix instructions of the current two run.  These waves also carry
+//     the softmax-key compaction (below): it costs the feature-map waves nothing but issue slots.
+// Barrier A of a tile: the contraction of the previous tile has read both LDS tiles; barrier B: both are refilled.
+// Every wave of either role passes both barriers once per tile, and both roles count the same tiles.
 #include "ha_device.h"
 #include "ha_plan.h"
 
@@ -66,10 +68,10 @@ static __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 // Softmax-key compaction inside the state pass (COMPACT; bf16, the plain operator).  The softmax tokens T_S (Sec. 3.2)
 // still have to reach the query kernel as matrix-core fragments (ks_frag / vs_frag, see compact_kernel): the 32-key
 // blocks of a head are dealt to the head's workgroups, block chunk + j * (workgroups per head), and ride along with
-// the tiles, two blocks per tile: requested when a tile's contraction has ended, written out one tile later behind
-// the next barrier.  K pieces pass through registers (a fragment piece is 16 contiguous bytes of a key row), V rows
-// go into a small row-major LDS area of the wave's own (direct-to-LDS) and come out through transposing reads in the
-// slot order the query kernel's second product needs.  Every K, V row of the sequence is then read by exactly one
+// the tiles, two blocks per tile: requested before a tile's contraction, written out behind it.  K pieces pass
+// through registers (a fragment piece is 16 contiguous bytes of a key row), V rows go into a small row-major LDS
+// area of the wave's own (direct-to-LDS) and come out through transposing reads in the slot order the query
+// kernel's second product needs.  Every K, V row of the sequence is then read by exactly one
 // pass.  Key indices past the last softmax key repeat it (their logits are masked by the query kernel).
 struct CompactArgs {
   bf16x8 *ks_frag, *vs_frag;   // [B*H][n_kblocks][512]
@@ -77,7 +79,7 @@ struct CompactArgs {
 };
 
 template <bool F32, bool ACT0, bool COMPACT>
-__global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__restrict__ k, const void *__restrict__ v,
+__global__ __launch_bounds__(512, 1) void state_pipelined_kernel(const void *__restrict__ k, const void *__restrict__ v,
                                                                  const void *w1_src, const void *w2_src,
                                                                  const float *__restrict__ b1_all,
                                                                  const float *__restrict__ b2_all, float *__restrict__ part,
@@ -100,7 +102,8 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H;
   const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w = wave & 3;                            // index within the role
   // Weight fragments of this head: 64 KiB global -> LDS with direct-to-LDS loads, all in flight at once.
   // bf16 weights are gathered straight from the caller's row-major tensors (no preparation pass): a fragment piece is 16
   // contiguous bytes of a weight row.  For layer 2 that holds because the hidden units of every 32-block are kept in
@@ -117,30 +120,20 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
       const unsigned l = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)chunk);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gp) : "memory");
     };
-    for (int c = w; c < HB * KS; c += 4) {          // fragment (hb, ks) of W1: rows 32 hb + pi(r), columns 16 ks + 8 g ..
+    for (int c = wave; c < HB * KS; c += 8) {       // fragment (hb, ks) of W1: rows 32 hb + pi(r), columns 16 ks + 8 g ..
       const int hb = c / KS, ks = c % KS;
       dma(w1r + (int64_t)(32 * hb + pi(r)) * D + 16 * ks + 8 * g, &wlds[c * 64]);
     }
-    for (int c = w; c < FB * HB * 2; c += 4) {      // fragment (fb, hb, s) of W2: rows 32 fb + r, columns 32 hb + 16 s + 8 g ..
+    for (int c = wave; c < FB * HB * 2; c += 8) {   // fragment (fb, hb, s) of W2: rows 32 fb + r, columns 32 hb + 16 s + 8 g ..
       const int s2 = c & 1, hb = (c >> 1) % HB, fb = (c >> 1) / HB;
       dma(w2r + (int64_t)(32 * fb + r) * HD + 32 * hb + 16 * s2 + 8 * g, &wlds[HD * D / 8 + c * 64]);
     }
   } else {
-    dma_to_lds(static_cast<const bf16x8 *>(w1_src) + (int64_t)h * (HD * D / 8), &wlds[0], HD * D / 8 / 64, w, 4, lane);
-    dma_to_lds(static_cast<const bf16x8 *>(w2_src) + (int64_t)h * (F * HD / 8), &wlds[HD * D / 8], F * HD / 8 / 64, w, 4, lane);
+    dma_to_lds(static_cast<const bf16x8 *>(w1_src) + (int64_t)h * (HD * D / 8), &wlds[0], HD * D / 8 / 64, wave, 8, lane);
+    dma_to_lds(static_cast<const bf16x8 *>(w2_src) + (int64_t)h * (F * HD / 8), &wlds[HD * D / 8], F * HD / 8 / 64, wave, 8, lane);
   }
-  for (int i = tid; i < HD; i += 256) blds[i] = b1_all ? b1_all[(int64_t)h * HD + (RAWW ? (i & ~31) + pi(i & 31) : i)] : 0.f;
-  for (int i = tid; i < F; i += 256) blds[HD + i] = b2_all ? b2_all[(int64_t)h * F + i] : 0.f;
-  // a chain's accumulator starts as the bias of its 32 channels: four 16-byte LDS reads (registers 4 v .. 4 v + 3 are
-  // four consecutive channels), no vector instruction
-  auto bias_tile = [&](const float *b, int blk) {
-    const f32x4 *src = reinterpret_cast<const f32x4 *>(b + 32 * blk + 4 * g);
-    const f32x8 lo = __builtin_shufflevector(src[0], src[2], 0, 1, 2, 3, 4, 5, 6, 7);
-    const f32x8 hi = __builtin_shufflevector(src[4], src[6], 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-  };
-  const float *b1 = &blds[0], *b2 = &blds[HD];
-  const lds_frag_ptr w1f = (lds_frag_ptr)&wlds[0], w2f = (lds_frag_ptr)&wlds[HD * D / 8];
+  for (int i = tid; i < HD; i += 512) blds[i] = b1_all ? b1_all[(int64_t)h * HD + (RAWW ? (i & ~31) + pi(i & 31) : i)] : 0.f;
+  for (int i = tid; i < F; i += 512) blds[HD + i] = b2_all ? b2_all[(int64_t)h * F + i] : 0.f;
   const LinearMap lmap(R, G);
 
   // this workgroup's range of linear tokens (see the chunking of the plan)
@@ -152,25 +145,250 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
     lt_end = min(lt_begin + CH, hi - softmax_before(hi, R, G));
   }
 
+  if (wave < 4) {
+    // =============================== the feature map: phi_k of 32 token rows per wave ===============================
+    // a chain's accumulator starts as the bias of its 32 channels: four 16-byte LDS reads (registers 4 v .. 4 v + 3 are
+    // four consecutive channels), no vector instruction
+    auto bias_tile = [&](const float *b, int blk) {
+      const f32x4 *src = reinterpret_cast<const f32x4 *>(b + 32 * blk + 4 * g);
+      const f32x8 lo = __builtin_shufflevector(src[0], src[2], 0, 1, 2, 3, 4, 5, 6, 7);
+      const f32x8 hi = __builtin_shufflevector(src[4], src[6], 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+    };
+    const float *b1 = &blds[0], *b2 = &blds[HD];
+    const lds_frag_ptr w1f = (lds_frag_ptr)&wlds[0], w2f = (lds_frag_ptr)&wlds[HD * D / 8];
+    // phi writes: this lane owns token row tf and, per (fb, q), the 8-byte run of channels 32 fb + 8 q + 4 g .. + 3.
+    // The phi tile is swizzled over sixteen rows: piece p of row t sits at p ^ psw(t), psw(t) = 4 (t % 4) + (t / 4) % 4,
+    // so that the 32 rows one write instruction touches fall on 16 different 16-byte pieces (two rows per piece pair
+    // with the 8-byte halves of g: conflict-free in two passes) while a transposing read still finds its four rows in
+    // four different 64-byte groups.
+    const int tf = w * 32 + r;
+    auto psw = [](int t) { return 4 * (t & 3) + ((t >> 2) & 3); };
+    int phi_base[FB][4];
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) phi_base[fb][q] = tf * ROWB + 8 * g + (((4 * fb + q) ^ psw(tf)) << 4);
+    auto load_k = [&](int t0, bf16x8 (&dst)[KS]) {
+      const int tok = lmap.token(min(t0 + tf, NL - 1));   // rows past the end repeat the last linear token; masked later
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) dst[ks] = load8<F32>(k, base + (int64_t)tok * sn + 16 * ks + 8 * g);
+    };
+    bf16x8 xf[KS];
+    load_k(lt_begin, xf);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(F32 ? 0 : KS) : "memory");     // the weight fragments are older than the K loads
+    __syncthreads();                                   // weights and biases are in LDS
+
+    for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
+      u32x4 h_hi[HB][2], h_lo[HB][2];                  // relu(W1 x + b1) as hi + lo bf16 pairs, chained order
+      f32x16 u[FB];
+      // registers x, x + 1 of a finished layer-1 tile -> ReLU -> hi + lo (8 vector instructions)
+      auto conv2 = [&](const f32x16 &hh, int hb, int x) {
+        const float a = fmaxf(hh[x], 0.f), b = fmaxf(hh[x + 1], 0.f);
+        const unsigned hi = pack_bf16(a, b);
+        h_hi[hb][x >> 3][(x & 7) >> 1] = hi;
+        h_lo[hb][x >> 3][(x & 7) >> 1] = pack_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+      };
+      auto hop = [&](const u32x4 &t) { return __builtin_bit_cast(bf16x8, t); };
+      {
+        // ---------------- layer 1: two row blocks at a time (two independent chains, alternating); the fragments of
+        // the second pair arrive four k-steps ahead of their use
+        f32x16 ha0, ha1, ha2, ha3;
+        bf16x8 wA[2][KS], wB[2][KS / 2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) wA[e][ks] = frag_at(w1f, e * KS + ks, lane);
+        ha0 = bias_tile(b1, 0);
+        ha1 = bias_tile(b1, 1);
+        ha2 = bias_tile(b1, 2);
+        ha3 = bias_tile(b1, 3);
+        HA_FENCE();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {              // blocks 0, 1
+          ha0 = mfma32(wA[0][ks], xf[ks], ha0);
+          if (ks >= KS / 2) wB[0][ks - KS / 2] = frag_at(w1f, 2 * KS + ks - KS / 2, lane);
+          HA_FENCE();
+          ha1 = mfma32(wA[1][ks], xf[ks], ha1);
+          if (ks >= KS / 2) wB[1][ks - KS / 2] = frag_at(w1f, 3 * KS + ks - KS / 2, lane);
+          HA_FENCE();
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {              // blocks 2, 3 under the conversion of blocks 0, 1
+          ha2 = mfma32(wB[0][ks % (KS / 2)], xf[ks], ha2);
+          if (ks < KS / 2) wB[0][ks] = frag_at(w1f, 2 * KS + ks + KS / 2, lane);
+          conv2(ha0, 0, 2 * ks);
+          ha3 = mfma32(wB[1][ks % (KS / 2)], xf[ks], ha3);
+          if (ks < KS / 2) wB[1][ks] = frag_at(w1f, 3 * KS + ks + KS / 2, lane);
+          conv2(ha1, 1, 2 * ks);
+        }
+        // one matrix instruction, then one conversion's worth of vector instructions, sixteen times; the accumulators
+        // are tied to the end of this stretch so that the matrix instructions cannot drift out of it
+#pragma unroll
+        for (int i = 0; i < 2 * KS; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+        }
+        asm volatile("" : "+v"(ha2), "+v"(ha3));
+        HA_FENCE();
+        load_k(t0 + TOK, xf);                          // the K rows of the next tile travel during the rest of this one
+        HA_FENCE();
+
+        // ---------------- layer 2: u = W2 h + b2, two 32-channel tiles at a time, one hidden block (8 matrix
+        // instructions, 4 fragments) per step; the fragments of the next step are requested behind the step's first
+        // matrix instruction.  Under the steps: first the conversion of layer-1 blocks 2, 3, later the softmax
+        // exponentials of the finished pair of tiles.
+        bf16x8 wa[2][2], wb[2][2];
+        auto w2_frags = [&](int fp, int hb, bf16x8 (&dst)[2][2]) {
+#pragma unroll
+          for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) dst[e][s] = frag_at(w2f, ((fp + e) * HB + hb) * 2 + s, lane);
+        };
+        w2_frags(0, 0, wa);
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb) u[fb] = bias_tile(b2, fb);
+        float m0 = 0.f, off0 = 0.f, sum0 = 0.f;
+        HA_FENCE();
+#pragma unroll
+        for (int fp = 0; fp < FB; fp += 2) {
+#pragma unroll
+          for (int hb = 0; hb < HB; ++hb) {
+            bf16x8 (&cur)[2][2] = (hb & 1) ? wb : wa;
+            bf16x8 (&nxt)[2][2] = (hb & 1) ? wa : wb;
+#pragma unroll
+            for (int slot = 0; slot < 8; ++slot) {
+              const int e = slot & 1, hi = (slot >> 1) & 1, s = slot >> 2;
+              u[fp + e] = mfma32(cur[e][s], hop(hi ? h_hi[hb][s] : h_lo[hb][s]), u[fp + e]);
+              if (slot == 0) {
+                if (hb + 1 < HB) w2_frags(fp, hb + 1, nxt);
+                else if (fp + 2 < FB) w2_frags(fp + 2, 0, nxt);
+              }
+              const int n = hb * 8 + slot;             // 0 .. 31 within the pair
+              if (fp == 0) {
+                if (n < 8) conv2(ha2, 2, 2 * n);       // needed from step 2 on
+                else if (n < 16) conv2(ha3, 3, 2 * (n - 8));
+              } else if constexpr (ACT0) {
+                // softmax of tiles 0, 1: their maximum in the first two slots, then one exponential per slot
+                if (n == 0) {
+                  float t = fmaxf(u[0][0], u[0][1]);
+#pragma unroll
+                  for (int x = 2; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[0][x]), u[0][x + 1]);
+                  m0 = t;
+                } else if (n == 1) {
+                  float t = m0;
+#pragma unroll
+                  for (int x = 0; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[1][x]), u[1][x + 1]);
+                  m0 = xhalf_max(t);
+                  off0 = -m0 * kLog2e;
+                } else {
+                  auto ex = [&](int i) {
+                    u[i >> 4][i & 15] = fast_exp2(__builtin_fmaf(u[i >> 4][i & 15], kLog2e, off0));
+                    sum0 += u[i >> 4][i & 15];
+                  };
+                  ex(n - 2);
+                  if (n >= 30) ex(n);                  // 30 slots for 32 values: the last two slots take two each
+                }
+              }
+              HA_FENCE();
+            }
+          }
+        }
+        if constexpr (ACT0) {
+          // tiles 2, 3 against the overall maximum, which is known now
+          float t = fmaxf(u[2][0], u[2][1]);
+#pragma unroll
+          for (int x = 2; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[2][x]), u[2][x + 1]);
+#pragma unroll
+          for (int x = 0; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[3][x]), u[3][x + 1]);
+          const float m = fmaxf(m0, xhalf_max(t));
+          const float off = -m * kLog2e;
+          float sum1 = 0.f;
+#pragma unroll
+          for (int fb = 2; fb < 4; ++fb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+              u[fb][x] = fast_exp2(__builtin_fmaf(u[fb][x], kLog2e, off));
+              sum1 += u[fb][x];
+            }
+          const float carry = fast_exp2((m0 - m) * kLog2e);        // tiles 0, 1 were exponentiated against m0
+          const float inv = 1.0f / xhalf_sum(sum0 * carry + sum1);
+          const float f0 = carry * inv;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) {
+            u[0][x] *= f0;
+            u[1][x] *= f0;
+            u[2][x] *= inv;
+            u[3][x] *= inv;
+          }
+        } else if (act == 1) {
+#pragma unroll
+          for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) u[fb][x] = fast_exp2(u[fb][x] * kLog2e);
+        } else {
+#pragma unroll
+          for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) u[fb][x] = fmaxf(u[fb][x], 0.f);
+        }
+      }
+      if (P == 2) {
+        // the paper's default degree: the upper half of the channels is squared
+#pragma unroll
+        for (int fb = FB / 2; fb < FB; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) u[fb][x] *= u[fb][x];
+      } else if (P > 1) {
+        // slice p = channel / Dp (0-based) gets p extra multiplications by the activation value; Dp is a multiple
+        // of 8, so the power depends only on the group of four registers
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int extra = ((32 * fb + 8 * q) * P) / F;
+            if (extra > 0) {
+              const float t0_ = u[fb][4 * q], t1_ = u[fb][4 * q + 1], t2_ = u[fb][4 * q + 2], t3_ = u[fb][4 * q + 3];
+              for (int i = 0; i < extra; ++i) {
+                u[fb][4 * q] *= t0_;
+                u[fb][4 * q + 1] *= t1_;
+                u[fb][4 * q + 2] *= t2_;
+                u[fb][4 * q + 3] *= t3_;
+              }
+            }
+          }
+      }
+      if (t0 + TOK > lt_end) {                        // ragged end of the range: padded tokens add nothing
+        const float keep = t0 + tf < lt_end ? 1.f : 0.f;
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) u[fb][x] *= keep;
+      }
+      // ---------------- phi -> LDS, row-major: registers 4 q .. 4 q + 3 of tile fb are channels 32 fb + 8 q + 4 g .. + 3
+      typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+      u32x2 four[FB][4];
+#pragma unroll
+      for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          four[fb][q] = u32x2{pack_bf16(u[fb][4 * q], u[fb][4 * q + 1]), pack_bf16(u[fb][4 * q + 2], u[fb][4 * q + 3])};
+      __syncthreads();                                 // A: the contraction of the previous tile has read phi_t
+#pragma unroll
+      for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x2 *>(phi_t + phi_base[fb][q]) = four[fb][q];
+      __syncthreads();                                 // B: phi_t and v_t hold this tile
+    }
+    return;
+  }
+
+  // ================= the contraction over the tokens, V, and the softmax-key compaction (waves 4 .. 7) =================
   f32x16 acc[NCB];                                   // wave w owns row block w of [S | z]
 #pragma unroll
   for (int i = 0; i < NCB; ++i)
 #pragma unroll
     for (int x = 0; x < 16; ++x) acc[i][x] = 0.f;
-
-  // ---- addressing of the two row-major tiles
-  // phi writes: this lane owns token row tf and, per (fb, q), the 8-byte run of channels 32 fb + 8 q + 4 g .. + 3
-  const int tf = w * 32 + r;
-  // The phi tile is swizzled over sixteen rows: piece p of row t sits at p ^ psw(t), psw(t) = 4 (t % 4) + (t / 4) % 4,
-  // so that the 32 rows one write instruction touches fall on 16 different 16-byte pieces (two rows per piece pair
-  // with the 8-byte halves of g: conflict-free in two passes) while a transposing read still finds its four rows in
-  // four different 64-byte groups.
-  auto psw = [](int t) { return 4 * (t & 3) + ((t >> 2) & 3); };
-  int phi_base[FB][4];
-#pragma unroll
-  for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) phi_base[fb][q] = tf * ROWB + 8 * g + (((4 * fb + q) ^ psw(tf)) << 4);
   // transposing reads: lane = (group m, i, a); see ds_read_tr.  Rows T0 + i with T0 a multiple of 4, so the swizzle
   // of the row is a per-lane constant; per column block one base offset, k-steps and half-fragments are immediates
   const int tm = lane >> 4, ti = (lane >> 2) & 3, ta = lane & 3, tg = tm >> 1;
@@ -186,22 +404,16 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
 #pragma unroll
   for (int jj = 0; jj < 2; ++jj)
     a_base[jj] = (8 * tg + ti) * ROWB + (((4 * w + 2 * (tm & 1) + (ta >> 1)) ^ (4 * ti + ((2 * tg + jj) & 3))) << 4) + 8 * (ta & 1);
-  // V: 1 KiB (64 pieces) per direct-to-LDS instruction; lane -> (row, physical piece) -> logical piece of that row
-  constexpr int RPI = 1024 / ROWB;                   // rows per instruction
-  constexpr int NVI = TOK / RPI;                     // instructions per tile, dealt round-robin to the 4 waves
-  const int v_row = lane / PPR, v_pp = lane % PPR;
-
-  auto load_k = [&](int t0, bf16x8 (&dst)[KS]) {
-    const int tok = lmap.token(min(t0 + tf, NL - 1));   // rows past the end repeat the last linear token; masked later
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) dst[ks] = load8<F32>(k, base + (int64_t)tok * sn + 16 * ks + 8 * g);
-  };
-  // V rows of the tile that starts at linear token t0 into v_t (bf16: direct-to-LDS; fp32: through registers).
+  // V rows travel global -> registers one tile ahead and are written into v_t (row-major, 1 KiB = 4 rows per
+  // instruction, lane -> (row, physical piece) -> logical piece of that row) between the two barriers of a tile.
   // This lane's rows are 4 RPI apart: one exact division gives the first one's group, the others follow by adding
   // the quotient and remainder of the row distance (a tile that reaches past the last linear token clamps every row
   // on its own instead).
+  constexpr int RPI = 1024 / ROWB, NVI = TOK / RPI;
+  const int v_row = lane / PPR, v_pp = lane % PPR;
   const int step_q = (4 * RPI) / lmap.d, step_r = (4 * RPI) % lmap.d;
-  auto request_v = [&](int t0) {
+  bf16x8 vreg[NVI / 4];
+  auto load_v = [&](int t0) {
     const bool whole = t0 + TOK <= NL;                 // wave-uniform
     const int i0 = t0 + w * RPI + v_row;
     int grp = 0, rem = 0;
@@ -222,23 +434,14 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
       } else {
         tok = lmap.token(min(t0 + row, NL - 1));
       }
-      const int p = v_pp ^ RT::sw(row);
-      if constexpr (F32) {
-        *reinterpret_cast<bf16x8 *>(v_t + row * ROWB + (v_pp << 4)) = load8<true>(v, base + (int64_t)tok * sn + p * 8);
-      } else {
-        const unsigned l = __builtin_amdgcn_readfirstlane(
-            (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)(v_t + (4 * c + w) * 1024));
-        const __bf16 *gp = static_cast<const __bf16 *>(v) + base + (int64_t)tok * sn + p * 8;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gp) : "memory");
-      }
+      vreg[c] = load8<F32>(v, base + (int64_t)tok * sn + (v_pp ^ RT::sw(row)) * 8);
     }
   };
-
-  bf16x8 xf[KS];
-  load_k(lt_begin, xf);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(F32 ? 0 : KS) : "memory");     // the weight fragments are older than the K loads
-  __syncthreads();                                   // weights and biases are in LDS
-  if (lt_begin < lt_end) request_v(lt_begin);
+  auto write_v = [&]() {
+#pragma unroll
+    for (int c = 0; c < NVI / 4; ++c)
+      *reinterpret_cast<bf16x8 *>(v_t + ((4 * c + w) * RPI + v_row) * ROWB + (v_pp << 4)) = vreg[c];
+  };
 
   // ---- softmax-key compaction riding along (see CompactArgs)
   const int n_wg = gridDim.x;
@@ -287,217 +490,21 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
       vdst[((2 * (w >> 1) + rbl) * 2 + (w & 1)) * 64 + lane] = join(half[0], half[1]);
     }
   };
-  if constexpr (COMPACT) {
-#pragma unroll
-    for (int c = 0; c < CB; ++c)
-      if (c < nb) compact_request(c, c);
-  }
+
+  if (lt_begin < lt_end) load_v(lt_begin);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(F32 ? 0 : NVI / 4) : "memory");   // the weight fragments are older than the V loads
+  __syncthreads();                                   // weights and biases are in LDS
   int cj = 0;                                        // first of the (up to CB) blocks in flight
-
   for (int t0 = lt_begin; t0 < lt_end; t0 += TOK) {
-    u32x4 h_hi[HB][2], h_lo[HB][2];                  // relu(W1 x + b1) as hi + lo bf16 pairs, chained order
-    f32x16 u[FB];
-    // registers x, x + 1 of a finished layer-1 tile -> ReLU -> hi + lo (8 vector instructions)
-    auto conv2 = [&](const f32x16 &hh, int hb, int x) {
-      const float a = fmaxf(hh[x], 0.f), b = fmaxf(hh[x + 1], 0.f);
-      const unsigned hi = pack_bf16(a, b);
-      h_hi[hb][x >> 3][(x & 7) >> 1] = hi;
-      h_lo[hb][x >> 3][(x & 7) >> 1] = pack_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
-    };
-    auto hop = [&](const u32x4 &t) { return __builtin_bit_cast(bf16x8, t); };
-    {
-      // ---------------- layer 1: two row blocks at a time (two independent chains, alternating)
-      f32x16 ha0, ha1, ha2, ha3;
-      bf16x8 wA[2][KS], wB[2][KS];
-#pragma unroll
-      for (int e = 0; e < 2; ++e)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wA[e][ks] = frag_at(w1f, e * KS + ks, lane);
-      ha0 = bias_tile(b1, 0);
-      ha1 = bias_tile(b1, 1);
-      ha2 = bias_tile(b1, 2);
-      ha3 = bias_tile(b1, 3);
-      HA_FENCE();
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {              // blocks 0, 1; the fragments of blocks 2, 3 are requested on the way
-        ha0 = mfma32(wA[0][ks], xf[ks], ha0);
-        wB[0][ks] = frag_at(w1f, 2 * KS + ks, lane);
-        HA_FENCE();
-        ha1 = mfma32(wA[1][ks], xf[ks], ha1);
-        wB[1][ks] = frag_at(w1f, 3 * KS + ks, lane);
-        HA_FENCE();
-      }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {              // blocks 2, 3 under the conversion of blocks 0, 1
-        ha2 = mfma32(wB[0][ks], xf[ks], ha2);
-        conv2(ha0, 0, 2 * ks);
-        ha3 = mfma32(wB[1][ks], xf[ks], ha3);
-        conv2(ha1, 1, 2 * ks);
-      }
-      // one matrix instruction, then one conversion's worth of vector instructions, sixteen times; the accumulators
-      // are tied to the end of this stretch so that the matrix instructions cannot drift out of it
-#pragma unroll
-      for (int i = 0; i < 2 * KS; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
-      }
-      asm volatile("" : "+v"(ha2), "+v"(ha3));
-      HA_FENCE();
-      load_k(t0 + TOK, xf);                          // the K rows of the next tile travel during the rest of this one
-      HA_FENCE();
-
-      // ---------------- layer 2: u = W2 h + b2, two 32-channel tiles at a time, one hidden block (8 matrix
-      // instructions, 4 fragments) per step; the fragments of the next step are requested behind the step's first
-      // matrix instruction.  Under the steps: first the conversion of layer-1 blocks 2, 3, later the softmax
-      // exponentials of the finished pair of tiles.
-      bf16x8 wa[2][2], wb[2][2];
-      auto w2_frags = [&](int fp, int hb, bf16x8 (&dst)[2][2]) {
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-          for (int s = 0; s < 2; ++s) dst[e][s] = frag_at(w2f, ((fp + e) * HB + hb) * 2 + s, lane);
-      };
-      w2_frags(0, 0, wa);
-#pragma unroll
-      for (int fb = 0; fb < FB; ++fb) u[fb] = bias_tile(b2, fb);
-      float m0 = 0.f, off0 = 0.f, sum0 = 0.f;
-      HA_FENCE();
-#pragma unroll
-      for (int fp = 0; fp < FB; fp += 2) {
-#pragma unroll
-        for (int hb = 0; hb < HB; ++hb) {
-          bf16x8 (&cur)[2][2] = (hb & 1) ? wb : wa;
-          bf16x8 (&nxt)[2][2] = (hb & 1) ? wa : wb;
-#pragma unroll
-          for (int slot = 0; slot < 8; ++slot) {
-            const int e = slot & 1, hi = (slot >> 1) & 1, s = slot >> 2;
-            u[fp + e] = mfma32(cur[e][s], hop(hi ? h_hi[hb][s] : h_lo[hb][s]), u[fp + e]);
-            if (slot == 0) {
-              if (hb + 1 < HB) w2_frags(fp, hb + 1, nxt);
-              else if (fp + 2 < FB) w2_frags(fp + 2, 0, nxt);
-            }
-            const int n = hb * 8 + slot;             // 0 .. 31 within the pair
-            if (fp == 0) {
-              if (n < 8) conv2(ha2, 2, 2 * n);       // needed from step 2 on
-              else if (n < 16) conv2(ha3, 3, 2 * (n - 8));
-            } else if constexpr (ACT0) {
-              // softmax of tiles 0, 1: their maximum in the first two slots, then one exponential per slot
-              if (n == 0) {
-                float t = fmaxf(u[0][0], u[0][1]);
-#pragma unroll
-                for (int x = 2; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[0][x]), u[0][x + 1]);
-                m0 = t;
-              } else if (n == 1) {
-                float t = m0;
-#pragma unroll
-                for (int x = 0; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[1][x]), u[1][x + 1]);
-                m0 = xhalf_max(t);
-                off0 = -m0 * kLog2e;
-              } else {
-                auto ex = [&](int i) {
-                  u[i >> 4][i & 15] = fast_exp2(__builtin_fmaf(u[i >> 4][i & 15], kLog2e, off0));
-                  sum0 += u[i >> 4][i & 15];
-                };
-                ex(n - 2);
-                if (n >= 30) ex(n);                  // 30 slots for 32 values: the last two slots take two each
-              }
-            }
-            HA_FENCE();
-          }
-        }
-      }
-      if constexpr (ACT0) {
-        // tiles 2, 3 against the overall maximum, which is known now
-        float t = fmaxf(u[2][0], u[2][1]);
-#pragma unroll
-        for (int x = 2; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[2][x]), u[2][x + 1]);
-#pragma unroll
-        for (int x = 0; x < 16; x += 2) t = __builtin_fmaxf(__builtin_fmaxf(t, u[3][x]), u[3][x + 1]);
-        const float m = fmaxf(m0, xhalf_max(t));
-        const float off = -m * kLog2e;
-        float sum1 = 0.f;
-#pragma unroll
-        for (int fb = 2; fb < 4; ++fb)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) {
-            u[fb][x] = fast_exp2(__builtin_fmaf(u[fb][x], kLog2e, off));
-            sum1 += u[fb][x];
-          }
-        const float carry = fast_exp2((m0 - m) * kLog2e);        // tiles 0, 1 were exponentiated against m0
-        const float inv = 1.0f / xhalf_sum(sum0 * carry + sum1);
-        const float f0 = carry * inv;
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          u[0][x] *= f0;
-          u[1][x] *= f0;
-          u[2][x] *= inv;
-          u[3][x] *= inv;
-        }
-      } else if (act == 1) {
-#pragma unroll
-        for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) u[fb][x] = fast_exp2(u[fb][x] * kLog2e);
-      } else {
-#pragma unroll
-        for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) u[fb][x] = fmaxf(u[fb][x], 0.f);
-      }
-    }
-    if (P == 2) {
-      // the paper's default degree: the upper half of the channels is squared
-#pragma unroll
-      for (int fb = FB / 2; fb < FB; ++fb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) u[fb][x] *= u[fb][x];
-    } else if (P > 1) {
-      // slice p = channel / Dp (0-based) gets p extra multiplications by the activation value; Dp is a multiple
-      // of 8, so the power depends only on the group of four registers
-#pragma unroll
-      for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int extra = ((32 * fb + 8 * q) * P) / F;
-          if (extra > 0) {
-            const float t0_ = u[fb][4 * q], t1_ = u[fb][4 * q + 1], t2_ = u[fb][4 * q + 2], t3_ = u[fb][4 * q + 3];
-            for (int i = 0; i < extra; ++i) {
-              u[fb][4 * q] *= t0_;
-              u[fb][4 * q + 1] *= t1_;
-              u[fb][4 * q + 2] *= t2_;
-              u[fb][4 * q + 3] *= t3_;
-            }
-          }
-        }
-    }
-    // ---------------- phi -> LDS, row-major: registers 4 q .. 4 q + 3 of tile fb are channels 32 fb + 8 q + 4 g .. + 3
-    {
-      if (t0 + TOK > lt_end) {                        // ragged end of the range: padded tokens add nothing
-        const float keep = t0 + tf < lt_end ? 1.f : 0.f;
-#pragma unroll
-        for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) u[fb][x] *= keep;
-      }
-      typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-#pragma unroll
-      for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const u32x2 four = {pack_bf16(u[fb][4 * q], u[fb][4 * q + 1]), pack_bf16(u[fb][4 * q + 2], u[fb][4 * q + 3])};
-          *reinterpret_cast<u32x2 *>(phi_t + phi_base[fb][q]) = four;
-        }
-    }
-    // this wave's V requests of this tile are older than the K loads of the next one just issued
-    if constexpr (F32 || COMPACT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (loads and stores are mixed: no counting)
-    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KS) : "memory");
-    __syncthreads();
+    __syncthreads();                                 // A: every wave has finished the previous tile's contraction
+    write_v();
+    __syncthreads();                                 // B: phi_t and v_t hold this tile
+    if (t0 + TOK < lt_end) load_v(t0 + TOK);
     if constexpr (COMPACT) {
 #pragma unroll
       for (int c = 0; c < CB; ++c)
-        if (cj + c < nb) compact_store(cj + c, c);
+        if (cj + c < nb) compact_request(cj + c, c);
     }
-
     // ---------------- [S | z] += phi^T [V | 1] over the 128 tokens: two 16-token slices (10 matrix instructions)
     // per batch, the 20 transposing reads of the next batch placed two behind each matrix instruction
     {
@@ -531,15 +538,12 @@ __global__ __launch_bounds__(256, 1) void state_pipelined_kernel(const void *__r
         }
       }
     }
-    __syncthreads();
-    if (t0 + TOK < lt_end) request_v(t0 + TOK);
     if constexpr (COMPACT) {
-      cj += CB;
-      if (t0 + TOK < lt_end) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the staged V rows of the blocks have landed
 #pragma unroll
-        for (int c = 0; c < CB; ++c)
-          if (cj + c < nb) compact_request(cj + c, c);
-      }
+      for (int c = 0; c < CB; ++c)
+        if (cj + c < nb) compact_store(cj + c, c);
+      cj += CB;
     }
   }
   if constexpr (COMPACT) {
@@ -579,7 +583,7 @@ hipError_t launch_state_pipelined(const Plan &pl, const void *k, const void *v, 
   ca.n_kblocks = pl.n_kblocks;
   const bool cmp = state_compacts_softmax_keys(pl);
 #define HA_STATE(F32, ACT0, CMP) \
-  state_pipelined_kernel<F32, ACT0, CMP><<<grid, 256, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.G, pl.CH, \
+  state_pipelined_kernel<F32, ACT0, CMP><<<grid, 512, 0, st>>>(k, v, w1f, w2f, fm.b1, fm.b2, part, pl.H, pl.NL, pl.R, pl.G, pl.CH, \
                                                               pl.P, pl.act_k, pl.sb, pl.sh, pl.sn, pl.N, pl.CC, pl.nsub, ca)
   if (pl.act_k == HA_ACT_SOFTMAX) {
     if (pl.f32) HA_STATE(true, true, false);
