@@ -184,6 +184,7 @@ def distill_step_mode(args, w, ha, torch, q, k, v, fq, fk):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / args.steps, e0.elapsed_time(e1) / args.steps
 
+    settle_clocks(torch, full_step)           # (defined below; the GPU leaves its idle clock state)
     wall_full, ev_full = timed(full_step)
     _, ev_bwd = timed(backward_only)          # state pass + loss + backward (no student query kernel)
     n_l = w.n_linear
@@ -274,6 +275,28 @@ def mfma_probe_rates(ha, torch, dev):
     out["clock_ghz_zero_operands"] = out["zero_operands_tflops"] * 1e12 / (256 * 4096) / 1e9
     out["clock_ghz_random_operands"] = out["random_operands_tflops"] * 1e12 / (256 * 4096) / 1e9
     return out
+
+
+def settle_clocks(torch, step, batch=10, max_steps=200, tol=0.005):
+    """Untimed steps until the GPU has left its idle clock state.  A process that has just generated its inputs finds
+    the GPU idle, and the shader clock needs some tens of milliseconds of load to come up: the first five forwards at
+    480p/81f take 1.66 ms, the next twenty 1.40 ms, every later one 1.35 ms (one box, 600 forwards in a row).  A loop
+    of forwards (a 30-layer stack, a sampler's steps) runs at the last figure, so that is the state the timed region
+    starts in: batches of `batch` steps until two batches in a row take the same time within `tol`, at most
+    `max_steps` steps.  Returns the number of steps run (reported in the JSON line)."""
+    prev, n = None, 0
+    while n < max_steps:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(batch):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        n += batch
+        if prev is not None and abs(dt - prev) <= tol * prev:
+            break
+        prev = dt
+    return n
 
 
 def time_forward(ha, torch, step, steps, warmup):
@@ -423,6 +446,7 @@ def rate_sweep_mode(args, ha, W, torch):
 
             def step():
                 ha.hybrid_attn_forward(q, k, v, fq, fk, R, w.block_size, w.scale, out=out, workspace=ws, stream=stream)
+            settle_clocks(torch, step)
             ms, kernel_ms, _ = time_forward(ha, torch, step, args.steps, args.warmup)
             fl = W.algorithmic_flops(w)
             row = {"R": R, "r": (1.0 / R if R else 0.0), "forward_ms": ms, "query_kernel_ms": kernel_ms, "algorithmic_gflop": fl / 1e9,
@@ -496,6 +520,8 @@ def main():
     ap.add_argument("--zero-inputs", action="store_true",
                     help="all-zero q, k, v: NOT a benchmark, a power / clock experiment (same instruction stream, idle data wires)")
     ap.add_argument("--no-cold-cache", action="store_true", help="skip the extra forwards with flushed caches")
+    ap.add_argument("--no-clock-settle", action="store_true",
+                    help="skip the untimed steps that bring the GPU out of its idle clock state before the warm-up")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the matrix-core probe (sustained MFMA-only rate of this device, zero and random operands)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -561,6 +587,7 @@ def main():
         dst.copy_(src)                     # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
+    settle_steps = 0 if args.no_clock_settle else settle_clocks(torch, step)
     ms_per_step, kernel_ms, kernel_sorted = time_forward(ha, torch, step, args.steps, args.warmup)
     assert torch.isfinite(out.float()).all().item(), "non-finite output"
     mean, fwd_sorted = stage_breakdown(ha, torch, step, args.steps)
@@ -616,6 +643,7 @@ def main():
     rec = {
         "metric": "hybrid-attention fwd tokens/s", "value": w.B * w.N / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "clock_settle_steps": settle_steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic" if not args.zero_inputs else "all-zero q, k, v (clock experiment, not a benchmark)",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d_head": w.d, "io_dtype": w.dtype,
