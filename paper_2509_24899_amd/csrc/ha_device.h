@@ -188,6 +188,21 @@ static __device__ __forceinline__ void dma_to_lds(const bf16x8 *gsrc, bf16x8 *ld
   }
 }
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+
+// Transposing read: every 16 lanes form a group; lane j of a group receives, as its slot i, element j % 4 of what
+// lane 4 i + j / 4 of the group addressed (4 consecutive 16-bit values).  With lane 4 i + a of a group pointing at
+// columns c0 + 4 a .. + 3 of row T0 + i, lane j holds column c0 + j of rows T0 .. T0 + 3: four consecutive tokens of
+// one column, i.e. half of a matrix-core operand fragment.
+static __device__ __forceinline__ s16x4 ds_read_tr(const char *tile, int byte_off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + byte_off));
+}
+static __device__ __forceinline__ bf16x8 join(s16x4 a, s16x4 b) {
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 // A zero the compiler cannot see through.  Added to the scalar offset of fragment reads inside a loop whose
 // fragments are the same in every iteration, it keeps those reads in the loop (hoisted, a whole operand matrix
 // would sit in registers, i.e. in scratch).

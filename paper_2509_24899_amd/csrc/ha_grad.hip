@@ -428,6 +428,357 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// grad_split_kernel: the pass of grad_kernel for d = 128 in two roles (the arrangement of the forward's state pass):
+// grid (n_chunks, B*H), 8 waves, two per SIMD.
+//   waves 0 - 3  per tile of 128 tokens, 32 token rows each, all in registers: the map recomputed, dphi, du; dpre.
+//                Their operands for the two contractions leave as row-major bf16 tiles in LDS ([token][channel],
+//                8-byte pieces of four consecutive channels, the C layout of the matrix instructions; x as 16-byte
+//                pieces), 16-byte pieces XOR-swizzled over sixteen rows.
+//   waves 4 - 7  own row block w of both partial sums, [dW2 | db2] += du [h | 1]^T and [dW1 | db1] += dpre [x | 1]^T,
+//                and contract over the tokens with both operands read through the transposing LDS reads
+//                (ds_read_b64_tr_b16), while the first four waves go on: W2^T du runs under the first contraction,
+//                the next tile's map under the second.
+// M (S or dS as hi + lo fragments, 64 KiB) passes through the same two tiles: the contraction waves fetch it
+// (direct-to-LDS) once the tiles are free, the other waves read their fragments of it from LDS instead of each from
+// L2.  W2^T sits in LDS for the whole workgroup (30 of its 32 fragments: that is what fits; the last two come from L2).
+// Six barriers per tile: A1 (the second contraction of the tile before has read both tiles), M1 (M has landed), M2
+// (its fragments have been read), B1 (h and du are in place), A2 (the first contraction has read them), B2 (dpre and x
+// are in place).  Every wave of either role passes all six once per tile and both roles count the same tiles.
+// Partial tiles as grad_kernel writes them.
+template <bool F32, bool QUERY>
+__global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
+  constexpr int D = 128, TOK = 128, ROWB = 2 * D;
+  constexpr int KS = D / 16, T = D / 32, NCB = T + 1, NT2 = T * NCB;
+  constexpr int NSET = 2;
+  __shared__ bf16x8 wlds[2 * D * D / 8];
+  constexpr int W2T_LDS = 30;                        // fragments of W2^T that fit next to everything else (of 32)
+  __shared__ bf16x8 w2t_lds[W2T_LDS * 64];
+  __shared__ float blds[3 * D];
+  __shared__ __align__(16) char a_t[TOK * ROWB];     // A side of a contraction: du, then dpre
+  __shared__ __align__(16) char b_t[TOK * ROWB];     // B side: h, then x
+  const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % a.H;
+  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)h * a.sh;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w = wave & 3;
+  {
+    const bf16x8 *w1g = a.w1f + (int64_t)h * (D * D / 8), *w2g = a.w2f + (int64_t)h * (D * D / 8);
+    const bf16x8 *w2tg = a.w2tf + (int64_t)h * (D * D / 8);
+    for (int i = tid; i < D * D / 8; i += 512) {
+      wlds[i] = w1g[i];
+      wlds[D * D / 8 + i] = w2g[i];
+      if (i < W2T_LDS * 64) w2t_lds[i] = w2tg[i];
+    }
+    for (int i = tid; i < D; i += 512) {
+      blds[i] = a.b1 ? a.b1[(int64_t)h * D + i] : 0.f;
+      blds[D + i] = a.b2 ? a.b2[(int64_t)h * D + i] : 0.f;
+      blds[2 * D + i] = a.zvec[(int64_t)bh * D + i];
+    }
+  }
+  const int t_begin = chunk * a.CH;
+  const int t_end = min(t_begin + a.CH, a.NT);
+  // piece p (16 bytes) of token row t sits at p ^ psw(t): the 32 rows one 8-byte write instruction touches fall on
+  // sixteen different pieces, and a transposing read finds its four rows in four different 64-byte groups
+  auto psw = [](int t) { return 4 * (t & 3) + ((t >> 2) & 3); };
+
+  if (wave < 4) {
+    // ============================== the map and its backward chain, 32 token rows per wave ==============================
+    const lds_frag_ptr w1f = (lds_frag_ptr)&wlds[0], w2f = (lds_frag_ptr)&wlds[D * D / 8];
+    const GlobalFrags w2tf = global_frags(a.w2tf + (int64_t)h * (D * D / 8), D * D * 2);
+    const lds_frag_ptr w2tl = (lds_frag_ptr)&w2t_lds[0];
+    const lds_frag_ptr mhi = (lds_frag_ptr)(const bf16x8 *)a_t, mlo = (lds_frag_ptr)(const bf16x8 *)b_t;   // M while it is staged
+    const float *b1 = &blds[0], *b2 = &blds[D], *zl = &blds[2 * D];
+    const LinearMap lmap(QUERY ? 0 : a.R, a.G);
+    const int tf = w * 32 + r;
+    const int row_off = tf * ROWB, row_sw = psw(tf);
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    // a [T][2] set of chained-order bf16 tiles (registers 4 q .. 4 q + 3 of tile fb: channels 32 fb + 8 q + 4 g .. + 3)
+    // as 8-byte pieces of this lane's token row
+    auto write_chained = [&](char *tile, const bf16x8 (&val)[T][2]) {
+#pragma unroll
+      for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const u32x4 t4 = __builtin_bit_cast(u32x4, val[fb][q >> 1]);
+          const u32x2 four = {t4[2 * (q & 1)], t4[2 * (q & 1) + 1]};
+          *reinterpret_cast<u32x2 *>(tile + row_off + 8 * g + (((4 * fb + q) ^ row_sw) << 4)) = four;
+        }
+    };
+    bf16x8 xf[KS], uf[KS];
+    auto request_x = [&](int t0, bf16x8 (&dst)[KS]) {
+      const int tok = lmap.token(min(t0 + tf, a.NT - 1));
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) dst[ks] = load8<F32>(a.x, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
+    };
+    auto request_u = [&](int t0) {
+      const int tok = lmap.token(min(t0 + tf, a.NT - 1));
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if constexpr (QUERY) uf[ks] = static_cast<const bf16x8 *>(a.u)[((int64_t)bh * a.N + tok) * (D / 8) + 2 * ks + g];
+        else uf[ks] = load8<F32>(a.u, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
+      }
+    };
+    request_x(t_begin, xf);
+    request_u(t_begin);
+    __syncthreads();                                  // weights, biases and z are in LDS
+    for (int t0 = t_begin; t0 < t_end; t0 += TOK) {
+      const bool valid = t0 + tf < a.NT;
+      const int tok = lmap.token(min(t0 + tf, a.NT - 1));
+      // weights, biases and the fragments of M are the same in every tile: reading them through an offset the
+      // compiler cannot see through keeps the reads in the loop (hoisted, they would fill the register file)
+      const int z0 = opaque_zero();
+      const lds_frag_ptr w1t = w1f + z0, w2t = w2f + z0;
+      const float *b1t = b1 + z0, *b2t = b2 + z0, *zt = zl + z0;
+      __builtin_assume(b1t != nullptr);
+      __builtin_assume(b2t != nullptr);
+      float rs_ = 1.f, wp_ = 1.f;
+      if constexpr (QUERY) {
+        rs_ = a.rs[(int64_t)bh * a.N + tok];
+        wp_ = a.wp[(int64_t)bh * a.N + tok];
+      }
+      const float wz_ = QUERY ? wp_ * rs_ : 1.f;             // dden_i = -(g_i . y_hat_i) / den_i
+
+      // the map, recomputed: h (hi + lo), t = positive output before the slice powers; the ReLU gate is kept as one
+      // bit per hidden unit, h itself goes to the B side tile right away
+      f32x16 tt[T];
+      unsigned gate[(T + 1) / 2];
+      bf16x8 hpark[T][2];                               // h, kept until the tiles are free to take it
+      {
+        bf16x8 h_hi[T][2], h_lo[T][2];
+        feature_mlp_layer1<D, D, true>(xf, w1t, b1t, lane, g, h_hi, h_lo);
+        __syncthreads();                                // A1: the second contraction of the tile before is done
+#pragma unroll
+        for (int i = 0; i < (T + 1) / 2; ++i) gate[i] = 0u;
+#pragma unroll
+        for (int hb = 0; hb < T; ++hb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x)
+            gate[hb >> 1] |= (static_cast<float>(h_hi[hb][x >> 3][x & 7]) > 0.f ? 1u : 0u) << (16 * (hb & 1) + x);
+        feature_mlp_layer2<D, D, true>(h_hi, h_lo, w2t, b2t, lane, g, tt);
+        feature_activation<T>(tt, g, a.act, 1, D);
+#pragma unroll
+        for (int hb = 0; hb < T; ++hb) {
+          hpark[hb][0] = h_hi[hb][0];
+          hpark[hb][1] = h_hi[hb][1];
+        }
+      }
+      __syncthreads();                                  // M1: the fragments of M have landed in the two tiles
+      // dphi = rs (M u) + wz zvec   (the fragments of M come from L2: the next half block (lo or hi part of one
+      // channel block, 8 fragments) is requested before the chain of the current one starts)
+      f32x16 dv[T];
+      {
+        // steps of four fragments: step = 4 fb + 2 (0: lo part, 1: hi part) + (which half of the d contraction)
+        constexpr int QF = KS / 2;
+        bf16x8 mf[2][QF];
+        auto request_m = [&](int step, bf16x8 (&dst)[QF]) {
+          const int fb = step >> 2, hi = (step >> 1) & 1, q4 = step & 1;
+#pragma unroll
+          for (int i = 0; i < QF; ++i)
+            dst[i] = hi ? frag_at(mhi, fb * KS + q4 * QF + i, lane) : frag_at(mlo, fb * KS + q4 * QF + i, lane);
+        };
+        request_m(0, mf[0]);
+#pragma unroll
+        for (int fb = 0; fb < T; ++fb) {
+          f32x16 acc;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub) {
+            const int step = 4 * fb + sub;
+            if (step + 1 < 4 * T) request_m(step + 1, mf[(step + 1) & 1]);
+#pragma unroll
+            for (int i = 0; i < QF; ++i) acc = mfma32(mf[step & 1][i], uf[(sub & 1) * QF + i], acc);
+          }
+#pragma unroll
+          for (int x = 0; x < 16; ++x) dv[fb][x] = rs_ * acc[x] + wz_ * zt[32 * fb + crow(x, g)];
+        }
+      }
+      // back through the slice powers and the activation: dv becomes du.  The slice power of a channel is wave-uniform
+      // (it depends on the group of four registers only); the degrees the paper uses are compiled in, so that the
+      // factor p t^(p-1) costs p - 1 multiplications and no selects.
+      {
+        float dot = 0.f;
+        auto powers_back = [&](auto pc) {
+          constexpr int PC = decltype(pc)::value;              // 0: any degree, taken at run time
+#pragma unroll
+          for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+              const float t0v = tt[fb][x];
+              if constexpr (PC == 0) {
+                const int extra = ((32 * fb + 8 * (x >> 2)) * a.P) / D;   // channel / Dp: slice power p = extra + 1
+                dv[fb][x] *= (float)(extra + 1) * pow_small(t0v, extra);   // d/dt of t^p
+              } else {
+                constexpr int dummy = 0;
+                (void)dummy;
+                const int extra = ((32 * fb + 8 * (x >> 2)) * PC) / D;     // folds to a constant after unrolling
+                float f = (float)(extra + 1);
+                for (int i = 0; i < extra; ++i) f *= t0v;
+                if (extra > 0) dv[fb][x] *= f;
+              }
+              dot += t0v * dv[fb][x];
+            }
+        };
+        if (a.P == 1) powers_back(std::integral_constant<int, 1>{});
+        else if (a.P == 2) powers_back(std::integral_constant<int, 2>{});
+        else if (a.P == 4) powers_back(std::integral_constant<int, 4>{});
+        else powers_back(std::integral_constant<int, 0>{});
+        if (a.act == 0) {
+          dot = xhalf_sum(dot);
+#pragma unroll
+          for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) dv[fb][x] = tt[fb][x] * (dv[fb][x] - dot);
+        } else if (a.act == 1) {
+#pragma unroll
+          for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) dv[fb][x] *= tt[fb][x];
+        } else {
+#pragma unroll
+          for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) dv[fb][x] = tt[fb][x] > 0.f ? dv[fb][x] : 0.f;
+        }
+      }
+      bf16x8 dub[T][2];
+#pragma unroll
+      for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) dub[fb][x >> 3][x & 7] = static_cast<__bf16>(valid ? dv[fb][x] : 0.f);
+      __syncthreads();                                  // M2: every wave has read its fragments of M
+      write_chained(b_t, hpark);
+      write_chained(a_t, dub);
+      __syncthreads();                                  // B1: h and du are in place
+      // dpre = (W2^T du) [h > 0], under the first contraction; the x rows come back from L2 meanwhile
+      bf16x8 dpb[T][2];
+      bf16x8 xp[KS];
+      {
+        bf16x8 wt[2][2 * T], wlast[T * T * 2 - W2T_LDS];
+#pragma unroll
+        for (int i = 0; i < T * T * 2 - W2T_LDS; ++i) wlast[i] = frag_at(w2tf, W2T_LDS + i, lane, z0);
+        auto request_w = [&](int hb, bf16x8 (&dst)[2 * T]) {
+#pragma unroll
+          for (int i = 0; i < 2 * T; ++i) {
+            const int idx = hb * T * 2 + i;
+            if (idx < W2T_LDS) dst[i] = frag_at(w2tl, idx, lane);
+            else dst[i] = wlast[idx - W2T_LDS];
+          }
+        };
+        request_w(0, wt[0]);
+#pragma unroll
+        for (int hb = 0; hb < T; ++hb) {
+          f32x16 acc;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+          if (hb + 1 < T) request_w(hb + 1, wt[(hb + 1) & 1]);
+          if (hb == 0) request_x(t0, xp);             // this tile's x rows once more (they go to the B side tile)
+          if (hb == 1) request_x(t0 + TOK, xf);       // and the rows of the next tile
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int fb = 0; fb < T; ++fb)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) acc = mfma32(wt[hb & 1][fb * 2 + s], dub[fb][s], acc);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int x = 0; x < 16; ++x)
+            dpb[hb][x >> 3][x & 7] = static_cast<__bf16>((gate[hb >> 1] >> (16 * (hb & 1) + x)) & 1u ? acc[x] : 0.f);
+        }
+      }
+      __syncthreads();                                  // A2: the first contraction has read both tiles
+      write_chained(a_t, dpb);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)                   // x: channels 16 ks + 8 g .. + 7 = piece 2 ks + g of the row
+        *reinterpret_cast<bf16x8 *>(b_t + row_off + (((2 * ks + g) ^ row_sw) << 4)) = xp[ks];
+      request_u(t0 + TOK);
+      __syncthreads();                                  // B2: dpre and x are in place
+    }
+    return;
+  }
+
+  // =============================== the two contractions over the tokens (waves 4 .. 7) ===============================
+  f32x16 acc2[NCB], acc1[NCB];
+#pragma unroll
+  for (int i = 0; i < NCB; ++i)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      acc2[i][x] = 0.f;
+      acc1[i][x] = 0.f;
+    }
+  // transposing reads: lane = (group m, i, a), see ds_read_tr.  A fragment half covers rows T0 + i, T0 = 16 ks + 8 g
+  // + 4 jj, so psw(T0 + i) = 4 i + (2 g + jj) % 4 is a per-lane constant per half; k-steps are immediates
+  const int tm = lane >> 4, ti = (lane >> 2) & 3, ta = lane & 3, tg = tm >> 1;
+  auto tr_base = [&](int blk, int jj) {
+    return (8 * tg + ti) * ROWB + (((4 * blk + 2 * (tm & 1) + (ta >> 1)) ^ (4 * ti + ((2 * tg + jj) & 3))) << 4) + 8 * (ta & 1);
+  };
+  int ab[2], bb[T][2];
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    ab[jj] = tr_base(w, jj);
+#pragma unroll
+    for (int cb = 0; cb < T; ++cb) bb[cb][jj] = tr_base(cb, jj);
+  }
+  const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);     // the "1" column that yields the bias gradient
+  const bf16x8 ones = bf16x8{one, one, one, one, one, one, one, one};
+  // row block w of (A side)^T (B side | 1): one 16-token slice (5 matrix instructions) per batch, the 10 transposing
+  // reads of the next batch placed behind the matrix instructions of the current one (the two partial sums leave
+  // room for no more)
+  auto contract = [&](f32x16 (&acc)[NCB]) {
+    constexpr int KB = 1, NBATCH = TOK / 16 / KB, NOP = KB * NCB;
+    bf16x8 fr[2][NOP];                               // [buffer][(kk, operand)]: operand 0 = A side, 1 + cb = B side
+    auto rd = [&](int batch, int buf, int i) {
+      const int kk = i / NCB, op = i % NCB;
+      const int off = (batch * KB + kk) * 16 * ROWB;
+      fr[buf][i] = op == 0 ? join(ds_read_tr(a_t, ab[0] + off), ds_read_tr(a_t, ab[1] + off + 4 * ROWB))
+                           : join(ds_read_tr(b_t, bb[op - 1][0] + off), ds_read_tr(b_t, bb[op - 1][1] + off + 4 * ROWB));
+    };
+#pragma unroll
+    for (int i = 0; i < NOP; ++i) rd(0, 0, i);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int batch = 0; batch < NBATCH; ++batch) {
+      const int buf = batch & 1;
+#pragma unroll
+      for (int kk = 0; kk < KB; ++kk) {
+        const bf16x8 a8 = fr[buf][kk * NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          acc[cb] = mfma32(a8, cb < T ? fr[buf][kk * NCB + 1 + cb] : ones, acc[cb]);
+          if (batch + 1 < NBATCH) rd(batch + 1, buf ^ 1, kk * NCB + cb);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  };
+  __syncthreads();                                    // weights, biases and z are in LDS
+  for (int t0 = t_begin; t0 < t_end; t0 += TOK) {
+    __syncthreads();                                  // A1
+    // M (natural-order fragments, hi and lo part, 32 KiB each) into the two tiles, which are free until h and du arrive
+    dma_to_lds(a.m_hi + (int64_t)bh * (D * D / 8), reinterpret_cast<bf16x8 *>(a_t), D * D / 8 / 64, w, 4, lane);
+    dma_to_lds(a.m_lo + (int64_t)bh * (D * D / 8), reinterpret_cast<bf16x8 *>(b_t), D * D / 8 / 64, w, 4, lane);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                  // M1
+    __syncthreads();                                  // M2
+    __syncthreads();                                  // B1
+    contract(acc2);
+    __syncthreads();                                  // A2
+    __syncthreads();                                  // B2
+    contract(acc1);
+  }
+  {
+    float *dst = a.part + (((int64_t)bh * gridDim.x + chunk) * NSET) * NT2 * 1024 + (int64_t)w * NCB * 1024;
+#pragma unroll
+    for (int i = 0; i < NCB; ++i)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        dst[i * 1024 + x * 64 + lane] = acc2[i][x];
+        dst[(NT2 + i) * 1024 + x * 64 + lane] = acc1[i][x];
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // grad_reduce_kernel: grid (T*(T+1)*1024 / 256, n_out).  Output o sums set `set` of the partials over the
 // chunks of (batch b, head o) for every b (n_sum = B, shared parameters) or of (batch, head) pair o alone
 // (n_sum = 1), in a fixed order.  mat[o][row][col] row-major fp32, vec[o][row] = the extra column block
@@ -580,7 +931,7 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     a.NT = pl.N; a.CH = gp.CHq; a.act = pl.act_q;
     dim3 grid(gp.n_chunks_q, BH);
     if (D == 64) { if (pl.f32) grad_kernel<64, true, true><<<grid, 256, 0, st>>>(a); else grad_kernel<64, false, true><<<grid, 256, 0, st>>>(a); }
-    else { if (pl.f32) grad_kernel<128, true, true><<<grid, 256, 0, st>>>(a); else grad_kernel<128, false, true><<<grid, 256, 0, st>>>(a); }
+    else { if (pl.f32) grad_split_kernel<true, true><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, true><<<grid, 512, 0, st>>>(a); }
     HA_CHECK();
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w2, gq.b2, D, gp.n_chunks_q, 2, 0, pl.B, pl.H);
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w1, gq.b1, D, gp.n_chunks_q, 2, 1, pl.B, pl.H);
@@ -606,7 +957,7 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     a.NT = pl.NL; a.CH = gp.CHk; a.act = pl.act_k;
     dim3 grid(gp.n_chunks_k, BH);
     if (D == 64) { if (pl.f32) grad_kernel<64, true, false><<<grid, 256, 0, st>>>(a); else grad_kernel<64, false, false><<<grid, 256, 0, st>>>(a); }
-    else { if (pl.f32) grad_kernel<128, true, false><<<grid, 256, 0, st>>>(a); else grad_kernel<128, false, false><<<grid, 256, 0, st>>>(a); }
+    else { if (pl.f32) grad_split_kernel<true, false><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, false><<<grid, 512, 0, st>>>(a); }
     HA_CHECK();
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w2, gk.b2, D, gp.n_chunks_k, 2, 0, pl.B, pl.H);
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w1, gk.b1, D, gp.n_chunks_k, 2, 1, pl.B, pl.H);
