@@ -480,6 +480,14 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
   // piece p (16 bytes) of token row t sits at p ^ psw(t): the 32 rows one 8-byte write instruction touches fall on
   // sixteen different pieces, and a transposing read finds its four rows in four different 64-byte groups
   auto psw = [](int t) { return 4 * (t & 3) + ((t >> 2) & 3); };
+  const LinearMap lmap(QUERY ? 0 : a.R, a.G);
+  const int tf = w * 32 + r;                         // this lane's token row of a tile, in either role
+  const int row_off = tf * ROWB, row_sw = psw(tf);
+  auto request_x = [&](int t0, bf16x8 (&dst)[KS]) {
+    const int tok = lmap.token(min(t0 + tf, a.NT - 1));
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) dst[ks] = load8<F32>(a.x, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
+  };
 
   if (wave < 4) {
     // ============================== the map and its backward chain, 32 token rows per wave ==============================
@@ -488,29 +496,24 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
     const lds_frag_ptr w2tl = (lds_frag_ptr)&w2t_lds[0];
     const lds_frag_ptr mhi = (lds_frag_ptr)(const bf16x8 *)a_t, mlo = (lds_frag_ptr)(const bf16x8 *)b_t;   // M while it is staged
     const float *b1 = &blds[0], *b2 = &blds[D], *zl = &blds[2 * D];
-    const LinearMap lmap(QUERY ? 0 : a.R, a.G);
-    const int tf = w * 32 + r;
-    const int row_off = tf * ROWB, row_sw = psw(tf);
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     // a [T][2] set of chained-order bf16 tiles (registers 4 q .. 4 q + 3 of tile fb: channels 32 fb + 8 q + 4 g .. + 3)
     // as 8-byte pieces of this lane's token row
+    // (the addresses are formed where they are used, from a swizzle value the compiler cannot see through: kept across
+    // the tile they would be spilled, and a reload costs more than the two instructions that make one)
     auto write_chained = [&](char *tile, const bf16x8 (&val)[T][2]) {
+      const int sw_now = row_sw + opaque_zero();
 #pragma unroll
       for (int fb = 0; fb < T; ++fb)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const u32x4 t4 = __builtin_bit_cast(u32x4, val[fb][q >> 1]);
           const u32x2 four = {t4[2 * (q & 1)], t4[2 * (q & 1) + 1]};
-          *reinterpret_cast<u32x2 *>(tile + row_off + 8 * g + (((4 * fb + q) ^ row_sw) << 4)) = four;
+          *reinterpret_cast<u32x2 *>(tile + row_off + 8 * g + (((4 * fb + q) ^ sw_now) << 4)) = four;
         }
     };
     bf16x8 xf[KS], uf[KS];
-    auto request_x = [&](int t0, bf16x8 (&dst)[KS]) {
-      const int tok = lmap.token(min(t0 + tf, a.NT - 1));
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) dst[ks] = load8<F32>(a.x, base + (int64_t)tok * a.sn + 16 * ks + 8 * g);
-    };
     auto request_u = [&](int t0) {
       const int tok = lmap.token(min(t0 + tf, a.NT - 1));
 #pragma unroll
@@ -598,7 +601,7 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
       // (it depends on the group of four registers only); the degrees the paper uses are compiled in, so that the
       // factor p t^(p-1) costs p - 1 multiplications and no selects.
       {
-        float dot = 0.f;
+        float dots[4] = {0.f, 0.f, 0.f, 0.f};              // four chains instead of one of 64 dependent additions
         auto powers_back = [&](auto pc) {
           constexpr int PC = decltype(pc)::value;              // 0: any degree, taken at run time
 #pragma unroll
@@ -617,13 +620,14 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
                 for (int i = 0; i < extra; ++i) f *= t0v;
                 if (extra > 0) dv[fb][x] *= f;
               }
-              dot += t0v * dv[fb][x];
+              dots[x & 3] += t0v * dv[fb][x];
             }
         };
         if (a.P == 1) powers_back(std::integral_constant<int, 1>{});
         else if (a.P == 2) powers_back(std::integral_constant<int, 2>{});
         else if (a.P == 4) powers_back(std::integral_constant<int, 4>{});
         else powers_back(std::integral_constant<int, 0>{});
+        float dot = (dots[0] + dots[1]) + (dots[2] + dots[3]);
         if (a.act == 0) {
           dot = xhalf_sum(dot);
 #pragma unroll
@@ -654,32 +658,31 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
       // dpre = (W2^T du) [h > 0], under the first contraction; the x rows come back from L2 meanwhile
       bf16x8 dpb[T][2];
       bf16x8 xp[KS];
+      request_x(t0, xp);                                // this tile's x rows once more (L2): they go to the B side tile
       {
-        bf16x8 wt[2][2 * T], wlast[T * T * 2 - W2T_LDS];
+        // the fragments of one hidden block at a time (LDS; the last two of the 32 from L2)
+        bf16x8 wlast[T * T * 2 - W2T_LDS];
 #pragma unroll
         for (int i = 0; i < T * T * 2 - W2T_LDS; ++i) wlast[i] = frag_at(w2tf, W2T_LDS + i, lane, z0);
-        auto request_w = [&](int hb, bf16x8 (&dst)[2 * T]) {
+#pragma unroll
+        for (int hb = 0; hb < T; ++hb) {
+          bf16x8 wt[2 * T];
 #pragma unroll
           for (int i = 0; i < 2 * T; ++i) {
             const int idx = hb * T * 2 + i;
-            if (idx < W2T_LDS) dst[i] = frag_at(w2tl, idx, lane);
-            else dst[i] = wlast[idx - W2T_LDS];
+            if (idx < W2T_LDS) wt[i] = frag_at(w2tl, idx, lane);
+            else wt[i] = wlast[idx - W2T_LDS];
           }
-        };
-        request_w(0, wt[0]);
-#pragma unroll
-        for (int hb = 0; hb < T; ++hb) {
           f32x16 acc;
 #pragma unroll
           for (int x = 0; x < 16; ++x) acc[x] = 0.f;
-          if (hb + 1 < T) request_w(hb + 1, wt[(hb + 1) & 1]);
-          if (hb == 0) request_x(t0, xp);             // this tile's x rows once more (they go to the B side tile)
-          if (hb == 1) request_x(t0 + TOK, xf);       // and the rows of the next tile
+          if (hb == 1) request_x(t0 + TOK, xf);         // the rows of the next tile
+          if (hb == 2) request_u(t0 + TOK);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int fb = 0; fb < T; ++fb)
 #pragma unroll
-            for (int s = 0; s < 2; ++s) acc = mfma32(wt[hb & 1][fb * 2 + s], dub[fb][s], acc);
+            for (int s = 0; s < 2; ++s) acc = mfma32(wt[fb * 2 + s], dub[fb][s], acc);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int x = 0; x < 16; ++x)
@@ -688,10 +691,12 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
       }
       __syncthreads();                                  // A2: the first contraction has read both tiles
       write_chained(a_t, dpb);
+      {
+        const int sw_now = row_sw + opaque_zero();
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)                   // x: channels 16 ks + 8 g .. + 7 = piece 2 ks + g of the row
-        *reinterpret_cast<bf16x8 *>(b_t + row_off + (((2 * ks + g) ^ row_sw) << 4)) = xp[ks];
-      request_u(t0 + TOK);
+        for (int ks = 0; ks < KS; ++ks)                 // x: channels 16 ks + 8 g .. + 7 = piece 2 ks + g of the row
+          *reinterpret_cast<bf16x8 *>(b_t + row_off + (((2 * ks + g) ^ sw_now) << 4)) = xp[ks];
+      }
       __syncthreads();                                  // B2: dpre and x are in place
     }
     return;
@@ -722,32 +727,26 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
   const __bf16 one = static_cast<__bf16>(r == 0 ? 1.0f : 0.0f);     // the "1" column that yields the bias gradient
   const bf16x8 ones = bf16x8{one, one, one, one, one, one, one, one};
   // row block w of (A side)^T (B side | 1): one 16-token slice (5 matrix instructions) per batch, the 10 transposing
-  // reads of the next batch placed behind the matrix instructions of the current one (the two partial sums leave
-  // room for no more)
+  // reads of the next batch placed behind the matrix instructions of the current one
   auto contract = [&](f32x16 (&acc)[NCB]) {
-    constexpr int KB = 1, NBATCH = TOK / 16 / KB, NOP = KB * NCB;
-    bf16x8 fr[2][NOP];                               // [buffer][(kk, operand)]: operand 0 = A side, 1 + cb = B side
-    auto rd = [&](int batch, int buf, int i) {
-      const int kk = i / NCB, op = i % NCB;
-      const int off = (batch * KB + kk) * 16 * ROWB;
-      fr[buf][i] = op == 0 ? join(ds_read_tr(a_t, ab[0] + off), ds_read_tr(a_t, ab[1] + off + 4 * ROWB))
-                           : join(ds_read_tr(b_t, bb[op - 1][0] + off), ds_read_tr(b_t, bb[op - 1][1] + off + 4 * ROWB));
+    constexpr int NBATCH = TOK / 16;
+    bf16x8 fr[2][NCB];                               // [buffer][operand]: operand 0 = A side, 1 + cb = B side
+    auto rd = [&](int batch, int buf, int op) {
+      const int off = batch * 16 * ROWB;
+      fr[buf][op] = op == 0 ? join(ds_read_tr(a_t, ab[0] + off), ds_read_tr(a_t, ab[1] + off + 4 * ROWB))
+                            : join(ds_read_tr(b_t, bb[op - 1][0] + off), ds_read_tr(b_t, bb[op - 1][1] + off + 4 * ROWB));
     };
 #pragma unroll
-    for (int i = 0; i < NOP; ++i) rd(0, 0, i);
+    for (int i = 0; i < NCB; ++i) rd(0, 0, i);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int batch = 0; batch < NBATCH; ++batch) {
       const int buf = batch & 1;
 #pragma unroll
-      for (int kk = 0; kk < KB; ++kk) {
-        const bf16x8 a8 = fr[buf][kk * NCB];
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-          acc[cb] = mfma32(a8, cb < T ? fr[buf][kk * NCB + 1 + cb] : ones, acc[cb]);
-          if (batch + 1 < NBATCH) rd(batch + 1, buf ^ 1, kk * NCB + cb);
-          __builtin_amdgcn_sched_barrier(0);
-        }
+      for (int cb = 0; cb < NCB; ++cb) {
+        acc[cb] = mfma32(fr[buf][0], cb < T ? fr[buf][1 + cb] : ones, acc[cb]);
+        if (batch + 1 < NBATCH) rd(batch + 1, buf ^ 1, cb);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
