@@ -22,6 +22,7 @@
 //
 // As in the forward, every product is computed transposed (channels x tokens): one lane owns one token.
 #include "ha_device.h"
+#include "ha_mlp128.h"
 #include "ha_plan.h"
 
 namespace ha {
@@ -445,7 +446,8 @@ __global__ __launch_bounds__(256, 1) void grad_kernel(GradArgs a) {
 // (its fragments have been read), B1 (h and du are in place), A2 (the first contraction has read them), B2 (dpre and x
 // are in place).  Every wave of either role passes all six once per tile and both roles count the same tiles.
 // Partial tiles as grad_kernel writes them.
-template <bool F32, bool QUERY>
+// ACT0: the output activation of the map is the softmax over the channels.
+template <bool F32, bool QUERY, bool ACT0>
 __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
   constexpr int D = 128, TOK = 128, ROWB = 2 * D;
   constexpr int KS = D / 16, T = D / 32, NCB = T + 1, NT2 = T * NCB;
@@ -453,7 +455,7 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
   __shared__ bf16x8 wlds[2 * D * D / 8];
   constexpr int W2T_LDS = 30;                        // fragments of W2^T that fit next to everything else (of 32)
   __shared__ bf16x8 w2t_lds[W2T_LDS * 64];
-  __shared__ float blds[3 * D];
+  __shared__ __align__(16) float blds[3 * D];
   __shared__ __align__(16) char a_t[TOK * ROWB];     // A side of a contraction: du, then dpre
   __shared__ __align__(16) char b_t[TOK * ROWB];     // B side: h, then x
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % a.H;
@@ -523,7 +525,6 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
       }
     };
     request_x(t_begin, xf);
-    request_u(t_begin);
     __syncthreads();                                  // weights, biases and z are in LDS
     for (int t0 = t_begin; t0 < t_end; t0 += TOK) {
       const bool valid = t0 + tf < a.NT;
@@ -548,22 +549,28 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
       unsigned gate[(T + 1) / 2];
       bf16x8 hpark[T][2];                               // h, kept until the tiles are free to take it
       {
-        bf16x8 h_hi[T][2], h_lo[T][2];
-        feature_mlp_layer1<D, D, true>(xf, w1t, b1t, lane, g, h_hi, h_lo);
-        __syncthreads();                                // A1: the second contraction of the tile before is done
+        // between the two layers: barrier A1 (the second contraction of the tile before is done by then) and the
+        // request for this tile's u rows (they are needed behind the map, and would not fit beside layer 1)
+        u32x4 h_hi[T][2], h_lo[T][2];
+        auto mid = [&]() {
+          __syncthreads();
+          request_u(t0);
+        };
+        mlp128_pipelined<ACT0, true>(xf, w1t, w2t, b1t, b2t, lane, g, a.act, h_hi, h_lo, tt, mid);
 #pragma unroll
         for (int i = 0; i < (T + 1) / 2; ++i) gate[i] = 0u;
 #pragma unroll
         for (int hb = 0; hb < T; ++hb)
 #pragma unroll
-          for (int x = 0; x < 16; ++x)
-            gate[hb >> 1] |= (static_cast<float>(h_hi[hb][x >> 3][x & 7]) > 0.f ? 1u : 0u) << (16 * (hb & 1) + x);
-        feature_mlp_layer2<D, D, true>(h_hi, h_lo, w2t, b2t, lane, g, tt);
-        feature_activation<T>(tt, g, a.act, 1, D);
+          for (int x = 0; x < 16; ++x) {
+            // h >= 0 after the ReLU: positive unless its bf16 pattern is a zero of either sign
+            const unsigned half = (h_hi[hb][x >> 3][(x & 7) >> 1] >> (16 * (x & 1))) & 0x7fffu;
+            gate[hb >> 1] |= (half != 0u ? 1u : 0u) << (16 * (hb & 1) + x);
+          }
 #pragma unroll
         for (int hb = 0; hb < T; ++hb) {
-          hpark[hb][0] = h_hi[hb][0];
-          hpark[hb][1] = h_hi[hb][1];
+          hpark[hb][0] = __builtin_bit_cast(bf16x8, h_hi[hb][0]);
+          hpark[hb][1] = __builtin_bit_cast(bf16x8, h_hi[hb][1]);
         }
       }
       __syncthreads();                                  // M1: the fragments of M have landed in the two tiles
@@ -628,7 +635,7 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
         else if (a.P == 4) powers_back(std::integral_constant<int, 4>{});
         else powers_back(std::integral_constant<int, 0>{});
         float dot = (dots[0] + dots[1]) + (dots[2] + dots[3]);
-        if (a.act == 0) {
+        if constexpr (ACT0) {
           dot = xhalf_sum(dot);
 #pragma unroll
           for (int fb = 0; fb < T; ++fb)
@@ -677,7 +684,6 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
 #pragma unroll
           for (int x = 0; x < 16; ++x) acc[x] = 0.f;
           if (hb == 1) request_x(t0 + TOK, xf);         // the rows of the next tile
-          if (hb == 2) request_u(t0 + TOK);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int fb = 0; fb < T; ++fb)
@@ -930,7 +936,8 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     a.NT = pl.N; a.CH = gp.CHq; a.act = pl.act_q;
     dim3 grid(gp.n_chunks_q, BH);
     if (D == 64) { if (pl.f32) grad_kernel<64, true, true><<<grid, 256, 0, st>>>(a); else grad_kernel<64, false, true><<<grid, 256, 0, st>>>(a); }
-    else { if (pl.f32) grad_split_kernel<true, true><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, true><<<grid, 512, 0, st>>>(a); }
+    else if (a.act == HA_ACT_SOFTMAX) { if (pl.f32) grad_split_kernel<true, true, true><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, true, true><<<grid, 512, 0, st>>>(a); }
+    else { if (pl.f32) grad_split_kernel<true, true, false><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, true, false><<<grid, 512, 0, st>>>(a); }
     HA_CHECK();
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w2, gq.b2, D, gp.n_chunks_q, 2, 0, pl.B, pl.H);
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w1, gq.b1, D, gp.n_chunks_q, 2, 1, pl.B, pl.H);
@@ -956,7 +963,8 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     a.NT = pl.NL; a.CH = gp.CHk; a.act = pl.act_k;
     dim3 grid(gp.n_chunks_k, BH);
     if (D == 64) { if (pl.f32) grad_kernel<64, true, false><<<grid, 256, 0, st>>>(a); else grad_kernel<64, false, false><<<grid, 256, 0, st>>>(a); }
-    else { if (pl.f32) grad_split_kernel<true, false><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, false><<<grid, 512, 0, st>>>(a); }
+    else if (a.act == HA_ACT_SOFTMAX) { if (pl.f32) grad_split_kernel<true, false, true><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, false, true><<<grid, 512, 0, st>>>(a); }
+    else { if (pl.f32) grad_split_kernel<true, false, false><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, false, false><<<grid, 512, 0, st>>>(a); }
     HA_CHECK();
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w2, gk.b2, D, gp.n_chunks_k, 2, 0, pl.B, pl.H);
     grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w1, gk.b1, D, gp.n_chunks_k, 2, 1, pl.B, pl.H);
