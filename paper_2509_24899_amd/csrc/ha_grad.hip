@@ -611,13 +611,16 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
         float dots[4] = {0.f, 0.f, 0.f, 0.f};              // four chains instead of one of 64 dependent additions
         auto powers_back = [&](auto pc) {
           constexpr int PC = decltype(pc)::value;              // 0: any degree, taken at run time
+          // (the degree of the general form goes through a value the compiler cannot see through, so that its
+          // per-group exponents are formed inside this branch and not ahead of the dispatch for every degree)
+          const int p_any = PC == 0 ? a.P + opaque_zero() : PC;
 #pragma unroll
           for (int fb = 0; fb < T; ++fb)
 #pragma unroll
             for (int x = 0; x < 16; ++x) {
               const float t0v = tt[fb][x];
               if constexpr (PC == 0) {
-                const int extra = ((32 * fb + 8 * (x >> 2)) * a.P) / D;   // channel / Dp: slice power p = extra + 1
+                const int extra = ((32 * fb + 8 * (x >> 2)) * p_any) / D;  // channel / Dp: slice power p = extra + 1
                 dv[fb][x] *= (float)(extra + 1) * pow_small(t0v, extra);   // d/dt of t^p
               } else {
                 constexpr int dummy = 0;
@@ -654,10 +657,18 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
         }
       }
       bf16x8 dub[T][2];
+      {
+        const float keep = valid ? 1.f : 0.f;             // rows past the end of the token set contribute nothing
 #pragma unroll
-      for (int fb = 0; fb < T; ++fb)
+        for (int fb = 0; fb < T; ++fb)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) dub[fb][x >> 3][x & 7] = static_cast<__bf16>(valid ? dv[fb][x] : 0.f);
+          for (int sp = 0; sp < 2; ++sp) {
+            u32x4 t4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t4[j] = pack_bf16(dv[fb][8 * sp + 2 * j] * keep, dv[fb][8 * sp + 2 * j + 1] * keep);
+            dub[fb][sp] = __builtin_bit_cast(bf16x8, t4);
+          }
+      }
       __syncthreads();                                  // M2: every wave has read its fragments of M
       write_chained(b_t, hpark);
       write_chained(a_t, dub);
@@ -690,9 +701,18 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) acc = mfma32(wt[fb * 2 + s], dub[fb][s], acc);
           __builtin_amdgcn_sched_barrier(0);
+          {
+            // the ReLU gate: bit -> sign position -> select, then rounded in pairs
+            const unsigned gbits = gate[hb >> 1] >> (16 * (hb & 1));
+            auto gated = [&](int x) { return (int)(gbits << (31 - x)) < 0 ? acc[x] : 0.f; };
 #pragma unroll
-          for (int x = 0; x < 16; ++x)
-            dpb[hb][x >> 3][x & 7] = static_cast<__bf16>((gate[hb >> 1] >> (16 * (hb & 1) + x)) & 1u ? acc[x] : 0.f);
+            for (int sp = 0; sp < 2; ++sp) {
+              u32x4 t4;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) t4[j] = pack_bf16(gated(8 * sp + 2 * j), gated(8 * sp + 2 * j + 1));
+              dpb[hb][sp] = __builtin_bit_cast(bf16x8, t4);
+            }
+          }
         }
       }
       __syncthreads();                                  // A2: the first contraction has read both tiles
