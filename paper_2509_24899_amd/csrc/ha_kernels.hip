@@ -559,6 +559,8 @@ hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_f
 hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsign, const float *rs, const float *wp,
                                  const ha_feature_map &fm, const void *w1f_, const void *w2f_, float *part, int CH,
                                  int n_chunks, hipStream_t st) {
+  if (state_uses_pipelined_kernel(pl))
+    return launch_state_pipelined_weighted(pl, q, gsign, rs, wp, fm, w1f_, w2f_, part, CH, n_chunks, st);
   dim3 grid(n_chunks, pl.B * pl.H);
   const bf16x8 *w1f = static_cast<const bf16x8 *>(w1f_), *w2f = static_cast<const bf16x8 *>(w2f_);
 #define HA_WSTATE(DD, F32) \

@@ -74,7 +74,10 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, void *ws
 hipError_t launch_state(const Plan &pl, const void *k, const void *v, const ha_feature_map &phi_k, void *ws,
                         hipStream_t st);
 hipError_t launch_state_pipelined(const Plan &pl, const void *k, const void *v, const ha_feature_map &phi_k, void *ws,
-                                  hipStream_t st);   // ha_state.hip: the d -> d -> d maps
+                                  hipStream_t st);
+hipError_t launch_state_pipelined_weighted(const Plan &pl, const void *q, const void *gsign, const float *rs, const float *wp,
+                                           const ha_feature_map &fm, const void *w1f, const void *w2f, float *part, int CH,
+                                           int n_chunks, hipStream_t st);   // ha_state.hip: the d -> d -> d maps
 hipError_t launch_weighted_state(const Plan &pl, const void *q, const void *gsign, const float *rs, const float *wp,
                                  const ha_feature_map &fm, const void *w1f, const void *w2f, float *part, int CH,
                                  int n_chunks, hipStream_t st);

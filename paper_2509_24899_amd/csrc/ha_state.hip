@@ -53,16 +53,22 @@ struct CompactArgs {
   int NS, n_kblocks;
 };
 
-template <bool F32, bool ACT0, bool COMPACT>
+// WEIGHTED (the value-distillation gradient runs this pass over all query tokens for dS = sum_i phi_q(q_i)^T g_i /
+// den_i and dz = sum_i dden_i phi_q(q_i)): `k` holds the queries, `v` a dense bf16 [B*H][NL][D] tensor, token i's
+// feature row is multiplied by rs[i] before it is rounded, and the "1" column becomes the pair of columns (hi, lo) of
+// wp[i].
+template <bool F32, bool ACT0, bool COMPACT, bool WEIGHTED = false>
 __global__ __launch_bounds__(512, 1) void state_pipelined_kernel(const void *__restrict__ k, const void *__restrict__ v,
                                                                  const void *w1_src, const void *w2_src,
                                                                  const float *__restrict__ b1_all,
                                                                  const float *__restrict__ b2_all, float *__restrict__ part,
                                                                  int H, int NL, int R, int G, int CH, int P, int act,
                                                                  int64_t sb, int64_t sh, int64_t sn, int N, int CC, int nsub,
-                                                                 CompactArgs ca) {
+                                                                 CompactArgs ca, const float *__restrict__ rs_all = nullptr,
+                                                                 const float *__restrict__ wp_all = nullptr) {
   constexpr int D = 128, HD = D, F = D, TOK = 128;
   static_assert(!(COMPACT && F32), "the compaction rides on direct-to-LDS loads of bf16 rows");
+  static_assert(!(COMPACT && WEIGHTED), "the weighted pass has no softmax keys to compact");
   constexpr int KS = D / 16, HB = HD / 32, FB = F / 32, NCB = D / 32 + 1, NT = FB * NCB;
   static_assert(HB == 4 && FB == 4 && KS == 8, "the hand-placed schedule below is written for 128 -> 128 -> 128");
   typedef RowTile<D> RT;
@@ -73,6 +79,7 @@ __global__ __launch_bounds__(512, 1) void state_pipelined_kernel(const void *__r
   __shared__ __align__(16) char v_t[TOK * ROWB];
   constexpr int CB = 2;                              // softmax-key blocks in flight per tile
   __shared__ __align__(16) char cstage[COMPACT ? CB * 4 * 2048 : 16];   // per block and wave: 16 key rows x 128 bytes of V
+  __shared__ __align__(16) __bf16 et[WEIGHTED ? 2 : 1][WEIGHTED ? TOK : 8];   // hi and lo part of wp per token of the tile
 
   const int chunk = blockIdx.x, bh = blockIdx.y, h = bh % H;
   const int64_t base = (int64_t)(bh / H) * sb + (int64_t)h * sh;
@@ -176,6 +183,16 @@ __global__ __launch_bounds__(512, 1) void state_pipelined_kernel(const void *__r
             }
           }
       }
+      float wp_tok = 0.f;
+      if constexpr (WEIGHTED) {
+        const int64_t ti = (int64_t)bh * NL + lmap.token(min(t0 + tf, NL - 1));
+        const float rs = rs_all[ti];
+        wp_tok = wp_all[ti];
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) u[fb][x] *= rs;
+      }
       if (t0 + TOK > lt_end) {                        // ragged end of the range: padded tokens add nothing
         const float keep = t0 + tf < lt_end ? 1.f : 0.f;
 #pragma unroll
@@ -196,6 +213,13 @@ __global__ __launch_bounds__(512, 1) void state_pipelined_kernel(const void *__r
       for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
         for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x2 *>(phi_t + phi_base[fb][q]) = four[fb][q];
+      if constexpr (WEIGHTED) {
+        if (g == 0) {
+          const __bf16 whi = static_cast<__bf16>(wp_tok);
+          et[0][tf] = whi;
+          et[1][tf] = static_cast<__bf16>(wp_tok - static_cast<float>(whi));
+        }
+      }
       __syncthreads();                                 // B: phi_t and v_t hold this tile
     }
     return;
@@ -252,7 +276,8 @@ __global__ __launch_bounds__(512, 1) void state_pipelined_kernel(const void *__r
       } else {
         tok = lmap.token(min(t0 + row, NL - 1));
       }
-      vreg[c] = load8<F32>(v, base + (int64_t)tok * sn + (v_pp ^ RT::sw(row)) * 8);
+      if constexpr (WEIGHTED) vreg[c] = static_cast<const bf16x8 *>(v)[((int64_t)bh * NL + tok) * (D / 8) + (v_pp ^ RT::sw(row))];
+      else vreg[c] = load8<F32>(v, base + (int64_t)tok * sn + (v_pp ^ RT::sw(row)) * 8);
     }
   };
   auto write_v = [&]() {
@@ -347,9 +372,17 @@ __global__ __launch_bounds__(512, 1) void state_pipelined_kernel(const void *__r
 #pragma unroll
         for (int kk = 0; kk < KB; ++kk) {
           const bf16x8 a8 = opnd(buf, kk, 0);
+          bf16x8 last = ones;
+          if constexpr (WEIGHTED) {
+            // slot i of this lane is token 16 ks + 8 g + i of the tile: eight consecutive weights, hi part for column 0,
+            // lo part for column 1, nothing for the other columns
+            const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+            const bf16x8 e8 = *reinterpret_cast<const bf16x8 *>(&et[r & 1][(2 * (batch * KB + kk) + g) << 3]);
+            last = r < 2 ? e8 : zero;
+          }
 #pragma unroll
           for (int cb = 0; cb < NCB; ++cb) {
-            acc[cb] = mfma32(a8, cb < D / 32 ? opnd(buf, kk, 1 + cb) : ones, acc[cb]);
+            acc[cb] = mfma32(a8, cb < D / 32 ? opnd(buf, kk, 1 + cb) : last, acc[cb]);
             if (batch + 1 < NBATCH) rd(batch + 1, buf ^ 1, kk * NCB + cb);
             HA_FENCE();
           }
@@ -413,6 +446,24 @@ hipError_t launch_state_pipelined(const Plan &pl, const void *k, const void *v, 
     else HA_STATE(false, false, false);
   }
 #undef HA_STATE
+  return hipGetLastError();
+}
+
+// The weighted pass over all query tokens (see WEIGHTED): partial tiles into `part`, chunks of CH tokens.
+hipError_t launch_state_pipelined_weighted(const Plan &pl, const void *q, const void *gsign, const float *rs, const float *wp,
+                                           const ha_feature_map &fm, const void *w1f, const void *w2f, float *part, int CH,
+                                           int n_chunks, hipStream_t st) {
+  dim3 grid(n_chunks, pl.B * pl.H);
+  // bf16 weights are read in place; fp32 ones as the prepared bf16 fragments the caller hands in
+  const void *w1 = pl.f32 ? w1f : fm.w1;
+  const void *w2 = pl.f32 ? w2f : fm.w2;
+  CompactArgs ca = {nullptr, nullptr, 0, 0};
+#define HA_WSTATE(F32, ACT0) \
+  state_pipelined_kernel<F32, ACT0, false, true><<<grid, 512, 0, st>>>(q, gsign, w1, w2, fm.b1, fm.b2, part, pl.H, pl.N, 0, 1, CH, pl.P, \
+                                                                      pl.act_q, pl.sb, pl.sh, pl.sn, pl.N, 0, 1, ca, rs, wp)
+  if (pl.act_q == HA_ACT_SOFTMAX) { if (pl.f32) HA_WSTATE(true, true); else HA_WSTATE(false, true); }
+  else { if (pl.f32) HA_WSTATE(true, false); else HA_WSTATE(false, false); }
+#undef HA_WSTATE
   return hipGetLastError();
 }
 
