@@ -676,44 +676,68 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
       // dpre = (W2^T du) [h > 0], under the first contraction; the x rows come back from L2 meanwhile
       bf16x8 dpb[T][2];
       bf16x8 xp[KS];
-      request_x(t0, xp);                                // this tile's x rows once more (L2): they go to the B side tile
       {
-        // the fragments of one hidden block at a time (LDS; the last two of the 32 from L2)
+        // Software pipeline over the four hidden blocks: the fragments of block hb + 1 are requested (LDS; the last
+        // two of the 32 from L2) before the matrix instructions of block hb, whose chain runs over the gating and
+        // rounding of block hb - 1 (two accumulators take turns).
         bf16x8 wlast[T * T * 2 - W2T_LDS];
 #pragma unroll
         for (int i = 0; i < T * T * 2 - W2T_LDS; ++i) wlast[i] = frag_at(w2tf, W2T_LDS + i, lane, z0);
-#pragma unroll
-        for (int hb = 0; hb < T; ++hb) {
-          bf16x8 wt[2 * T];
+        // this tile's x rows once more (L2): they go to the B side tile.  Requested behind the two fragments above:
+        // loads return in order, and the last hidden block must not wait for these rows as well
+        request_x(t0, xp);
+        bf16x8 wt[2][2 * T];
+        auto request_w = [&](int hb, bf16x8 (&dst)[2 * T]) {
 #pragma unroll
           for (int i = 0; i < 2 * T; ++i) {
             const int idx = hb * T * 2 + i;
-            if (idx < W2T_LDS) wt[i] = frag_at(w2tl, idx, lane);
-            else wt[i] = wlast[idx - W2T_LDS];
+            if (idx < W2T_LDS) dst[i] = frag_at(w2tl, idx, lane);
+            else dst[i] = wlast[idx - W2T_LDS];
           }
-          f32x16 acc;
+        };
+        // the ReLU gate (bit -> sign position -> select) and the rounding in pairs of one finished block
+        auto finish = [&](int hb, const f32x16 &acc) {
+          const unsigned gbits = gate[hb >> 1] >> (16 * (hb & 1));
+          auto gated = [&](int x) { return (int)(gbits << (31 - x)) < 0 ? acc[x] : 0.f; };
+#pragma unroll
+          for (int sp = 0; sp < 2; ++sp) {
+            u32x4 t4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t4[j] = pack_bf16(gated(8 * sp + 2 * j), gated(8 * sp + 2 * j + 1));
+            dpb[hb][sp] = __builtin_bit_cast(bf16x8, t4);
+          }
+        };
+        f32x16 accs[2];
+        request_w(0, wt[0]);
+#pragma unroll
+        for (int hb = 0; hb < T; ++hb) {
+          f32x16 &acc = accs[hb & 1];
 #pragma unroll
           for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+          if (hb + 1 < T) request_w(hb + 1, wt[(hb + 1) & 1]);
           if (hb == 1) request_x(t0 + TOK, xf);         // the rows of the next tile
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int fb = 0; fb < T; ++fb)
 #pragma unroll
-            for (int s = 0; s < 2; ++s) acc = mfma32(wt[fb * 2 + s], dub[fb][s], acc);
-          __builtin_amdgcn_sched_barrier(0);
-          {
-            // the ReLU gate: bit -> sign position -> select, then rounded in pairs
-            const unsigned gbits = gate[hb >> 1] >> (16 * (hb & 1));
-            auto gated = [&](int x) { return (int)(gbits << (31 - x)) < 0 ? acc[x] : 0.f; };
-#pragma unroll
-            for (int sp = 0; sp < 2; ++sp) {
-              u32x4 t4;
-#pragma unroll
-              for (int j = 0; j < 4; ++j) t4[j] = pack_bf16(gated(8 * sp + 2 * j), gated(8 * sp + 2 * j + 1));
-              dpb[hb][sp] = __builtin_bit_cast(bf16x8, t4);
+            for (int s2 = 0; s2 < 2; ++s2) {
+              acc = mfma32(wt[hb & 1][fb * 2 + s2], dub[fb][s2], acc);
+              // a quarter of the previous block's finish behind every second matrix instruction
+              if (hb > 0 && s2 == 1) {
+                const f32x16 &prev = accs[(hb - 1) & 1];
+                const unsigned gbits = gate[(hb - 1) >> 1] >> (16 * ((hb - 1) & 1));
+                auto gated = [&](int x) { return (int)(gbits << (31 - x)) < 0 ? prev[x] : 0.f; };
+                const int sp = fb >> 1, j0 = 2 * (fb & 1);
+                u32x4 t4 = {0u, 0u, 0u, 0u};
+                if (j0 != 0) t4 = __builtin_bit_cast(u32x4, dpb[hb - 1][sp]);   // (the first half was set a step earlier)
+                t4[j0] = pack_bf16(gated(8 * sp + 2 * j0), gated(8 * sp + 2 * j0 + 1));
+                t4[j0 + 1] = pack_bf16(gated(8 * sp + 2 * j0 + 2), gated(8 * sp + 2 * j0 + 3));
+                dpb[hb - 1][sp] = __builtin_bit_cast(bf16x8, t4);
+              }
             }
-          }
+          __builtin_amdgcn_sched_barrier(0);
         }
+        finish(T - 1, accs[(T - 1) & 1]);
       }
       __syncthreads();                                  // A2: the first contraction has read both tiles
       write_chained(a_t, dpb);
