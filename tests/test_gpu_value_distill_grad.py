@@ -69,6 +69,10 @@ def bf16_representable(inp):
 # by that noise: no fixed tolerance means anything there.)
 LOGIT_STD1 = W.replace(SMALL, name="small_logit_std1", seed=21, qk_gain=float(128 ** 0.5))
 CASES = [(W.TINY, 4), (SMALL, 4), (SMALL, 3), (SMALL64, 2), (LOGIT_STD1, 0), (LOGIT_STD1, 4)]
+# The head-width maps at d = 128 with every slice degree the kernel compiles in (1, 2, 4), one it takes at run time (8),
+# and fp32 inputs and outputs: one (batch, head) pair more than one workgroup's worth of tokens, a ragged last tile.
+CASES += [(W.replace(SMALL, name=f"small_P{P}", B=1, H=2, N=700, poly_degree=P, seed=40 + P), 4) for P in (1, 4, 8)]
+CASES += [(W.replace(SMALL, name="small_f32io", B=1, H=2, N=413, dtype="f32", seed=49), 2)]
 
 
 @pytest.mark.parametrize("wl,R", CASES)
