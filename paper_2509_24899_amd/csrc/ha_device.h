@@ -203,6 +203,33 @@ static __device__ __forceinline__ bf16x8 join(s16x4 a, s16x4 b) {
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+// Element e of the fragment arrays of one head's MLP weights (one thread per element):
+//   w1f[h][hb][ks][lane][t] = W1[h][32hb + r][16ks + 8g + t]                       (natural order)
+//   w2f[h][fb][hb][s][lane][t] = W2[h][32fb + r][32hb + crow(8s + t, g)]           (chained order)
+template <bool F32>
+static __device__ __forceinline__ void weight_prep_body(const void *__restrict__ w1, const void *__restrict__ w2,
+                                                        __bf16 *__restrict__ w1f, __bf16 *__restrict__ w2f,
+                                                        int D, int HD, int F, int h, int e) {
+  const int t = e & 7, lane = (e >> 3) & 63, rest = e >> 9;
+  const int r = lane & 31, g = lane >> 5;
+  auto ld = [](const void *p, int64_t i) -> float {
+    if constexpr (F32) return static_cast<const float *>(p)[i];
+    else return static_cast<float>(static_cast<const __bf16 *>(p)[i]);
+  };
+  if (e < HD * D) {
+    const int KS = D / 16;
+    const int ks = rest % KS, hb = rest / KS;
+    w1f[(int64_t)h * HD * D + e] = static_cast<__bf16>(ld(w1, ((int64_t)h * HD + 32 * hb + r) * D + 16 * ks + 8 * g + t));
+  }
+  if (e < F * HD) {
+    const int HB = HD / 32;
+    const int s = rest & 1, hb = (rest >> 1) % HB, fb = (rest >> 1) / HB;
+    w2f[(int64_t)h * F * HD + e] =
+        static_cast<__bf16>(ld(w2, ((int64_t)h * F + 32 * fb + r) * HD + 32 * hb + crow(8 * s + t, g)));
+  }
+}
+
+
 // A zero the compiler cannot see through.  Added to the scalar offset of fragment reads inside a loop whose
 // fragments are the same in every iteration, it keeps those reads in the loop (hoisted, a whole operand matrix
 // would sit in registers, i.e. in scratch).

@@ -31,10 +31,8 @@ namespace ha {
 // grad_weight_prep_kernel: grid (ceil(HD*F / 256), H)
 //   w2tf[h][hb][fb][s][lane][t] = W2[h][32fb + crow(8s + t, g)][32hb + r]
 template <bool F32>
-__global__ __launch_bounds__(256) void grad_weight_prep_kernel(const void *__restrict__ w2, __bf16 *__restrict__ w2tf,
-                                                               int HD, int F) {
-  const int h = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
+static __device__ __forceinline__ void grad_weight_prep_body(const void *__restrict__ w2, __bf16 *__restrict__ w2tf, int HD,
+                                                             int F, int h, int e) {
   if (e >= HD * F) return;
   const int t = e & 7, lane = (e >> 3) & 63, rest = e >> 9;
   const int r = lane & 31, g = lane >> 5;
@@ -46,13 +44,16 @@ __global__ __launch_bounds__(256) void grad_weight_prep_kernel(const void *__res
   else val = static_cast<float>(static_cast<const __bf16 *>(w2)[src]);
   w2tf[(int64_t)h * HD * F + e] = static_cast<__bf16>(val);
 }
+template <bool F32>
+__global__ __launch_bounds__(256) void grad_weight_prep_kernel(const void *__restrict__ w2, __bf16 *__restrict__ w2tf,
+                                                               int HD, int F) {
+  grad_weight_prep_body<F32>(w2, w2tf, HD, F, blockIdx.y, blockIdx.x * 256 + threadIdx.x);
+}
 
 // natural_frags_kernel: grid (ceil(rows*cols / 256), n_mat)
 //   hi/lo[m][rb][ks][lane][t] = M[m][32rb + r][16ks + 8g + t]
-__global__ __launch_bounds__(256) void natural_frags_kernel(const float *__restrict__ M, __bf16 *__restrict__ hi,
-                                                            __bf16 *__restrict__ lo, int rows, int cols) {
-  const int m = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
+static __device__ __forceinline__ void natural_frags_body(const float *__restrict__ M, __bf16 *__restrict__ hi,
+                                                          __bf16 *__restrict__ lo, int rows, int cols, int m, int e) {
   if (e >= rows * cols) return;
   const int t = e & 7, lane = (e >> 3) & 63, rest = e >> 9;
   const int r = lane & 31, g = lane >> 5;
@@ -62,6 +63,30 @@ __global__ __launch_bounds__(256) void natural_frags_kernel(const float *__restr
   const __bf16 h = static_cast<__bf16>(val);
   hi[(int64_t)m * rows * cols + e] = h;
   lo[(int64_t)m * rows * cols + e] = static_cast<__bf16>(val - static_cast<float>(h));
+}
+__global__ __launch_bounds__(256) void natural_frags_kernel(const float *__restrict__ M, __bf16 *__restrict__ hi,
+                                                            __bf16 *__restrict__ lo, int rows, int cols) {
+  natural_frags_body(M, hi, lo, rows, cols, blockIdx.y, blockIdx.x * 256 + threadIdx.x);
+}
+
+// grad_operands_kernel: the five small jobs ahead of the gradient passes of the square maps (d -> d -> d) in one
+// launch, grid (ceil(D*D / 256), 4 H + B*H): rows [0, H) and [H, 2 H) the forward fragments of phi_q's and phi_k's
+// weights, [2 H, 3 H) and [3 H, 4 H) their W2^T fragments, the rest S as hi + lo natural-order fragments.
+struct GradOperands {
+  const void *w1q, *w2q, *w1k, *w2k;
+  __bf16 *w1qf, *w2qf, *w1kf, *w2kf, *w2tq, *w2tk;
+  const float *S;
+  __bf16 *s_hi, *s_lo;
+  int D, H;
+};
+template <bool F32>
+__global__ __launch_bounds__(256) void grad_operands_kernel(GradOperands o) {
+  const int e = blockIdx.x * 256 + threadIdx.x, y = blockIdx.y, D = o.D, H = o.H;
+  if (y < H) weight_prep_body<F32>(o.w1q, o.w2q, o.w1qf, o.w2qf, D, D, D, y, e);
+  else if (y < 2 * H) weight_prep_body<F32>(o.w1k, o.w2k, o.w1kf, o.w2kf, D, D, D, y - H, e);
+  else if (y < 3 * H) grad_weight_prep_body<F32>(o.w2q, o.w2tq, D, D, y - 2 * H, e);
+  else if (y < 4 * H) grad_weight_prep_body<F32>(o.w2k, o.w2tk, D, D, y - 3 * H, e);
+  else natural_frags_body(o.S, o.s_hi, o.s_lo, D, D, y - 4 * H, e);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -832,9 +857,17 @@ __global__ __launch_bounds__(512, 1) void grad_split_kernel(GradArgs a) {
 // chunks of (batch b, head o) for every b (n_sum = B, shared parameters) or of (batch, head) pair o alone
 // (n_sum = 1), in a fixed order.  mat[o][row][col] row-major fp32, vec[o][row] = the extra column block
 // (columns 0 and 1: the hi and lo parts of a weighted sum, or the plain sum and zero).
+// With mat1 given the launch has a third grid dimension: z = 1 sums set `set + 1` into (mat1, vec1).
 __global__ __launch_bounds__(256) void grad_reduce_kernel(const float *__restrict__ part, float *__restrict__ mat,
                                                           float *__restrict__ vec, int D, int n_chunks, int n_sets,
-                                                          int set, int n_sum, int stride_sum) {
+                                                          int set, int n_sum, int stride_sum, float *__restrict__ mat1 = nullptr,
+                                                          float *__restrict__ vec1 = nullptr, __bf16 *__restrict__ frag_hi = nullptr,
+                                                          __bf16 *__restrict__ frag_lo = nullptr) {
+  if (blockIdx.z == 1) {
+    mat = mat1;
+    vec = vec1;
+    set += 1;
+  }
   const int T = D / 32, NCB = T + 1, NT2 = T * NCB;
   const int o = blockIdx.y;
   const int e = blockIdx.x * 256 + threadIdx.x;
@@ -864,8 +897,20 @@ __global__ __launch_bounds__(256) void grad_reduce_kernel(const float *__restric
     for (; c < n_chunks; ++c) sum += src[c * cstride] + (two ? src[c * cstride + 1] : 0.f);
   }
   const int row = 32 * rb + crow(x, g);
-  if (cb < T) mat[((int64_t)o * D + row) * D + 32 * cb + r] = sum;
-  else vec[(int64_t)o * D + row] = sum;
+  if (cb < T) {
+    const int col = 32 * cb + r;
+    mat[((int64_t)o * D + row) * D + col] = sum;
+    if (frag_hi) {
+      // the same matrix as hi + lo natural-order fragments (see natural_frags_kernel), for the pass that reads it next
+      const int lane_f = ((col >> 3) & 1) * 32 + (row & 31);
+      const int64_t fi = (int64_t)o * D * D + ((((row >> 5) * (D / 16) + (col >> 4)) * 64 + lane_f) << 3) + (col & 7);
+      const __bf16 hpart = static_cast<__bf16>(sum);
+      frag_hi[fi] = hpart;
+      frag_lo[fi] = static_cast<__bf16>(sum - static_cast<float>(hpart));
+    }
+  } else {
+    vec[(int64_t)o * D + row] = sum;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -942,22 +987,19 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
   const int D = pl.D, BH = pl.B * pl.H;
   hipError_t e;
 #define HA_CHECK() if ((e = hipGetLastError()) != hipSuccess) return e
-  // operand fragments: W1, W2 of both maps (forward order), W2^T (chained), S (natural, hi + lo)
-  if ((e = launch_weight_prep(pl, phi_q, true, ws, st)) != hipSuccess) return e;
-  if ((e = launch_weight_prep(pl, phi_k, false, ws, st)) != hipSuccess) return e;
+  // operand fragments: W1, W2 of both maps (forward order), W2^T (chained), S (natural, hi + lo): one launch
   {
-    dim3 grid((D * D + 255) / 256, pl.H);
-    if (pl.f32) {
-      grad_weight_prep_kernel<true><<<grid, 256, 0, st>>>(phi_q.w2, ws_ptr<__bf16>(ws, gp.off_w2tq), D, D);
-      grad_weight_prep_kernel<true><<<grid, 256, 0, st>>>(phi_k.w2, ws_ptr<__bf16>(ws, gp.off_w2tk), D, D);
-    } else {
-      grad_weight_prep_kernel<false><<<grid, 256, 0, st>>>(phi_q.w2, ws_ptr<__bf16>(ws, gp.off_w2tq), D, D);
-      grad_weight_prep_kernel<false><<<grid, 256, 0, st>>>(phi_k.w2, ws_ptr<__bf16>(ws, gp.off_w2tk), D, D);
-    }
+    GradOperands o;
+    o.w1q = phi_q.w1; o.w2q = phi_q.w2; o.w1k = phi_k.w1; o.w2k = phi_k.w2;
+    o.w1qf = ws_ptr<__bf16>(ws, pl.off_w1q); o.w2qf = ws_ptr<__bf16>(ws, pl.off_w2q);
+    o.w1kf = ws_ptr<__bf16>(ws, pl.off_w1k); o.w2kf = ws_ptr<__bf16>(ws, pl.off_w2k);
+    o.w2tq = ws_ptr<__bf16>(ws, gp.off_w2tq); o.w2tk = ws_ptr<__bf16>(ws, gp.off_w2tk);
+    o.S = ws_ptr<float>(ws, pl.off_S); o.s_hi = ws_ptr<__bf16>(ws, gp.off_shi); o.s_lo = ws_ptr<__bf16>(ws, gp.off_slo);
+    o.D = D; o.H = pl.H;
+    dim3 grid((D * D + 255) / 256, 4 * pl.H + BH);
+    if (pl.f32) grad_operands_kernel<true><<<grid, 256, 0, st>>>(o);
+    else grad_operands_kernel<false><<<grid, 256, 0, st>>>(o);
     HA_CHECK();
-    if ((e = launch_natural_frags(ws_ptr<float>(ws, pl.off_S), ws_ptr<void>(ws, gp.off_shi), ws_ptr<void>(ws, gp.off_slo), D, D,
-                                  BH, st)) != hipSuccess)
-      return e;
   }
   // per-row factors
   if ((e = launch_vd_rows(pl, y_teacher, y_student, row_den, ws_ptr<void>(ws, gp.off_gsign), ws_ptr<float>(ws, gp.off_rs),
@@ -969,7 +1011,7 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
   a.part = ws_ptr<float>(ws, gp.off_part);
   a.rs = ws_ptr<float>(ws, gp.off_rs);
   a.wp = ws_ptr<float>(ws, gp.off_wp);
-  const dim3 rgrid(gp.tiles_per_set * 1024 / 256, pl.H), rgrid_bh(gp.tiles_per_set * 1024 / 256, BH);
+  const dim3 rgrid2(gp.tiles_per_set * 1024 / 256, pl.H, 2), rgrid_bh(gp.tiles_per_set * 1024 / 256, BH);
   // query pass: phi_q's gradient and [dS | dz]
   {
     a.x = q; a.u = ws_ptr<void>(ws, gp.off_gsign);
@@ -983,19 +1025,16 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     else if (a.act == HA_ACT_SOFTMAX) { if (pl.f32) grad_split_kernel<true, true, true><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, true, true><<<grid, 512, 0, st>>>(a); }
     else { if (pl.f32) grad_split_kernel<true, true, false><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, true, false><<<grid, 512, 0, st>>>(a); }
     HA_CHECK();
-    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w2, gq.b2, D, gp.n_chunks_q, 2, 0, pl.B, pl.H);
-    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gq.w1, gq.b1, D, gp.n_chunks_q, 2, 1, pl.B, pl.H);
+    grad_reduce_kernel<<<rgrid2, 256, 0, st>>>(a.part, gq.w2, gq.b2, D, gp.n_chunks_q, 2, 0, pl.B, pl.H, gq.w1, gq.b1);
     HA_CHECK();
     // [dS | dz]: the weighted state pass over all query tokens, reduced per (batch, head)
     if ((e = launch_weighted_state(pl, q, ws_ptr<void>(ws, gp.off_gsign), a.rs, a.wp, phi_q, a.w1f, a.w2f, a.part, gp.CHq,
                                    gp.n_chunks_q, st)) != hipSuccess)
       return e;
     grad_reduce_kernel<<<rgrid_bh, 256, 0, st>>>(a.part, ws_ptr<float>(ws, gp.off_dS), ws_ptr<float>(ws, gp.off_dz), D,
-                                                 gp.n_chunks_q, 1, 0, 1, 0);
+                                                 gp.n_chunks_q, 1, 0, 1, 0, nullptr, nullptr, ws_ptr<__bf16>(ws, gp.off_dshi),
+                                                 ws_ptr<__bf16>(ws, gp.off_dslo));
     HA_CHECK();
-    if ((e = launch_natural_frags(ws_ptr<float>(ws, gp.off_dS), ws_ptr<void>(ws, gp.off_dshi), ws_ptr<void>(ws, gp.off_dslo), D,
-                                  D, BH, st)) != hipSuccess)
-      return e;
   }
   // key pass over the linear tokens: phi_k's gradient
   {
@@ -1010,8 +1049,7 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
     else if (a.act == HA_ACT_SOFTMAX) { if (pl.f32) grad_split_kernel<true, false, true><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, false, true><<<grid, 512, 0, st>>>(a); }
     else { if (pl.f32) grad_split_kernel<true, false, false><<<grid, 512, 0, st>>>(a); else grad_split_kernel<false, false, false><<<grid, 512, 0, st>>>(a); }
     HA_CHECK();
-    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w2, gk.b2, D, gp.n_chunks_k, 2, 0, pl.B, pl.H);
-    grad_reduce_kernel<<<rgrid, 256, 0, st>>>(a.part, gk.w1, gk.b1, D, gp.n_chunks_k, 2, 1, pl.B, pl.H);
+    grad_reduce_kernel<<<rgrid2, 256, 0, st>>>(a.part, gk.w2, gk.b2, D, gp.n_chunks_k, 2, 0, pl.B, pl.H, gk.w1, gk.b1);
     HA_CHECK();
   }
 #undef HA_CHECK
