@@ -562,7 +562,11 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
     if (s != HA_OK) return s;
   }
   double *partial = reinterpret_cast<double *>(static_cast<char *>(workspace) + off_partial);
-  if ((e = ha::launch_l1_distance(ps, y_teacher, y_student, partial, loss, st)) != hipSuccess) return ha::device_error(e);
+  // bf16 outputs with a gradient to form: the pass that turns the two outputs into signs and row factors forms the
+  // loss as well (same partial sums, same number); otherwise the loss has a pass of its own
+  const bool loss_with_rows = !ps.f32 && ps.NL > 0;
+  if (!loss_with_rows && (e = ha::launch_l1_distance(ps, y_teacher, y_student, partial, loss, st)) != hipSuccess)
+    return ha::device_error(e);
   const size_t H = (size_t)p->H, D = (size_t)p->d_head, HD = (size_t)phi_q->d_hidden, F = (size_t)phi_q->d_out;
   const size_t DM = phi_q->w_mid ? (size_t)phi_q->d_mid : 0, KL = DM ? DM : HD;
   if (ps.NL == 0) {
@@ -578,10 +582,10 @@ ha_status hybrid_attn_value_distill_grad(const ha_problem *p, const void *q, con
   }
   if (gl.layered)
     e = ha::launch_wide_value_distill_backward(ps, gl.wp, gl.wgp, q, k, v, *phi_q, *phi_k, y_teacher, y_student, row_den,
-                                               *grad_q, *grad_k, workspace, st);
+                                               *grad_q, *grad_k, workspace, st, loss_with_rows ? partial : nullptr, loss);
   else
     e = ha::launch_value_distill_backward(ps, gl.gp, q, k, v, *phi_q, *phi_k, y_teacher, y_student, row_den, *grad_q, *grad_k,
-                                          workspace, st);
+                                          workspace, st, loss_with_rows ? partial : nullptr, loss);
   if (e != hipSuccess) return ha::device_error(e);
   return HA_OK;
 }

@@ -133,6 +133,64 @@ __global__ __launch_bounds__(256) void vd_rows_kernel(const void *__restrict__ y
   }
 }
 
+// vd_rows_loss_kernel (bf16 io): what vd_rows_kernel writes, and in the same pass over the two outputs the partial
+// sums of || y - y_hat ||_1 exactly as l1_partial_kernel forms them (same grid (parts, B*H), same walk of a
+// contiguous range of rows in 16-byte pieces, same order of the additions), so the loss is the same number bit for
+// bit and the two tensors are read once instead of twice.
+template <int D>
+__global__ __launch_bounds__(256) void vd_rows_loss_kernel(const void *__restrict__ y_teacher, const void *__restrict__ y_student,
+                                                           const float *__restrict__ row_den, bf16x8 *__restrict__ gsign,
+                                                           float *__restrict__ rs, float *__restrict__ wp,
+                                                           double *__restrict__ partial, int H, int N, int64_t sb, int64_t sh,
+                                                           int64_t sn) {
+  constexpr int TPR = D / 8;                          // 16-byte pieces (threads) per row; 256 is a multiple of it
+  const int part = blockIdx.x, bh = blockIdx.y;
+  const int64_t base = (int64_t)(bh / H) * sb + (int64_t)(bh % H) * sh;
+  const int rows_per = (N + kL1Parts - 1) / kL1Parts;
+  const int r0 = part * rows_per, r1 = min(r0 + rows_per, N);
+  const int n_pieces = max(r1 - r0, 0) * TPR;
+  float acc = 0.f;
+  // every thread of a row group runs the same number of trips, so that the exchange below is among live lanes
+  for (int i0 = 0; i0 < n_pieces; i0 += 256) {
+    const int i = i0 + threadIdx.x;
+    const bool valid = i < n_pieces;
+    const int row = r0 + (valid ? i / TPR : 0), c8 = i % TPR;
+    const int64_t off = base + (int64_t)row * sn + c8 * 8;
+    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(y_teacher) + off);
+    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(y_student) + off);
+    bf16x8 gs;
+    float dot = 0.f, ad[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float yt = static_cast<float>(a[t]), ys = static_cast<float>(b[t]);
+      const float diff = ys - yt;
+      const float sg = diff > 0.f ? 1.f : (diff < 0.f ? -1.f : 0.f);
+      gs[t] = static_cast<__bf16>(sg);
+      dot += sg * ys;
+      ad[t] = fabsf(yt - ys);
+    }
+#pragma unroll
+    for (int m = 1; m < TPR; m <<= 1) dot += __shfl_xor(dot, m);
+    if (valid) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc += ad[t];          // (one term at a time, as the loss kernel adds them)
+      gsign[((int64_t)bh * N + row) * TPR + c8] = gs;
+      if (c8 == 0) {
+        rs[(int64_t)bh * N + row] = 1.0f / row_den[(int64_t)bh * N + row];
+        wp[(int64_t)bh * N + row] = -dot;
+      }
+    }
+  }
+  __shared__ double red[256];
+  red[threadIdx.x] = (double)acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[(int64_t)bh * kL1Parts + part] = red[0];
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0.f;
@@ -960,7 +1018,19 @@ hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st) {
 }
 
 hipError_t launch_vd_rows(const Plan &pl, const void *y_teacher, const void *y_student, const float *row_den, void *gsign,
-                          float *rs, float *wp, hipStream_t st) {
+                          float *rs, float *wp, hipStream_t st, double *l1_partial, double *loss) {
+  if (l1_partial && !pl.f32) {
+    dim3 grid(kL1Parts, pl.B * pl.H);
+    if (pl.D == 64)
+      vd_rows_loss_kernel<64><<<grid, 256, 0, st>>>(y_teacher, y_student, row_den, static_cast<bf16x8 *>(gsign), rs, wp, l1_partial,
+                                                    pl.H, pl.N, pl.sb, pl.sh, pl.sn);
+    else
+      vd_rows_loss_kernel<128><<<grid, 256, 0, st>>>(y_teacher, y_student, row_den, static_cast<bf16x8 *>(gsign), rs, wp, l1_partial,
+                                                     pl.H, pl.N, pl.sb, pl.sh, pl.sn);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_l1_final(pl, l1_partial, loss, st);
+  }
   const int D = pl.D, rpb = 256 / (D / 8);
   dim3 grid((pl.N + rpb - 1) / rpb, pl.B * pl.H);
 #define HA_ROWS(DD, F32) \
@@ -983,7 +1053,8 @@ hipError_t launch_natural_frags(const float *M, void *hi, void *lo, int rows, in
 hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, const void *q, const void *k, const void *v,
                                          const ha_feature_map &phi_q, const ha_feature_map &phi_k, const void *y_teacher,
                                          const void *y_student, const float *row_den, const ha_feature_map_grad &gq,
-                                         const ha_feature_map_grad &gk, void *ws, hipStream_t st) {
+                                         const ha_feature_map_grad &gk, void *ws, hipStream_t st, double *l1_partial,
+                                         double *loss) {
   const int D = pl.D, BH = pl.B * pl.H;
   hipError_t e;
 #define HA_CHECK() if ((e = hipGetLastError()) != hipSuccess) return e
@@ -1003,7 +1074,7 @@ hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, con
   }
   // per-row factors
   if ((e = launch_vd_rows(pl, y_teacher, y_student, row_den, ws_ptr<void>(ws, gp.off_gsign), ws_ptr<float>(ws, gp.off_rs),
-                          ws_ptr<float>(ws, gp.off_wp), st)) != hipSuccess)
+                          ws_ptr<float>(ws, gp.off_wp), st, l1_partial, loss)) != hipSuccess)
     return e;
   GradArgs a;
   a.H = pl.H; a.N = pl.N; a.R = pl.R; a.G = pl.G; a.P = pl.P;

@@ -586,7 +586,7 @@ hipError_t launch_state_reduce(const Plan &pl, void *ws, hipStream_t st) {
 // rows in 16-byte pieces, each thread adds its absolute differences in fp32 (a few hundred terms), the
 // workgroup total is formed in fp64 in a fixed order.  l1_final_kernel adds the partials of every
 // (batch, head) in part order, then the (batch, head) totals in order: bitwise reproducible.
-constexpr int L1_PARTS = 64;
+constexpr int L1_PARTS = kL1Parts;
 
 template <bool F32>
 __global__ __launch_bounds__(256) void l1_partial_kernel(const void *__restrict__ ya, const void *__restrict__ yb,
@@ -652,6 +652,10 @@ hipError_t launch_l1_distance(const Plan &pl, const void *ya, const void *yb, do
   else l1_partial_kernel<false><<<grid, 256, 0, st>>>(ya, yb, partial, pl.H, pl.N, pl.D, pl.sb, pl.sh, pl.sn);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  return launch_l1_final(pl, partial, loss, st);
+}
+
+hipError_t launch_l1_final(const Plan &pl, const double *partial, double *loss, hipStream_t st) {
   l1_final_kernel<<<1, 64, 0, st>>>(partial, loss, pl.B * pl.H);
   return hipGetLastError();
 }

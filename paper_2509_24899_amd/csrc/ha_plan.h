@@ -95,15 +95,20 @@ hipError_t launch_wide_query_side(const Plan &pl, const WidePlan &wp, const void
 size_t l1_partial_bytes(const Plan &pl);
 hipError_t launch_l1_distance(const Plan &pl, const void *ya, const void *yb, double *partial, double *loss,
                               hipStream_t st);
+constexpr int kL1Parts = 64;   // partial sums of the loss per (batch, head)
+hipError_t launch_l1_final(const Plan &pl, const double *partial, double *loss, hipStream_t st);
 // ha_grad.hip
 void make_grad_plan(const Plan &pl, size_t base_off, GradPlan &gp);
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 hipError_t launch_value_distill_backward(const Plan &pl, const GradPlan &gp, const void *q, const void *k, const void *v,
                                          const ha_feature_map &phi_q, const ha_feature_map &phi_k, const void *y_teacher,
                                          const void *y_student, const float *row_den, const ha_feature_map_grad &gq,
-                                         const ha_feature_map_grad &gk, void *ws, hipStream_t st);
+                                         const ha_feature_map_grad &gk, void *ws, hipStream_t st, double *l1_partial = nullptr,
+                                         double *loss = nullptr);
+// l1_partial / loss given (bf16 io only): the pass over the two outputs also forms the loss (the partial sums of
+// l1_partial_kernel, bit for bit), and the final sum is launched behind it
 hipError_t launch_vd_rows(const Plan &pl, const void *y_teacher, const void *y_student, const float *row_den, void *gsign,
-                          float *rs, float *wp, hipStream_t st);
+                          float *rs, float *wp, hipStream_t st, double *l1_partial = nullptr, double *loss = nullptr);
 hipError_t launch_natural_frags(const float *M, void *hi, void *lo, int rows, int cols, int n_mat, hipStream_t st);
 // ha_wide.hip / ha_wide_grad.hip
 hipError_t launch_wide_map(const Plan &pl, const WidePlan &wp, const void *x, const ha_feature_map &fm, bool is_query, void *ws,
@@ -113,7 +118,7 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
                                               const void *k, const void *v, const ha_feature_map &phi_q,
                                               const ha_feature_map &phi_k, const void *y_teacher, const void *y_student,
                                               const float *row_den, const ha_feature_map_grad &gq, const ha_feature_map_grad &gk,
-                                              void *ws, hipStream_t st);
+                                              void *ws, hipStream_t st, double *l1_partial = nullptr, double *loss = nullptr);
 hipError_t launch_mfma_probe(float *sink, int workgroups, int iters, int random_operands, hipStream_t st);
 
 }  // namespace ha

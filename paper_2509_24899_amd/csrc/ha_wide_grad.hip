@@ -531,11 +531,11 @@ hipError_t launch_wide_value_distill_backward(const Plan &pl, const WidePlan &wp
                                               const void *k, const void *v, const ha_feature_map &phi_q,
                                               const ha_feature_map &phi_k, const void *y_teacher, const void *y_student,
                                               const float *row_den, const ha_feature_map_grad &gq, const ha_feature_map_grad &gk,
-                                              void *ws, hipStream_t st) {
+                                              void *ws, hipStream_t st, double *l1_partial, double *loss) {
   const int BH = pl.B * pl.H, D = pl.D, F = pl.F, HD = pl.HD, DM = pl.DM, KL = DM > 0 ? DM : HD;
   hipError_t e;
   if ((e = launch_vd_rows(pl, y_teacher, y_student, row_den, ws_ptr<void>(ws, gp.off_gsign), ws_ptr<float>(ws, gp.off_rs),
-                          ws_ptr<float>(ws, gp.off_wp), st)) != hipSuccess)
+                          ws_ptr<float>(ws, gp.off_wp), st, l1_partial, loss)) != hipSuccess)
     return e;
   if ((e = launch_natural_frags(ws_ptr<float>(ws, pl.off_S), ws_ptr<void>(ws, gp.off_shi), ws_ptr<void>(ws, gp.off_slo), F, D, BH,
                                 st)) != hipSuccess)

@@ -307,3 +307,15 @@ def test_strided_layout():
     print("  case strided layout", flush=True)
     got, want = _cached_run(W.make_inputs(SMALL), 4, layout="bnhd")
     assert compare("bnhd_R4", got, want) <= GRAD_REL_L2
+
+
+@pytest.mark.parametrize("N,H", [(1337, 3), (37, 2)])
+def test_loss_of_the_gradient_call_is_the_loss_entry_points_number(N, H):
+    """With bf16 outputs the gradient call forms the loss in the pass that also writes the signs and row factors; it
+    adds the same terms in the same order as the loss entry point, so the two calls return the same bits."""
+    w = W.replace(SMALL, name=f"loss_bits_{N}", B=2, H=H, N=N, seed=61)
+    q, k, v, fq, fk = ha.to_device(W.make_inputs(w))
+    loss, _, _, _, _, _ = ha.hybrid_attn_value_distill_grad(q, k, v, fq, fk, w.rate, w.block_size, w.scale)
+    loss2, _, _ = ha.hybrid_attn_value_distill_loss(q, k, v, fq, fk, w.rate, w.block_size, w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(loss, loss2)
