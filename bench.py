@@ -318,6 +318,29 @@ def time_forward(ha, torch, step, steps, warmup):
     return elapsed * 1e3 / steps, sum(kernel_ms) / len(kernel_ms), sorted(kernel_ms)
 
 
+def graph_replay_ms(torch, step_on_current_stream, steps):
+    """The same step captured once into a HIP graph and replayed `steps` times (the forward is a fixed sequence of
+    launches with no allocation, no host synchronisation and no memset): ms per replay.  A separate pass behind the
+    timed region; the headline stays the eager figure."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step_on_current_stream()                      # warm-up on a side stream, as capture requires
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step_on_current_stream()
+    for _ in range(5):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def stage_breakdown(ha, torch, step, steps):
     """A second, untimed-for-the-headline pass with the full tap (five event records per forward): mean stage ms."""
     ha.hybrid_attn_profile_enable(steps)
@@ -520,6 +543,9 @@ def main():
     ap.add_argument("--zero-inputs", action="store_true",
                     help="all-zero q, k, v: NOT a benchmark, a power / clock experiment (same instruction stream, idle data wires)")
     ap.add_argument("--no-cold-cache", action="store_true", help="skip the extra forwards with flushed caches")
+    ap.add_argument("--graph", action="store_true",
+                    help="one more pass that replays the forward from a HIP graph (forward_ms_hip_graph_replay; on this "
+                         "runtime a replay is no faster than the three eager launches: 1.38 vs 1.36 ms, 37 vs 39 us at 1024 tokens)")
     ap.add_argument("--no-clock-settle", action="store_true",
                     help="skip the untimed steps that bring the GPU out of its idle clock state before the warm-up")
     ap.add_argument("--no-mfma-probe", action="store_true",
@@ -608,6 +634,13 @@ def main():
         ha.hybrid_attn_profile_enable(0)
         del flush
 
+    graph_ms = None
+    if args.graph:
+        def step_on_current_stream():
+            ha.hybrid_attn_forward(q, k, v, fq, fk, w.rate, w.block_size, w.scale, out=out, workspace=ws,
+                                   stream=torch.cuda.current_stream())
+        graph_ms = graph_replay_ms(torch, step_on_current_stream, args.steps)
+
     mfma_probe = None if args.no_mfma_probe else mfma_probe_rates(ha, torch, dev)
 
     flops = W.algorithmic_flops(w)
@@ -659,6 +692,7 @@ def main():
         "pct_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "query_kernel_ms_median": kernel_sorted[len(kernel_sorted) // 2], "query_kernel_ms_min": kernel_sorted[0],
         "forward_ms_cold_cache_median": cold_sorted[len(cold_sorted) // 2] if cold_sorted else None,
+        "forward_ms_hip_graph_replay": graph_ms,
         "stage_ms": {"compact": mean[0], "state": mean[1], "wprep_q": mean[2], "query": mean[3], "forward": mean[4],
                      "forward_median": fwd_sorted[len(fwd_sorted) // 2], "forward_min": fwd_sorted[0],
                      "source": "a second pass of the same steps, outside the timed region, with an event record between all stages "
