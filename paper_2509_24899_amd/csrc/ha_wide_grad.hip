@@ -454,10 +454,28 @@ __global__ __launch_bounds__(256) void wide_grad_reduce_kernel(const float *__re
   float sum = 0.f;
   for (int b = 0; b < n_sum; ++b) {
     const int64_t bh = (int64_t)b * stride_sum + o;
-    for (int c = 0; c < n_chunks; ++c) {
-      const float *src = part + ((bh * n_chunks + c) * nslab) * 20 * 1024 + off;
-      sum += src[0];
-      if (col == WB) sum += src[1];
+    // four chunks per step: the loads of a step do not depend on each other (a plain running sum exposes one memory
+    // round trip per chunk); the order of the additions is the same as one chunk at a time
+    const int64_t cstride = (int64_t)nslab * 20 * 1024;
+    const float *src0 = part + (bh * n_chunks) * cstride + off;
+    const bool two = col == WB;
+    int c = 0;
+    for (; c + 4 <= n_chunks; c += 4) {
+      float v[4], u[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[i] = src0[(c + i) * cstride];
+        u[i] = two ? src0[(c + i) * cstride + 1] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sum += v[i];
+        if (two) sum += u[i];
+      }
+    }
+    for (; c < n_chunks; ++c) {
+      sum += src0[c * cstride];
+      if (two) sum += src0[c * cstride + 1];
     }
   }
   if (col < WB) mat[((int64_t)o * WA + row) * WB + col] = sum;
