@@ -346,10 +346,17 @@ static __device__ __forceinline__ void state_reduce_body(const float *__restrict
   const int NCB = D / 32 + 1, FB = F / 32, NT = FB * NCB;
   if (e >= NT * 1024) return;
   const int ti = e >> 10, x = (e >> 6) & 15, lane = e & 63, r = lane & 31, g = lane >> 5;
-  // four chunks per step so that their loads are in flight together; fixed order of additions
+  // eight chunks per step so that their loads are in flight together; fixed order of additions
   float sum = 0.f;
   const float *src = part + (int64_t)bh * n_chunks * NT * 1024 + e;
   int c = 0;
+  for (; c + 8 <= n_chunks; c += 8) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = src[(int64_t)(c + i) * NT * 1024];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += v[i];
+  }
   for (; c + 4 <= n_chunks; c += 4) {
     float v[4];
 #pragma unroll
